@@ -1,0 +1,383 @@
+"""Pins for oracle/schedule.py: closed forms, an independent time-stepped checker,
+brute-force enumeration of tiny schedules, a direct check of the paper's
+constraints on every simulated timing, and live-set memory accounting."""
+import itertools
+
+import pytest
+
+from oracle import schedule as S
+from stage_inputs import schedules as G
+
+TABLE = S.memory_table(S.LLAMA, hidden=64, n_q_heads=4, n_kv_heads=2, head_dim=16, ffn=96, tokens=32, elem_size=2)
+L = 2
+
+
+# ------------------------------------------------------------------ independent re-implementations
+def tick_sim(lists, t_op, t_comm, t_copy):
+    """Integer time-stepped polling simulator (nothing shared with S.simulate)."""
+    p = len(lists)
+    fin = [dict() for _ in range(p)]          # event index -> finish tick
+    begun = [dict() for _ in range(p)]
+    busy_c = [0] * p
+    busy_x = [0] * p
+    t = 0
+    total = sum(len(l) for l in lists)
+
+    def finished(i, n, t):
+        return n in fin[i] and fin[i][n] <= t
+
+    def find(i, op, j):
+        for n, ev in enumerate(lists[i]):
+            if ev[0] == op and ev[1] == j:
+                return n
+        return None
+
+    while sum(len(f) for f in fin) < total:
+        for i in range(p):
+            for n, ev in enumerate(lists[i]):               # OWAIT events complete when their copy did
+                if ev[0] == "OWAIT" and n not in fin[i]:
+                    o = [k for k, e in enumerate(lists[i]) if e[0] == "O" and e[1:] == ev[1:]][0]
+                    if finished(i, o, t) and all(m in begun[i] or lists[i][m][0] == "OWAIT" and m in fin[i] or lists[i][m][0] in ("O", "R") for m in range(n)):
+                        fin[i][n] = fin[i][o]
+            comp = [n for n, ev in enumerate(lists[i]) if ev[0] in "FBW" and n not in begun[i]]
+            if comp and busy_c[i] <= t:
+                n = comp[0]
+                op, j = lists[i][n][0], lists[i][n][1]
+                ok = True
+                for m in range(n):
+                    e = lists[i][m]
+                    if e[0] == "OWAIT":
+                        o = [k for k, e2 in enumerate(lists[i]) if e2[0] == "O" and e2[1:] == e[1:]][0]
+                        ok &= finished(i, o, t)
+                    if e[0] in "FBW":
+                        ok &= finished(i, m, t)
+                if op == "F" and i > 0:
+                    u = find(i - 1, "F", j)
+                    ok &= u in fin[i - 1] and fin[i - 1][u] + t_comm <= t
+                if op == "B":
+                    if i < p - 1:
+                        u = find(i + 1, "B", j)
+                        ok &= u in fin[i + 1] and fin[i + 1][u] + t_comm <= t
+                    for m, e in enumerate(lists[i]):
+                        if e[0] == "R" and e[1] == j:
+                            ok &= finished(i, m, t)
+                if ok:
+                    begun[i][n] = t
+                    fin[i][n] = t + t_op[i][op]
+                    busy_c[i] = fin[i][n]
+            xfer = [n for n, ev in enumerate(lists[i]) if ev[0] in ("O", "R") and n not in begun[i]]
+            if xfer and busy_x[i] <= t:
+                n = xfer[0]
+                ev = lists[i][n]
+                ok = True
+                if ev[0] == "O":
+                    ok &= finished(i, find(i, "F", ev[1]), t)
+                else:
+                    for m in range(n):
+                        if lists[i][m][0] in "FBW":
+                            ok &= finished(i, m, t)
+                    o = [k for k, e2 in enumerate(lists[i]) if e2[0] == "O" and e2[1:] == ev[1:]][0]
+                    ok &= finished(i, o, t)
+                if ok:
+                    begun[i][n] = t
+                    fin[i][n] = t + t_copy
+                    busy_x[i] = fin[i][n]
+        t += 1
+        assert t < 400, "tick simulator stuck"
+    comp_ends = [fin[i][n] for i in range(p) for n, ev in enumerate(lists[i]) if ev[0] in "FBW"]
+    comp_starts = [begun[i][n] for i in range(p) for n, ev in enumerate(lists[i]) if ev[0] in "FBW"]
+    return max(comp_ends) - min(comp_starts), begun, fin
+
+
+def liveset_peak(events, n_layers, table):
+    """Peak bytes by tracking the set of live buffers (not a running sum of deltas)."""
+    live = set()
+    peak = 0
+
+    def total():
+        return sum(table[k] for (_, _, k) in live)
+
+    for ev in events:
+        op, j = ev[0], ev[1]
+        if op == "F":
+            for l in range(n_layers):
+                for k in S.F_KINDS:
+                    live.add((j, l, k))
+            peak = max(peak, total())
+        elif op == "B":
+            live.add((j, n_layers - 1, "DY"))
+            peak = max(peak, total())
+            for l in reversed(range(n_layers)):
+                live.add((j, l, "DX_MID"))
+                peak = max(peak, total())
+                live -= {(j, l, "X_MID"), (j, l, "LSE")}
+                if l > 0:
+                    live.add((j, l - 1, "DY"))
+                    peak = max(peak, total())
+                live -= {(j, l, "X_IN"), (j, l, "STATS")}
+        elif op == "W":
+            live = {b for b in live if b[0] != j}
+        elif op == "OWAIT":
+            live -= {(j, ev[2], k) for k in ev[3]}
+        elif op == "R":
+            live |= {(j, ev[2], k) for k in ev[3]}
+            peak = max(peak, total())
+    assert not live
+    return peak
+
+
+def check_constraints(lists, tm, t_op, t_comm, t_copy):
+    """Every paper constraint, checked directly on a timed schedule."""
+    eps = 1e-9
+    p = len(lists)
+    for i in range(p):
+        ev = lists[i]
+        st, en = tm.start[i], tm.end[i]
+        comp = [n for n, e in enumerate(ev) if e[0] in "FBW"]
+        xfer = [n for n, e in enumerate(ev) if e[0] in ("O", "R")]
+        for a, b in itertools.combinations(comp, 2):                 # Eq. 5: no overlap
+            assert en[a] <= st[b] + eps or en[b] <= st[a] + eps
+        for a, b in itertools.combinations(xfer, 2):                 # Eq. 8-11: one transfer at a time
+            assert en[a] <= st[b] + eps or en[b] <= st[a] + eps
+        idx = {(e[0], e[1]): n for n, e in enumerate(ev) if e[0] in "FBW"}
+        for (op, j), n in idx.items():
+            assert abs(en[n] - st[n] - t_op[i][op]) < eps
+            if op == "F":
+                assert en[idx[("F", j)]] <= st[idx[("B", j)]] + eps  # Eq. 6
+                assert en[idx[("B", j)]] <= st[idx[("W", j)]] + eps
+                if i > 0:                                            # Eq. 3
+                    up = [k for k, e in enumerate(lists[i - 1]) if e[:2] == ("F", j)][0]
+                    assert st[n] + eps >= tm.end[i - 1][up] + t_comm
+            if op == "B" and i < p - 1:                              # Eq. 4
+                dn = [k for k, e in enumerate(lists[i + 1]) if e[:2] == ("B", j)][0]
+                assert st[n] + eps >= tm.end[i + 1][dn] + t_comm
+            if op != "F" and j > 0:                                  # fixed micro-batch order
+                assert en[idx[(op, j - 1)]] <= st[n] + eps
+        for n, e in enumerate(ev):
+            if e[0] == "O":
+                assert st[n] + eps >= en[idx[("F", e[1])]]           # offload after its F
+            if e[0] == "R":
+                o = [k for k, e2 in enumerate(ev) if e2[0] == "O" and e2[1:] == e[1:]][0]
+                assert st[n] + eps >= en[o]
+                assert en[n] <= st[idx[("B", e[1])]] + eps           # reload completes before its consumer
+                for m in comp:
+                    if m < n:
+                        assert st[n] + eps >= en[m]                  # Eq. 14
+            if e[0] == "OWAIT":
+                o = [k for k, e2 in enumerate(ev) if e2[0] == "O" and e2[1:] == e[1:]][0]
+                for m in comp:
+                    if m > n:
+                        assert st[m] + eps >= en[o]                  # Eq. 12
+
+
+# ------------------------------------------------------------------ closed forms
+@pytest.mark.parametrize("p,m", [(4, 4), (8, 16), (2, 3), (3, 7)])
+def test_1f1b_bubble_closed_form(p, m):
+    lists = [G.one_f_one_b(p, m, i) for i in range(p)]
+    for i in range(p):
+        S.check_order(lists[i], m, L)
+    t_op = [{"F": 1.0, "B": 2.0, "W": 0.0}] * p          # B and W fused, identical stages, T_comm = 0
+    tm = S.simulate(lists, t_op)
+    assert abs(tm.makespan_global - (m + p - 1) * 3.0) < 1e-12
+    for i in range(p):
+        assert abs(tm.bubble[i] - (p - 1) / (m + p - 1)) < 1e-12
+    if (p, m) == (4, 4):
+        assert abs(tm.bubble[0] - 3 / 7) < 1e-12
+    if (p, m) == (8, 16):
+        assert abs(tm.bubble[1] - 7 / 23) < 1e-12
+    check_constraints(lists, tm, t_op, 0.0, 0.0)
+    # in-flight micro-batches: Eq. 7 usage peaks at min(p - i, m) * Delta_F
+    dF = S.op_delta("F", L, TABLE)
+    for i in range(p):
+        use = max(u for _, u in S.eq7_usage(lists[i], L, TABLE))
+        assert use == min(p - i, m) * dF
+
+
+def test_single_microbatch_closed_form():
+    p = 5
+    lists = [[("F", 0), ("B", 0), ("W", 0)] for _ in range(p)]
+    t_op = [{"F": 1.0 + 0.1 * i, "B": 2.0 + 0.2 * i, "W": 0.7 + 0.05 * i} for i in range(p)]
+    tc = 0.3
+    tm = S.simulate(lists, t_op, t_comm=tc)
+    want = sum(t["F"] for t in t_op) + sum(t["B"] for t in t_op) + t_op[0]["W"] + 2 * (p - 1) * tc
+    assert abs(tm.makespan_global - want) < 1e-12
+    check_constraints(lists, tm, t_op, tc, 0.0)
+
+
+def test_memory_signs_and_conservation():
+    dF, dB, dW = (S.op_delta(c, L, TABLE) for c in "FBW")
+    assert dF > 0 and dB < 0 and dW < 0 and dF + dB + dW == 0
+    assert all(v % 256 == 0 for v in TABLE.values())
+    ev = G.one_f_one_b(4, 6, 1)
+    peak, trace = S.account_memory(ev, L, TABLE)
+    assert trace[-1] == 0 and peak >= dF
+    assert peak == liveset_peak(ev, L, TABLE)
+    # the fine-grained peak exceeds Eq. 7's op-level figure by at most B's two transient buffers
+    eq7 = max(u for _, u in S.eq7_usage(ev, L, TABLE))
+    assert eq7 <= peak <= eq7 + TABLE["DY"] + TABLE["DX_MID"]
+
+
+def test_memory_table_values():
+    # llama-style layer at hidden 4096, 32 heads x 128, ffn 11008, 4096 tokens, bf16: 514.5 MiB
+    t = S.memory_table(S.LLAMA, 4096, 32, 32, 128, 11008, 4096, 2)
+    assert sum(t[k] for k in S.F_KINDS) == int(514.5 * 2**20) + 32 * 1024
+    assert t["QKV"] == 96 * 2**20 and t["GU"] == 172 * 2**20 and t["LSE"] == 2**19
+    # rounding to 256 bytes
+    t = S.memory_table(S.GPT, 3, 1, 1, 5, 7, 3, 4)
+    assert t["X_IN"] == 256 and t["STATS"] == 256 and t["GU"] == 256
+
+
+# ------------------------------------------------------------------ brute force
+def all_orders(m):
+    ops = [(c, j) for j in range(m) for c in "FBW"]
+
+    def rec(prefix, remaining):
+        if not remaining:
+            yield list(prefix)
+            return
+        for o in sorted(remaining):
+            c, j = o
+            if c == "B" and ("F", j) in remaining:
+                continue
+            if c == "W" and ("B", j) in remaining:
+                continue
+            if j > 0 and (c, j - 1) in remaining:
+                continue
+            yield from rec(prefix + [o], remaining - {o})
+    return list(rec([], set(ops)))
+
+
+@pytest.mark.parametrize("m", [1, 2, 3])
+def test_bruteforce_makespan_agrees(m):
+    orders = all_orders(m)
+    t_op = [{"F": 1, "B": 2, "W": 1}, {"F": 2, "B": 1, "W": 1}]
+    best_a = best_b = None
+    n_checked = 0
+    stride = 1
+    for l0 in orders[::stride]:
+        for l1 in orders[::stride]:
+            try:
+                tm = S.simulate([l0, l1], t_op, t_comm=1)
+            except S.ScheduleError:
+                # stage 1 cannot run B j before stage 0's F j etc. -> the tick simulator must also stall
+                with pytest.raises(AssertionError):
+                    tick_sim([l0, l1], t_op, 1, 0)
+                continue
+            span, begun, fin = tick_sim([l0, l1], t_op, 1, 0)
+            assert span == tm.makespan_global
+            for i, lst in enumerate((l0, l1)):
+                for n in range(len(lst)):
+                    assert begun[i][n] == tm.start[i][n] and fin[i][n] == tm.end[i][n]
+            check_constraints([l0, l1], tm, t_op, 1, 0)
+            best_a = span if best_a is None else min(best_a, span)
+            best_b = tm.makespan_global if best_b is None else min(best_b, tm.makespan_global)
+            n_checked += 1
+    assert best_a == best_b and n_checked > 0
+
+
+def offload_variants(order, j, kinds=("X_IN",), layer=0):
+    """Every placement of O / OWAIT / R for micro-batch j's item in a compute order."""
+    nF = order.index(("F", j))
+    nB = order.index(("B", j))
+    out = []
+    n = len(order)
+    for a in range(nF + 1, nB + 1):
+        for b in range(a, nB + 1):
+            for c in range(b, nB + 1):
+                lst = list(order)
+                for pos, ev in sorted([(c, ("R", j, layer, kinds)), (b, ("OWAIT", j, layer, kinds)),
+                                       (a, ("O", j, layer, kinds))], key=lambda x: -x[0]):
+                    lst.insert(pos, ev)
+                # inserting at equal positions in reverse keeps O, OWAIT, R in order
+                i_o, i_w, i_r = (lst.index(e) for e in (("O", j, layer, kinds), ("OWAIT", j, layer, kinds), ("R", j, layer, kinds)))
+                if i_o < i_w < i_r:
+                    out.append(lst)
+    assert n and out
+    return out
+
+
+def test_bruteforce_with_offload_equal_times_capacity_three():
+    # toy setting of the paper's illustration: all processing times equal, memory holds three
+    # activations; the best makespan must be found identically by both simulators, and every
+    # schedule's peak identically by running-sum and live-set accounting
+    m = 3
+    dF = S.op_delta("F", L, TABLE)
+    limit = 3 * dF + TABLE["DY"] + TABLE["DX_MID"]
+    t_op = [{"F": 1, "B": 1, "W": 1}] * 2
+    best = {}
+    count = 0
+    for l0 in all_orders(m):
+        for v0 in offload_variants(l0, 0):
+            S.check_order(v0, m, L)
+            pk, _ = S.account_memory(v0, L, TABLE)
+            assert pk == liveset_peak(v0, L, TABLE)
+            l1 = G.one_f_one_b(2, m, 1)
+            try:
+                tm = S.simulate([v0, l1], t_op, t_comm=0, t_copy=lambda i, ev: 1)
+            except S.ScheduleError:
+                continue
+            span, begun, fin = tick_sim([v0, l1], t_op, 0, 1)
+            assert span == tm.makespan_global, (v0, span, tm.makespan_global)
+            for n, ev in enumerate(v0):
+                if ev[0] != "OWAIT":
+                    assert begun[0][n] == tm.start[0][n], (v0, n)
+            check_constraints([v0, l1], tm, t_op, 0, 1)
+            if pk <= limit:
+                best["a"] = min(best.get("a", 10**9), span)
+                best["b"] = min(best.get("b", 10**9), tm.makespan_global)
+            count += 1
+    assert count > 20 and best["a"] == best["b"]
+
+
+def test_offload_lowers_peak_monotonically():
+    m, p, i = 6, 4, 0
+    base = G.split_bw_greedy(p, m)[i]
+    S.check_order(base, m, L)
+    pk0, _ = S.account_memory(base, L, TABLE)
+    prev = pk0
+    for min_gap in (6, 4, 2):
+        ev = G.add_offload(base, L, ("X_IN", "QKV", "X_MID"), min_gap=min_gap)
+        S.check_order(ev, m, L)
+        pk, tr = S.account_memory(ev, L, TABLE)
+        assert tr[-1] == 0 and pk <= prev and pk == liveset_peak(ev, L, TABLE)
+        prev = pk
+    assert prev < pk0
+    with pytest.raises(S.ScheduleError):
+        S.account_memory(base, L, TABLE, limit=pk0 - 1)
+    S.account_memory(base, L, TABLE, limit=pk0)
+
+
+def test_order_violations_are_caught():
+    good = G.one_f_one_b(2, 2, 0)
+    S.check_order(good, 2, L)
+    bad_lists = [
+        [("B", 0), ("F", 0), ("W", 0), ("F", 1), ("B", 1), ("W", 1)],
+        [("F", 0), ("W", 0), ("B", 0), ("F", 1), ("B", 1), ("W", 1)],
+        [("F", 1), ("F", 0), ("B", 0), ("W", 0), ("B", 1), ("W", 1)],
+        [("F", 0), ("F", 0), ("B", 0), ("W", 0)],
+        [("F", 0), ("B", 0), ("W", 0)],
+        [("O", 0, 0, ("QKV",)), ("F", 0), ("B", 0), ("W", 0), ("F", 1), ("B", 1), ("W", 1)],
+        [("F", 0), ("O", 0, 0, ("QKV",)), ("OWAIT", 0, 0, ("QKV",)), ("B", 0), ("W", 0), ("F", 1), ("B", 1), ("W", 1)],
+        [("F", 0), ("O", 0, 0, ("QKV",)), ("R", 0, 0, ("QKV",)), ("B", 0), ("W", 0), ("F", 1), ("B", 1), ("W", 1)],
+        [("F", 0), ("O", 0, 0, ("DY",)), ("B", 0), ("W", 0), ("F", 1), ("B", 1), ("W", 1)],
+        [("F", 0), ("O", 0, 5, ("QKV",)), ("B", 0), ("W", 0), ("F", 1), ("B", 1), ("W", 1)],
+    ]
+    for b in bad_lists:
+        with pytest.raises(S.ScheduleError):
+            S.check_order(b, 2, L)
+
+
+def test_split_bw_generator_is_valid_and_beats_1f1b():
+    p, m = 4, 8
+    lists = G.split_bw_greedy(p, m)
+    for i in range(p):
+        S.check_order(lists[i], m, L)
+    t_op = [{"F": 1.0, "B": 1.0, "W": 1.0}] * p
+    tm = S.simulate(lists, t_op)
+    check_constraints(lists, tm, t_op, 0.0, 0.0)
+    ref = S.simulate([G.one_f_one_b(p, m, i) for i in range(p)], t_op)
+    assert tm.makespan_global <= ref.makespan_global
+    # in-flight cap p - i holds
+    dF = S.op_delta("F", L, TABLE)
+    for i in range(p):
+        assert max(u for _, u in S.eq7_usage(lists[i], L, TABLE)) <= (p - i) * dF
