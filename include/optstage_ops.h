@@ -1,0 +1,77 @@
+/*
+ * Single-kernel entry points of liboptstage: each launches one step of a stage's F / B / W op graph
+ * (paper Sec. 2.2: linear maps z = W x, grad_x = W^T grad_z, grad_W = grad_z x^T; everything else is the
+ * non-linear part the paper folds into sigma).  They exist so that every kernel can be checked against
+ * the CPU oracle and timed on its own; the stage calls in optstage.h launch exactly these kernels.
+ *
+ * All tensor pointers are DEVICE memory, caller-owned, 16-byte aligned, row-major with tokens as rows.
+ * dtype is optstage_dtype (storage type; arithmetic is fp32 / bf16 MFMA with fp32 accumulation).
+ * stream is a hipStream_t.  Calls only enqueue; errors are reported as optstage_status with a message
+ * in optstage_last_error().  Shapes the kernels cannot handle are rejected on the host (OPTSTAGE_E_ARG).
+ */
+#ifndef OPTSTAGE_OPS_H
+#define OPTSTAGE_OPS_H
+
+#include "optstage.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] = sum_k A(m,k) B(n,k).
+ * layout 0 (NT): A is [M,K] (lda), B is [N,K] (ldb)  -- forward Y = X W^T and dX = dY (W^T)^T
+ * layout 1 (TN): A is [K,M] (lda), B is [K,N] (ldb)  -- dW = dY^T X
+ * epilogue 0: C (stage dtype) = product; 1: C = product + R (R like C); 2: C (fp32) += product.
+ * bf16 needs lda, ldb multiples of 8, N and ldc multiples of 4, K (NT) or M and N (TN) multiples of 8. */
+optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilogue, const void* A, const void* B,
+                                 void* C, const void* R, uint32_t M, uint32_t N, uint32_t K, uint32_t lda,
+                                 uint32_t ldb, uint32_t ldc, void* stream);
+
+/* family LLAMA: RMSNorm, stats[rows] = rstd.  family GPT: LayerNorm, stats[2*row] = mean, [2*row+1] = rstd. */
+optstage_status optstage_op_norm_fwd(uint32_t dtype, uint32_t family, const void* x, const void* gamma,
+                                     const void* beta, void* out, float* stats, uint32_t rows, uint32_t hidden,
+                                     float eps, void* stream);
+/* dx = (dres ? dres : 0) + norm'(dn); dgamma (and dbeta for GPT) fp32 [hidden] are ADDED to.
+ * partial: fp32 scratch of 2 * min(rows, 512) * hidden elements. */
+optstage_status optstage_op_norm_bwd(uint32_t dtype, uint32_t family, const void* dn, const void* x,
+                                     const float* stats, const void* gamma, const void* dres, void* dx,
+                                     float* partial, float* dgamma, float* dbeta, uint32_t rows, uint32_t hidden,
+                                     void* stream);
+/* LLAMA: a[rows, f] = silu(gu[:, :f]) * gu[:, f:], gu is [rows, 2f].  GPT: a = gelu(gu), gu is [rows, f]. */
+optstage_status optstage_op_act_fwd(uint32_t dtype, uint32_t family, const void* gu, void* a, uint32_t rows,
+                                    uint32_t ffn, void* stream);
+/* dgu like gu; dgu may alias gu. */
+optstage_status optstage_op_act_bwd(uint32_t dtype, uint32_t family, const void* da, const void* gu, void* dgu,
+                                    uint32_t rows, uint32_t ffn, void* stream);
+/* table: fp32 [seq][head_dim/2][2] = (cos, sin)(pos * base^(-2k/head_dim)). */
+optstage_status optstage_op_rope_table(float* table, uint32_t seq, uint32_t head_dim, float base, void* stream);
+/* Rotates the q and k heads of packed qkv rows [rows, (n_q + 2 n_kv) * head_dim], position = row % seq,
+ * pairing element k with k + head_dim/2.  backward != 0 applies the transposed rotation.  dst may be src
+ * (in place); otherwise the v part is copied too. */
+optstage_status optstage_op_rope(uint32_t dtype, const void* src, void* dst, const float* table, uint32_t rows,
+                                 uint32_t seq, uint32_t n_q, uint32_t n_kv, uint32_t head_dim, uint32_t backward,
+                                 void* stream);
+/* Causal attention over packed qkv [batch*seq, (n_q + 2 n_kv) * d]; q-head a reads kv-head a*n_kv/n_q.
+ * o is [batch*seq, n_q*d]; lse fp32 [batch][n_q][seq] (natural log). head_dim 64 or 128. */
+optstage_status optstage_op_attn_fwd(uint32_t dtype, const void* qkv, void* o, float* lse, uint32_t seq,
+                                     uint32_t batch, uint32_t n_q, uint32_t n_kv, uint32_t head_dim, void* stream);
+/* dqkv like qkv (must not alias it).  ws: fp32 scratch of optstage_op_attn_bwd_ws_floats() elements. */
+optstage_status optstage_op_attn_bwd(uint32_t dtype, const void* qkv, const void* o, const void* dout,
+                                     const float* lse, void* dqkv, float* ws, uint32_t seq, uint32_t batch,
+                                     uint32_t n_q, uint32_t n_kv, uint32_t head_dim, void* stream);
+uint64_t optstage_op_attn_bwd_ws_floats(uint32_t seq, uint32_t batch, uint32_t n_q, uint32_t n_kv, uint32_t head_dim);
+/* out_dev[0] = sum of the buffer's 64-bit words mod 2^64, out_dev[1] = their xor.  bytes % 8 == 0. */
+optstage_status optstage_op_checksum(const void* buf, uint64_t bytes, uint64_t* out_dev, void* stream);
+
+/* Pure host, no GPU needed: runs the ordering rules and the list-order memory accounting (Eq. 6, Eq. 7,
+ * fixed micro-batch order, offload / reload rules) over a whole list for the stage described by desc
+ * (shape fields, n_microbatches and hbm_budget_bytes are read; 0 budget = unlimited).  *peak_bytes is the
+ * highest live byte count reached (up to the failing event on error); live_after (may be null, HOST,
+ * n entries) receives the live bytes after each event. */
+optstage_status optstage_plan(const optstage_desc* desc, const optstage_event* events, size_t n, size_t* first_bad,
+                              uint64_t* peak_bytes, uint64_t* live_after);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,429 @@
+// HBM-bound fused elementwise kernels of a stage: the non-linear parts that the paper's stage model
+// folds into sigma(.) (Sec. 2.2) — RMSNorm / LayerNorm, SwiGLU / GELU, rotary — forward and backward,
+// plus helpers (weight transpose, rotary table, buffer checksum).  All arithmetic is fp32 on 16-byte
+// vector accesses of the storage type; rows are tokens.
+#include "common.h"
+
+namespace {
+
+constexpr int NT = 256;
+constexpr int MAXC = 4;   // 16-byte chunks per thread per row: hidden <= 256 * 4 * (4 | 8)
+
+__device__ __forceinline__ float block_sum(float v, float* red /* [2][4] */, int parity) {
+  v = wave_sum(v);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[parity * 4 + wave] = v;
+  __syncthreads();
+  return red[parity * 4] + red[parity * 4 + 1] + red[parity * 4 + 2] + red[parity * 4 + 3];
+}
+
+// ---- norm forward: one row per workgroup ------------------------------------------------------------
+template <typename T, bool LN>
+__global__ __launch_bounds__(NT) void norm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                      const T* __restrict__ beta, T* __restrict__ out,
+                                                      float* __restrict__ stats, int rows, int h, float eps) {
+  typedef Vec16<T> V;
+  __shared__ float red[16];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int nvec = h / V::N;
+  V xv[MAXC];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    int ci = tid + c * NT;
+    if (ci < nvec) {
+      xv[c] = *reinterpret_cast<const V*>(x + (size_t)row * h + ci * V::N);
+#pragma unroll
+      for (int e = 0; e < V::N; ++e) { float f = xv[c].get(e); s1 += f; s2 += f * f; }
+    }
+  }
+  float mean = 0.f;
+  if (LN) {
+    mean = block_sum(s1, red, 0) / h;
+    // two-pass variance for accuracy
+    s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = tid + c * NT;
+      if (ci < nvec)
+#pragma unroll
+        for (int e = 0; e < V::N; ++e) { float f = xv[c].get(e) - mean; s2 += f * f; }
+    }
+  }
+  const float var = block_sum(s2, red, 1) / h;
+  const float r = rsqrtf(var + eps);
+  if (tid == 0) {
+    if (LN) { stats[2 * row] = mean; stats[2 * row + 1] = r; } else stats[row] = r;
+  }
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    int ci = tid + c * NT;
+    if (ci < nvec) {
+      V g = *reinterpret_cast<const V*>(gamma + ci * V::N), o;
+      V b;
+      if (LN) b = *reinterpret_cast<const V*>(beta + ci * V::N);
+#pragma unroll
+      for (int e = 0; e < V::N; ++e) {
+        float f = (xv[c].get(e) - mean) * r * g.get(e);
+        if (LN) f += b.get(e);
+        o.set(e, f);
+      }
+      *reinterpret_cast<V*>(out + (size_t)row * h + ci * V::N) = o;
+    }
+  }
+}
+
+// ---- norm backward: workgroup b handles rows b, b + gridDim.x, ...; per-column partial sums of the
+// gain / bias gradients stay in registers and are written once per workgroup -------------------------
+template <typename T, bool LN>
+__global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, const T* __restrict__ x,
+                                                      const float* __restrict__ stats, const T* __restrict__ gamma,
+                                                      const T* __restrict__ dres, T* __restrict__ dx,
+                                                      float* __restrict__ partial, int rows, int h) {
+  typedef Vec16<T> V;
+  __shared__ float red[16];
+  const int tid = threadIdx.x;
+  const int nvec = h / V::N;
+  float pg[MAXC][V::N], pb[MAXC][V::N];
+  V gv[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    int ci = tid + c * NT;
+    if (ci < nvec) gv[c] = *reinterpret_cast<const V*>(gamma + ci * V::N);
+#pragma unroll
+    for (int e = 0; e < V::N; ++e) { pg[c][e] = 0.f; pb[c][e] = 0.f; }
+  }
+  int it = 0;
+  for (int row = blockIdx.x; row < rows; row += gridDim.x, ++it) {
+    float mean = 0.f, r;
+    if (LN) { mean = stats[2 * row]; r = stats[2 * row + 1]; } else r = stats[row];
+    V xv[MAXC], dv[MAXC];
+    float sg = 0.f, sgx = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = tid + c * NT;
+      if (ci < nvec) {
+        xv[c] = *reinterpret_cast<const V*>(x + (size_t)row * h + ci * V::N);
+        dv[c] = *reinterpret_cast<const V*>(dn + (size_t)row * h + ci * V::N);
+#pragma unroll
+        for (int e = 0; e < V::N; ++e) {
+          float xh = (xv[c].get(e) - mean) * r;
+          float d = dv[c].get(e);
+          float g = d * gv[c].get(e);
+          sg += g;
+          sgx += g * xh;
+          pg[c][e] += d * xh;
+          pb[c][e] += d;
+        }
+      }
+    }
+    const int par = (it & 1) * 2;
+    // two reductions share one barrier: pack both partials before the sync
+    sgx = wave_sum(sgx);
+    sg = wave_sum(sg);
+    const int wave = tid >> 6;
+    if ((tid & 63) == 0) { red[par * 4 + wave] = sgx; red[(par + 1) * 4 + wave] = sg; }
+    __syncthreads();
+    const float mgx = (red[par * 4] + red[par * 4 + 1] + red[par * 4 + 2] + red[par * 4 + 3]) / h;
+    const float mg = LN ? (red[(par + 1) * 4] + red[(par + 1) * 4 + 1] + red[(par + 1) * 4 + 2] + red[(par + 1) * 4 + 3]) / h : 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = tid + c * NT;
+      if (ci < nvec) {
+        V o, rs;
+        if (dres) rs = *reinterpret_cast<const V*>(dres + (size_t)row * h + ci * V::N);
+#pragma unroll
+        for (int e = 0; e < V::N; ++e) {
+          float xh = (xv[c].get(e) - mean) * r;
+          float g = dv[c].get(e) * gv[c].get(e);
+          float d = r * (g - mg - xh * mgx);
+          if (dres) d += rs.get(e);
+          o.set(e, d);
+        }
+        *reinterpret_cast<V*>(dx + (size_t)row * h + ci * V::N) = o;
+      }
+    }
+  }
+  float* pgo = partial + (size_t)blockIdx.x * h;
+  float* pbo = partial + (size_t)(gridDim.x + blockIdx.x) * h;
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    int ci = tid + c * NT;
+    if (ci < nvec)
+#pragma unroll
+      for (int e = 0; e < V::N; ++e) {
+        pgo[ci * V::N + e] = pg[c][e];
+        if (LN) pbo[ci * V::N + e] = pb[c][e];
+      }
+  }
+}
+
+// sums the per-workgroup partials column-wise and adds them into the caller's fp32 accumulators
+__global__ void norm_bwd_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dgamma,
+                                       float* __restrict__ dbeta, int nb, int h) {
+  int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= h) return;
+  const float* p = partial + (size_t)blockIdx.y * nb * h;
+  float s = 0.f;
+  for (int b = 0; b < nb; ++b) s += p[(size_t)b * h + col];
+  float* dst = blockIdx.y == 0 ? dgamma : dbeta;
+  dst[col] += s;
+}
+
+// ---- MLP activations --------------------------------------------------------------------------------
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + expf(-x)); }
+
+template <typename T, bool SWIGLU>
+__global__ void act_fwd_kernel(const T* __restrict__ gu, T* __restrict__ a, int rows, int f) {
+  typedef Vec16<T> V;
+  const int nvec = f / V::N;
+  const size_t total = (size_t)rows * nvec;
+  const int ldg = SWIGLU ? 2 * f : f;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    int row = i / nvec, c = i % nvec;
+    V g = *reinterpret_cast<const V*>(gu + (size_t)row * ldg + c * V::N), u, o;
+    if (SWIGLU) u = *reinterpret_cast<const V*>(gu + (size_t)row * ldg + f + c * V::N);
+#pragma unroll
+    for (int e = 0; e < V::N; ++e) {
+      float x = g.get(e);
+      if (SWIGLU) o.set(e, x * sigmoidf_(x) * u.get(e));
+      else o.set(e, 0.5f * x * (1.f + erff(x * 0.70710678118654752f)));
+    }
+    *reinterpret_cast<V*>(a + (size_t)row * f + c * V::N) = o;
+  }
+}
+
+// dgu may alias gu (each thread reads its elements before writing the same positions)
+template <typename T, bool SWIGLU>
+__global__ void act_bwd_kernel(const T* __restrict__ da, const T* gu, T* dgu, int rows, int f) {
+  typedef Vec16<T> V;
+  const int nvec = f / V::N;
+  const size_t total = (size_t)rows * nvec;
+  const int ldg = SWIGLU ? 2 * f : f;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    int row = i / nvec, c = i % nvec;
+    V d = *reinterpret_cast<const V*>(da + (size_t)row * f + c * V::N);
+    V g = *reinterpret_cast<const V*>(gu + (size_t)row * ldg + c * V::N), u, og, ou;
+    if (SWIGLU) u = *reinterpret_cast<const V*>(gu + (size_t)row * ldg + f + c * V::N);
+#pragma unroll
+    for (int e = 0; e < V::N; ++e) {
+      float x = g.get(e), dd = d.get(e);
+      if (SWIGLU) {
+        float s = sigmoidf_(x);
+        og.set(e, dd * u.get(e) * s * (1.f + x * (1.f - s)));
+        ou.set(e, dd * x * s);
+      } else {
+        float Phi = 0.5f * (1.f + erff(x * 0.70710678118654752f));
+        float phi = 0.39894228040143268f * expf(-0.5f * x * x);
+        og.set(e, dd * (Phi + x * phi));
+      }
+    }
+    *reinterpret_cast<V*>(dgu + (size_t)row * ldg + c * V::N) = og;
+    if (SWIGLU) *reinterpret_cast<V*>(dgu + (size_t)row * ldg + f + c * V::N) = ou;
+  }
+}
+
+// ---- rotary -----------------------------------------------------------------------------------------
+// table[pos][k] = (cos, sin)(pos * base^(-2k/d)), k < d/2, evaluated in fp64 once
+__global__ void rope_table_kernel(float2* __restrict__ table, int seq, int half, double base) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= seq * half) return;
+  int pos = i / half, k = i % half;
+  double theta = pow(base, -(double)k / (double)half);
+  double ang = (double)pos * theta;
+  table[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+// rotates the q and k heads of packed qkv rows, pairing element k with k + d/2; sign = -1 applies the
+// transposed rotation (gradients).  When dst != src the v part is copied as well.
+template <typename T>
+__global__ void rope_kernel(const T* src, T* dst, const float2* __restrict__ table, int rows, int seq, int n_rot,
+                            int n_v, int d, float sign, int do_rotate) {
+  typedef Vec16<T> V;
+  const int half = d / 2, vph = half / V::N;        // vectors per half head
+  const int ld = (n_rot + n_v) * d;
+  const size_t rot_items = (size_t)rows * n_rot * vph;
+  const size_t cp_items = (src != dst) ? (size_t)rows * n_v * (d / V::N) : 0;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < rot_items + cp_items; i += (size_t)gridDim.x * blockDim.x) {
+    if (i < rot_items) {
+      int c = i % vph;
+      size_t t = i / vph;
+      int head = t % n_rot, row = t / n_rot;
+      int pos = row % seq;
+      size_t off = (size_t)row * ld + head * d + c * V::N;
+      V lo = *reinterpret_cast<const V*>(src + off), hi = *reinterpret_cast<const V*>(src + off + half), olo, ohi;
+#pragma unroll
+      for (int e = 0; e < V::N; ++e) {
+        float cs = 1.f, sn = 0.f;
+        if (do_rotate) { float2 cssn = table[(size_t)pos * half + c * V::N + e]; cs = cssn.x; sn = sign * cssn.y; }
+        float a = lo.get(e), b = hi.get(e);
+        olo.set(e, a * cs - b * sn);
+        ohi.set(e, b * cs + a * sn);
+      }
+      *reinterpret_cast<V*>(dst + off) = olo;
+      *reinterpret_cast<V*>(dst + off + half) = ohi;
+    } else {
+      size_t k = i - rot_items;
+      int per_row = n_v * (d / V::N);
+      int row = k / per_row, c = k % per_row;
+      size_t off = (size_t)row * ld + (size_t)n_rot * d + c * V::N;
+      *reinterpret_cast<V*>(dst + off) = *reinterpret_cast<const V*>(src + off);
+    }
+  }
+}
+
+// ---- transpose (weights, once per weight update) ------------------------------------------------------
+template <typename T>
+__global__ void transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int rows, int cols) {
+  __shared__ T tile[64][65];
+  int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int e = threadIdx.x; e < 64 * 64; e += blockDim.x) {
+    int r = e / 64, c = e % 64;
+    if (r0 + r < rows && c0 + c < cols) tile[r][c] = src[(size_t)(r0 + r) * cols + c0 + c];
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * 64; e += blockDim.x) {
+    int c = e / 64, r = e % 64;
+    if (r0 + r < rows && c0 + c < cols) dst[(size_t)(c0 + c) * rows + r0 + r] = tile[r][c];
+  }
+}
+
+// ---- checksum: out[0] = sum of 64-bit words (mod 2^64), out[1] = xor of 64-bit words ---------------------
+__global__ void checksum_zero_kernel(unsigned long long* out) { out[0] = 0ull; out[1] = 0ull; }
+__global__ void checksum_kernel(const unsigned long long* __restrict__ w, size_t n, unsigned long long* out) {
+  unsigned long long s = 0, x = 0;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    unsigned long long v = w[i];
+    s += v;
+    x ^= v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    s += __shfl_xor(s, o, 64);
+    x ^= __shfl_xor(x, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    atomicAdd(&out[0], s);
+    atomicXor(&out[1], x);
+  }
+}
+
+int grid_for(size_t items, int block) {
+  size_t g = (items + block - 1) / block;
+  return (int)(g < 1 ? 1 : (g > 256 * 32 ? 256 * 32 : g));
+}
+
+template <typename T> bool norm_shape_ok(int h) { return h > 0 && h % Vec16<T>::N == 0 && h / Vec16<T>::N <= NT * MAXC; }
+
+}  // namespace
+
+hipError_t launch_norm_fwd(int dtype, int family, const void* x, const void* gamma, const void* beta, void* out,
+                           float* stats, int rows, int h, float eps, hipStream_t s) {
+  if (rows <= 0) return hipErrorInvalidValue;
+  const bool ln = family == FAM_GPT;
+  if (dtype == DT_BF16) {
+    if (!norm_shape_ok<bf16_t>(h)) return hipErrorInvalidValue;
+    if (ln) hipLaunchKernelGGL((norm_fwd_kernel<bf16_t, true>), dim3(rows), dim3(NT), 0, s, (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, stats, rows, h, eps);
+    else hipLaunchKernelGGL((norm_fwd_kernel<bf16_t, false>), dim3(rows), dim3(NT), 0, s, (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, stats, rows, h, eps);
+  } else {
+    if (!norm_shape_ok<float>(h)) return hipErrorInvalidValue;
+    if (ln) hipLaunchKernelGGL((norm_fwd_kernel<float, true>), dim3(rows), dim3(NT), 0, s, (const float*)x, (const float*)gamma, (const float*)beta, (float*)out, stats, rows, h, eps);
+    else hipLaunchKernelGGL((norm_fwd_kernel<float, false>), dim3(rows), dim3(NT), 0, s, (const float*)x, (const float*)gamma, (const float*)beta, (float*)out, stats, rows, h, eps);
+  }
+  return hipGetLastError();
+}
+
+int norm_bwd_partial_rows(int rows) { return rows < 512 ? rows : 512; }
+
+hipError_t launch_norm_bwd(int dtype, int family, const void* dn, const void* x, const float* stats,
+                           const void* gamma, const void* dres, void* dx, float* partial, float* dgamma,
+                           float* dbeta, int rows, int h, hipStream_t s) {
+  if (rows <= 0) return hipErrorInvalidValue;
+  const bool ln = family == FAM_GPT;
+  const int nb = norm_bwd_partial_rows(rows);
+  if (dtype == DT_BF16) {
+    if (!norm_shape_ok<bf16_t>(h)) return hipErrorInvalidValue;
+    if (ln) hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    else hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, false>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+  } else {
+    if (!norm_shape_ok<float>(h)) return hipErrorInvalidValue;
+    if (ln) hipLaunchKernelGGL((norm_bwd_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    else hipLaunchKernelGGL((norm_bwd_kernel<float, false>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(norm_bwd_reduce_kernel, dim3((h + 255) / 256, ln ? 2 : 1), dim3(256), 0, s, partial, dgamma, dbeta, nb, h);
+  return hipGetLastError();
+}
+
+hipError_t launch_act_fwd(int dtype, int family, const void* gu, void* a, int rows, int f, hipStream_t s) {
+  if (rows <= 0 || f <= 0) return hipErrorInvalidValue;
+  const bool sw = family == FAM_LLAMA;
+  if (dtype == DT_BF16) {
+    if (f % 8) return hipErrorInvalidValue;
+    int g = grid_for((size_t)rows * (f / 8), 256);
+    if (sw) hipLaunchKernelGGL((act_fwd_kernel<bf16_t, true>), dim3(g), dim3(256), 0, s, (const bf16_t*)gu, (bf16_t*)a, rows, f);
+    else hipLaunchKernelGGL((act_fwd_kernel<bf16_t, false>), dim3(g), dim3(256), 0, s, (const bf16_t*)gu, (bf16_t*)a, rows, f);
+  } else {
+    if (f % 4) return hipErrorInvalidValue;
+    int g = grid_for((size_t)rows * (f / 4), 256);
+    if (sw) hipLaunchKernelGGL((act_fwd_kernel<float, true>), dim3(g), dim3(256), 0, s, (const float*)gu, (float*)a, rows, f);
+    else hipLaunchKernelGGL((act_fwd_kernel<float, false>), dim3(g), dim3(256), 0, s, (const float*)gu, (float*)a, rows, f);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_act_bwd(int dtype, int family, const void* da, const void* gu, void* dgu, int rows, int f,
+                          hipStream_t s) {
+  if (rows <= 0 || f <= 0) return hipErrorInvalidValue;
+  const bool sw = family == FAM_LLAMA;
+  if (dtype == DT_BF16) {
+    if (f % 8) return hipErrorInvalidValue;
+    int g = grid_for((size_t)rows * (f / 8), 256);
+    if (sw) hipLaunchKernelGGL((act_bwd_kernel<bf16_t, true>), dim3(g), dim3(256), 0, s, (const bf16_t*)da, (const bf16_t*)gu, (bf16_t*)dgu, rows, f);
+    else hipLaunchKernelGGL((act_bwd_kernel<bf16_t, false>), dim3(g), dim3(256), 0, s, (const bf16_t*)da, (const bf16_t*)gu, (bf16_t*)dgu, rows, f);
+  } else {
+    if (f % 4) return hipErrorInvalidValue;
+    int g = grid_for((size_t)rows * (f / 4), 256);
+    if (sw) hipLaunchKernelGGL((act_bwd_kernel<float, true>), dim3(g), dim3(256), 0, s, (const float*)da, (const float*)gu, (float*)dgu, rows, f);
+    else hipLaunchKernelGGL((act_bwd_kernel<float, false>), dim3(g), dim3(256), 0, s, (const float*)da, (const float*)gu, (float*)dgu, rows, f);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(float* table, int seq, int d, float base, hipStream_t s) {
+  if (seq <= 0 || d <= 0 || (d & 1)) return hipErrorInvalidValue;
+  int n = seq * (d / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, (float2*)table, seq, d / 2, (double)base);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope(int dtype, const void* src, void* dst, const float* table, int rows, int seq, int n_q, int n_kv,
+                       int d, int backward, int do_rotate, hipStream_t s) {
+  if (rows <= 0 || seq <= 0) return hipErrorInvalidValue;
+  const int vn = dtype == DT_BF16 ? 8 : 4;
+  if ((d / 2) % vn) return hipErrorInvalidValue;
+  const int n_rot = n_q + n_kv;
+  size_t items = (size_t)rows * n_rot * (d / 2 / vn) + (src != dst ? (size_t)rows * n_kv * (d / vn) : 0);
+  int g = grid_for(items, 256);
+  float sign = backward ? -1.f : 1.f;
+  if (dtype == DT_BF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(g), dim3(256), 0, s, (const bf16_t*)src, (bf16_t*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate);
+  else hipLaunchKernelGGL(rope_kernel<float>, dim3(g), dim3(256), 0, s, (const float*)src, (float*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose(int dtype, const void* src, void* dst, int rows, int cols, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipErrorInvalidValue;
+  dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+  if (dtype == DT_BF16) hipLaunchKernelGGL(transpose_kernel<unsigned short>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, rows, cols);
+  else hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, s, (const float*)src, (float*)dst, rows, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_checksum(const void* buf, uint64_t bytes, uint64_t* out_dev, hipStream_t s) {
+  if (bytes % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(checksum_zero_kernel, dim3(1), dim3(1), 0, s, (unsigned long long*)out_dev);
+  size_t n = bytes / 8;
+  if (n) hipLaunchKernelGGL(checksum_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, (const unsigned long long*)buf, n, (unsigned long long*)out_dev);
+  return hipGetLastError();
+}

@@ -1,0 +1,124 @@
+// Single-kernel C-ABI entry points (include/optstage_ops.h) and the attention dispatch between the
+// MFMA kernels and the general path.
+#include "../../include/optstage_ops.h"
+#include "common.h"
+
+int optstage_fail_(int status, const char* msg);
+hipError_t launch_attn_fwd_simple(int dtype, const void* qkv, void* o, float* lse, int seq, int batch, int n_q,
+                                  int n_kv, int d, hipStream_t s);
+hipError_t launch_attn_bwd_simple(int dtype, const void* qkv, const void* o, const void* dout, const float* lse,
+                                  void* dqkv, float* ws, int seq, int batch, int n_q, int n_kv, int d, hipStream_t s);
+
+hipError_t launch_attn_fwd(int dtype, const void* qkv, void* o, float* lse, int seq, int batch, int n_q, int n_kv,
+                           int d, hipStream_t s) {
+  if (seq <= 0 || batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv) return hipErrorInvalidValue;
+  return launch_attn_fwd_simple(dtype, qkv, o, lse, seq, batch, n_q, n_kv, d, s);
+}
+
+hipError_t launch_attn_bwd(int dtype, const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv,
+                           float* ws, int seq, int batch, int n_q, int n_kv, int d, hipStream_t s) {
+  if (seq <= 0 || batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv) return hipErrorInvalidValue;
+  return launch_attn_bwd_simple(dtype, qkv, o, dout, lse, dqkv, ws, seq, batch, n_q, n_kv, d, s);
+}
+
+uint64_t attn_bwd_ws_floats(int seq, int batch, int n_q, int n_kv, int d) {
+  (void)n_kv; (void)d;
+  return (uint64_t)batch * n_q * seq;   // D_t = <dO_t, O_t> per query row and head
+}
+
+namespace {
+optstage_status wrap(hipError_t e, const char* what) {
+  if (e == hipSuccess) return OPTSTAGE_OK;
+  char msg[256];
+  snprintf(msg, sizeof msg, "%s: %s", what, hipGetErrorString(e));
+  return (optstage_status)optstage_fail_(e == hipErrorInvalidValue ? OPTSTAGE_E_ARG : OPTSTAGE_E_HIP, msg);
+}
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+#define REQ(cond, what) \
+  if (!(cond)) return (optstage_status)optstage_fail_(OPTSTAGE_E_ARG, what)
+}  // namespace
+
+extern "C" {
+
+optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilogue, const void* A, const void* B,
+                                 void* C, const void* R, uint32_t M, uint32_t N, uint32_t K, uint32_t lda,
+                                 uint32_t ldb, uint32_t ldc, void* stream) {
+  REQ(A && B && C && (epilogue != 1 || R), "gemm: null operand");
+  REQ(aligned16(A) && aligned16(B) && aligned16(C) && aligned16(R), "gemm: operands must be 16-byte aligned");
+  REQ(dtype <= 1 && layout <= 1 && epilogue <= 2, "gemm: bad dtype / layout / epilogue");
+  REQ(M && N && K && M < (1u << 30) && N < (1u << 30) && K < (1u << 30), "gemm: bad extent");
+  if (layout == 0) { REQ(lda >= K && ldb >= K, "gemm: leading dimension smaller than K"); }
+  else { REQ(lda >= M && ldb >= N, "gemm: leading dimension smaller than the row length"); }
+  REQ(ldc >= N, "gemm: ldc smaller than N");
+  hipError_t e = dtype == OPTSTAGE_BF16
+                     ? launch_gemm_bf16(layout, epilogue, A, B, C, R, M, N, K, lda, ldb, ldc, (hipStream_t)stream)
+                     : launch_gemm_f32(layout, epilogue, A, B, C, R, M, N, K, lda, ldb, ldc, (hipStream_t)stream);
+  return wrap(e, "gemm");
+}
+
+optstage_status optstage_op_norm_fwd(uint32_t dtype, uint32_t family, const void* x, const void* gamma,
+                                     const void* beta, void* out, float* stats, uint32_t rows, uint32_t hidden,
+                                     float eps, void* stream) {
+  REQ(x && gamma && out && stats && (family == OPTSTAGE_LLAMA || beta), "norm_fwd: null operand");
+  REQ(dtype <= 1 && family <= 1 && rows && rows < (1u << 30), "norm_fwd: bad argument");
+  return wrap(launch_norm_fwd(dtype, family, x, gamma, beta, out, stats, rows, hidden, eps, (hipStream_t)stream), "norm_fwd");
+}
+
+optstage_status optstage_op_norm_bwd(uint32_t dtype, uint32_t family, const void* dn, const void* x,
+                                     const float* stats, const void* gamma, const void* dres, void* dx,
+                                     float* partial, float* dgamma, float* dbeta, uint32_t rows, uint32_t hidden,
+                                     void* stream) {
+  REQ(dn && x && stats && gamma && dx && partial && dgamma && (family == OPTSTAGE_LLAMA || dbeta), "norm_bwd: null operand");
+  REQ(dtype <= 1 && family <= 1 && rows && rows < (1u << 30), "norm_bwd: bad argument");
+  return wrap(launch_norm_bwd(dtype, family, dn, x, stats, gamma, dres, dx, partial, dgamma, dbeta, rows, hidden, (hipStream_t)stream), "norm_bwd");
+}
+
+optstage_status optstage_op_act_fwd(uint32_t dtype, uint32_t family, const void* gu, void* a, uint32_t rows,
+                                    uint32_t ffn, void* stream) {
+  REQ(gu && a && dtype <= 1 && family <= 1 && rows < (1u << 30) && ffn < (1u << 30), "act_fwd: bad argument");
+  return wrap(launch_act_fwd(dtype, family, gu, a, rows, ffn, (hipStream_t)stream), "act_fwd");
+}
+
+optstage_status optstage_op_act_bwd(uint32_t dtype, uint32_t family, const void* da, const void* gu, void* dgu,
+                                    uint32_t rows, uint32_t ffn, void* stream) {
+  REQ(da && gu && dgu && dtype <= 1 && family <= 1 && rows < (1u << 30) && ffn < (1u << 30), "act_bwd: bad argument");
+  return wrap(launch_act_bwd(dtype, family, da, gu, dgu, rows, ffn, (hipStream_t)stream), "act_bwd");
+}
+
+optstage_status optstage_op_rope_table(float* table, uint32_t seq, uint32_t head_dim, float base, void* stream) {
+  REQ(table && seq && seq < (1u << 24) && head_dim && head_dim <= 1024, "rope_table: bad argument");
+  return wrap(launch_rope_table(table, seq, head_dim, base, (hipStream_t)stream), "rope_table");
+}
+
+optstage_status optstage_op_rope(uint32_t dtype, const void* src, void* dst, const float* table, uint32_t rows,
+                                 uint32_t seq, uint32_t n_q, uint32_t n_kv, uint32_t head_dim, uint32_t backward,
+                                 void* stream) {
+  REQ(src && dst && table && dtype <= 1 && rows && seq && n_q && n_kv && rows < (1u << 30), "rope: bad argument");
+  return wrap(launch_rope(dtype, src, dst, table, rows, seq, n_q, n_kv, head_dim, backward ? 1 : 0, 1, (hipStream_t)stream), "rope");
+}
+
+optstage_status optstage_op_attn_fwd(uint32_t dtype, const void* qkv, void* o, float* lse, uint32_t seq,
+                                     uint32_t batch, uint32_t n_q, uint32_t n_kv, uint32_t head_dim, void* stream) {
+  REQ(qkv && o && lse && dtype <= 1, "attn_fwd: bad argument");
+  REQ(seq < (1u << 24) && batch < 65536 && n_q < 65536 && n_kv <= n_q, "attn_fwd: extent out of range");
+  return wrap(launch_attn_fwd(dtype, qkv, o, lse, seq, batch, n_q, n_kv, head_dim, (hipStream_t)stream), "attn_fwd");
+}
+
+optstage_status optstage_op_attn_bwd(uint32_t dtype, const void* qkv, const void* o, const void* dout,
+                                     const float* lse, void* dqkv, float* ws, uint32_t seq, uint32_t batch,
+                                     uint32_t n_q, uint32_t n_kv, uint32_t head_dim, void* stream) {
+  REQ(qkv && o && dout && lse && dqkv && ws && dtype <= 1 && qkv != dqkv, "attn_bwd: bad argument");
+  REQ(seq < (1u << 24) && batch < 65536 && n_q < 65536 && n_kv <= n_q, "attn_bwd: extent out of range");
+  return wrap(launch_attn_bwd(dtype, qkv, o, dout, lse, dqkv, ws, seq, batch, n_q, n_kv, head_dim, (hipStream_t)stream), "attn_bwd");
+}
+
+uint64_t optstage_op_attn_bwd_ws_floats(uint32_t seq, uint32_t batch, uint32_t n_q, uint32_t n_kv, uint32_t head_dim) {
+  return attn_bwd_ws_floats(seq, batch, n_q, n_kv, head_dim);
+}
+
+optstage_status optstage_op_checksum(const void* buf, uint64_t bytes, uint64_t* out_dev, void* stream) {
+  REQ(buf && out_dev && ((uintptr_t)buf & 7) == 0, "checksum: bad argument");
+  return wrap(launch_checksum(buf, bytes, out_dev, (hipStream_t)stream), "checksum");
+}
+
+}  // extern "C"

@@ -1,0 +1,792 @@
+// Stage runtime: memory table, list-order activation accounting under the HBM budget (Eq. 7), the
+// physical arena, the offload / reload engine (side stream + events, Eq. 12-14) and the executor that
+// walks a per-stage event list and enqueues the F / B / W op graphs (Sec. 2.2, Sec. 3).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/optstage.h"
+#include "../../include/optstage_ops.h"
+#include "arena.h"
+#include "common.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+optstage_status fail(optstage_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+}  // namespace
+
+// used by the single-op wrappers in ops.hip
+int optstage_fail_(int status, const char* msg) {
+  snprintf(g_err, sizeof g_err, "%s", msg);
+  return status;
+}
+
+namespace {
+
+#define HIP_TRY(expr)                                                                         \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess) return fail(OPTSTAGE_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr uint64_t ALIGN = 256;
+constexpr int NK = OPTSTAGE_N_KINDS;
+constexpr int NFK = OPTSTAGE_N_F_KINDS;
+uint64_t round_up(uint64_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Shape {
+  int family, dtype, L, h, nq, nkv, d, f, seq, mb, tokens, qkv_w, up_w, e;
+};
+
+optstage_status shape_from_desc(const optstage_desc* d, Shape* s) {
+  if (!d) return fail(OPTSTAGE_E_ARG, "desc is null");
+  if (d->struct_size != sizeof(optstage_desc)) return fail(OPTSTAGE_E_ARG, "desc.struct_size mismatch");
+  if (d->family > 1 || d->dtype > 1) return fail(OPTSTAGE_E_ARG, "bad family or dtype");
+  if (!d->n_layers || !d->hidden || !d->n_q_heads || !d->n_kv_heads || !d->ffn || !d->seq || !d->micro_batch || !d->n_microbatches)
+    return fail(OPTSTAGE_E_ARG, "zero-sized shape field");
+  if (d->head_dim != 64 && d->head_dim != 128) return fail(OPTSTAGE_E_ARG, "head_dim must be 64 or 128");
+  if (d->n_q_heads % d->n_kv_heads) return fail(OPTSTAGE_E_ARG, "n_q_heads must be a multiple of n_kv_heads");
+  const int vec = d->dtype == OPTSTAGE_BF16 ? 8 : 4;
+  if (d->hidden % vec || d->ffn % vec) return fail(OPTSTAGE_E_ARG, "hidden and ffn must be multiples of %d", vec);
+  if (d->hidden / vec > 1024) return fail(OPTSTAGE_E_ARG, "hidden too large for the norm kernels");
+  if ((uint64_t)d->seq * d->micro_batch > (1u << 24)) return fail(OPTSTAGE_E_ARG, "too many tokens per micro-batch");
+  s->family = d->family; s->dtype = d->dtype; s->L = d->n_layers; s->h = d->hidden; s->nq = d->n_q_heads;
+  s->nkv = d->n_kv_heads; s->d = d->head_dim; s->f = d->ffn; s->seq = d->seq; s->mb = d->micro_batch;
+  s->tokens = d->seq * d->micro_batch;
+  s->qkv_w = (s->nq + 2 * s->nkv) * s->d;
+  s->up_w = s->family == OPTSTAGE_LLAMA ? 2 * s->f : s->f;
+  s->e = s->dtype == OPTSTAGE_BF16 ? 2 : 4;
+  return OPTSTAGE_OK;
+}
+
+// exact (unpadded) byte size of each activation kind for one layer of one micro-batch
+void kind_raw_bytes(const Shape& s, uint64_t raw[NK]) {
+  const uint64_t t = s.tokens, e = s.e;
+  raw[OPTSTAGE_K_X_IN] = t * s.h * e;
+  raw[OPTSTAGE_K_N1] = t * s.h * e;
+  raw[OPTSTAGE_K_QKV] = t * s.qkv_w * e;
+  raw[OPTSTAGE_K_O] = t * s.nq * s.d * e;
+  raw[OPTSTAGE_K_LSE] = (uint64_t)s.nq * t * 4;
+  raw[OPTSTAGE_K_X_MID] = t * s.h * e;
+  raw[OPTSTAGE_K_N2] = t * s.h * e;
+  raw[OPTSTAGE_K_GU] = t * s.up_w * e;
+  raw[OPTSTAGE_K_A] = t * s.f * e;
+  raw[OPTSTAGE_K_STATS] = (s.family == OPTSTAGE_LLAMA ? 2 : 4) * t * 4;
+  raw[OPTSTAGE_K_DY] = t * s.h * e;
+  raw[OPTSTAGE_K_DX_MID] = t * s.h * e;
+}
+
+struct WorkspaceLayout {
+  uint64_t rope, wt_base, wt[OPTSTAGE_N_WEIGHTS], wt_layer_stride, da, dn, dout, dqkv, attn, partial, csum, total;
+};
+
+uint64_t weight_elems(const Shape& s, int which) {
+  switch (which) {
+    case OPTSTAGE_W_QKV: return (uint64_t)s.qkv_w * s.h;
+    case OPTSTAGE_W_O: return (uint64_t)s.h * s.nq * s.d;
+    case OPTSTAGE_W_GU: return (uint64_t)s.up_w * s.h;
+    case OPTSTAGE_W_D: return (uint64_t)s.h * s.f;
+    default: return s.h;
+  }
+}
+
+WorkspaceLayout workspace_layout(const Shape& s) {
+  WorkspaceLayout w;
+  memset(&w, 0, sizeof w);
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) { uint64_t o = off; off += round_up(bytes); return o; };
+  w.rope = take(s.family == OPTSTAGE_LLAMA ? (uint64_t)s.seq * (s.d / 2) * 8 : 0);
+  uint64_t lstart = off;
+  w.wt_base = lstart;
+  for (int k : {OPTSTAGE_W_QKV, OPTSTAGE_W_O, OPTSTAGE_W_GU, OPTSTAGE_W_D}) w.wt[k] = take(weight_elems(s, k) * s.e) - lstart;
+  w.wt_layer_stride = off - lstart;
+  off = lstart + w.wt_layer_stride * s.L;
+  w.da = take((uint64_t)s.tokens * s.f * s.e);
+  w.dn = take((uint64_t)s.tokens * s.h * s.e);
+  w.dout = take((uint64_t)s.tokens * s.nq * s.d * s.e);
+  w.dqkv = take((uint64_t)s.tokens * s.qkv_w * s.e);
+  w.attn = take(attn_bwd_ws_floats(s.seq, s.mb, s.nq, s.nkv, s.d) * 4);
+  w.partial = take((uint64_t)2 * norm_bwd_partial_rows(s.tokens) * s.h * 4);
+  w.csum = take(16);
+  w.total = off;
+  return w;
+}
+
+enum BufState : uint8_t { B_NONE = 0, B_DEV, B_OFFLOADING, B_HOST, B_RELOADED };
+
+struct BufRec {
+  uint8_t state = B_NONE;
+  uint64_t dev_off = 0, host_off = 0;
+};
+
+struct MbState {
+  bool f = false, b = false, w = false;
+};
+
+// Pure host, copyable: everything the validator needs.
+struct Logical {
+  int L = 0, m = 0;
+  uint64_t bytes[NK] = {}, budget = 0, live = 0, peak = 0;
+  int next_f = 0, next_b = 0, next_w = 0;
+  std::vector<MbState> mbs;
+  std::vector<BufRec> bufs;   // [mb][layer][kind]
+  BlockArena arena, host;
+  BufRec& buf(int j, int l, int k) { return bufs[((size_t)j * L + l) * NK + k]; }
+};
+
+struct OpBufs {   // device offsets an op touches, captured before its releases; host offsets for O / R
+  std::vector<uint64_t> dev, host;   // [layer][kind]
+};
+
+struct TimedSpan { int op; hipEvent_t a, b; };
+
+}  // namespace
+
+struct optstage {
+  optstage_desc desc;
+  Shape sh;
+  WorkspaceLayout ws;
+  uint64_t raw[NK];
+  Logical lg;
+  hipStream_t cs, xs;   // compute, copy
+  std::vector<const void*> w;          // [layer][which]
+  std::vector<float*> gw;              // [layer][which]
+  std::vector<const void*> x_in, dy_out;
+  std::vector<void*> y_out, dx_in;
+  std::vector<hipEvent_t> ev_f, ev_o, ev_r, ev_pos;   // [mb], [mb][layer] x3
+  std::vector<hipEvent_t> tpool;
+  size_t tnext = 0;
+  std::vector<TimedSpan> spans;
+  optstage_stats stats;
+  char* arena() const { return (char*)desc.arena; }
+  char* wsp() const { return (char*)desc.workspace; }
+};
+
+namespace {
+
+optstage_status alloc_dev(Logical& lg, int j, int l, int k) {
+  BufRec& b = lg.buf(j, l, k);
+  const uint64_t n = lg.bytes[k];
+  if (lg.budget && lg.live + n > lg.budget)
+    return fail(OPTSTAGE_E_BUDGET, "micro-batch %d layer %d kind %d needs %llu live bytes, budget %llu", j, l, k,
+                (unsigned long long)(lg.live + n), (unsigned long long)lg.budget);
+  uint64_t off = lg.arena.alloc(n);
+  if (off == UINT64_MAX)
+    return fail(OPTSTAGE_E_ARENA, "arena cannot place %llu bytes (largest free range %llu of %llu)", (unsigned long long)n,
+                (unsigned long long)lg.arena.largest_free(), (unsigned long long)lg.arena.capacity());
+  b.dev_off = off;
+  lg.live += n;
+  if (lg.live > lg.peak) lg.peak = lg.live;
+  return OPTSTAGE_OK;
+}
+
+void free_dev(Logical& lg, int j, int l, int k) {
+  BufRec& b = lg.buf(j, l, k);
+  lg.arena.release(b.dev_off, lg.bytes[k]);
+  lg.live -= lg.bytes[k];
+}
+
+// Applies one event to the logical state.  On error the state may be partly modified: callers run it
+// on a scratch copy first.
+optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) {
+  const int L = lg.L;
+  const int j = (int)ev.microbatch;
+  if (ev.microbatch >= (uint32_t)lg.m) return fail(OPTSTAGE_E_ARG, "micro-batch %u out of range", ev.microbatch);
+  if (out) { out->dev.assign((size_t)L * NK, UINT64_MAX); out->host.assign((size_t)L * NK, UINT64_MAX); }
+  auto note = [&](int l, int k) { if (out) out->dev[(size_t)l * NK + k] = lg.buf(j, l, k).dev_off; };
+  MbState& mb = lg.mbs[j];
+  optstage_status st;
+  switch (ev.op) {
+    case OPTSTAGE_F: {
+      if (mb.f) return fail(OPTSTAGE_E_ORDER, "F %d listed twice", j);
+      if (j != lg.next_f) return fail(OPTSTAGE_E_ORDER, "F ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_f, j);
+      for (int l = 0; l < L; ++l)
+        for (int k = 0; k < NFK; ++k) {
+          if ((st = alloc_dev(lg, j, l, k)) != OPTSTAGE_OK) return st;
+          lg.buf(j, l, k).state = B_DEV;
+          note(l, k);
+        }
+      mb.f = true;
+      lg.next_f++;
+      return OPTSTAGE_OK;
+    }
+    case OPTSTAGE_B: {
+      if (mb.b) return fail(OPTSTAGE_E_ORDER, "B %d listed twice", j);
+      if (!mb.f) return fail(OPTSTAGE_E_ORDER, "B %d before F %d", j, j);
+      if (j != lg.next_b) return fail(OPTSTAGE_E_ORDER, "B ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_b, j);
+      for (int l = 0; l < L; ++l)
+        for (int k = 0; k < NFK; ++k) {
+          uint8_t s = lg.buf(j, l, k).state;
+          if (s != B_DEV && s != B_RELOADED)
+            return fail(OPTSTAGE_E_ORDER, "B %d while layer %d kind %d is offloaded and not reloaded", j, l, k);
+          note(l, k);
+        }
+      auto make = [&](int l, int k) -> optstage_status {
+        optstage_status s2 = alloc_dev(lg, j, l, k);
+        if (s2 == OPTSTAGE_OK) { lg.buf(j, l, k).state = B_DEV; note(l, k); }
+        return s2;
+      };
+      auto drop = [&](int l, int k) { free_dev(lg, j, l, k); lg.buf(j, l, k).state = B_NONE; };
+      if ((st = make(L - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
+      for (int l = L - 1; l >= 0; --l) {
+        if ((st = make(l, OPTSTAGE_K_DX_MID)) != OPTSTAGE_OK) return st;
+        drop(l, OPTSTAGE_K_X_MID);
+        drop(l, OPTSTAGE_K_LSE);
+        if (l > 0 && (st = make(l - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
+        drop(l, OPTSTAGE_K_X_IN);
+        drop(l, OPTSTAGE_K_STATS);
+      }
+      mb.b = true;
+      lg.next_b++;
+      return OPTSTAGE_OK;
+    }
+    case OPTSTAGE_W: {
+      if (mb.w) return fail(OPTSTAGE_E_ORDER, "W %d listed twice", j);
+      if (!mb.b) return fail(OPTSTAGE_E_ORDER, "W %d before B %d", j, j);
+      if (j != lg.next_w) return fail(OPTSTAGE_E_ORDER, "W ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_w, j);
+      static const int freed[] = {OPTSTAGE_K_N1, OPTSTAGE_K_QKV, OPTSTAGE_K_O, OPTSTAGE_K_DX_MID,
+                                  OPTSTAGE_K_N2, OPTSTAGE_K_GU, OPTSTAGE_K_A, OPTSTAGE_K_DY};
+      for (int l = 0; l < L; ++l)
+        for (int k : freed) {
+          note(l, k);
+          free_dev(lg, j, l, k);
+          lg.buf(j, l, k).state = B_NONE;
+        }
+      mb.w = true;
+      lg.next_w++;
+      return OPTSTAGE_OK;
+    }
+    case OPTSTAGE_O:
+    case OPTSTAGE_OWAIT:
+    case OPTSTAGE_R: {
+      if (ev.layer >= (uint32_t)L) return fail(OPTSTAGE_E_ARG, "layer %u out of range", ev.layer);
+      if (!ev.kind_mask || (ev.kind_mask >> NFK)) return fail(OPTSTAGE_E_ARG, "kind_mask 0x%x names no offloadable kind or a non-offloadable one", ev.kind_mask);
+      const int l = (int)ev.layer;
+      for (int k = 0; k < NFK; ++k) {
+        if (!(ev.kind_mask & (1u << k))) continue;
+        BufRec& b = lg.buf(j, l, k);
+        if (ev.op == OPTSTAGE_O) {
+          if (!mb.f || mb.b) return fail(OPTSTAGE_E_ORDER, "offload of micro-batch %d outside its F..B window", j);
+          if (b.state != B_DEV) return fail(OPTSTAGE_E_ORDER, "offload of micro-batch %d layer %d kind %d: not resident or already offloaded", j, l, k);
+          uint64_t ho = lg.host.alloc(lg.bytes[k]);
+          if (ho == UINT64_MAX) return fail(OPTSTAGE_E_HOSTPOOL, "pinned host pool exhausted (%llu bytes)", (unsigned long long)lg.host.capacity());
+          b.host_off = ho;
+          b.state = B_OFFLOADING;
+        } else if (ev.op == OPTSTAGE_OWAIT) {
+          if (b.state != B_OFFLOADING) return fail(OPTSTAGE_E_ORDER, "OWAIT of micro-batch %d layer %d kind %d without a pending offload", j, l, k);
+          note(l, k);
+          free_dev(lg, j, l, k);
+          b.state = B_HOST;
+        } else {
+          if (b.state != B_HOST) return fail(OPTSTAGE_E_ORDER, "reload of micro-batch %d layer %d kind %d before its offload completed", j, l, k);
+          if ((st = alloc_dev(lg, j, l, k)) != OPTSTAGE_OK) return st;
+          lg.host.release(b.host_off, lg.bytes[k]);
+          b.state = B_RELOADED;
+        }
+        if (out) {
+          out->dev[(size_t)l * NK + k] = b.dev_off;
+          out->host[(size_t)l * NK + k] = b.host_off;
+        }
+      }
+      return OPTSTAGE_OK;
+    }
+    default:
+      return fail(OPTSTAGE_E_ARG, "unknown op %u", ev.op);
+  }
+}
+
+optstage_status check_complete(const Logical& lg) {
+  for (int j = 0; j < lg.m; ++j)
+    if (!lg.mbs[j].f || !lg.mbs[j].b || !lg.mbs[j].w) return fail(OPTSTAGE_E_ORDER, "micro-batch %d is missing F, B or W", j);
+  return OPTSTAGE_OK;
+}
+
+hipError_t gemm(const Shape& s, int layout, int epi, const void* A, const void* B, void* C, const void* R, int M, int N,
+                int K, int lda, int ldb, int ldc, hipStream_t st) {
+  return s.dtype == OPTSTAGE_BF16 ? launch_gemm_bf16(layout, epi, A, B, C, R, M, N, K, lda, ldb, ldc, st)
+                                  : launch_gemm_f32(layout, epi, A, B, C, R, M, N, K, lda, ldb, ldc, st);
+}
+
+hipEvent_t timing_event(optstage* st) {
+  if (st->tnext == st->tpool.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    st->tpool.push_back(e);
+  }
+  return st->tpool[st->tnext++];
+}
+
+optstage_status span_begin(optstage* st, int op, hipStream_t s, TimedSpan* sp) {
+  sp->op = op;
+  sp->a = timing_event(st);
+  sp->b = timing_event(st);
+  if (!sp->a || !sp->b) return fail(OPTSTAGE_E_HIP, "hipEventCreate failed");
+  HIP_TRY(hipEventRecord(sp->a, s));
+  return OPTSTAGE_OK;
+}
+optstage_status span_end(optstage* st, hipStream_t s, const TimedSpan& sp) {
+  HIP_TRY(hipEventRecord(sp.b, s));
+  st->spans.push_back(sp);
+  return OPTSTAGE_OK;
+}
+
+const void* W(optstage* st, int l, int which) { return st->w[(size_t)l * OPTSTAGE_N_WEIGHTS + which]; }
+float* GW(optstage* st, int l, int which) { return st->gw[(size_t)l * OPTSTAGE_N_WEIGHTS + which]; }
+const void* WT(optstage* st, int l, int which) { return st->wsp() + st->ws.wt_base + st->ws.wt_layer_stride * l + st->ws.wt[which]; }
+
+optstage_status check_weights(optstage* st, bool need_grads) {
+  const bool gpt = st->sh.family == OPTSTAGE_GPT;
+  for (int l = 0; l < st->sh.L; ++l)
+    for (int k = 0; k < OPTSTAGE_N_WEIGHTS; ++k) {
+      if (!gpt && (k == OPTSTAGE_W_B1 || k == OPTSTAGE_W_B2)) continue;
+      if (!W(st, l, k)) return fail(OPTSTAGE_E_STATE, "layer %d weight %d not set", l, k);
+      if (need_grads && !GW(st, l, k)) return fail(OPTSTAGE_E_STATE, "layer %d weight %d has no gradient accumulator", l, k);
+    }
+  return OPTSTAGE_OK;
+}
+
+optstage_status exec_forward(optstage* st, int j, const OpBufs& ob) {
+  const Shape& s = st->sh;
+  hipStream_t cs = st->cs;
+  const int T = s.tokens;
+  auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
+  HIP_TRY(hipMemcpyAsync(P(0, OPTSTAGE_K_X_IN), st->x_in[j], st->raw[OPTSTAGE_K_X_IN], hipMemcpyDeviceToDevice, cs));
+  const int nstat = s.family == OPTSTAGE_LLAMA ? 1 : 2;
+  for (int l = 0; l < s.L; ++l) {
+    void* x = P(l, OPTSTAGE_K_X_IN);
+    float* stats = (float*)P(l, OPTSTAGE_K_STATS);
+    HIP_TRY(launch_norm_fwd(s.dtype, s.family, x, W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats, T, s.h, st->desc.norm_eps, cs));
+    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N1), W(st, l, OPTSTAGE_W_QKV), P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w, cs));
+    if (s.family == OPTSTAGE_LLAMA)
+      HIP_TRY(launch_rope(s.dtype, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), (const float*)(st->wsp() + st->ws.rope), T, s.seq, s.nq, s.nkv, s.d, 0, 1, cs));
+    HIP_TRY(launch_attn_fwd(s.dtype, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), (float*)P(l, OPTSTAGE_K_LSE), s.seq, s.mb, s.nq, s.nkv, s.d, cs));
+    HIP_TRY(gemm(s, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_O), W(st, l, OPTSTAGE_W_O), P(l, OPTSTAGE_K_X_MID), x, T, s.h, s.nq * s.d, s.nq * s.d, s.nq * s.d, s.h, cs));
+    HIP_TRY(launch_norm_fwd(s.dtype, s.family, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T, T, s.h, st->desc.norm_eps, cs));
+    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N2), W(st, l, OPTSTAGE_W_GU), P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w, cs));
+    HIP_TRY(launch_act_fwd(s.dtype, s.family, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_A), T, s.f, cs));
+    void* y = l + 1 < s.L ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[j];
+    HIP_TRY(gemm(s, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_A), W(st, l, OPTSTAGE_W_D), y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h, cs));
+  }
+  return OPTSTAGE_OK;
+}
+
+optstage_status exec_backward_input(optstage* st, int j, const OpBufs& ob) {
+  const Shape& s = st->sh;
+  hipStream_t cs = st->cs;
+  const int T = s.tokens;
+  auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
+  char* ws = st->wsp();
+  void *da = ws + st->ws.da, *dn = ws + st->ws.dn, *dout = ws + st->ws.dout, *dqkv = ws + st->ws.dqkv;
+  float* partial = (float*)(ws + st->ws.partial);
+  const int nstat = s.family == OPTSTAGE_LLAMA ? 1 : 2;
+  HIP_TRY(hipMemcpyAsync(P(s.L - 1, OPTSTAGE_K_DY), st->dy_out[j], st->raw[OPTSTAGE_K_DY], hipMemcpyDeviceToDevice, cs));
+  for (int l = s.L - 1; l >= 0; --l) {
+    void* dy = P(l, OPTSTAGE_K_DY);
+    float* stats = (float*)P(l, OPTSTAGE_K_STATS);
+    // da = dy W_d ; dgu = act'(gu) da (over gu) ; dn2 = dgu W_gu
+    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, dy, WT(st, l, OPTSTAGE_W_D), da, nullptr, T, s.f, s.h, s.h, s.h, s.f, cs));
+    HIP_TRY(launch_act_bwd(s.dtype, s.family, da, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_GU), T, s.f, cs));
+    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_GU), WT(st, l, OPTSTAGE_W_GU), dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h, cs));
+    // dx_mid = dy + norm2'(dn2)
+    HIP_TRY(launch_norm_bwd(s.dtype, s.family, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), partial, GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2), T, s.h, cs));
+    // do = dx_mid W_o ; attention backward ; rotary backward into the qkv buffer
+    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_DX_MID), WT(st, l, OPTSTAGE_W_O), dout, nullptr, T, s.nq * s.d, s.h, s.h, s.h, s.nq * s.d, cs));
+    HIP_TRY(launch_attn_bwd(s.dtype, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), dout, (const float*)P(l, OPTSTAGE_K_LSE), dqkv, (float*)(ws + st->ws.attn), s.seq, s.mb, s.nq, s.nkv, s.d, cs));
+    if (s.family == OPTSTAGE_LLAMA)
+      HIP_TRY(launch_rope(s.dtype, dqkv, P(l, OPTSTAGE_K_QKV), (const float*)(ws + st->ws.rope), T, s.seq, s.nq, s.nkv, s.d, 1, 1, cs));
+    else
+      HIP_TRY(hipMemcpyAsync(P(l, OPTSTAGE_K_QKV), dqkv, st->raw[OPTSTAGE_K_QKV], hipMemcpyDeviceToDevice, cs));
+    // dn1 = dqkv W_qkv ; dx_in = dx_mid + norm1'(dn1)
+    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_QKV), WT(st, l, OPTSTAGE_W_QKV), dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h, cs));
+    void* dx = l > 0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[j];
+    HIP_TRY(launch_norm_bwd(s.dtype, s.family, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, partial, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1), T, s.h, cs));
+  }
+  return OPTSTAGE_OK;
+}
+
+optstage_status exec_backward_weight(optstage* st, int j, const OpBufs& ob) {
+  const Shape& s = st->sh;
+  hipStream_t cs = st->cs;
+  const int T = s.tokens;
+  auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
+  for (int l = 0; l < s.L; ++l) {
+    // dW += dY^T X for the four linears (fp32 accumulators)
+    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DY), P(l, OPTSTAGE_K_A), GW(st, l, OPTSTAGE_W_D), nullptr, s.h, s.f, T, s.h, s.f, s.f, cs));
+    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_N2), GW(st, l, OPTSTAGE_W_GU), nullptr, s.up_w, s.h, T, s.up_w, s.h, s.h, cs));
+    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DX_MID), P(l, OPTSTAGE_K_O), GW(st, l, OPTSTAGE_W_O), nullptr, s.h, s.nq * s.d, T, s.h, s.nq * s.d, s.nq * s.d, cs));
+    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_N1), GW(st, l, OPTSTAGE_W_QKV), nullptr, s.qkv_w, s.h, T, s.qkv_w, s.h, s.h, cs));
+  }
+  return OPTSTAGE_OK;
+}
+
+optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs& ob) {
+  const int j = ev.microbatch, L = st->sh.L;
+  TimedSpan sp;
+  optstage_status rc;
+  switch (ev.op) {
+    case OPTSTAGE_F:
+      if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
+      if ((rc = exec_forward(st, j, ob)) != OPTSTAGE_OK) return rc;
+      if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
+      HIP_TRY(hipEventRecord(st->ev_f[j], st->cs));
+      break;
+    case OPTSTAGE_B:
+      // every reload of this micro-batch must have completed (the reload ends before its consumer starts)
+      for (int l = 0; l < L; ++l) HIP_TRY(hipStreamWaitEvent(st->cs, st->ev_r[(size_t)j * L + l], 0));
+      if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
+      if ((rc = exec_backward_input(st, j, ob)) != OPTSTAGE_OK) return rc;
+      if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
+      break;
+    case OPTSTAGE_W:
+      if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
+      if ((rc = exec_backward_weight(st, j, ob)) != OPTSTAGE_OK) return rc;
+      if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
+      break;
+    case OPTSTAGE_O: {
+      // the offload starts after the F that produced the data has ended
+      HIP_TRY(hipStreamWaitEvent(st->xs, st->ev_f[j], 0));
+      if ((rc = span_begin(st, ev.op, st->xs, &sp)) != OPTSTAGE_OK) return rc;
+      for (int k = 0; k < NFK; ++k)
+        if (ev.kind_mask & (1u << k)) {
+          size_t i = (size_t)ev.layer * NK + k;
+          HIP_TRY(hipMemcpyAsync((char*)st->desc.host_pool + ob.host[i], st->arena() + ob.dev[i], st->raw[k], hipMemcpyDeviceToHost, st->xs));
+          st->stats.bytes_offloaded += st->raw[k];
+        }
+      if ((rc = span_end(st, st->xs, sp)) != OPTSTAGE_OK) return rc;
+      HIP_TRY(hipEventRecord(st->ev_o[(size_t)j * L + ev.layer], st->xs));
+      break;
+    }
+    case OPTSTAGE_OWAIT:
+      // compute ops listed from here on may reuse the freed bytes: they start after the offload ended
+      HIP_TRY(hipStreamWaitEvent(st->cs, st->ev_o[(size_t)j * L + ev.layer], 0));
+      break;
+    case OPTSTAGE_R: {
+      // the reload starts after the compute ops listed before it have ended
+      hipEvent_t pos = st->ev_pos[(size_t)j * L + ev.layer];
+      HIP_TRY(hipEventRecord(pos, st->cs));
+      HIP_TRY(hipStreamWaitEvent(st->xs, pos, 0));
+      if ((rc = span_begin(st, ev.op, st->xs, &sp)) != OPTSTAGE_OK) return rc;
+      for (int k = 0; k < NFK; ++k)
+        if (ev.kind_mask & (1u << k)) {
+          size_t i = (size_t)ev.layer * NK + k;
+          HIP_TRY(hipMemcpyAsync(st->arena() + ob.dev[i], (char*)st->desc.host_pool + ob.host[i], st->raw[k], hipMemcpyHostToDevice, st->xs));
+          st->stats.bytes_reloaded += st->raw[k];
+        }
+      if ((rc = span_end(st, st->xs, sp)) != OPTSTAGE_OK) return rc;
+      HIP_TRY(hipEventRecord(st->ev_r[(size_t)j * L + ev.layer], st->xs));
+      break;
+    }
+  }
+  st->stats.n_ops[ev.op]++;
+  return OPTSTAGE_OK;
+}
+
+optstage_status precheck(optstage* st, const optstage_event* events, size_t n) {
+  bool needs_host = false;
+  for (size_t i = 0; i < n; ++i) {
+    const optstage_event& ev = events[i];
+    if (ev.op > OPTSTAGE_R) return fail(OPTSTAGE_E_ARG, "event %zu: unknown op %u", i, ev.op);
+    if (ev.microbatch >= st->desc.n_microbatches) return fail(OPTSTAGE_E_ARG, "event %zu: micro-batch out of range", i);
+    const int j = ev.microbatch;
+    if (ev.op == OPTSTAGE_F && (!st->x_in[j] || !st->y_out[j])) return fail(OPTSTAGE_E_STATE, "event %zu: x_in / y_out of micro-batch %d not bound", i, j);
+    if (ev.op == OPTSTAGE_B && (!st->dy_out[j] || !st->dx_in[j])) return fail(OPTSTAGE_E_STATE, "event %zu: dy_out / dx_in of micro-batch %d not bound", i, j);
+    if (ev.op == OPTSTAGE_O) needs_host = true;
+  }
+  if (needs_host && !st->desc.host_pool) return fail(OPTSTAGE_E_HOSTPOOL, "offload requested but no pinned host pool was given");
+  bool any_bw = false;
+  for (size_t i = 0; i < n; ++i) any_bw |= events[i].op == OPTSTAGE_B || events[i].op == OPTSTAGE_W;
+  return check_weights(st, any_bw);
+}
+
+optstage_status run_list(optstage* st, const optstage_event* events, size_t n) {
+  if (!st || (!events && n)) return fail(OPTSTAGE_E_ARG, "null argument");
+  optstage_status rc = precheck(st, events, n);
+  if (rc != OPTSTAGE_OK) return rc;
+  {
+    Logical trial = st->lg;   // validate on a copy: a failing list changes nothing
+    for (size_t i = 0; i < n; ++i)
+      if ((rc = apply_event(trial, events[i], nullptr)) != OPTSTAGE_OK) {
+        char tmp[400];
+        snprintf(tmp, sizeof tmp, "%s", g_err);
+        return fail(rc, "event %zu: %s", i, tmp);
+      }
+  }
+  OpBufs ob;
+  for (size_t i = 0; i < n; ++i) {
+    if ((rc = apply_event(st->lg, events[i], &ob)) != OPTSTAGE_OK) return rc;   // cannot fail: same steps as the trial
+    if ((rc = exec_event(st, events[i], ob)) != OPTSTAGE_OK) return rc;
+  }
+  return OPTSTAGE_OK;
+}
+
+void reset_logical(optstage* st) {
+  Logical& lg = st->lg;
+  lg.L = st->sh.L;
+  lg.m = st->desc.n_microbatches;
+  lg.budget = st->desc.hbm_budget_bytes;
+  lg.live = lg.peak = 0;
+  lg.next_f = lg.next_b = lg.next_w = 0;
+  lg.mbs.assign(lg.m, MbState());
+  lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());
+  lg.arena.reset(st->desc.arena_bytes / ALIGN * ALIGN);
+  lg.host.reset(st->desc.host_pool ? st->desc.host_pool_bytes / ALIGN * ALIGN : 0);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* optstage_last_error(void) { return g_err; }
+
+optstage_status optstage_query_sizes(const optstage_desc* desc, uint64_t* min_workspace, uint64_t* act_bytes_per_mb,
+                                     uint64_t* bytes_per_kind) {
+  Shape s;
+  optstage_status rc = shape_from_desc(desc, &s);
+  if (rc != OPTSTAGE_OK) return rc;
+  uint64_t raw[NK];
+  kind_raw_bytes(s, raw);
+  uint64_t per_layer = 0;
+  for (int k = 0; k < NK; ++k) {
+    if (bytes_per_kind) bytes_per_kind[k] = round_up(raw[k]);
+    if (k < NFK) per_layer += round_up(raw[k]);
+  }
+  if (act_bytes_per_mb) *act_bytes_per_mb = per_layer * s.L;
+  if (min_workspace) *min_workspace = workspace_layout(s).total;
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
+  if (!out) return fail(OPTSTAGE_E_ARG, "out is null");
+  *out = nullptr;
+  Shape s;
+  optstage_status rc = shape_from_desc(desc, &s);
+  if (rc != OPTSTAGE_OK) return rc;
+  if (!desc->arena || !desc->workspace) return fail(OPTSTAGE_E_ARG, "arena and workspace must be given");
+  if (((uintptr_t)desc->arena | (uintptr_t)desc->workspace | (uintptr_t)desc->host_pool) & (ALIGN - 1))
+    return fail(OPTSTAGE_E_ARG, "arena, workspace and host_pool must be 256-byte aligned");
+  WorkspaceLayout ws = workspace_layout(s);
+  if (desc->workspace_bytes < ws.total)
+    return fail(OPTSTAGE_E_ARG, "workspace_bytes %llu < required %llu", (unsigned long long)desc->workspace_bytes, (unsigned long long)ws.total);
+  optstage* st = new (std::nothrow) optstage();
+  if (!st) return fail(OPTSTAGE_E_ARG, "out of host memory");
+  st->desc = *desc;
+  st->sh = s;
+  st->ws = ws;
+  kind_raw_bytes(s, st->raw);
+  for (int k = 0; k < NK; ++k) {
+    st->lg.bytes[k] = round_up(st->raw[k]);
+    if (st->raw[k] % 8) { delete st; return fail(OPTSTAGE_E_ARG, "activation kind %d is not a multiple of 8 bytes", k); }
+  }
+  st->cs = (hipStream_t)desc->compute_stream;
+  st->xs = (hipStream_t)desc->copy_stream;
+  const size_t m = desc->n_microbatches, L = s.L;
+  st->w.assign(L * OPTSTAGE_N_WEIGHTS, nullptr);
+  st->gw.assign(L * OPTSTAGE_N_WEIGHTS, nullptr);
+  st->x_in.assign(m, nullptr); st->dy_out.assign(m, nullptr); st->y_out.assign(m, nullptr); st->dx_in.assign(m, nullptr);
+  memset(&st->stats, 0, sizeof st->stats);
+  reset_logical(st);
+  auto mk = [&](std::vector<hipEvent_t>& v, size_t n) -> bool {
+    v.assign(n, nullptr);
+    for (size_t i = 0; i < n; ++i)
+      if (hipEventCreateWithFlags(&v[i], hipEventDisableTiming) != hipSuccess) return false;
+    return true;
+  };
+  if (!mk(st->ev_f, m) || !mk(st->ev_o, m * L) || !mk(st->ev_r, m * L) || !mk(st->ev_pos, m * L)) {
+    optstage_destroy(st);
+    return fail(OPTSTAGE_E_HIP, "hipEventCreateWithFlags failed");
+  }
+  // an event that was never recorded counts as complete, so B may wait on every ev_r unconditionally
+  if (s.family == OPTSTAGE_LLAMA) {
+    hipError_t e = launch_rope_table((float*)(st->wsp() + ws.rope), s.seq, s.d, desc->rope_base, st->cs);
+    if (e != hipSuccess) { optstage_destroy(st); return fail(OPTSTAGE_E_HIP, "rope table: %s", hipGetErrorString(e)); }
+  }
+  *out = st;
+  return OPTSTAGE_OK;
+}
+
+void optstage_destroy(optstage_t* st) {
+  if (!st) return;
+  for (auto* v : {&st->ev_f, &st->ev_o, &st->ev_r, &st->ev_pos, &st->tpool})
+    for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
+  delete st;
+}
+
+optstage_status optstage_set_weight(optstage_t* st, uint32_t layer, uint32_t which, const void* weight_dev, float* grad) {
+  if (!st || !weight_dev) return fail(OPTSTAGE_E_ARG, "null argument");
+  if (layer >= (uint32_t)st->sh.L || which >= OPTSTAGE_N_WEIGHTS) return fail(OPTSTAGE_E_ARG, "layer or weight id out of range");
+  if (st->sh.family == OPTSTAGE_LLAMA && (which == OPTSTAGE_W_B1 || which == OPTSTAGE_W_B2)) return fail(OPTSTAGE_E_ARG, "this family has no norm bias");
+  if (((uintptr_t)weight_dev | (uintptr_t)grad) & 15) return fail(OPTSTAGE_E_ARG, "weights and gradients must be 16-byte aligned");
+  st->w[(size_t)layer * OPTSTAGE_N_WEIGHTS + which] = weight_dev;
+  st->gw[(size_t)layer * OPTSTAGE_N_WEIGHTS + which] = grad;
+  const Shape& s = st->sh;
+  int rows = 0, cols = 0;
+  switch (which) {
+    case OPTSTAGE_W_QKV: rows = s.qkv_w; cols = s.h; break;
+    case OPTSTAGE_W_O: rows = s.h; cols = s.nq * s.d; break;
+    case OPTSTAGE_W_GU: rows = s.up_w; cols = s.h; break;
+    case OPTSTAGE_W_D: rows = s.h; cols = s.f; break;
+    default: return OPTSTAGE_OK;
+  }
+  HIP_TRY(launch_transpose(s.dtype, weight_dev, (void*)WT(st, layer, which), rows, cols, st->cs));
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_bind_io(optstage_t* st, uint32_t mb, const void* x_in, const void* dy_out, void* y_out, void* dx_in) {
+  if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
+  if (mb >= st->desc.n_microbatches) return fail(OPTSTAGE_E_ARG, "micro-batch out of range");
+  if (((uintptr_t)x_in | (uintptr_t)dy_out | (uintptr_t)y_out | (uintptr_t)dx_in) & 15) return fail(OPTSTAGE_E_ARG, "io tensors must be 16-byte aligned");
+  st->x_in[mb] = x_in; st->dy_out[mb] = dy_out; st->y_out[mb] = y_out; st->dx_in[mb] = dx_in;
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_validate(const optstage_t* st, const optstage_event* events, size_t n, size_t* first_bad) {
+  if (!st || (!events && n)) return fail(OPTSTAGE_E_ARG, "null argument");
+  Logical lg;
+  lg.L = st->sh.L;
+  lg.m = st->desc.n_microbatches;
+  lg.budget = st->desc.hbm_budget_bytes;
+  memcpy(lg.bytes, st->lg.bytes, sizeof lg.bytes);
+  lg.mbs.assign(lg.m, MbState());
+  lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());
+  lg.arena.reset(st->desc.arena_bytes / ALIGN * ALIGN);
+  lg.host.reset(st->desc.host_pool ? st->desc.host_pool_bytes / ALIGN * ALIGN : 0);
+  for (size_t i = 0; i < n; ++i) {
+    optstage_status rc = apply_event(lg, events[i], nullptr);
+    if (rc != OPTSTAGE_OK) {
+      if (first_bad) *first_bad = i;
+      return rc;
+    }
+  }
+  optstage_status rc = check_complete(lg);
+  if (rc == OPTSTAGE_OK)
+    for (auto& b : lg.bufs)
+      if (b.state == B_OFFLOADING || b.state == B_HOST) { rc = fail(OPTSTAGE_E_ORDER, "an offloaded activation is never reloaded"); break; }
+  if (rc != OPTSTAGE_OK && first_bad) *first_bad = n;
+  return rc;
+}
+
+optstage_status optstage_plan(const optstage_desc* desc, const optstage_event* events, size_t n, size_t* first_bad,
+                              uint64_t* peak_bytes, uint64_t* live_after) {
+  Shape s;
+  optstage_status rc = shape_from_desc(desc, &s);
+  if (rc != OPTSTAGE_OK) return rc;
+  if (!events && n) return fail(OPTSTAGE_E_ARG, "events is null");
+  uint64_t raw[NK];
+  kind_raw_bytes(s, raw);
+  Logical lg;
+  lg.L = s.L;
+  lg.m = desc->n_microbatches;
+  lg.budget = desc->hbm_budget_bytes;
+  for (int k = 0; k < NK; ++k) lg.bytes[k] = round_up(raw[k]);
+  lg.mbs.assign(lg.m, MbState());
+  lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());
+  lg.arena.reset(UINT64_MAX / 2 / ALIGN * ALIGN);   // logical accounting only: unbounded placement space
+  lg.host.reset(UINT64_MAX / 2 / ALIGN * ALIGN);
+  if (peak_bytes) *peak_bytes = 0;
+  for (size_t i = 0; i < n; ++i) {
+    rc = apply_event(lg, events[i], nullptr);
+    if (peak_bytes) *peak_bytes = lg.peak;
+    if (rc != OPTSTAGE_OK) {
+      if (first_bad) *first_bad = i;
+      return rc;
+    }
+    if (live_after) live_after[i] = lg.live;
+  }
+  rc = check_complete(lg);
+  if (rc == OPTSTAGE_OK)
+    for (auto& b : lg.bufs)
+      if (b.state == B_OFFLOADING || b.state == B_HOST) { rc = fail(OPTSTAGE_E_ORDER, "an offloaded activation is never reloaded"); break; }
+  if (rc != OPTSTAGE_OK && first_bad) *first_bad = n;
+  return rc;
+}
+
+optstage_status optstage_run(optstage_t* st, const optstage_event* events, size_t n) { return run_list(st, events, n); }
+
+static optstage_status one(optstage_t* st, uint32_t op, uint32_t mb, uint32_t layer, uint32_t mask) {
+  optstage_event ev = {op, mb, layer, mask};
+  return run_list(st, &ev, 1);
+}
+optstage_status optstage_forward(optstage_t* st, uint32_t mb) { return one(st, OPTSTAGE_F, mb, 0, 0); }
+optstage_status optstage_backward_input(optstage_t* st, uint32_t mb) { return one(st, OPTSTAGE_B, mb, 0, 0); }
+optstage_status optstage_backward_weight(optstage_t* st, uint32_t mb) { return one(st, OPTSTAGE_W, mb, 0, 0); }
+optstage_status optstage_offload(optstage_t* st, uint32_t mb, uint32_t layer, uint32_t mask) { return one(st, OPTSTAGE_O, mb, layer, mask); }
+optstage_status optstage_offload_wait(optstage_t* st, uint32_t mb, uint32_t layer, uint32_t mask) { return one(st, OPTSTAGE_OWAIT, mb, layer, mask); }
+optstage_status optstage_reload(optstage_t* st, uint32_t mb, uint32_t layer, uint32_t mask) { return one(st, OPTSTAGE_R, mb, layer, mask); }
+
+optstage_status optstage_synchronize(optstage_t* st) {
+  if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
+  HIP_TRY(hipStreamSynchronize(st->cs));
+  HIP_TRY(hipStreamSynchronize(st->xs));
+  for (const TimedSpan& sp : st->spans) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+    st->stats.ms_ops[sp.op] += ms;
+  }
+  st->spans.clear();
+  st->tnext = 0;
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_reset(optstage_t* st) {
+  if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
+  if (!st->spans.empty()) return fail(OPTSTAGE_E_STATE, "reset with work in flight: call optstage_synchronize first");
+  reset_logical(st);
+  memset(&st->stats, 0, sizeof st->stats);
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_get_stats(optstage_t* st, optstage_stats* out) {
+  if (!st || !out) return fail(OPTSTAGE_E_ARG, "null argument");
+  *out = st->stats;
+  out->live_bytes = st->lg.live;
+  out->peak_bytes = st->lg.peak;
+  out->arena_high_water = st->lg.arena.high_water();
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_debug_checksum(optstage_t* st, uint32_t mb, uint32_t layer, uint32_t kind, uint32_t where, uint64_t* out) {
+  if (!st || !out) return fail(OPTSTAGE_E_ARG, "null argument");
+  if (mb >= st->desc.n_microbatches || layer >= (uint32_t)st->sh.L || kind >= NK || where > 1) return fail(OPTSTAGE_E_ARG, "index out of range");
+  const BufRec& b = st->lg.buf(mb, layer, kind);
+  HIP_TRY(hipStreamSynchronize(st->cs));
+  HIP_TRY(hipStreamSynchronize(st->xs));
+  if (where == 0) {
+    if (b.state != B_DEV && b.state != B_OFFLOADING && b.state != B_RELOADED) return fail(OPTSTAGE_E_STATE, "buffer has no device copy");
+    uint64_t* dev = (uint64_t*)(st->wsp() + st->ws.csum);
+    HIP_TRY(launch_checksum(st->arena() + b.dev_off, st->raw[kind], dev, st->cs));
+    HIP_TRY(hipMemcpyAsync(out, dev, 16, hipMemcpyDeviceToHost, st->cs));
+    HIP_TRY(hipStreamSynchronize(st->cs));
+  } else {
+    if (b.state != B_OFFLOADING && b.state != B_HOST) return fail(OPTSTAGE_E_STATE, "buffer has no host copy");
+    const uint64_t* p = (const uint64_t*)((char*)st->desc.host_pool + b.host_off);
+    uint64_t s = 0, x = 0;
+    for (uint64_t i = 0; i < st->raw[kind] / 8; ++i) { s += p[i]; x ^= p[i]; }
+    out[0] = s; out[1] = x;
+  }
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_debug_read(optstage_t* st, uint32_t mb, uint32_t layer, uint32_t kind, void* dst, uint64_t dst_bytes) {
+  if (!st || !dst) return fail(OPTSTAGE_E_ARG, "null argument");
+  if (mb >= st->desc.n_microbatches || layer >= (uint32_t)st->sh.L || kind >= NK) return fail(OPTSTAGE_E_ARG, "index out of range");
+  if (dst_bytes < st->raw[kind]) return fail(OPTSTAGE_E_ARG, "dst too small: need %llu bytes", (unsigned long long)st->raw[kind]);
+  const BufRec& b = st->lg.buf(mb, layer, kind);
+  if (b.state != B_DEV && b.state != B_OFFLOADING && b.state != B_RELOADED) return fail(OPTSTAGE_E_STATE, "buffer has no device copy");
+  HIP_TRY(hipStreamSynchronize(st->xs));
+  HIP_TRY(hipMemcpyAsync(dst, st->arena() + b.dev_off, st->raw[kind], hipMemcpyDeviceToHost, st->cs));
+  HIP_TRY(hipStreamSynchronize(st->cs));
+  return OPTSTAGE_OK;
+}
+
+}  // extern "C"

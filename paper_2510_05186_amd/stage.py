@@ -1,0 +1,129 @@
+"""Thin convenience layer over the C-ABI: obtains device / pinned memory and streams from
+PyTorch, hands raw pointers to liboptstage and keeps the tensors alive.  No arithmetic
+happens here."""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_TORCH_DT = {0: torch.float32, 1: torch.bfloat16}
+
+
+def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
+    """float32 numpy (already rounded to the stage dtype) -> device tensor of the stage dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(device="cuda", dtype=_TORCH_DT[dtype]).contiguous()
+
+
+def to_numpy(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(dtype=torch.float32, device="cpu").numpy().astype(np.float64)
+
+
+class Stage:
+    def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("optstage needs a GPU: there is no CPU path")
+        self.cfg = cfg
+        self.lib = B.lib()
+        ws_bytes, act_per_mb, self.kind_bytes = B.query_sizes(cfg)
+        self.act_bytes_per_mb = act_per_mb
+        if arena_bytes is None:
+            arena_bytes = int((budget if budget else act_per_mb * cfg.n_microbatches) * 1.25) + (64 << 20)
+        self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        self.host_pool = torch.empty(host_pool_bytes, dtype=torch.uint8, pin_memory=True) if host_pool_bytes else None
+        self.compute_stream = torch.cuda.Stream()
+        self.copy_stream = torch.cuda.Stream()
+        self.desc = B.make_desc(
+            cfg, budget=budget, arena=self.arena.data_ptr(), arena_bytes=arena_bytes,
+            workspace=self.workspace.data_ptr(), workspace_bytes=ws_bytes,
+            host_pool=self.host_pool.data_ptr() if self.host_pool is not None else 0,
+            host_pool_bytes=host_pool_bytes, compute_stream=self.compute_stream.cuda_stream,
+            copy_stream=self.copy_stream.cuda_stream)
+        h = C.c_void_p()
+        B.check(self.lib.optstage_create(C.byref(self.desc), C.byref(h)))
+        self.h = h
+        self.weights, self.grads = [], []
+        self.x, self.dy, self.y, self.dx = {}, {}, {}, {}
+
+    def close(self):
+        if getattr(self, "h", None):
+            torch.cuda.synchronize()
+            self.lib.optstage_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- setup
+    def set_weights(self, weights: list):
+        """weights: per layer dict name -> float32 numpy (rounded to the stage dtype)."""
+        self.weights, self.grads = [], []
+        for l, w in enumerate(weights):
+            dw, dg = {}, {}
+            for name, arr in w.items():
+                dw[name] = to_device(arr, self.cfg.dtype)
+                dg[name] = torch.zeros(arr.shape, dtype=torch.float32, device="cuda")
+                B.check(self.lib.optstage_set_weight(self.h, l, B.WEIGHT_ID[name], dw[name].data_ptr(), dg[name].data_ptr()))
+            self.weights.append(dw)
+            self.grads.append(dg)
+        torch.cuda.synchronize()
+
+    def zero_grads(self):
+        for g in self.grads:
+            for t in g.values():
+                t.zero_()
+        torch.cuda.synchronize()
+
+    def bind(self, mb: int, x: np.ndarray | torch.Tensor, dy: np.ndarray | torch.Tensor):
+        dt = self.cfg.dtype
+        self.x[mb] = x if isinstance(x, torch.Tensor) else to_device(x, dt)
+        self.dy[mb] = dy if isinstance(dy, torch.Tensor) else to_device(dy, dt)
+        self.y[mb] = torch.empty_like(self.x[mb])
+        self.dx[mb] = torch.empty_like(self.x[mb])
+        B.check(self.lib.optstage_bind_io(self.h, mb, self.x[mb].data_ptr(), self.dy[mb].data_ptr(),
+                                          self.y[mb].data_ptr(), self.dx[mb].data_ptr()))
+
+    # ---- execution
+    def validate(self, events):
+        arr = B.make_events(events)
+        bad = C.c_size_t(0)
+        st = self.lib.optstage_validate(self.h, arr, len(events), C.byref(bad))
+        return st, bad.value
+
+    def run(self, events):
+        arr = events if not isinstance(events, (list, tuple)) else B.make_events(events)
+        n = len(events) if isinstance(events, (list, tuple)) else len(arr)
+        B.check(self.lib.optstage_run(self.h, arr, n))
+
+    def run_raw(self, arr, n):
+        B.check(self.lib.optstage_run(self.h, arr, n))
+
+    def synchronize(self):
+        B.check(self.lib.optstage_synchronize(self.h))
+
+    def reset(self):
+        B.check(self.lib.optstage_reset(self.h))
+
+    def stats(self) -> B.Stats:
+        s = B.Stats()
+        B.check(self.lib.optstage_get_stats(self.h, C.byref(s)))
+        return s
+
+    def checksum(self, mb, layer, kind, where=0):
+        out = (C.c_uint64 * 2)()
+        B.check(self.lib.optstage_debug_checksum(self.h, mb, layer, B.KIND_ID[kind], where, out))
+        return out[0], out[1]
+
+    def read(self, mb, layer, kind) -> np.ndarray:
+        n = self.kind_bytes[kind]
+        buf = np.empty(n, dtype=np.uint8)
+        B.check(self.lib.optstage_debug_read(self.h, mb, layer, B.KIND_ID[kind], buf.ctypes.data, n))
+        return buf

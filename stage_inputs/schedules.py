@@ -88,7 +88,7 @@ def add_offload(compute_list: list, n_layers: int, kinds: tuple, min_gap: int = 
     before = {n: [] for n in range(len(comp) + 1)}      # events to emit before compute op n
     for j in sorted(pos_f):
         gap = pos_b[j] - pos_f[j] - 1
-        if gap < min_gap:
+        if gap < max(1, min_gap):
             continue
         o_at = pos_f[j] + 1
         wait_at = min(pos_f[j] + 2, pos_b[j])
