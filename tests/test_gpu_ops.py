@@ -1,0 +1,211 @@
+"""Kernel-by-kernel parity of the HIP path against the fp64 oracle, through the C-ABI.
+Sizes span several tiles and a ragged tail; the oracle finishes each in well under a second."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stage_fp64 as O
+from paper_2510_05186_amd import binding as B
+from gpu_util import TOL, dev, host, ok, q, rel_err, stream
+
+pytestmark = pytest.mark.gpu
+RNG = np.random.default_rng(42)
+FP32, BF16 = 0, 1
+
+
+def lib():
+    return B.lib()
+
+
+# ------------------------------------------------------------------ GEMM
+@pytest.mark.parametrize("dtype,M,N,K", [
+    (BF16, 520, 776, 328),        # 128x128 tiles, ragged in M, N and K
+    (BF16, 2824, 3080, 264),      # 256x256 tiles (12 x 13), ragged
+    (BF16, 256, 256, 64),
+    (BF16, 8, 8, 8),
+    (FP32, 130, 77, 50),
+    (FP32, 128, 256, 1024),
+])
+def test_gemm_nt_store_and_residual(dtype, M, N, K):
+    a = q(RNG.standard_normal((M, K)), dtype)
+    w = q(0.05 * RNG.standard_normal((N, K)), dtype)
+    r = q(RNG.standard_normal((M, N)), dtype)
+    A, W, R = dev(a, dtype), dev(w, dtype), dev(r, dtype)
+    C = torch.empty_like(R)
+    ok(lib().optstage_op_gemm(dtype, B.GEMM_NT, B.EPI_STORE, A.data_ptr(), W.data_ptr(), C.data_ptr(), 0, M, N, K, K, K, N, stream()))
+    torch.cuda.synchronize()
+    assert rel_err(host(C), O.linear_fwd(a, w)) < TOL[dtype]
+    ok(lib().optstage_op_gemm(dtype, B.GEMM_NT, B.EPI_RESID, A.data_ptr(), W.data_ptr(), C.data_ptr(), R.data_ptr(), M, N, K, K, K, N, stream()))
+    torch.cuda.synchronize()
+    assert rel_err(host(C), r + O.linear_fwd(a, w)) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,M,N,K", [
+    (BF16, 520, 776, 333),        # K (tokens) need not be a multiple of anything
+    (BF16, 2824, 3080, 200),
+    (BF16, 8, 16, 1),
+    (FP32, 130, 76, 50),
+])
+def test_gemm_tn_accumulate(dtype, M, N, K):
+    # dW[M,N] += dY^T X with dY [K,M], X [K,N]
+    dy = q(RNG.standard_normal((K, M)), dtype)
+    x = q(RNG.standard_normal((K, N)), dtype)
+    c0 = RNG.standard_normal((M, N)).astype(np.float32)
+    DY, X = dev(dy, dtype), dev(x, dtype)
+    C = torch.from_numpy(c0.copy()).cuda()
+    for rep in range(2):
+        ok(lib().optstage_op_gemm(dtype, B.GEMM_TN, B.EPI_ACCUM, DY.data_ptr(), X.data_ptr(), C.data_ptr(), 0, M, N, K, M, N, N, stream()))
+    torch.cuda.synchronize()
+    ref = c0.astype(np.float64) + 2 * O.linear_bwd_weight(dy, x)
+    assert rel_err(host(C), ref) < (1e-5 if dtype == FP32 else 1e-4)    # fp32 accumulators: no bf16 rounding of C
+
+
+def test_gemm_rejects_bad_shapes():
+    A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    f = lib().optstage_op_gemm
+    assert f(BF16, 0, 0, A.data_ptr(), A.data_ptr(), A.data_ptr(), 0, 64, 64, 60, 60, 60, 64, stream()) == B.E_ARG   # K % 8
+    assert f(BF16, 0, 0, A.data_ptr(), A.data_ptr(), A.data_ptr(), 0, 64, 62, 64, 64, 64, 62, stream()) == B.E_ARG   # N % 4
+    assert f(BF16, 0, 0, 0, A.data_ptr(), A.data_ptr(), 0, 64, 64, 64, 64, 64, 64, stream()) == B.E_ARG              # null
+    assert f(BF16, 0, 1, A.data_ptr(), A.data_ptr(), A.data_ptr(), 0, 64, 64, 64, 64, 64, 64, stream()) == B.E_ARG   # residual missing
+    assert f(BF16, 0, 0, A.data_ptr(), A.data_ptr(), A.data_ptr(), 0, 64, 64, 64, 32, 64, 64, stream()) == B.E_ARG   # lda < K
+    assert f(BF16, 1, 2, A.data_ptr(), A.data_ptr(), A.data_ptr(), 0, 60, 64, 64, 64, 64, 64, stream()) == B.E_ARG   # TN: M % 8
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ norms
+@pytest.mark.parametrize("dtype,family,rows,h", [
+    (BF16, O.LLAMA, 300, 4096), (BF16, O.LLAMA, 37, 520), (BF16, O.GPT, 64, 1024), (BF16, O.LLAMA, 700, 8192),
+    (FP32, O.GPT, 128, 256), (FP32, O.LLAMA, 130, 1000),
+])
+def test_norm_fwd_bwd(dtype, family, rows, h):
+    eps = 1e-5
+    x = q(2.0 * RNG.standard_normal((rows, h)) + 0.3, dtype)
+    g = q(1 + 0.1 * RNG.standard_normal(h), dtype)
+    b = q(0.1 * RNG.standard_normal(h), dtype)
+    dn = q(RNG.standard_normal((rows, h)), dtype)
+    dres = q(RNG.standard_normal((rows, h)), dtype)
+    X, G, Bt, DN, DR = (dev(a, dtype) for a in (x, g, b, dn, dres))
+    OUT = torch.empty_like(X)
+    nst = 1 if family == O.LLAMA else 2
+    ST = torch.empty(rows * nst, dtype=torch.float32, device="cuda")
+    ok(lib().optstage_op_norm_fwd(dtype, family, X.data_ptr(), G.data_ptr(), Bt.data_ptr(), OUT.data_ptr(), ST.data_ptr(), rows, h, eps, stream()))
+    DX = torch.empty_like(X)
+    part = torch.empty(2 * min(rows, 512) * h, dtype=torch.float32, device="cuda")
+    dg0 = RNG.standard_normal(h).astype(np.float32)
+    DG, DB = torch.from_numpy(dg0.copy()).cuda(), torch.zeros(h, dtype=torch.float32, device="cuda")
+    ok(lib().optstage_op_norm_bwd(dtype, family, DN.data_ptr(), X.data_ptr(), ST.data_ptr(), G.data_ptr(), DR.data_ptr(), DX.data_ptr(), part.data_ptr(), DG.data_ptr(), DB.data_ptr(), rows, h, stream()))
+    torch.cuda.synchronize()
+    if family == O.LLAMA:
+        n, r = O.rmsnorm_fwd(x, g, eps)
+        dx, dgam = O.rmsnorm_bwd(dn, x, r, g)
+        assert rel_err(host(ST), r[:, 0]) < 1e-5
+    else:
+        n, mu, r = O.layernorm_fwd(x, g, b, eps)
+        dx, dgam, dbeta = O.layernorm_bwd(dn, x, mu, r, g)
+        st = host(ST).reshape(rows, 2)
+        assert rel_err(st[:, 0], mu[:, 0]) < 1e-5 and rel_err(st[:, 1], r[:, 0]) < 1e-5
+        assert rel_err(host(DB), dbeta) < 1e-5
+    assert rel_err(host(OUT), n) < TOL[dtype]
+    assert rel_err(host(DX), dres + dx) < TOL[dtype]
+    assert rel_err(host(DG), dg0 + dgam) < 1e-5      # fp32 accumulation of exactly representable inputs
+
+
+# ------------------------------------------------------------------ activations
+@pytest.mark.parametrize("dtype,family,rows,f", [(BF16, O.LLAMA, 333, 1376), (BF16, O.GPT, 50, 1024),
+                                                  (FP32, O.GPT, 128, 1024), (FP32, O.LLAMA, 17, 100)])
+def test_activation_fwd_bwd(dtype, family, rows, f):
+    w = 2 * f if family == O.LLAMA else f
+    gu = q(1.5 * RNG.standard_normal((rows, w)), dtype)
+    da = q(RNG.standard_normal((rows, f)), dtype)
+    GU, DA = dev(gu, dtype), dev(da, dtype)
+    A = torch.empty(rows, f, dtype=GU.dtype, device="cuda")
+    ok(lib().optstage_op_act_fwd(dtype, family, GU.data_ptr(), A.data_ptr(), rows, f, stream()))
+    ok(lib().optstage_op_act_bwd(dtype, family, DA.data_ptr(), GU.data_ptr(), GU.data_ptr(), rows, f, stream()))   # in place
+    torch.cuda.synchronize()
+    if family == O.LLAMA:
+        a, dgu = O.swiglu_fwd(gu), O.swiglu_bwd(da, gu)
+    else:
+        a, dgu = O.gelu_fwd(gu), O.gelu_bwd(da, gu)
+    assert rel_err(host(A), a) < TOL[dtype]
+    assert rel_err(host(GU), dgu) < TOL[dtype]
+
+
+# ------------------------------------------------------------------ rotary
+@pytest.mark.parametrize("dtype,seq,batch,nq,nkv,d", [(BF16, 300, 1, 4, 2, 128), (FP32, 70, 2, 3, 3, 64), (BF16, 4096, 1, 2, 1, 128)])
+def test_rotary(dtype, seq, batch, nq, nkv, d):
+    base = 10000.0
+    rows = seq * batch
+    w = (nq + 2 * nkv) * d
+    qkv = q(RNG.standard_normal((rows, w)), dtype)
+    table = torch.empty(seq * d, dtype=torch.float32, device="cuda")
+    ok(lib().optstage_op_rope_table(table.data_ptr(), seq, d, base, stream()))
+    SRC = dev(qkv, dtype)
+    DST = torch.zeros_like(SRC)
+    ok(lib().optstage_op_rope(dtype, SRC.data_ptr(), DST.data_ptr(), table.data_ptr(), rows, seq, nq, nkv, d, 1, stream()))   # backward, out of place
+    ok(lib().optstage_op_rope(dtype, SRC.data_ptr(), SRC.data_ptr(), table.data_ptr(), rows, seq, nq, nkv, d, 0, stream()))   # forward, in place
+    torch.cuda.synchronize()
+    # table against fp64
+    k = np.arange(d // 2)
+    ang = np.arange(seq)[:, None] * base ** (-2.0 * k / d)[None, :]
+    tb = host(table).reshape(seq, d // 2, 2)
+    assert np.max(np.abs(tb[..., 0] - np.cos(ang))) < 1e-7 and np.max(np.abs(tb[..., 1] - np.sin(ang))) < 1e-7
+
+    def ref(sign):
+        out = qkv.copy().reshape(batch, seq, w)
+        for b in range(batch):
+            qq = out[b, :, : nq * d].reshape(seq, nq, d)
+            kk = out[b, :, nq * d: (nq + nkv) * d].reshape(seq, nkv, d)
+            out[b, :, : nq * d] = O.rope_apply(qq, base, sign).reshape(seq, -1)
+            out[b, :, nq * d: (nq + nkv) * d] = O.rope_apply(kk, base, sign).reshape(seq, -1)
+        return out.reshape(rows, w)
+    assert rel_err(host(SRC), ref(1.0)) < TOL[dtype]
+    assert rel_err(host(DST), ref(-1.0)) < TOL[dtype]
+
+
+# ------------------------------------------------------------------ attention
+@pytest.mark.parametrize("dtype,seq,batch,nq,nkv,d", [
+    (FP32, 128, 1, 4, 4, 64), (FP32, 67, 2, 4, 2, 64), (BF16, 200, 1, 4, 2, 128), (BF16, 130, 1, 2, 2, 64),
+    (BF16, 512, 1, 8, 2, 128), (BF16, 1, 1, 2, 1, 128), (BF16, 384, 2, 2, 2, 128),
+])
+def test_attention_fwd_bwd(dtype, seq, batch, nq, nkv, d):
+    rows = seq * batch
+    w = (nq + 2 * nkv) * d
+    qkv = q(RNG.standard_normal((rows, w)), dtype)
+    do = q(RNG.standard_normal((rows, nq * d)), dtype)
+    QKV, DO = dev(qkv, dtype), dev(do, dtype)
+    Ot = torch.empty(rows, nq * d, dtype=QKV.dtype, device="cuda")
+    LSE = torch.empty(batch * nq * seq, dtype=torch.float32, device="cuda")
+    ok(lib().optstage_op_attn_fwd(dtype, QKV.data_ptr(), Ot.data_ptr(), LSE.data_ptr(), seq, batch, nq, nkv, d, stream()))
+    DQKV = torch.zeros_like(QKV)
+    nws = lib().optstage_op_attn_bwd_ws_floats(seq, batch, nq, nkv, d)
+    WS = torch.empty(max(1, nws), dtype=torch.float32, device="cuda")
+    ok(lib().optstage_op_attn_bwd(dtype, QKV.data_ptr(), Ot.data_ptr(), DO.data_ptr(), LSE.data_ptr(), DQKV.data_ptr(), WS.data_ptr(), seq, batch, nq, nkv, d, stream()))
+    torch.cuda.synchronize()
+    o_g, lse_g, dq_g = host(Ot), host(LSE).reshape(batch, nq, seq), host(DQKV)
+    for b in range(batch):
+        sl = slice(b * seq, (b + 1) * seq)
+        qq = qkv[sl, : nq * d].reshape(seq, nq, d)
+        kk = qkv[sl, nq * d: (nq + nkv) * d].reshape(seq, nkv, d)
+        vv = qkv[sl, (nq + nkv) * d:].reshape(seq, nkv, d)
+        o, lse = O.attention_fwd(qq, kk, vv)
+        assert rel_err(o_g[sl], o.reshape(seq, -1)) < TOL[dtype]
+        assert np.max(np.abs(lse_g[b] - lse)) < (1e-4 if dtype == FP32 else 2e-2)
+        # backward is fed the GPU's own (stored-precision) o, as in the stage
+        dq, dk, dv = O.attention_bwd(qq, kk, vv, o_g[sl].reshape(seq, nq, d), do[sl].reshape(seq, nq, d))
+        ref = np.concatenate([dq.reshape(seq, -1), dk.reshape(seq, -1), dv.reshape(seq, -1)], axis=1)
+        for lo, hi in ((0, nq * d), (nq * d, (nq + nkv) * d), ((nq + nkv) * d, w)):
+            assert rel_err(dq_g[sl, lo:hi], ref[:, lo:hi]) < TOL[dtype], (lo, hi)
+
+
+# ------------------------------------------------------------------ checksum
+def test_checksum_matches_host_arithmetic():
+    for n in (0, 8, 4096, 1 << 20, (1 << 20) + 8):
+        a = RNG.integers(0, 2**63, size=max(1, n // 8), dtype=np.uint64)[: n // 8]
+        t = torch.from_numpy(a.view(np.int64).copy()).cuda() if n else torch.zeros(1, dtype=torch.int64, device="cuda")
+        out = torch.zeros(2, dtype=torch.int64, device="cuda")
+        ok(lib().optstage_op_checksum(t.data_ptr(), n, out.data_ptr(), stream()))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().view(np.uint64)
+        s = int(np.sum(a, dtype=np.uint64)) if n else 0
+        x = int(np.bitwise_xor.reduce(a)) if n else 0
+        assert int(got[0]) == s and int(got[1]) == x
