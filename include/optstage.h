@@ -90,6 +90,12 @@ typedef struct {
   uint32_t kind_mask;   /* O / OWAIT / R only: bit k set = activation kind k (k < OPTSTAGE_N_F_KINDS) */
 } optstage_event;
 
+typedef enum {
+  OPTSTAGE_KC_GEMM_NT_STORE = 0, OPTSTAGE_KC_GEMM_NT_RESID = 1, OPTSTAGE_KC_GEMM_TN_ACCUM = 2,
+  OPTSTAGE_KC_ATTN_FWD = 3, OPTSTAGE_KC_ATTN_BWD = 4, OPTSTAGE_KC_NORM_FWD = 5, OPTSTAGE_KC_NORM_BWD = 6,
+  OPTSTAGE_KC_ACT_FWD = 7, OPTSTAGE_KC_ACT_BWD = 8, OPTSTAGE_KC_ROPE = 9, OPTSTAGE_N_KERNEL_CLASSES = 10
+} optstage_kernel_class;
+
 typedef struct {
   uint64_t live_bytes, peak_bytes;              /* logical (list-order) activation accounting */
   uint64_t bytes_offloaded, bytes_reloaded;
@@ -97,6 +103,14 @@ typedef struct {
   double ms_ops[6];                             /* summed device time per optstage_op (F, B, W on the compute
                                                    stream; O, R on the copy stream); valid after synchronize */
   uint64_t arena_high_water;                    /* highest physical arena offset ever used */
+  /* per kernel class, filled only while kernel timing is on (optstage_set_kernel_timing): launches,
+   * summed device time, and summed algorithmic work (flops for GEMM / attention classes: 2*M*N*K, causal
+   * attention 2*s^2*n_q*d forward and 5*s^2*n_q*d backward; bytes for the elementwise classes: norm
+   * forward 2e per element, norm backward 4e, activation forward 3e per output element, backward 5e,
+   * rotary 2e over the q and k heads; e = element size) */
+  uint64_t kernel_launches[OPTSTAGE_N_KERNEL_CLASSES];
+  double kernel_ms[OPTSTAGE_N_KERNEL_CLASSES];
+  double kernel_work[OPTSTAGE_N_KERNEL_CLASSES];
 } optstage_stats;
 
 /* The memory table (the parameters Delta and Gamma of Eq. 7): bytes of each activation kind for one
@@ -145,6 +159,9 @@ optstage_status optstage_synchronize(optstage_t* st);
  * cleared).  Requires that nothing is in flight (call after optstage_synchronize). */
 optstage_status optstage_reset(optstage_t* st);
 optstage_status optstage_get_stats(optstage_t* st, optstage_stats* out /* HOST */);
+/* on != 0: bracket every kernel launch of the op graphs with timing events on the compute stream (the
+ * measurement mode the benchmark uses for per-kernel roofline figures); off by default. */
+optstage_status optstage_set_kernel_timing(optstage_t* st, uint32_t on);
 
 /* Test support: 64-bit checksum (sum of 64-bit words and xor of 64-bit words, combined) of a live or
  * offloaded activation buffer.  where: 0 = the device copy, 1 = the pinned host copy.  Blocks. */

@@ -18,6 +18,8 @@ KIND_ID = {k: i for i, k in enumerate(KINDS)}
 N_KINDS, N_F_KINDS = 12, 10
 WEIGHTS = ("g1", "b1", "wqkv", "wo", "g2", "b2", "wgu", "wd")
 WEIGHT_ID = {k: i for i, k in enumerate(WEIGHTS)}
+KERNEL_CLASSES = ("gemm_nt_store", "gemm_nt_resid", "gemm_tn_accum", "attn_fwd", "attn_bwd", "norm_fwd", "norm_bwd",
+                  "act_fwd", "act_bwd", "rope")
 GEMM_NT, GEMM_TN = 0, 1
 EPI_STORE, EPI_RESID, EPI_ACCUM = 0, 1, 2
 
@@ -40,7 +42,8 @@ class Event(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("live_bytes", C.c_uint64), ("peak_bytes", C.c_uint64), ("bytes_offloaded", C.c_uint64),
                 ("bytes_reloaded", C.c_uint64), ("n_ops", C.c_uint64 * 6), ("ms_ops", C.c_double * 6),
-                ("arena_high_water", C.c_uint64)]
+                ("arena_high_water", C.c_uint64), ("kernel_launches", C.c_uint64 * 10),
+                ("kernel_ms", C.c_double * 10), ("kernel_work", C.c_double * 10)]
 
 
 class OptstageError(RuntimeError):
@@ -68,6 +71,7 @@ _SIGS = {
     "optstage_synchronize": [_vp],
     "optstage_reset": [_vp],
     "optstage_get_stats": [_vp, C.POINTER(Stats)],
+    "optstage_set_kernel_timing": [_vp, _u32],
     "optstage_debug_checksum": [_vp, _u32, _u32, _u32, _u32, C.POINTER(_u64)],
     "optstage_debug_read": [_vp, _u32, _u32, _u32, _vp, _u64],
     "optstage_plan": [C.POINTER(Desc), C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(_u64), C.POINTER(_u64)],

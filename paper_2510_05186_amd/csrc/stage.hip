@@ -149,7 +149,7 @@ struct OpBufs {   // device offsets an op touches, captured before its releases;
   std::vector<uint64_t> dev, host;   // [layer][kind]
 };
 
-struct TimedSpan { int op; hipEvent_t a, b; };
+struct TimedSpan { int op; hipEvent_t a, b; };   // op >= 0: schedule op; op < 0: kernel class -(op + 1)
 
 }  // namespace
 
@@ -169,6 +169,7 @@ struct optstage {
   size_t tnext = 0;
   std::vector<TimedSpan> spans;
   optstage_stats stats;
+  bool ktiming = false;
   char* arena() const { return (char*)desc.arena; }
   char* wsp() const { return (char*)desc.workspace; }
 };
@@ -341,9 +342,75 @@ optstage_status span_end(optstage* st, hipStream_t s, const TimedSpan& sp) {
   return OPTSTAGE_OK;
 }
 
+// optional per-kernel timing: brackets one launch with events and books its algorithmic work
+#define KT(cls, work, call)                                                   \
+  do {                                                                        \
+    TimedSpan ksp_;                                                           \
+    if (st->ktiming) {                                                        \
+      optstage_status r_ = span_begin(st, -(int)(cls) - 1, st->cs, &ksp_);    \
+      if (r_ != OPTSTAGE_OK) return r_;                                       \
+    }                                                                         \
+    HIP_TRY(call);                                                            \
+    if (st->ktiming) {                                                        \
+      optstage_status r_ = span_end(st, st->cs, ksp_);                        \
+      if (r_ != OPTSTAGE_OK) return r_;                                       \
+      st->stats.kernel_launches[cls]++;                                       \
+      st->stats.kernel_work[cls] += (double)(work);                           \
+    }                                                                         \
+  } while (0)
+
 const void* W(optstage* st, int l, int which) { return st->w[(size_t)l * OPTSTAGE_N_WEIGHTS + which]; }
 float* GW(optstage* st, int l, int which) { return st->gw[(size_t)l * OPTSTAGE_N_WEIGHTS + which]; }
 const void* WT(optstage* st, int l, int which) { return st->wsp() + st->ws.wt_base + st->ws.wt_layer_stride * l + st->ws.wt[which]; }
+
+
+#define TRY(x)                               \
+  do {                                       \
+    optstage_status t_ = (x);                \
+    if (t_ != OPTSTAGE_OK) return t_;        \
+  } while (0)
+
+optstage_status k_gemm(optstage* st, int layout, int epi, const void* A, const void* B, void* C, const void* R, int M,
+                       int N, int K, int lda, int ldb, int ldc) {
+  const int cls = layout == GEMM_TN ? OPTSTAGE_KC_GEMM_TN_ACCUM : (epi == EPI_RESID ? OPTSTAGE_KC_GEMM_NT_RESID : OPTSTAGE_KC_GEMM_NT_STORE);
+  KT(cls, 2.0 * M * N * K, gemm(st->sh, layout, epi, A, B, C, R, M, N, K, lda, ldb, ldc, st->cs));
+  return OPTSTAGE_OK;
+}
+optstage_status k_norm_fwd(optstage* st, const void* x, const void* g, const void* b, void* out, float* stats) {
+  const Shape& s = st->sh;
+  KT(OPTSTAGE_KC_NORM_FWD, 2.0 * s.e * s.tokens * s.h, launch_norm_fwd(s.dtype, s.family, x, g, b, out, stats, s.tokens, s.h, st->desc.norm_eps, st->cs));
+  return OPTSTAGE_OK;
+}
+optstage_status k_norm_bwd(optstage* st, const void* dn, const void* x, const float* stats, const void* g, const void* dres, void* dx, float* dg, float* db) {
+  const Shape& s = st->sh;
+  KT(OPTSTAGE_KC_NORM_BWD, 4.0 * s.e * s.tokens * s.h, launch_norm_bwd(s.dtype, s.family, dn, x, stats, g, dres, dx, (float*)(st->wsp() + st->ws.partial), dg, db, s.tokens, s.h, st->cs));
+  return OPTSTAGE_OK;
+}
+optstage_status k_act_fwd(optstage* st, const void* gu, void* a) {
+  const Shape& s = st->sh;
+  KT(OPTSTAGE_KC_ACT_FWD, (s.family == OPTSTAGE_LLAMA ? 3.0 : 2.0) * s.e * s.tokens * s.f, launch_act_fwd(s.dtype, s.family, gu, a, s.tokens, s.f, st->cs));
+  return OPTSTAGE_OK;
+}
+optstage_status k_act_bwd(optstage* st, const void* da, const void* gu, void* dgu) {
+  const Shape& s = st->sh;
+  KT(OPTSTAGE_KC_ACT_BWD, (s.family == OPTSTAGE_LLAMA ? 5.0 : 3.0) * s.e * s.tokens * s.f, launch_act_bwd(s.dtype, s.family, da, gu, dgu, s.tokens, s.f, st->cs));
+  return OPTSTAGE_OK;
+}
+optstage_status k_rope(optstage* st, const void* src, void* dst, int backward) {
+  const Shape& s = st->sh;
+  KT(OPTSTAGE_KC_ROPE, 2.0 * s.e * s.tokens * (s.nq + s.nkv) * s.d, launch_rope(s.dtype, src, dst, (const float*)(st->wsp() + st->ws.rope), s.tokens, s.seq, s.nq, s.nkv, s.d, backward, 1, st->cs));
+  return OPTSTAGE_OK;
+}
+optstage_status k_attn_fwd(optstage* st, const void* qkv, void* o, float* lse) {
+  const Shape& s = st->sh;
+  KT(OPTSTAGE_KC_ATTN_FWD, 2.0 * s.mb * s.seq * s.seq * s.nq * s.d, launch_attn_fwd(s.dtype, qkv, o, lse, s.seq, s.mb, s.nq, s.nkv, s.d, st->cs));
+  return OPTSTAGE_OK;
+}
+optstage_status k_attn_bwd(optstage* st, const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv) {
+  const Shape& s = st->sh;
+  KT(OPTSTAGE_KC_ATTN_BWD, 5.0 * s.mb * s.seq * s.seq * s.nq * s.d, launch_attn_bwd(s.dtype, qkv, o, dout, lse, dqkv, (float*)(st->wsp() + st->ws.attn), s.seq, s.mb, s.nq, s.nkv, s.d, st->cs));
+  return OPTSTAGE_OK;
+}
 
 optstage_status check_weights(optstage* st, bool need_grads) {
   const bool gpt = st->sh.family == OPTSTAGE_GPT;
@@ -366,17 +433,17 @@ optstage_status exec_forward(optstage* st, int j, const OpBufs& ob) {
   for (int l = 0; l < s.L; ++l) {
     void* x = P(l, OPTSTAGE_K_X_IN);
     float* stats = (float*)P(l, OPTSTAGE_K_STATS);
-    HIP_TRY(launch_norm_fwd(s.dtype, s.family, x, W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats, T, s.h, st->desc.norm_eps, cs));
-    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N1), W(st, l, OPTSTAGE_W_QKV), P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w, cs));
+    TRY(k_norm_fwd(st, x, W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N1), W(st, l, OPTSTAGE_W_QKV), P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
     if (s.family == OPTSTAGE_LLAMA)
-      HIP_TRY(launch_rope(s.dtype, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), (const float*)(st->wsp() + st->ws.rope), T, s.seq, s.nq, s.nkv, s.d, 0, 1, cs));
-    HIP_TRY(launch_attn_fwd(s.dtype, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), (float*)P(l, OPTSTAGE_K_LSE), s.seq, s.mb, s.nq, s.nkv, s.d, cs));
-    HIP_TRY(gemm(s, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_O), W(st, l, OPTSTAGE_W_O), P(l, OPTSTAGE_K_X_MID), x, T, s.h, s.nq * s.d, s.nq * s.d, s.nq * s.d, s.h, cs));
-    HIP_TRY(launch_norm_fwd(s.dtype, s.family, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T, T, s.h, st->desc.norm_eps, cs));
-    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N2), W(st, l, OPTSTAGE_W_GU), P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w, cs));
-    HIP_TRY(launch_act_fwd(s.dtype, s.family, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_A), T, s.f, cs));
+      TRY(k_rope(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), 0));
+    TRY(k_attn_fwd(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), (float*)P(l, OPTSTAGE_K_LSE)));
+    TRY(k_gemm(st, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_O), W(st, l, OPTSTAGE_W_O), P(l, OPTSTAGE_K_X_MID), x, T, s.h, s.nq * s.d, s.nq * s.d, s.nq * s.d, s.h));
+    TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N2), W(st, l, OPTSTAGE_W_GU), P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
+    TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_A)));
     void* y = l + 1 < s.L ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[j];
-    HIP_TRY(gemm(s, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_A), W(st, l, OPTSTAGE_W_D), y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h, cs));
+    TRY(k_gemm(st, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_A), W(st, l, OPTSTAGE_W_D), y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
   }
   return OPTSTAGE_OK;
 }
@@ -388,29 +455,28 @@ optstage_status exec_backward_input(optstage* st, int j, const OpBufs& ob) {
   auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
   char* ws = st->wsp();
   void *da = ws + st->ws.da, *dn = ws + st->ws.dn, *dout = ws + st->ws.dout, *dqkv = ws + st->ws.dqkv;
-  float* partial = (float*)(ws + st->ws.partial);
   const int nstat = s.family == OPTSTAGE_LLAMA ? 1 : 2;
   HIP_TRY(hipMemcpyAsync(P(s.L - 1, OPTSTAGE_K_DY), st->dy_out[j], st->raw[OPTSTAGE_K_DY], hipMemcpyDeviceToDevice, cs));
   for (int l = s.L - 1; l >= 0; --l) {
     void* dy = P(l, OPTSTAGE_K_DY);
     float* stats = (float*)P(l, OPTSTAGE_K_STATS);
     // da = dy W_d ; dgu = act'(gu) da (over gu) ; dn2 = dgu W_gu
-    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, dy, WT(st, l, OPTSTAGE_W_D), da, nullptr, T, s.f, s.h, s.h, s.h, s.f, cs));
-    HIP_TRY(launch_act_bwd(s.dtype, s.family, da, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_GU), T, s.f, cs));
-    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_GU), WT(st, l, OPTSTAGE_W_GU), dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h, cs));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, dy, WT(st, l, OPTSTAGE_W_D), da, nullptr, T, s.f, s.h, s.h, s.h, s.f));
+    TRY(k_act_bwd(st, da, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_GU)));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_GU), WT(st, l, OPTSTAGE_W_GU), dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h));
     // dx_mid = dy + norm2'(dn2)
-    HIP_TRY(launch_norm_bwd(s.dtype, s.family, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), partial, GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2), T, s.h, cs));
+    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2)));
     // do = dx_mid W_o ; attention backward ; rotary backward into the qkv buffer
-    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_DX_MID), WT(st, l, OPTSTAGE_W_O), dout, nullptr, T, s.nq * s.d, s.h, s.h, s.h, s.nq * s.d, cs));
-    HIP_TRY(launch_attn_bwd(s.dtype, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), dout, (const float*)P(l, OPTSTAGE_K_LSE), dqkv, (float*)(ws + st->ws.attn), s.seq, s.mb, s.nq, s.nkv, s.d, cs));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_DX_MID), WT(st, l, OPTSTAGE_W_O), dout, nullptr, T, s.nq * s.d, s.h, s.h, s.h, s.nq * s.d));
+    TRY(k_attn_bwd(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), dout, (const float*)P(l, OPTSTAGE_K_LSE), dqkv));
     if (s.family == OPTSTAGE_LLAMA)
-      HIP_TRY(launch_rope(s.dtype, dqkv, P(l, OPTSTAGE_K_QKV), (const float*)(ws + st->ws.rope), T, s.seq, s.nq, s.nkv, s.d, 1, 1, cs));
+      TRY(k_rope(st, dqkv, P(l, OPTSTAGE_K_QKV), 1));
     else
       HIP_TRY(hipMemcpyAsync(P(l, OPTSTAGE_K_QKV), dqkv, st->raw[OPTSTAGE_K_QKV], hipMemcpyDeviceToDevice, cs));
     // dn1 = dqkv W_qkv ; dx_in = dx_mid + norm1'(dn1)
-    HIP_TRY(gemm(s, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_QKV), WT(st, l, OPTSTAGE_W_QKV), dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h, cs));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_QKV), WT(st, l, OPTSTAGE_W_QKV), dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h));
     void* dx = l > 0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[j];
-    HIP_TRY(launch_norm_bwd(s.dtype, s.family, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, partial, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1), T, s.h, cs));
+    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1)));
   }
   return OPTSTAGE_OK;
 }
@@ -422,10 +488,10 @@ optstage_status exec_backward_weight(optstage* st, int j, const OpBufs& ob) {
   auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
   for (int l = 0; l < s.L; ++l) {
     // dW += dY^T X for the four linears (fp32 accumulators)
-    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DY), P(l, OPTSTAGE_K_A), GW(st, l, OPTSTAGE_W_D), nullptr, s.h, s.f, T, s.h, s.f, s.f, cs));
-    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_N2), GW(st, l, OPTSTAGE_W_GU), nullptr, s.up_w, s.h, T, s.up_w, s.h, s.h, cs));
-    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DX_MID), P(l, OPTSTAGE_K_O), GW(st, l, OPTSTAGE_W_O), nullptr, s.h, s.nq * s.d, T, s.h, s.nq * s.d, s.nq * s.d, cs));
-    HIP_TRY(gemm(s, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_N1), GW(st, l, OPTSTAGE_W_QKV), nullptr, s.qkv_w, s.h, T, s.qkv_w, s.h, s.h, cs));
+    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DY), P(l, OPTSTAGE_K_A), GW(st, l, OPTSTAGE_W_D), nullptr, s.h, s.f, T, s.h, s.f, s.f));
+    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_N2), GW(st, l, OPTSTAGE_W_GU), nullptr, s.up_w, s.h, T, s.up_w, s.h, s.h));
+    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DX_MID), P(l, OPTSTAGE_K_O), GW(st, l, OPTSTAGE_W_O), nullptr, s.h, s.nq * s.d, T, s.h, s.nq * s.d, s.nq * s.d));
+    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_N1), GW(st, l, OPTSTAGE_W_QKV), nullptr, s.qkv_w, s.h, T, s.qkv_w, s.h, s.h));
   }
   return OPTSTAGE_OK;
 }
@@ -731,7 +797,7 @@ optstage_status optstage_synchronize(optstage_t* st) {
   for (const TimedSpan& sp : st->spans) {
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
-    st->stats.ms_ops[sp.op] += ms;
+    if (sp.op >= 0) st->stats.ms_ops[sp.op] += ms; else st->stats.kernel_ms[-sp.op - 1] += ms;
   }
   st->spans.clear();
   st->tnext = 0;
@@ -743,6 +809,12 @@ optstage_status optstage_reset(optstage_t* st) {
   if (!st->spans.empty()) return fail(OPTSTAGE_E_STATE, "reset with work in flight: call optstage_synchronize first");
   reset_logical(st);
   memset(&st->stats, 0, sizeof st->stats);
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_set_kernel_timing(optstage_t* st, uint32_t on) {
+  if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
+  st->ktiming = on != 0;
   return OPTSTAGE_OK;
 }
 

@@ -76,6 +76,24 @@ class Stage:
             self.grads.append(dg)
         torch.cuda.synchronize()
 
+    def set_weights_device(self, weights: list):
+        """weights: per layer dict name -> device tensor already in the stage dtype."""
+        self.weights, self.grads = [], []
+        for l, w in enumerate(weights):
+            dg = {}
+            for name, t in w.items():
+                dg[name] = torch.zeros(t.shape, dtype=torch.float32, device="cuda")
+                B.check(self.lib.optstage_set_weight(self.h, l, B.WEIGHT_ID[name], t.data_ptr(), dg[name].data_ptr()))
+            self.weights.append(w)
+            self.grads.append(dg)
+        torch.cuda.synchronize()
+
+    def zero_grads_async(self):
+        """Clears the fp32 gradient accumulators on torch's current stream (no synchronisation)."""
+        for g in self.grads:
+            for t in g.values():
+                t.zero_()
+
     def zero_grads(self):
         for g in self.grads:
             for t in g.values():
