@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liboptstage.so")
-SOURCES = ["gemm_bf16.hip", "gemm_f32.hip", "elementwise.hip", "attention_simple.hip", "ops.hip", "stage.hip"]
+SOURCES = ["gemm_bf16.hip", "gemm_f32.hip", "elementwise.hip", "attention_simple.hip", "attention_mfma.hip", "ops.hip", "stage.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -23,6 +23,8 @@ def build(verbose: bool = True) -> str:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
         cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if os.environ.get("OPTSTAGE_SAVE_TEMPS"):
+            cmd.append("-save-temps=obj")
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
     for src, p in procs:

@@ -158,16 +158,26 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, 
   }
 }
 
-// sums the per-workgroup partials column-wise and adds them into the caller's fp32 accumulators
-__global__ void norm_bwd_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dgamma,
-                                       float* __restrict__ dbeta, int nb, int h) {
-  int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= h) return;
+// sums the per-workgroup partials column-wise and adds them into the caller's fp32 accumulators:
+// workgroup = 32 columns x 8 row groups, fixed summation order (deterministic)
+__global__ __launch_bounds__(256) void norm_bwd_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dgamma,
+                                                              float* __restrict__ dbeta, int nb, int h) {
+  __shared__ float red[8][33];
+  const int cx = threadIdx.x & 31, rg = threadIdx.x >> 5;
+  const int col = blockIdx.x * 32 + cx;
   const float* p = partial + (size_t)blockIdx.y * nb * h;
   float s = 0.f;
-  for (int b = 0; b < nb; ++b) s += p[(size_t)b * h + col];
-  float* dst = blockIdx.y == 0 ? dgamma : dbeta;
-  dst[col] += s;
+  if (col < h)
+    for (int b = rg; b < nb; b += 8) s += p[(size_t)b * h + col];
+  red[rg][cx] = s;
+  __syncthreads();
+  if (rg == 0 && col < h) {
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) t += red[r][cx];
+    float* dst = blockIdx.y == 0 ? dgamma : dbeta;
+    dst[col] += t;
+  }
 }
 
 // ---- MLP activations --------------------------------------------------------------------------------
@@ -352,7 +362,7 @@ hipError_t launch_norm_bwd(int dtype, int family, const void* dn, const void* x,
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(norm_bwd_reduce_kernel, dim3((h + 255) / 256, ln ? 2 : 1), dim3(256), 0, s, partial, dgamma, dbeta, nb, h);
+  hipLaunchKernelGGL(norm_bwd_reduce_kernel, dim3((h + 31) / 32, ln ? 2 : 1), dim3(256), 0, s, partial, dgamma, dbeta, nb, h);
   return hipGetLastError();
 }
 

@@ -165,7 +165,8 @@ def test_rotary(dtype, seq, batch, nq, nkv, d):
 # ------------------------------------------------------------------ attention
 @pytest.mark.parametrize("dtype,seq,batch,nq,nkv,d", [
     (FP32, 128, 1, 4, 4, 64), (FP32, 67, 2, 4, 2, 64), (BF16, 200, 1, 4, 2, 128), (BF16, 130, 1, 2, 2, 64),
-    (BF16, 512, 1, 8, 2, 128), (BF16, 1, 1, 2, 1, 128), (BF16, 384, 2, 2, 2, 128),
+    (BF16, 512, 1, 8, 2, 128), (BF16, 1, 1, 2, 1, 128), (BF16, 384, 2, 2, 2, 128), (BF16, 1000, 1, 4, 1, 128),
+    (BF16, 65, 1, 1, 1, 128), (BF16, 129, 3, 2, 2, 128),
 ])
 def test_attention_fwd_bwd(dtype, seq, batch, nq, nkv, d):
     rows = seq * batch
