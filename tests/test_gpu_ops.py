@@ -21,6 +21,9 @@ def lib():
 @pytest.mark.parametrize("dtype,M,N,K", [
     (BF16, 520, 776, 328),        # 128x128 tiles, ragged in M, N and K
     (BF16, 2824, 3080, 264),      # 256x256 tiles (12 x 13), ragged
+    (BF16, 2824, 3080, 320),      # same, K a multiple of 64: direct global->LDS tile loads, ragged M and N
+    (BF16, 4096, 2048, 64),       # direct path, a single k-tile
+    (BF16, 3000, 4096, 128),      # direct path, two k-tiles
     (BF16, 256, 256, 64),
     (BF16, 8, 8, 8),
     (FP32, 130, 77, 50),
