@@ -178,6 +178,9 @@ def main():
     ap.add_argument("--config", default="cfg2_llama_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offload-leg", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (a kernel of known traffic "
+                         "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
@@ -200,6 +203,12 @@ def main():
         base_ev, _ = build_schedule(CFG.CFG2)
         budget = int(cfg.budget_frac_of_peak * B.plan(CFG.CFG2, base_ev)[2])
     events, knobs = build_schedule(cfg, budget)
+    if args.calibration_copy_mib:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     st, peak_plan = make_stage(cfg, events, budget, torch)
     wall, agg = time_steps(st, events, args.steps, args.warmup, torch)
     flops = schedule_flops(cfg) * cfg.n_microbatches

@@ -120,11 +120,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const bf16_t* _
   const int wm = wave / WN, wn = wave % WN;
 
   // XCD-aware tile order: consecutive hardware ids go to different XCDs, so give every XCD one
-  // contiguous range of the tile sequence, and walk that sequence in groups of 4 tile rows.
+  // contiguous range of the tile sequence, and walk that sequence in groups of 8 tile rows.
   int pid = blockIdx.x;
   const int nblk = tiles_m * tiles_n;
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  constexpr int GM = 4;
+  constexpr int GM = 8;
   const int grp = pid / (GM * tiles_n);
   const int first_m = grp * GM;
   const int gsz = min(tiles_m - first_m, GM);
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
   int pid = blockIdx.x;
   const int nblk = tiles_m * tiles_n;
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  constexpr int GM = 4;
+  constexpr int GM = 8;
   const int grp = pid / (GM * tiles_n);
   const int first_m = grp * GM;
   const int gsz = min(tiles_m - first_m, GM);
