@@ -9,7 +9,7 @@ hipError_t launch_attn_fwd_simple(int dtype, const void* qkv, void* o, float* ls
 hipError_t launch_attn_bwd_simple(int dtype, const void* qkv, const void* o, const void* dout, const float* lse,
                                   void* dqkv, float* ws, int seq, int batch, int n_q, int n_kv, int d, hipStream_t s);
 
-bool attn_mfma_applies(int dtype, int d);
+bool attn_mfma_applies(int dtype, int d, int seq, int n_q, int n_kv);
 hipError_t launch_attn_fwd_mfma(const void* qkv, void* o, float* lse, int seq, int batch, int n_q, int n_kv, hipStream_t s);
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv, float* ws,
                                 int seq, int batch, int n_q, int n_kv, hipStream_t s);
@@ -17,14 +17,14 @@ hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout
 hipError_t launch_attn_fwd(int dtype, const void* qkv, void* o, float* lse, int seq, int batch, int n_q, int n_kv,
                            int d, hipStream_t s) {
   if (seq <= 0 || batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv) return hipErrorInvalidValue;
-  if (attn_mfma_applies(dtype, d)) return launch_attn_fwd_mfma(qkv, o, lse, seq, batch, n_q, n_kv, s);
+  if (attn_mfma_applies(dtype, d, seq, n_q, n_kv)) return launch_attn_fwd_mfma(qkv, o, lse, seq, batch, n_q, n_kv, s);
   return launch_attn_fwd_simple(dtype, qkv, o, lse, seq, batch, n_q, n_kv, d, s);
 }
 
 hipError_t launch_attn_bwd(int dtype, const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv,
                            float* ws, int seq, int batch, int n_q, int n_kv, int d, hipStream_t s) {
   if (seq <= 0 || batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv) return hipErrorInvalidValue;
-  if (attn_mfma_applies(dtype, d)) return launch_attn_bwd_mfma(qkv, o, dout, lse, dqkv, ws, seq, batch, n_q, n_kv, s);
+  if (attn_mfma_applies(dtype, d, seq, n_q, n_kv)) return launch_attn_bwd_mfma(qkv, o, dout, lse, dqkv, ws, seq, batch, n_q, n_kv, s);
   return launch_attn_bwd_simple(dtype, qkv, o, dout, lse, dqkv, ws, seq, batch, n_q, n_kv, d, s);
 }
 
