@@ -74,11 +74,17 @@ def build_schedule(cfg, budget=0):
         comp = G.split_bw_greedy(p, m, cap_of_stage=lambda s, c=cap: c)[i]
         if B.plan(cfg, comp, budget=budget)[0] == B.OK:
             return comp, {"in_flight_cap": cap, "offload": False}
-        for gap in (1, 2, 3):
-            for lead in (3, 2, 1):
-                ev = G.add_offload(comp, cfg.n_layers, cfg.offload_kinds, min_gap=gap, lead=lead)
-                if B.plan(cfg, ev, budget=budget)[0] == B.OK:
-                    return ev, {"in_flight_cap": cap, "offload": True, "min_gap": gap, "lead": lead}
+        def fits(ev):
+            st, bad, _, _ = B.plan(cfg, ev, budget=budget)
+            return st == B.OK, bad
+        for lead in (2, 1):
+            # optimistic placement (copies overlap neighbouring ops), then repaired against the planner
+            ev = G.add_offload(comp, cfg.n_layers, cfg.offload_kinds, min_gap=1, lead=lead, wait_delay=2)
+            if not any(e[0] == "O" for e in ev):
+                continue
+            ev = G.repair_to_fit(ev, fits)
+            if ev is not None:
+                return ev, {"in_flight_cap": cap, "offload": True, "lead": lead, "placement": "repaired"}
     raise RuntimeError("no schedule fits the budget")
 
 

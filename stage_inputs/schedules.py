@@ -74,14 +74,15 @@ def split_bw_greedy(p: int, m: int, cap_of_stage=None) -> list:
     return lists
 
 
-def add_offload(compute_list: list, n_layers: int, kinds: tuple, min_gap: int = 2, lead: int = 1) -> list:
+def add_offload(compute_list: list, n_layers: int, kinds: tuple, min_gap: int = 2, lead: int = 1,
+                wait_delay: int = 1) -> list:
     """Insert O / OWAIT / R events into a compute order.
 
     A micro-batch j is offloaded when at least `min_gap` compute ops lie between F j and
     B j.  Its O events (one per layer, all `kinds`) follow F j directly; the matching
-    OWAITs sit just before the next compute op that follows F j's successor (so the
-    copy overlaps one compute op); the R events sit `lead` compute ops ahead of B j so
-    the reload overlaps them."""
+    OWAITs sit `wait_delay` compute ops later (the copy overlaps that many ops; 0 = the
+    next op waits for the copy); the R events sit `lead` compute ops ahead of B j so the
+    reload overlaps them (0 = B j waits for the whole reload)."""
     comp = [e for e in compute_list]
     pos_f = {e[1]: n for n, e in enumerate(comp) if e[0] == "F"}
     pos_b = {e[1]: n for n, e in enumerate(comp) if e[0] == "B"}
@@ -91,19 +92,65 @@ def add_offload(compute_list: list, n_layers: int, kinds: tuple, min_gap: int = 
         if gap < max(1, min_gap):
             continue
         o_at = pos_f[j] + 1
-        wait_at = min(pos_f[j] + 2, pos_b[j])
+        wait_at = min(pos_f[j] + 1 + wait_delay, pos_b[j])
         r_at = max(wait_at, pos_b[j] - lead)
         for l in range(n_layers):
-            before[o_at].append((0, ("O", j, l, tuple(kinds))))
+            before[o_at].append((1, ("O", j, l, tuple(kinds))))
         for l in range(n_layers):
-            before[wait_at].append((1, ("OWAIT", j, l, tuple(kinds))))
+            before[wait_at].append((2 if wait_at == o_at else 0, ("OWAIT", j, l, tuple(kinds))))
         for l in reversed(range(n_layers)):             # B consumes the last layer first
-            before[r_at].append((2, ("R", j, l, tuple(kinds))))
+            before[r_at].append((3, ("R", j, l, tuple(kinds))))
     out = []
     for n in range(len(comp) + 1):
-        # at one position: waits first (free memory), then reloads, then new offloads
-        for _, ev in sorted(before[n], key=lambda x: {1: 0, 2: 1, 0: 2}[x[0]]):
+        # at one position: completions of earlier offloads first (they free memory), then the offloads that
+        # start here and (zero overlap) their own completions, then reloads
+        for _, ev in sorted(before[n], key=lambda x: x[0]):
             out.append(ev)
         if n < len(comp):
             out.append(comp[n])
     return out
+
+
+def repair_to_fit(events: list, fits, max_rounds: int = 2000) -> list | None:
+    """Feedback-driven repair of an offloading list that overruns its budget.  `fits(events)` is the
+    consumer's planner: it returns (ok, index of the first failing event).  While the list fails at an
+    allocating event, the earliest offload still pending at that point has its OWAIT moved to just
+    before the failing event (its memory is then credited there); if none is pending, the latest
+    reload that was issued early is moved down to just before its consumer B.  Returns None when no
+    move is left.  No accounting happens here: only the planner's verdicts steer the moves."""
+    ev = list(events)
+    for _ in range(max_rounds):
+        ok, bad = fits(ev)
+        if ok:
+            return ev
+        if bad >= len(ev):
+            return None
+        moved = False
+        # (a) an offload issued before `bad` whose OWAIT comes after it
+        seen_o = {}
+        for n in range(bad):
+            e = ev[n]
+            if e[0] == "O":
+                seen_o[e[1:]] = n
+            elif e[0] == "OWAIT":
+                seen_o.pop(e[1:], None)
+        if seen_o:
+            key = min(seen_o, key=lambda k: seen_o[k])
+            w = next(n for n in range(bad, len(ev)) if ev[n][0] == "OWAIT" and ev[n][1:] == key)
+            item = ev.pop(w)
+            ev.insert(bad, item)
+            moved = True
+        else:
+            # (b) the latest reload before `bad` whose B comes after `bad`: push it down to its B
+            for n in range(bad - 1, -1, -1):
+                e = ev[n]
+                if e[0] == "R":
+                    b = next(k for k in range(n, len(ev)) if ev[k][0] == "B" and ev[k][1] == e[1])
+                    if b > bad:
+                        item = ev.pop(n)
+                        ev.insert(b - 1, item)
+                        moved = True
+                        break
+        if not moved:
+            return None
+    return None

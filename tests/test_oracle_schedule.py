@@ -381,3 +381,37 @@ def test_split_bw_generator_is_valid_and_beats_1f1b():
     dF = S.op_delta("F", L, TABLE)
     for i in range(p):
         assert max(u for _, u in S.eq7_usage(lists[i], L, TABLE)) <= (p - i) * dF
+
+
+def test_repair_to_fit_with_the_oracle_as_planner():
+    m, p, i = 8, 6, 1
+    comp = G.split_bw_greedy(p, m, cap_of_stage=lambda s: 3)[i]
+    S.check_order(comp, m, L)
+    pk0, _ = S.account_memory(comp, L, TABLE)
+    kinds = ("X_IN", "QKV", "X_MID", "GU")
+    opt = G.add_offload(comp, L, kinds, min_gap=1, lead=2, wait_delay=2)
+    pk_opt, _ = S.account_memory(opt, L, TABLE)
+
+    def planner(limit):
+        def fits(ev):
+            try:
+                S.check_order(ev, m, L)
+                S.account_memory(ev, L, TABLE, limit=limit)
+                return True, len(ev)
+            except S.ScheduleError as e:
+                return False, e.index
+        return fits
+    # a budget between what the tightest placement needs and what the optimistic one needs
+    tight = G.add_offload(comp, L, kinds, min_gap=1, lead=0, wait_delay=0)
+    pk_tight, _ = S.account_memory(tight, L, TABLE)
+    assert pk_tight < pk_opt <= pk0
+    limit = (pk_tight + pk_opt) // 2
+    fixed = G.repair_to_fit(opt, planner(limit))
+    assert fixed is not None
+    S.check_order(fixed, m, L)
+    pk, tr = S.account_memory(fixed, L, TABLE, limit=limit)
+    assert pk <= limit and tr[-1] == 0
+    assert sorted(map(str, fixed)) == sorted(map(str, opt))          # same events, only moved
+    assert [e for e in fixed if e[0] in "FBW"] == comp                # compute order untouched
+    # an impossible budget is reported, not looped on
+    assert G.repair_to_fit(opt, planner(S.op_delta("F", L, TABLE) - 1)) is None
