@@ -11,6 +11,14 @@ import torch
 from . import binding as B
 
 _TORCH_DT = {0: torch.float32, 1: torch.bfloat16}
+_STREAMS = []   # one (compute, copy) pair per process: every Stage shares it, so the two streams keep the
+                # distinct hardware queues they were given when created and copies overlap compute
+
+
+def _streams():
+    if not _STREAMS:
+        _STREAMS.extend([torch.cuda.Stream(), torch.cuda.Stream()])
+    return _STREAMS
 
 
 def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
@@ -36,8 +44,7 @@ class Stage:
         self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         self.host_pool = torch.empty(host_pool_bytes, dtype=torch.uint8, pin_memory=True) if host_pool_bytes else None
-        self.compute_stream = torch.cuda.Stream()
-        self.copy_stream = torch.cuda.Stream()
+        self.compute_stream, self.copy_stream = _streams()
         self.desc = B.make_desc(
             cfg, budget=budget, arena=self.arena.data_ptr(), arena_bytes=arena_bytes,
             workspace=self.workspace.data_ptr(), workspace_bytes=ws_bytes,
