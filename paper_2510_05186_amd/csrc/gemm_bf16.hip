@@ -105,6 +105,63 @@ template <int R_T, int NTH> struct StageRC {
 template <int R_T, int NTH, bool RC> struct StageSel { typedef StageKC<R_T, NTH> type; };
 template <int R_T, int NTH> struct StageSel<R_T, NTH, true> { typedef StageRC<R_T, NTH> type; };
 
+// Epilogue through LDS for 256 x 256 workgroup tiles: each wave transposes its accumulator tile (32 TM rows
+// x 128 columns), 32 * 128 KB / (NWAVES * 16 KB) rows at a time, through a private slice of the 128 KB of
+// LDS (16-byte chunks XOR-swizzled by the row, conflict free both ways), so that global memory sees whole
+// 512-byte row segments instead of 16-byte pieces of 32 different rows.  The caller has made sure that no
+// wave still reads operand tiles.
+template <int EPI, int TM, int TN, int NWAVES>
+__device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* smem, int wave, int lane, void* Cv,
+                                                 const bf16_t* R, int M, int N, int ldc, int mw, int nw) {
+  static_assert(TN == 4, "a wave tile is 128 columns wide");
+  constexpr int SLICE = 131072 / NWAVES, IPP = SLICE / 16384;     // MFMA tile rows (32 matrix rows) per pass
+  static_assert(IPP >= 1 && TM % IPP == 0, "wave tile must split into whole passes");
+  char* const wl = smem + wave * SLICE;
+  const int khalf = lane >> 5;
+#pragma unroll
+  for (int pass = 0; pass < TM / IPP; ++pass) {
+#pragma unroll
+    for (int i2 = 0; i2 < IPP; ++i2) {
+      const int row = i2 * 32 + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int chunk = j * 8 + g * 2 + khalf;
+          f32x4_t v;
+          v[0] = acc[pass * IPP + i2][j][g * 4 + 0]; v[1] = acc[pass * IPP + i2][j][g * 4 + 1];
+          v[2] = acc[pass * IPP + i2][j][g * 4 + 2]; v[3] = acc[pass * IPP + i2][j][g * 4 + 3];
+          *reinterpret_cast<f32x4_t*>(wl + row * 512 + ((chunk ^ (row & 31)) << 4)) = v;
+        }
+    }
+    const int c = lane & 31;
+    const int n = nw + c * 4;
+#pragma unroll 4
+    for (int p2 = 0; p2 < 16 * IPP; ++p2) {
+      const int row = 2 * p2 + khalf;
+      const int m = mw + pass * IPP * 32 + row;
+      f32x4_t v = *reinterpret_cast<const f32x4_t*>(wl + row * 512 + ((c ^ (row & 31)) << 4));
+      if (m < M && n < N) {
+        const size_t off = (size_t)m * ldc + n;
+        if (EPI == EPI_ACCUM) {
+          float* C = reinterpret_cast<float*>(Cv);
+          f32x4_t o = *reinterpret_cast<const f32x4_t*>(C + off);
+          o[0] += v[0]; o[1] += v[1]; o[2] += v[2]; o[3] += v[3];
+          *reinterpret_cast<f32x4_t*>(C + off) = o;
+        } else {
+          if (EPI == EPI_RESID) {
+            bf16x4_t r = *reinterpret_cast<const bf16x4_t*>(R + off);
+            v[0] += (float)r[0]; v[1] += (float)r[1]; v[2] += (float)r[2]; v[3] += (float)r[3];
+          }
+          bf16x4_t o;
+          o[0] = (bf16_t)v[0]; o[1] = (bf16_t)v[1]; o[2] = (bf16_t)v[2]; o[3] = (bf16_t)v[3];
+          *reinterpret_cast<bf16x4_t*>(reinterpret_cast<bf16_t*>(Cv) + off) = o;
+        }
+      }
+    }
+  }
+}
+
 // ---- kernel ---------------------------------------------------------------------------------------
 template <int BM, int BN, int WM, int WN, bool A_RC, bool B_RC, int EPI>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
@@ -224,6 +281,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const bf16_t* _
     sb.store(cur + A_BYTES, tid);
   }
 
+  if constexpr (BM == 256 && BN == 256 && TN == 4) {
+    __syncthreads();                                 // every wave is done with the operand tiles
+    epilogue_via_lds<EPI, TM, TN, WM * WN>(acc, smem, wave, lane, Cv, R, M, N, ldc, m0 + wm * (BM / WM), n0 + wn * (BN / WN));
+    return;
+  }
   // epilogue: lane owns m = .. + (lane & 31) and, per register group g, n = .. + 8 g + 4 (lane >> 5) + 0..3
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -309,7 +371,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
     b_sw[j] = swz(row);
   }
   const int khalf = lane >> 5;
-
   // tile loads: wave w fills LDS rows 64 w .. 64 w + 63 of each operand, 8 rows per instruction
   __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, a_bytes, 0x00020000);
   __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, b_bytes, 0x00020000);
@@ -374,35 +435,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
     mma(fa1, fb1);
   }
 
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm * (BM / WM) + i * 32 + (lane & 31);
-    if (m >= M) continue;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn * (BN / WN) + j * 32 + g * 8 + khalf * 4;
-        if (n >= N) continue;
-        const size_t off = (size_t)m * ldc + n;
-        float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1], v2 = acc[i][j][g * 4 + 2], v3 = acc[i][j][g * 4 + 3];
-        if (EPI == EPI_ACCUM) {
-          float* C = reinterpret_cast<float*>(Cv);
-          f32x4_t c = *reinterpret_cast<const f32x4_t*>(C + off);
-          c[0] += v0; c[1] += v1; c[2] += v2; c[3] += v3;
-          *reinterpret_cast<f32x4_t*>(C + off) = c;
-        } else {
-          if (EPI == EPI_RESID) {
-            bf16x4_t r = *reinterpret_cast<const bf16x4_t*>(R + off);
-            v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
-          }
-          bf16x4_t o;
-          o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
-          *reinterpret_cast<bf16x4_t*>(reinterpret_cast<bf16_t*>(Cv) + off) = o;
-        }
-      }
-    }
-  }
+  __syncthreads();                                   // every wave is done with the operand tiles
+  epilogue_via_lds<EPI, TM, TN, 4>(acc, smem, wave, lane, Cv, R, M, N, ldc, m0 + wm * (BM / WM), n0 + wn * (BN / WN));
 }
 
 template <int EPI>
@@ -417,6 +451,7 @@ hipError_t launch_nt_lds(const void* A, const void* B, void* C, const void* R, i
     attr_set = true;
   }
   const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+  // byte extent of each operand: rows past the end fall outside the buffer range and read as zero
   const unsigned a_bytes = (unsigned)(((size_t)(M - 1) * lda + K) * 2), b_bytes = (unsigned)(((size_t)(N - 1) * ldb + K) * 2);
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, (const bf16_t*)A, (const bf16_t*)B, C, (const bf16_t*)R,
                      M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes);
@@ -430,7 +465,6 @@ bool nt_lds_applies(int M, int N, int K, int lda, int ldb) {
   const unsigned long long lim = 0xF0000000ull;
   return ((unsigned long long)(M + 256) * lda * 2 < lim) && ((unsigned long long)(N + 256) * ldb * 2 < lim);
 }
-
 template <int BM, int BN, int WM, int WN, bool A_RC, bool B_RC, int EPI>
 hipError_t launch_cfg(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
                       int ldc, hipStream_t s) {
@@ -453,10 +487,13 @@ hipError_t launch_layout(const void* A, const void* B, void* C, const void* R, i
                          int ldc, hipStream_t s) {
   long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
   if (big_tiles >= 128) {
-    if (!RC && nt_lds_applies(M, N, K, lda, ldb)) return launch_nt_lds<EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
     // register-staged path: 8 waves (4 x 2) for the transposing TN loader, 4 waves (2 x 2) otherwise
-    if (RC) return launch_cfg<256, 256, 4, 2, RC, RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
-    return launch_cfg<256, 256, 2, 2, RC, RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
+    if constexpr (RC) {
+      return launch_cfg<256, 256, 4, 2, RC, RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
+    } else {
+      if (nt_lds_applies(M, N, K, lda, ldb)) return launch_nt_lds<EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
+      return launch_cfg<256, 256, 2, 2, RC, RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
+    }
   }
   return launch_cfg<128, 128, 2, 2, RC, RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
 }

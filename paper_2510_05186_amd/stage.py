@@ -78,6 +78,7 @@ class Stage:
             for name, arr in w.items():
                 dw[name] = to_device(arr, self.cfg.dtype)
                 dg[name] = torch.zeros(arr.shape, dtype=torch.float32, device="cuda")
+                self._order_after_torch()
                 B.check(self.lib.optstage_set_weight(self.h, l, B.WEIGHT_ID[name], dw[name].data_ptr(), dg[name].data_ptr()))
             self.weights.append(dw)
             self.grads.append(dg)
@@ -86,6 +87,7 @@ class Stage:
     def set_weights_device(self, weights: list):
         """weights: per layer dict name -> device tensor already in the stage dtype."""
         self.weights, self.grads = [], []
+        self._order_after_torch()
         for l, w in enumerate(weights):
             dg = {}
             for name, t in w.items():
@@ -116,6 +118,13 @@ class Stage:
         B.check(self.lib.optstage_bind_io(self.h, mb, self.x[mb].data_ptr(), self.dy[mb].data_ptr(),
                                           self.y[mb].data_ptr(), self.dx[mb].data_ptr()))
 
+    def _order_after_torch(self):
+        """The library's streams know nothing of torch's: work torch has queued on its current stream (tensor
+        creation, copies, fills) must finish before the library reads those tensors."""
+        cur = torch.cuda.current_stream()
+        self.compute_stream.wait_stream(cur)
+        self.copy_stream.wait_stream(cur)
+
     # ---- execution
     def validate(self, events):
         arr = B.make_events(events)
@@ -126,9 +135,11 @@ class Stage:
     def run(self, events):
         arr = events if not isinstance(events, (list, tuple)) else B.make_events(events)
         n = len(events) if isinstance(events, (list, tuple)) else len(arr)
+        self._order_after_torch()
         B.check(self.lib.optstage_run(self.h, arr, n))
 
     def run_raw(self, arr, n):
+        self._order_after_torch()
         B.check(self.lib.optstage_run(self.h, arr, n))
 
     def synchronize(self):
