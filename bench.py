@@ -31,6 +31,30 @@ def schedule_flops(cfg):
     return cfg.n_layers * (3 * gemm + 7 * att)
 
 
+def nt_store_algorithmic_bytes(cfg):
+    """Mean algorithmic HBM bytes of one launch of the dominant kernel class (C = A B^T, plain store): each
+    operand read once and the result written once, (M K + N K + M N) * elem_size, averaged over the six such
+    GEMMs a layer runs per micro-batch (QKV and gate/up projections in F; the four dX GEMMs of B)."""
+    t, h, f = cfg.seq * cfg.micro_batch, cfg.hidden, cfg.ffn
+    hq = cfg.n_q_heads * cfg.head_dim
+    shapes = [(t, cfg.qkv_width, h), (t, cfg.up_width, h), (t, f, h), (t, h, cfg.up_width), (t, hq, h), (t, h, cfg.qkv_width)]
+    es = 2 if cfg.dtype == 1 else 4
+    return sum((m * k + n * k + m * n) * es for m, n, k in shapes) / len(shapes)
+
+
+def measured_traffic(cfg):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of this same
+    command (FETCH_SIZE and WRITE_SIZE, scaled by what a plain copy of known size reads); None when no
+    summary exists for this workload."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"bench_{cfg.name.split('_')[0]}_hbm_traffic.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), re.M)
+    except OSError:
+        return None
+    return int(m.group(1)) if m else None
+
+
 def device_weights(cfg, torch):
     """Seeded synthetic parameters generated on the device: linear weights N(0, 0.02), gains 1 + N(0, 0.02)."""
     from stage_inputs import tensors as T
@@ -231,9 +255,10 @@ def main():
             kernels[name] = {"launches_per_step": agg["k_n"][i] // args.steps, "avg_ms": ms / agg["k_n"][i],
                              "achieved": rate, "unit": unit, "share_of_step": ms / args.steps / ms_per_step}
     dom = kernels.get("gemm_nt_store", {"achieved": 0.0})
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,NT,store>" if cfg.dtype == 1 else "gemm_f32_kernel",
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_nt_lds_kernel<store>" if cfg.dtype == 1 else "gemm_f32_kernel",
                 "achieved": dom["achieved"], "peak": peak_tf, "unit": "TFLOP/s", "frac": dom["achieved"] / peak_tf,
-                "traffic": None}
+                "avg_launch_ms": dom.get("avg_ms"), "launches_per_step": dom.get("launches_per_step"),
+                "algorithmic_bytes": nt_store_algorithmic_bytes(cfg), "traffic": measured_traffic(cfg)}
     busy_ms = sum(agg["ms_ops"][:3]) / args.steps
     n_f = cfg.n_microbatches
     t_op_ms = [agg["ms_ops"][k] / args.steps / n_f for k in range(3)]

@@ -19,6 +19,9 @@
  *    optstage_synchronize() returns.
  *  - Compute ops are enqueued on desc.compute_stream, transfers on desc.copy_stream (both hipStream_t
  *    passed as void*).  Calls return after enqueueing; only optstage_synchronize() blocks.
+ *  - The library orders its own two streams against each other and nothing else: work the caller has
+ *    queued on OTHER streams that produces a buffer the library will read (a weight, x[j], dy[j]) must
+ *    have completed, or been made a dependency of both streams, before the call that reads it.
  *  - A failing call changes no accounting state (validate, then commit).
  *  - A handle is not thread-safe; use one host thread per handle.
  */

@@ -319,13 +319,100 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const bf16_t* _
 }
 
 // ---- NT kernel with direct global -> LDS tile loads -------------------------------------------------
-// Same tile shape (256 x 256 x 64, 2 x 2 waves), LDS layout, fragment pipeline and epilogue as above, but
-// the tiles never pass through registers: every wave issues 16 `buffer_load_dwordx4 ... lds` per k-tile,
-// each filling 1 KB of LDS (lane i writes 16 bytes at base + 16 i).  The XOR swizzle is realised by the
-// choice of the global address each lane loads (lane i of the load for tile rows 8 q .. 8 q + 7 fetches
-// row 8 q + i / 8, logical chunk (i % 8) ^ swizzle(row)).  Rows past M or N read as zero through the
-// buffer range check.  Requires K % 64 == 0 and operands below 4 GiB (checked on the host).
+// 256 x 256 x 64 tiles, 2 x 2 waves (one per SIMD; each owns 128 x 128 of the output in 256 accumulator
+// registers).  The tiles never pass through registers: every wave issues 16 `buffer_load_dwordx4 ... lds` per
+// k-tile, each filling 1 KB of LDS (lane i writes 16 bytes at base + 16 i).  The XOR swizzle is realised by the
+// choice of the global address each lane loads (lane i of the load for tile rows 8 q .. 8 q + 7 fetches row
+// 8 q + i / 8, logical chunk (i % 8) ^ swizzle(row)).  Rows past M or N read as zero through the buffer range
+// check.  Requires K % 64 == 0 and operands below 4 GiB (checked on the host).
+//
+// With a single wave per SIMD nothing hides an instruction that waits, so the main loop is laid out by hand
+// (the scheduling barriers pin the order):
+//  * LDS is split [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KB each: the stage is a 16-bit immediate
+//    offset of the fragment reads, whose 32 per-lane addresses (8 fragments x 4 k-steps) are computed once;
+//    two k-tiles per loop trip make the stage a compile-time constant, so the loop has no address arithmetic.
+//  * One fragment read is issued ahead of every pair of MFMAs (k-step s + 1 is fetched under the MFMAs of
+//    k-step s), one tile load ahead of every MFMA of the last k-step; the fragments of the last k-step of a
+//    tile are requested early in the k-step before, so they have landed when the tile barrier is reached.
+//  * The loop is rotated so that the one barrier per tile (next tile landed, this stage free to refill) sits
+//    at the top of the trip.
+//  * Tiles are taken in pairs; a tile index past the end is fetched through a zero-length descriptor, which
+//    zero-fills its stage, so an odd tile count needs no second code path.
 typedef __attribute__((address_space(3))) void lds_void_t;
+
+// Epilogue of the direct kernel for bf16 outputs: the wave converts its 128 x 128 accumulator tile to bf16
+// (after adding the residual, read in accumulator layout, when there is one), transposes it through its own
+// 32 KB of LDS ([128 rows][256 B], 16-byte chunks XOR-swizzled by the row) and writes whole 256-byte row
+// segments, 16 bytes per lane.  Rows 16..31 of every 32 keep the two 8-byte halves of a chunk swapped so that
+// a 32-lane 8-byte write touches all 64 banks once.
+template <int EPI>
+__device__ __forceinline__ void epilogue_bf16_rows(f32x16_t (&acc)[4][4], char* smem, int wave, int lane, bf16_t* C,
+                                                   const bf16_t* R, int M, int N, int ldc, int mw, int nw) {
+  char* const wl = smem + wave * 32768;
+  const int khalf = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = i * 32 + (lane & 31);
+    const int hoff = ((khalf ^ ((row >> 4) & 1)) << 3);
+    bf16x4_t res[16];
+    if (EPI == EPI_RESID) {
+      const int m = mw + row;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = nw + j * 32 + g * 8 + khalf * 4;
+          bf16x4_t r = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+          if (m < M && n < N) r = *reinterpret_cast<const bf16x4_t*>(R + (size_t)m * ldc + n);
+          res[j * 4 + g] = r;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1], v2 = acc[i][j][g * 4 + 2], v3 = acc[i][j][g * 4 + 3];
+        if (EPI == EPI_RESID) {
+          const bf16x4_t r = res[j * 4 + g];
+          v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
+        }
+        bf16x4_t o;
+        o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
+        const int chunk = j * 4 + g;
+        *reinterpret_cast<bf16x4_t*>(wl + row * 256 + ((chunk ^ (row & 15)) << 4) + hoff) = o;
+      }
+  }
+  // every wave reads back only what it wrote itself: no workgroup barrier
+  const int c = lane & 15, rsub = lane >> 4;
+  const int n = nw + c * 8;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  auto fetch = [&](int row) {
+    u32x4 v = *reinterpret_cast<const u32x4*>(wl + row * 256 + ((c ^ (row & 15)) << 4));
+    if (row & 16) { unsigned t0 = v[0], t1 = v[1]; v[0] = v[2]; v[1] = v[3]; v[2] = t0; v[3] = t1; }
+    return v;
+  };
+  if (mw + 128 <= M && nw + 128 <= N && (ldc & 7) == 0) {        // interior wave tile: 16-byte stores, no checks
+    bf16_t* dst = C + (size_t)(mw + rsub) * ldc + n;
+    const size_t step = (size_t)4 * ldc;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+      *reinterpret_cast<u32x4*>(dst) = fetch(it * 4 + rsub);
+      dst += step;
+    }
+  } else {
+    for (int it = 0; it < 32; ++it) {
+      const int row = it * 4 + rsub;
+      const u32x4 v = fetch(row);
+      const int m = mw + row;
+      if (m < M) {
+        bf16_t* dst = C + (size_t)m * ldc + n;
+        if (n + 4 <= N) { u32x2 lo; lo[0] = v[0]; lo[1] = v[1]; *reinterpret_cast<u32x2*>(dst) = lo; }
+        if (n + 8 <= N) { u32x2 hi; hi[0] = v[2]; hi[1] = v[3]; *reinterpret_cast<u32x2*>(dst + 4) = hi; }
+      }
+    }
+  }
+}
 
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
@@ -334,8 +421,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
                                                                unsigned a_bytes, unsigned b_bytes) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int BM = 256, BN = 256, WM = 2, WN = 2, TM = 4, TN = 4;
-  constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, BUF = A_BYTES + B_BYTES;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int OPB = 256 * ROW_BYTES;          // one operand of one stage: 32 KB
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
   int pid = blockIdx.x;
@@ -357,86 +445,127 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  int a_off[TM], a_sw[TM], b_off[TN], b_sw[TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    int row = wm * (BM / WM) + i * 32 + (lane & 31);
-    a_off[i] = row * ROW_BYTES;
-    a_sw[i] = swz(row);
-  }
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    int row = wn * (BN / WN) + j * 32 + (lane & 31);
-    b_off[j] = A_BYTES + row * ROW_BYTES;
-    b_sw[j] = swz(row);
-  }
+  // fragment q: 0..3 = A rows (i = q), 4..7 = B rows (j = q - 4); byte address within stage 0 for each k-step
+  int faddr[8][4];
   const int khalf = lane >> 5;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int row = (q < 4 ? wm * (BM / WM) + q * 32 : wn * (BN / WN) + (q - 4) * 32) + (lane & 31);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      faddr[q][ks] = (q < 4 ? 0 : 2 * OPB) + row * ROW_BYTES + (((ks * 2 + khalf) ^ swz(row)) << 4);
+  }
   // tile loads: wave w fills LDS rows 64 w .. 64 w + 63 of each operand, 8 rows per instruction
-  __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, a_bytes, 0x00020000);
-  __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, b_bytes, 0x00020000);
   const int lrow = lane >> 3, c0 = (lane & 7) ^ lrow;
   const unsigned a_row_off = (unsigned)(m0 + wave * 64 + lrow) * (unsigned)lda * 2u;
   const unsigned b_row_off = (unsigned)(n0 + wave * 64 + lrow) * (unsigned)ldb * 2u;
   const unsigned a_step = 8u * (unsigned)lda * 2u, b_step = 8u * (unsigned)ldb * 2u;
-  auto issue_tile = [&](char* buf, int k0) {
-    const int soff = k0 * 2;
+  unsigned voff[16];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const unsigned coff = (unsigned)((c0 ^ j) << 4);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(buf + (wave * 8 + j) * 1024), 16, a_row_off + j * a_step + coff, soff, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(buf + A_BYTES + (wave * 8 + j) * 1024), 16, b_row_off + j * b_step + coff, soff, 0, 0);
-    }
-  };
-  auto load_frags = [&](bf16x8_t (&af)[TM], bf16x8_t (&bfr)[TN], const char* buf, int ks) {
-    const int chunk = ks * 2 + khalf;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(buf + a_off[i] + ((chunk ^ a_sw[i]) << 4));
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(buf + b_off[j] + ((chunk ^ b_sw[j]) << 4));
-  };
-  auto mma = [&](const bf16x8_t (&af)[TM], const bf16x8_t (&bfr)[TN]) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-  };
-
-  const int nk = K / BK;
-  char* const buf0 = smem;
-  char* const buf1 = smem + BUF;
-  issue_tile(buf0, 0);
-  if (nk > 1) issue_tile(buf1, BK);
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-  bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  load_frags(fa0, fb0, buf0, 0);
-  for (int kt = 0; kt < nk; ++kt) {
-    char* cur = (kt & 1) ? buf1 : buf0;
-    char* nxt = (kt & 1) ? buf0 : buf1;
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(fa1, fb1, cur, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(fa0, fb0, cur, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(fa1, fb1, cur, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    // tile kt+1 (issued one iteration ago) has landed in nxt and every read of cur has been issued
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (kt + 2 < nk) issue_tile(cur, (kt + 2) * BK);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(fa0, fb0, nxt, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(fa1, fb1);
+  for (int j = 0; j < 8; ++j) {
+    const unsigned coff = (unsigned)((c0 ^ j) << 4);
+    voff[2 * j] = a_row_off + j * a_step + coff;
+    voff[2 * j + 1] = b_row_off + j * b_step + coff;
   }
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, a_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, b_bytes, 0x00020000);
+  // load t of a tile: t even -> 8 A rows, t odd -> 8 B rows (1 KB of LDS each); soff = byte offset along k
+  auto issue_one = [&](__amdgpu_buffer_rsrc_t da, __amdgpu_buffer_rsrc_t db, int stage, int soff, int t) {
+    char* dst = smem + ((t & 1) ? 2 * OPB : 0) + stage * OPB + (wave * 8 + (t >> 1)) * 1024;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds((t & 1) ? db : da, (lds_void_t*)dst, 16, voff[t], soff, 0, 0);
+  };
+  bf16x8_t fr[2][8];
+  auto load_one = [&](int set, int stage, int ks, int q) {
+    fr[set][q] = *reinterpret_cast<const bf16x8_t*>(smem + stage * OPB + faddr[q][ks]);
+  };
+  // fragments are read in the order a0 b0 a1 b1 ...; the MFMA order uses the ones read first first
+  constexpr int MI[16] = {0, 1, 0, 1, 2, 2, 0, 1, 2, 3, 3, 3, 0, 1, 2, 3};
+  constexpr int MJ[16] = {0, 0, 1, 1, 0, 1, 2, 2, 2, 0, 1, 2, 3, 3, 3, 3};
+  constexpr int LQ[8] = {0, 4, 1, 5, 2, 6, 3, 7};
+  auto mma_one = [&](int set, int t) {
+    acc[MI[t]][MJ[t]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][4 + MJ[t]], fr[set][MI[t]], acc[MI[t]][MJ[t]], 0, 0, 0);
+  };
+  // k-steps 0..2 of the tile in `stage`: the MFMAs of step ks run over the fragment reads of step ks + 1
+  auto steps_012 = [&](int stage) {
+#pragma unroll
+    for (int ks = 0; ks < 3; ++ks) {
+      const int set = ks & 1;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks < 2) {
+          load_one(set ^ 1, stage, ks + 1, LQ[q]);
+        } else if (q < 4) {                        // last reads of this stage: all requested in the first half
+          load_one(set ^ 1, stage, ks + 1, LQ[2 * q]);
+          load_one(set ^ 1, stage, ks + 1, LQ[2 * q + 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mma_one(set, 2 * q);
+        mma_one(set, 2 * q + 1);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // k-step 3 of the tile in `stage` (fragment set 1); meanwhile that stage is refilled with the tile two ahead
+  // and the first fragments of the next tile are read from the other stage
+  auto step_3 = [&](int stage, __amdgpu_buffer_rsrc_t da, __amdgpu_buffer_rsrc_t db, int soff, bool refill, bool next) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (refill) issue_one(da, db, stage, soff, 2 * q);
+      if (next) load_one(0, stage ^ 1, 0, LQ[q]);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one(1, 2 * q);
+      __builtin_amdgcn_sched_barrier(0);
+      if (refill) issue_one(da, db, stage, soff, 2 * q + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one(1, 2 * q + 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // the next tile has landed (this wave's part; the barrier covers the others) and every read of the
+  // stage about to be refilled has returned
+#define OPTSTAGE_TILE_SYNC() asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
-  __syncthreads();                                   // every wave is done with the operand tiles
-  epilogue_via_lds<EPI, TM, TN, 4>(acc, smem, wave, lane, Cv, R, M, N, ldc, m0 + wm * (BM / WM), n0 + wn * (BN / WN));
+  const int nk = K / BK, npair = (nk + 1) >> 1;
+  {
+    const bool two = nk > 1;
+    const __amdgpu_buffer_rsrc_t ra1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, two ? a_bytes : 0u, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, two ? b_bytes : 0u, 0x00020000);
+#pragma unroll
+    for (int t = 0; t < 16; ++t) issue_one(ra, rb, 0, 0, t);
+#pragma unroll
+    for (int t = 0; t < 16; ++t) issue_one(ra1, rb1, 1, BK * 2, t);
+  }
+  OPTSTAGE_TILE_SYNC();
+#pragma unroll
+  for (int q = 0; q < 8; ++q) load_one(0, 0, 0, LQ[q]);
+  steps_012(0);
+  // at the top of a trip: k-steps 0..2 of tile 2 p (stage 0) are issued, tile 2 p + 1 is in flight to stage 1
+  for (int p = 0; p + 1 < npair; ++p) {
+    const bool odd_ok = 2 * p + 3 < nk;
+    const __amdgpu_buffer_rsrc_t ra1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, odd_ok ? a_bytes : 0u, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, odd_ok ? b_bytes : 0u, 0x00020000);
+    OPTSTAGE_TILE_SYNC();
+    step_3(0, ra, rb, (2 * p + 2) * BK * 2, true, true);
+    steps_012(1);
+    OPTSTAGE_TILE_SYNC();
+    step_3(1, ra1, rb1, (2 * p + 3) * BK * 2, true, true);
+    steps_012(0);
+  }
+  OPTSTAGE_TILE_SYNC();
+  step_3(0, ra, rb, 0, false, true);
+  steps_012(1);
+  OPTSTAGE_TILE_SYNC();
+  step_3(1, ra, rb, 0, false, false);
+
+  OPTSTAGE_TILE_SYNC();                              // every wave is done with the operand tiles
+#undef OPTSTAGE_TILE_SYNC
+  if (EPI == EPI_ACCUM)
+    epilogue_via_lds<EPI, TM, TN, 4>(acc, smem, wave, lane, Cv, R, M, N, ldc, m0 + wm * (BM / WM), n0 + wn * (BN / WN));
+  else
+    epilogue_bf16_rows<EPI>(acc, smem, wave, lane, reinterpret_cast<bf16_t*>(Cv), R, M, N, ldc, m0 + wm * (BM / WM),
+                            n0 + wn * (BN / WN));
 }
 
 template <int EPI>
