@@ -5,8 +5,8 @@
 //
 // Design (CDNA4): one workgroup of 4 or 8 waves owns a BM x BN output tile (256 x 256 for large problems);
 // the K loop advances 64 elements at a time through double-buffered LDS tiles with one barrier per step.
-// NT problems with K % 64 == 0 load their tiles straight from global memory into LDS (no registers, no
-// ds_write); everything else stages tiles global -> registers -> LDS.  LDS tiles are always [row][64 k] with the 16-byte chunk index XOR-swizzled by the row so that
+// Large problems with K % 64 == 0 load their tiles straight from global memory into LDS (no registers, no
+// ds_write; see the direct kernels below); everything else stages tiles global -> registers -> LDS.  LDS tiles are always [row][64 k] with the 16-byte chunk index XOR-swizzled by the row so that
 // both the 16-byte operand reads of v_mfma_f32_32x32x16_bf16 and the tile writes are bank-conflict
 // free.  Operands that are contiguous along their output index (TN) are transposed in registers on the
 // way into LDS (each thread gathers a KV x 8 patch and writes 8 k-contiguous pieces), so the MFMA read
@@ -116,10 +116,34 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* 
   static_assert(TN == 4, "a wave tile is 128 columns wide");
   constexpr int SLICE = 131072 / NWAVES, IPP = SLICE / 16384;     // MFMA tile rows (32 matrix rows) per pass
   static_assert(IPP >= 1 && TM % IPP == 0, "wave tile must split into whole passes");
+  constexpr int NIT = 16 * IPP;                                   // row pairs per pass
   char* const wl = smem + wave * SLICE;
   const int khalf = lane >> 5;
+  const int c = lane & 31;
+  const int n = nw + c * 4;
 #pragma unroll
   for (int pass = 0; pass < TM / IPP; ++pass) {
+    // accumulate / residual: request this pass's rows of the old values first, so that their latency runs
+    // under the LDS transposition
+    // (only where the register budget allows it: 4-wave kernels)
+    constexpr bool PRE = NWAVES == 4;
+    f32x4_t cold[EPI == EPI_ACCUM && PRE ? NIT : 1];
+    bf16x4_t rold[EPI == EPI_RESID && PRE ? NIT : 1];
+    if (EPI != EPI_STORE && PRE) {
+#pragma unroll
+      for (int p2 = 0; p2 < NIT; ++p2) {
+        const int m = mw + pass * IPP * 32 + 2 * p2 + khalf;
+        const bool ok = m < M && n < N;
+        const size_t off = (size_t)m * ldc + n;
+        if (EPI == EPI_ACCUM) {
+          f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+          cold[p2] = ok ? *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off) : z;
+        } else {
+          bf16x4_t z = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+          rold[p2] = ok ? *reinterpret_cast<const bf16x4_t*>(R + off) : z;
+        }
+      }
+    }
 #pragma unroll
     for (int i2 = 0; i2 < IPP; ++i2) {
       const int row = i2 * 32 + (lane & 31);
@@ -134,23 +158,20 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* 
           *reinterpret_cast<f32x4_t*>(wl + row * 512 + ((chunk ^ (row & 31)) << 4)) = v;
         }
     }
-    const int c = lane & 31;
-    const int n = nw + c * 4;
-#pragma unroll 4
-    for (int p2 = 0; p2 < 16 * IPP; ++p2) {
+#pragma unroll
+    for (int p2 = 0; p2 < NIT; ++p2) {
       const int row = 2 * p2 + khalf;
       const int m = mw + pass * IPP * 32 + row;
       f32x4_t v = *reinterpret_cast<const f32x4_t*>(wl + row * 512 + ((c ^ (row & 31)) << 4));
       if (m < M && n < N) {
         const size_t off = (size_t)m * ldc + n;
         if (EPI == EPI_ACCUM) {
-          float* C = reinterpret_cast<float*>(Cv);
-          f32x4_t o = *reinterpret_cast<const f32x4_t*>(C + off);
-          o[0] += v[0]; o[1] += v[1]; o[2] += v[2]; o[3] += v[3];
-          *reinterpret_cast<f32x4_t*>(C + off) = o;
+          const f32x4_t o = PRE ? cold[PRE ? p2 : 0] : *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off);
+          v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+          *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off) = v;
         } else {
           if (EPI == EPI_RESID) {
-            bf16x4_t r = *reinterpret_cast<const bf16x4_t*>(R + off);
+            const bf16x4_t r = PRE ? rold[PRE ? p2 : 0] : *reinterpret_cast<const bf16x4_t*>(R + off);
             v[0] += (float)r[0]; v[1] += (float)r[1]; v[2] += (float)r[2]; v[3] += (float)r[3];
           }
           bf16x4_t o;
@@ -318,29 +339,43 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const bf16_t* _
   }
 }
 
-// ---- NT kernel with direct global -> LDS tile loads -------------------------------------------------
+// ---- kernels with direct global -> LDS tile loads (NT and TN) -----------------------------------------
 // 256 x 256 x 64 tiles, 2 x 2 waves (one per SIMD; each owns 128 x 128 of the output in 256 accumulator
 // registers).  The tiles never pass through registers: every wave issues 16 `buffer_load_dwordx4 ... lds` per
-// k-tile, each filling 1 KB of LDS (lane i writes 16 bytes at base + 16 i).  The XOR swizzle is realised by the
-// choice of the global address each lane loads (lane i of the load for tile rows 8 q .. 8 q + 7 fetches row
-// 8 q + i / 8, logical chunk (i % 8) ^ swizzle(row)).  Rows past M or N read as zero through the buffer range
-// check.  Requires K % 64 == 0 and operands below 4 GiB (checked on the host).
+// k-tile, each filling 1 KB of LDS (lane i writes 16 bytes at base + 16 i); which global address a lane loads
+// realises the LDS swizzle.  Requires K % 64 == 0 and operands below 4 GiB (checked on the host); rows or
+// columns past the operand read as zero through the buffer range check.
+//
+//  NT (operands contiguous along k): a stage holds [256 rows][64 k]; the load for rows 8 q .. 8 q + 7 has lane i
+//     fetch row 8 q + i / 8, logical 16-byte chunk (i % 8) ^ swz(row); fragments are plain 16-byte reads.
+//  TN (operands contiguous along their output index): a stage holds the tile as it lies in memory,
+//     [64 k][256 columns]; one load fills k-rows 2 b, 2 b + 1, lane i fetching k-row 2 b + i / 32, logical chunk
+//     (i % 32) ^ ((k & 3) << 2).  Fragments come from the transposing read ds_read_b64_tr_b16: in every 16-lane
+//     group lane 4 e + r reads 8 bytes of k-row e, columns 4 r .. 4 r + 3, and the instruction hands lane i the
+//     4 k values of column i; two of them make the 8 k of an MFMA operand.  The chunk XOR spreads the 4 k-rows
+//     of such a read over the four 64-byte bank groups.
 //
 // With a single wave per SIMD nothing hides an instruction that waits, so the main loop is laid out by hand
 // (the scheduling barriers pin the order):
-//  * LDS is split [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KB each: the stage is a 16-bit immediate
-//    offset of the fragment reads, whose 32 per-lane addresses (8 fragments x 4 k-steps) are computed once;
-//    two k-tiles per loop trip make the stage a compile-time constant, so the loop has no address arithmetic.
-//  * One fragment read is issued ahead of every pair of MFMAs (k-step s + 1 is fetched under the MFMAs of
+//  * LDS is split [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KB each: the stage (and for TN the
+//    k-step) is an immediate offset of the fragment reads, whose per-lane addresses are computed once; two
+//    k-tiles per loop trip make the stage a compile-time constant, so the loop has no address arithmetic.
+//  * Fragment reads are issued ahead of every pair of MFMAs (k-step s + 1 is fetched under the MFMAs of
 //    k-step s), one tile load ahead of every MFMA of the last k-step; the fragments of the last k-step of a
 //    tile are requested early in the k-step before, so they have landed when the tile barrier is reached.
 //  * The loop is rotated so that the one barrier per tile (next tile landed, this stage free to refill) sits
 //    at the top of the trip.
 //  * Tiles are taken in pairs; a tile index past the end is fetched through a zero-length descriptor, which
 //    zero-fills its stage, so an odd tile count needs no second code path.
+//  * The tile loads are written in assembly: issued through the compiler builtin, every later transposing
+//    read is ordered after them with a full vmcnt(0) wait, which serialises the loop.  The one wait + barrier
+//    per tile orders them instead.
 typedef __attribute__((address_space(3))) void lds_void_t;
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4_t lds_i16x4_t;
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
-// Epilogue of the direct kernel for bf16 outputs: the wave converts its 128 x 128 accumulator tile to bf16
+// Epilogue of the direct kernels for bf16 outputs: the wave converts its 128 x 128 accumulator tile to bf16
 // (after adding the residual, read in accumulator layout, when there is one), transposes it through its own
 // 32 KB of LDS ([128 rows][256 B], 16-byte chunks XOR-swizzled by the row) and writes whole 256-byte row
 // segments, 16 bytes per lane.  Rows 16..31 of every 32 keep the two 8-byte halves of a chunk swapped so that
@@ -414,14 +449,15 @@ __device__ __forceinline__ void epilogue_bf16_rows(f32x16_t (&acc)[4][4], char* 
   }
 }
 
-template <int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+// TNL = false: A(m, k) at A[m * lda + k], B(n, k) at B[n * ldb + k].  TNL = true: A[k * lda + m], B[k * ldb + n].
+template <bool TNL, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n,
                                                                unsigned a_bytes, unsigned b_bytes) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int BM = 256, BN = 256, WM = 2, WN = 2, TM = 4, TN = 4;
-  constexpr int OPB = 256 * ROW_BYTES;          // one operand of one stage: 32 KB
+  constexpr int OPB = 32768;                    // one operand of one stage
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
@@ -445,45 +481,87 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // fragment q: 0..3 = A rows (i = q), 4..7 = B rows (j = q - 4); byte address within stage 0 for each k-step
-  int faddr[8][4];
-  const int khalf = lane >> 5;
+  // fragment q: 0..3 = A rows (i = q), 4..7 = B rows (j = q - 4).  Byte address of this lane's read within
+  // stage 0: NT one per k-step, TN one (k-step and k-quad are immediates: 8192 and 2048 bytes)
+  int faddr[8][TNL ? 1 : 4];
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
-    const int row = (q < 4 ? wm * (BM / WM) + q * 32 : wn * (BN / WN) + (q - 4) * 32) + (lane & 31);
+    const int base = (q < 4 ? 0 : 2 * OPB);
+    const int first = q < 4 ? wm * (BM / WM) + q * 32 : wn * (BN / WN) + (q - 4) * 32;
+    if (TNL) {
+      const int khalf = lane >> 5, cgrp = (lane >> 4) & 1, e = (lane >> 2) & 3, r = lane & 3;
+      const int c16 = (first + cgrp * 16 + r * 4) >> 3;
+      faddr[q][0] = base + (khalf * 8 + e) * 512 + ((c16 ^ (e << 2)) << 4) + (r & 1) * 8;
+    } else {
+      const int row = first + (lane & 31), khalf = lane >> 5;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      faddr[q][ks] = (q < 4 ? 0 : 2 * OPB) + row * ROW_BYTES + (((ks * 2 + khalf) ^ swz(row)) << 4);
+      for (int ks = 0; ks < (TNL ? 1 : 4); ++ks) faddr[q][ks] = base + row * ROW_BYTES + (((ks * 2 + khalf) ^ swz(row)) << 4);
+    }
   }
-  // tile loads: wave w fills LDS rows 64 w .. 64 w + 63 of each operand, 8 rows per instruction
-  const int lrow = lane >> 3, c0 = (lane & 7) ^ lrow;
-  const unsigned a_row_off = (unsigned)(m0 + wave * 64 + lrow) * (unsigned)lda * 2u;
-  const unsigned b_row_off = (unsigned)(n0 + wave * 64 + lrow) * (unsigned)ldb * 2u;
-  const unsigned a_step = 8u * (unsigned)lda * 2u, b_step = 8u * (unsigned)ldb * 2u;
+  // tile loads: 16 per wave and tile, t even -> A, t odd -> B, each 1 KB of LDS; voff = this lane's byte offset
+  // within the k-tile (out of range for rows or columns past the operand), the k-tile offset is scalar
   unsigned voff[16];
+  unsigned a_tile, b_tile;
+  if (TNL) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const unsigned coff = (unsigned)((c0 ^ j) << 4);
-    voff[2 * j] = a_row_off + j * a_step + coff;
-    voff[2 * j + 1] = b_row_off + j * b_step + coff;
+    for (int j = 0; j < 8; ++j) {
+      const int k = 2 * (wave * 8 + j) + (lane >> 5);
+      const int c16 = (lane & 31) ^ ((k & 3) << 2);
+      const int ca = m0 + c16 * 8, cb = n0 + c16 * 8;
+      voff[2 * j] = ca < M ? (unsigned)k * (unsigned)lda * 2u + (unsigned)ca * 2u : 0xFFFFFF00u;
+      voff[2 * j + 1] = cb < N ? (unsigned)k * (unsigned)ldb * 2u + (unsigned)cb * 2u : 0xFFFFFF00u;
+    }
+    a_tile = 64u * (unsigned)lda * 2u;
+    b_tile = 64u * (unsigned)ldb * 2u;
+  } else {
+    const int lrow = lane >> 3, c0 = (lane & 7) ^ lrow;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const unsigned coff = (unsigned)((c0 ^ j) << 4);
+      voff[2 * j] = (unsigned)(m0 + wave * 64 + j * 8 + lrow) * (unsigned)lda * 2u + coff;
+      voff[2 * j + 1] = (unsigned)(n0 + wave * 64 + j * 8 + lrow) * (unsigned)ldb * 2u + coff;
+    }
+    a_tile = b_tile = BK * 2;
   }
-  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, a_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, b_bytes, 0x00020000);
-  // load t of a tile: t even -> 8 A rows, t odd -> 8 B rows (1 KB of LDS each); soff = byte offset along k
-  auto issue_one = [&](__amdgpu_buffer_rsrc_t da, __amdgpu_buffer_rsrc_t db, int stage, int soff, int t) {
-    char* dst = smem + ((t & 1) ? 2 * OPB : 0) + stage * OPB + (wave * 8 + (t >> 1)) * 1024;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds((t & 1) ? db : da, (lds_void_t*)dst, 16, voff[t], soff, 0, 0);
+  auto make_desc = [](const void* p, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)p;
+    i32x4_t d;
+    d[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    d[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32) & 0xffff);
+    d[2] = (int)bytes;
+    d[3] = 0x00020000;
+    return d;
   };
-  bf16x8_t fr[2][8];
-  auto load_one = [&](int set, int stage, int ks, int q) {
-    fr[set][q] = *reinterpret_cast<const bf16x8_t*>(smem + stage * OPB + faddr[q][ks]);
+  const i32x4_t ra = make_desc(A, a_bytes), rb = make_desc(B, b_bytes);
+  const unsigned lds0 = (unsigned)(size_t)(lds_void_t*)smem;
+  auto issue_one = [&](i32x4_t da, i32x4_t db, int stage, int kt, int t) {
+    const unsigned dst = lds0 + ((t & 1) ? 2 * OPB : 0) + stage * OPB + (wave * 8 + (t >> 1)) * 1024;
+    const unsigned soff = (t & 1) ? kt * b_tile : kt * a_tile;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(dst), "v"(voff[t]), "s"((t & 1) ? db : da), "s"(soff) : "memory", "m0");
+  };
+  i16x4_t fr[2][8][2];
+  // half 0 / 1: the two 8-byte halves of fragment q (TN: one transposing read each; NT: one 16-byte read at half 0)
+  auto load_half = [&](int set, int stage, int ks, int q, int half) {
+    if (TNL) {
+      fr[set][q][half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_i16x4_t*)(smem + stage * OPB + ks * 8192 + half * 2048 + faddr[q][0]));
+    } else if (half == 0) {
+      typedef short i16x8_t __attribute__((ext_vector_type(8)));
+      const i16x8_t v = *reinterpret_cast<const i16x8_t*>(smem + stage * OPB + faddr[q][TNL ? 0 : ks]);
+      fr[set][q][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+      fr[set][q][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+    }
+  };
+  auto frag = [&](int set, int q) {
+    return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(fr[set][q][0], fr[set][q][1], 0, 1, 2, 3, 4, 5, 6, 7));
   };
   // fragments are read in the order a0 b0 a1 b1 ...; the MFMA order uses the ones read first first
   constexpr int MI[16] = {0, 1, 0, 1, 2, 2, 0, 1, 2, 3, 3, 3, 0, 1, 2, 3};
   constexpr int MJ[16] = {0, 0, 1, 1, 0, 1, 2, 2, 2, 0, 1, 2, 3, 3, 3, 3};
   constexpr int LQ[8] = {0, 4, 1, 5, 2, 6, 3, 7};
   auto mma_one = [&](int set, int t) {
-    acc[MI[t]][MJ[t]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][4 + MJ[t]], fr[set][MI[t]], acc[MI[t]][MJ[t]], 0, 0, 0);
+    acc[MI[t]][MJ[t]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(set, 4 + MJ[t]), frag(set, MI[t]), acc[MI[t]][MJ[t]], 0, 0, 0);
   };
   // k-steps 0..2 of the tile in `stage`: the MFMAs of step ks run over the fragment reads of step ks + 1
   auto steps_012 = [&](int stage) {
@@ -494,10 +572,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
       for (int q = 0; q < 8; ++q) {
         __builtin_amdgcn_sched_barrier(0);
         if (ks < 2) {
-          load_one(set ^ 1, stage, ks + 1, LQ[q]);
+          load_half(set ^ 1, stage, ks + 1, LQ[q], 0);
+          load_half(set ^ 1, stage, ks + 1, LQ[q], 1);
         } else if (q < 4) {                        // last reads of this stage: all requested in the first half
-          load_one(set ^ 1, stage, ks + 1, LQ[2 * q]);
-          load_one(set ^ 1, stage, ks + 1, LQ[2 * q + 1]);
+          load_half(set ^ 1, stage, ks + 1, LQ[2 * q], 0);
+          load_half(set ^ 1, stage, ks + 1, LQ[2 * q], 1);
+          load_half(set ^ 1, stage, ks + 1, LQ[2 * q + 1], 0);
+          load_half(set ^ 1, stage, ks + 1, LQ[2 * q + 1], 1);
         }
         __builtin_amdgcn_sched_barrier(0);
         mma_one(set, 2 * q);
@@ -506,18 +587,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  // k-step 3 of the tile in `stage` (fragment set 1); meanwhile that stage is refilled with the tile two ahead
-  // and the first fragments of the next tile are read from the other stage
-  auto step_3 = [&](int stage, __amdgpu_buffer_rsrc_t da, __amdgpu_buffer_rsrc_t db, int soff, bool refill, bool next) {
+  // k-step 3 of the tile in `stage` (fragment set 1); meanwhile that stage is refilled with tile kt and the
+  // first fragments of the next tile are read from the other stage
+  auto step_3 = [&](int stage, i32x4_t da, i32x4_t db, int kt, bool refill, bool next) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       __builtin_amdgcn_sched_barrier(0);
-      if (refill) issue_one(da, db, stage, soff, 2 * q);
-      if (next) load_one(0, stage ^ 1, 0, LQ[q]);
+      if (refill) issue_one(da, db, stage, kt, 2 * q);
+      if (next) load_half(0, stage ^ 1, 0, LQ[q], 0);
       __builtin_amdgcn_sched_barrier(0);
       mma_one(1, 2 * q);
       __builtin_amdgcn_sched_barrier(0);
-      if (refill) issue_one(da, db, stage, soff, 2 * q + 1);
+      if (refill) issue_one(da, db, stage, kt, 2 * q + 1);
+      if (next) load_half(0, stage ^ 1, 0, LQ[q], 1);
       __builtin_amdgcn_sched_barrier(0);
       mma_one(1, 2 * q + 1);
     }
@@ -529,28 +611,28 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
 
   const int nk = K / BK, npair = (nk + 1) >> 1;
   {
-    const bool two = nk > 1;
-    const __amdgpu_buffer_rsrc_t ra1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, two ? a_bytes : 0u, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rb1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, two ? b_bytes : 0u, 0x00020000);
+    i32x4_t ra1 = ra, rb1 = rb;
+    ra1[2] = nk > 1 ? ra1[2] : 0;                    // word 2 of the descriptor: bytes in range
+    rb1[2] = nk > 1 ? rb1[2] : 0;
 #pragma unroll
     for (int t = 0; t < 16; ++t) issue_one(ra, rb, 0, 0, t);
 #pragma unroll
-    for (int t = 0; t < 16; ++t) issue_one(ra1, rb1, 1, BK * 2, t);
+    for (int t = 0; t < 16; ++t) issue_one(ra1, rb1, 1, 1, t);
   }
   OPTSTAGE_TILE_SYNC();
 #pragma unroll
-  for (int q = 0; q < 8; ++q) load_one(0, 0, 0, LQ[q]);
+  for (int q = 0; q < 8; ++q) { load_half(0, 0, 0, LQ[q], 0); load_half(0, 0, 0, LQ[q], 1); }
   steps_012(0);
   // at the top of a trip: k-steps 0..2 of tile 2 p (stage 0) are issued, tile 2 p + 1 is in flight to stage 1
   for (int p = 0; p + 1 < npair; ++p) {
-    const bool odd_ok = 2 * p + 3 < nk;
-    const __amdgpu_buffer_rsrc_t ra1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, odd_ok ? a_bytes : 0u, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rb1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, odd_ok ? b_bytes : 0u, 0x00020000);
+    i32x4_t ra1 = ra, rb1 = rb;
+    ra1[2] = 2 * p + 3 < nk ? ra1[2] : 0;
+    rb1[2] = 2 * p + 3 < nk ? rb1[2] : 0;
     OPTSTAGE_TILE_SYNC();
-    step_3(0, ra, rb, (2 * p + 2) * BK * 2, true, true);
+    step_3(0, ra, rb, 2 * p + 2, true, true);
     steps_012(1);
     OPTSTAGE_TILE_SYNC();
-    step_3(1, ra1, rb1, (2 * p + 3) * BK * 2, true, true);
+    step_3(1, ra1, rb1, 2 * p + 3, true, true);
     steps_012(0);
   }
   OPTSTAGE_TILE_SYNC();
@@ -568,11 +650,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_lds_kernel(const bf16_t* __r
                             n0 + wn * (BN / WN));
 }
 
-template <int EPI>
-hipError_t launch_nt_lds(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
+template <bool TNL, int EPI>
+hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
                          int ldc, hipStream_t s) {
-  auto kern = gemm_bf16_nt_lds_kernel<EPI>;
-  constexpr int smem = 2 * 512 * ROW_BYTES;
+  auto kern = gemm_bf16_direct_kernel<TNL, EPI>;
+  constexpr int smem = 131072;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -580,18 +662,20 @@ hipError_t launch_nt_lds(const void* A, const void* B, void* C, const void* R, i
     attr_set = true;
   }
   const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-  // byte extent of each operand: rows past the end fall outside the buffer range and read as zero
-  const unsigned a_bytes = (unsigned)(((size_t)(M - 1) * lda + K) * 2), b_bytes = (unsigned)(((size_t)(N - 1) * ldb + K) * 2);
+  // byte extent of each operand: whatever lies past it reads as zero
+  const unsigned a_bytes = (unsigned)(TNL ? ((size_t)(K - 1) * lda + M) * 2 : ((size_t)(M - 1) * lda + K) * 2);
+  const unsigned b_bytes = (unsigned)(TNL ? ((size_t)(K - 1) * ldb + N) * 2 : ((size_t)(N - 1) * ldb + K) * 2);
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, (const bf16_t*)A, (const bf16_t*)B, C, (const bf16_t*)R,
                      M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes);
   return hipGetLastError();
 }
 
-// the direct path needs whole 64-wide k-tiles and 32-bit byte offsets, including the rows a partial edge
-// tile reaches past the operand
-bool nt_lds_applies(int M, int N, int K, int lda, int ldb) {
+// the direct path needs whole 64-wide k-tiles and 32-bit byte offsets (NT: including the rows a partial edge
+// tile reaches past the operand)
+bool direct_applies(bool tnl, int M, int N, int K, int lda, int ldb) {
   if (K % 64) return false;
   const unsigned long long lim = 0xF0000000ull;
+  if (tnl) return ((unsigned long long)K * lda * 2 < lim) && ((unsigned long long)K * ldb * 2 < lim);
   return ((unsigned long long)(M + 256) * lda * 2 < lim) && ((unsigned long long)(N + 256) * ldb * 2 < lim);
 }
 template <int BM, int BN, int WM, int WN, bool A_RC, bool B_RC, int EPI>
@@ -616,11 +700,11 @@ hipError_t launch_layout(const void* A, const void* B, void* C, const void* R, i
                          int ldc, hipStream_t s) {
   long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
   if (big_tiles >= 128) {
+    if (direct_applies(RC, M, N, K, lda, ldb)) return launch_direct<RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
     // register-staged path: 8 waves (4 x 2) for the transposing TN loader, 4 waves (2 x 2) otherwise
     if constexpr (RC) {
       return launch_cfg<256, 256, 4, 2, RC, RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
     } else {
-      if (nt_lds_applies(M, N, K, lda, ldb)) return launch_nt_lds<EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
       return launch_cfg<256, 256, 2, 2, RC, RC, EPI>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
     }
   }
