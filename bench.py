@@ -255,7 +255,7 @@ def main():
             kernels[name] = {"launches_per_step": agg["k_n"][i] // args.steps, "avg_ms": ms / agg["k_n"][i],
                              "achieved": rate, "unit": unit, "share_of_step": ms / args.steps / ms_per_step}
     dom = kernels.get("gemm_nt_store", {"achieved": 0.0})
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_nt_lds_kernel<store>" if cfg.dtype == 1 else "gemm_f32_kernel",
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_direct_kernel<NT,store>" if cfg.dtype == 1 else "gemm_f32_kernel",
                 "achieved": dom["achieved"], "peak": peak_tf, "unit": "TFLOP/s", "frac": dom["achieved"] / peak_tf,
                 "avg_launch_ms": dom.get("avg_ms"), "launches_per_step": dom.get("launches_per_step"),
                 "algorithmic_bytes": nt_store_algorithmic_bytes(cfg), "traffic": measured_traffic(cfg)}
