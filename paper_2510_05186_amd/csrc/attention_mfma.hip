@@ -56,6 +56,7 @@ struct FragAddr {
 // dc = tid % 16) holds rows 4 kq .. 4 kq + 3 of 16-byte column chunk dc; the same registers feed both the
 // row-major and the transposed LDS store
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
 // Tiles are fetched with raw buffer loads: one 32-bit lane offset (row 4 kq, chunk dc) plus a scalar offset
 // for (first row + kk, head); rows at or past the end of the tensor fall outside the buffer range and read
 // as zero, so there is neither predication nor 64-bit address arithmetic in the loops.
@@ -144,7 +145,7 @@ __device__ __forceinline__ void accumulate_transposed(const FragAddr& fr, const 
 }
 
 // ---- forward ------------------------------------------------------------------------------------------
-// grid (ceil(seq / 128), n_q, batch); 4 waves x 32 query rows; key blocks of 64
+// grid (n_q, batch, ceil(seq / 128)); 4 waves x 32 query rows; key blocks of 64
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                         float* __restrict__ lse, int seq, int n_q, int n_kv) {
   __shared__ __attribute__((aligned(16))) char smem[2 * 16384];
@@ -153,8 +154,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16_t* __restrict
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c32 = lane & 31;
   const FragAddr fr(c32, g);
   const int nqb = (seq + 127) / 128;
-  const int q0 = (nqb - 1 - (int)blockIdx.x) * 128;          // longest rows first
-  const int a = blockIdx.y, b = blockIdx.z, kvh = a * n_kv / n_q;
+  const int q0 = (nqb - 1 - (int)blockIdx.z) * 128;          // longest rows are dispatched first, for every head
+  const int a = blockIdx.x, b = blockIdx.y, kvh = a * n_kv / n_q;
   const int ld = (n_q + 2 * n_kv) * D;
   const bf16_t* base = qkv + (size_t)b * seq * ld;
   const int qglob = q0 + 32 * wave + c32;
@@ -278,7 +279,7 @@ __global__ void attn_bwd_delta(const bf16_t* __restrict__ o, const bf16_t* __res
   if (lane == 0) delta[((size_t)b * n_q + a) * seq + t] = s;
 }
 
-// ---- backward, dQ: grid (ceil(seq / 128), n_q, batch); 4 waves x 32 query rows; key blocks of 64 ---------
+// ---- backward, dQ: grid (n_q, batch, ceil(seq / 128)); 4 waves x 32 query rows; key blocks of 64 ---------
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, int seq, int n_q, int n_kv) {
@@ -289,8 +290,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16_t* __restr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c32 = lane & 31;
   const FragAddr fr(c32, g);
   const int nqb = (seq + 127) / 128;
-  const int q0 = (nqb - 1 - (int)blockIdx.x) * 128;
-  const int a = blockIdx.y, b = blockIdx.z, kvh = a * n_kv / n_q;
+  const int q0 = (nqb - 1 - (int)blockIdx.z) * 128;
+  const int a = blockIdx.x, b = blockIdx.y, kvh = a * n_kv / n_q;
   const int ld = (n_q + 2 * n_kv) * D;
   const bf16_t* base = qkv + (size_t)b * seq * ld;
   const int qglob = q0 + 32 * wave + c32;
@@ -366,152 +367,293 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16_t* __restr
     }
 }
 
-// ---- backward, dK / dV: grid (ceil(seq / 128), n_kv, batch); query blocks of 64 ---------------------------
-// 8 waves share the LDS tiles of one workgroup.  Waves 0-3 own dV of 32 keys each (S -> P -> dV^T += dO^T P)
-// and stage the Q / dO tiles; waves 4-7 own dK of the same keys (S, dP -> dS -> dK^T += Q^T dS).  Each SIMD
-// thus runs one dV wave and one dK wave whose MFMA and exp2 phases interleave, and both stay within 256
-// VGPRs, so MFMA results are written to ordinary VGPRs (no accumulator-file copies).
-__global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+// ---- backward, dK / dV: grid (n_kv, batch, ceil(seq / 256)); 4 waves (one per SIMD) ----------------------
+// Wave w owns keys k0 + 64 w .. + 63 as two 32-key tiles: their K operand fragments stay in registers for the
+// whole kernel (the V rows of the workgroup's 256 keys stay in LDS: both operand sets do not fit beside the
+// accumulators) and dK^T, dV^T ([d 128][64 keys] each) in the 256 accumulator registers, so every Q / dO
+// fragment read from LDS feeds two MFMAs.  Query blocks of 64 (Q and dO rows plus their lse and D)
+// stream through a two-stage LDS ring, loaded straight from global memory (`buffer_load ... lds`); one copy
+// of a tile serves both contractions: over head_dim with 16-byte row reads (S = Q K^T, dP = dO V^T) and over
+// the queries with transposing reads (dV^T += dO^T P, dK^T += Q^T dS).  16-byte chunk c of tile row r is
+// stored at chunk c ^ f(r), f(r) = ((r & 3) << 2) | ((r >> 2) & 3): 16 consecutive rows get 16 different
+// values (row reads of one chunk hit every bank once) and 4 consecutive rows differ in the 64-byte group
+// (the 4 rows of a transposing read do too).
+constexpr int DKV_STAGE = 32768 + 512;       // Q tile, dO tile, 64 lse, 64 D
+constexpr int DKV_VTILE = 256 * 256;         // V rows of the workgroup's keys, behind the two stages
+constexpr int DKV_SMEM = 2 * DKV_STAGE + DKV_VTILE;
+
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16_t* __restrict__ dqkv, int seq, int n_q, int n_kv) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  // [K | V] of the workgroup's 128 keys (32 KB each, loaded once), [Q | dO | Q^T | dO^T] of the current
-  // 64-query block (16 KB each), then lse*log2e and D for those queries
-  char* sK = smem;
-  char* sV = smem + 32768;
-  char* sQ = smem + 65536;
-  char* sDO = sQ + 16384;
-  char* sQt = sQ + 32768;
-  char* sDOt = sQ + 49152;
-  float* sL = reinterpret_cast<float*>(sQ + 65536);
-  float* sD = sL + 64;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c32 = lane & 31;
-  const FragAddr fr(c32, g);
-  const bool is_dk = wave >= 4;          // wave-uniform role
-  const int kw = wave & 3;               // which 32 keys of the block
-  const bool loader = !is_dk;            // waves 0-3 (threads 0..255) stage the tiles
-  const int k0 = blockIdx.x * 128;
-  const int kvh = blockIdx.y, b = blockIdx.z;
-  const int ld = (n_q + 2 * n_kv) * D;
-  const int ldo = n_q * D;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int k0 = blockIdx.z * 256;               // first key blocks (most queries) are dispatched first, for every head
+  const int kvh = blockIdx.x, b = blockIdx.y;
+  const int ld = (n_q + 2 * n_kv) * D, ldo = n_q * D;
   const bf16_t* base = qkv + (size_t)b * seq * ld;
-  const int kglob = k0 + 32 * kw + c32;
-  const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(base, (unsigned)seq * ld * 2u);
-  const __amdgpu_buffer_rsrc_t rs_do = make_rsrc(dout + (size_t)b * seq * ldo, (unsigned)seq * ldo * 2u);
-  const unsigned lane_off_qkv = tile_lane_offset(ld, tid & 255), lane_off_do = tile_lane_offset(ldo, tid & 255);
-  if (loader) {
-    uint4 r0[4], r1[4];
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const unsigned row_off = (unsigned)(k0 + 64 * half) * ld * 2u;
-      tile_load(r0, rs_qkv, lane_off_qkv, row_off + (unsigned)(n_q + kvh) * D * 2u, ld);
-      tile_load(r1, rs_qkv, lane_off_qkv, row_off + (unsigned)(n_q + n_kv + kvh) * D * 2u, ld);
-      tile_store_rowmajor(sK + 16384 * half, r0, tid);
-      tile_store_rowmajor(sV + 16384 * half, r1, tid);
-    }
-  }
+  const int wave_first_k = k0 + 64 * wave;
   const float scale = rsqrtf((float)D), c = scale * LOG2E;
-  f32x16_t acc[4];                        // dV^T (waves 0-3) or dK^T (waves 4-7): [d 128][32 keys]
+
+  // K, V operand fragments of this wave's keys (rows past the end are clamped: their results are not stored)
+  bf16x8_t Kf[2][8];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int kk = 0; kk < 2; ++kk) {
+    const int krow = min(wave_first_k + 32 * kk + c32, seq - 1);
+    const bf16_t* kp = base + (size_t)krow * ld + (size_t)(n_q + kvh) * D + 8 * g;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
-  const int rep = n_q / n_kv;
-  const int qb0 = k0 / 64, nqb = (seq + 63) / 64;
-  const int wave_first_k = k0 + 32 * kw;
-  const int iters = rep * (nqb - qb0);
-  uint4 qreg[4], doreg[4];
-  float lreg = 0.f, dreg = 0.f;
-  auto issue_loads = [&](int it) {
-    const int a = kvh * rep + it / (nqb - qb0);
-    const int r0 = 64 * (qb0 + it % (nqb - qb0));
-    tile_load(qreg, rs_qkv, lane_off_qkv, (unsigned)r0 * ld * 2u + (unsigned)a * D * 2u, ld);
-    tile_load(doreg, rs_do, lane_off_do, (unsigned)r0 * ldo * 2u + (unsigned)a * D * 2u, ldo);
-    if (tid < 64) {
-      int r = min(r0 + tid, seq - 1);
-      lreg = lse[((size_t)b * n_q + a) * seq + r] * LOG2E;
-      dreg = delta[((size_t)b * n_q + a) * seq + r];
-    }
-  };
-  if (loader && iters > 0) issue_loads(0);
-  for (int it = 0; it < iters; ++it) {
-    const int r0 = 64 * (qb0 + it % (nqb - qb0));
-    __syncthreads();
-    if (loader) {
-      tile_store_rowmajor(sQ, qreg, tid);
-      tile_store_rowmajor(sDO, doreg, tid);
-      tile_store_transposed(sQt, qreg, tid);
-      tile_store_transposed(sDOt, doreg, tid);
-      if (tid < 64) { sL[tid] = lreg; sD[tid] = dreg; }
-    }
-    __syncthreads();
-    if (loader && it + 1 < iters) issue_loads(it + 1);
-    if (r0 + 63 < wave_first_k) continue;                      // wave-uniform: all queries precede this wave's keys
-    // lane = key (column), registers = queries: row v of tile t is query r0 + 32 t + 8 (v / 4) + 4 g + v % 4
-    const bool edge = r0 < wave_first_k + 32 || r0 + 64 > seq;   // wave-uniform: diagonal or ragged tail
-    if (!is_dk) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x16_t s, unused;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 0.f;
-        score_tiles<false, true, true>(fr, sQ, nullptr, t, sK, nullptr, kw, nullptr, nullptr, nullptr, nullptr, s, unused);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int ql0 = 32 * t + 8 * j + 4 * g;
-          const f32x4_t L4 = *reinterpret_cast<const f32x4_t*>(sL + ql0);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int v = 4 * j + i;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[v], c, -L4[i]));
-            if (edge) {
-              const int qg = r0 + ql0 + i;
-              if (qg < kglob || qg >= seq) p = 0.f;
-            }
-            s[v] = p;
-          }
-        }
-        accumulate_transposed(fr, sDOt, t, s, acc);
-      }
-    } else {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x16_t s, dp;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
-        score_tiles<true, true, true>(fr, sQ, sDO, t, sK, sV, kw, nullptr, nullptr, nullptr, nullptr, s, dp);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int ql0 = 32 * t + 8 * j + 4 * g;
-          const f32x4_t L4 = *reinterpret_cast<const f32x4_t*>(sL + ql0);
-          const f32x4_t D4 = *reinterpret_cast<const f32x4_t*>(sD + ql0);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int v = 4 * j + i;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[v], c, -L4[i]));
-            if (edge) {
-              const int qg = r0 + ql0 + i;
-              if (qg < kglob || qg >= seq) p = 0.f;
-            }
-            s[v] = p * (dp[v] - D4[i]);                           // dS
-          }
-        }
-        accumulate_transposed(fr, sQt, t, s, acc);
-      }
-    }
+    for (int ks = 0; ks < 8; ++ks) Kf[kk][ks] = *reinterpret_cast<const bf16x8_t*>(kp + 16 * ks);
   }
-  if (kglob >= seq) return;
-  const float osc = is_dk ? scale : 1.f;
-  bf16_t* orow = dqkv + ((size_t)b * seq + kglob) * ld + (size_t)(is_dk ? n_q + kvh : n_q + n_kv + kvh) * D;
+  f32x16_t accK[2][4], accV[2][4];            // [key tile][d tile]: lane = key, registers = d
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { accK[kk][dt][v] = 0.f; accV[kk][dt][v] = 0.f; }
+
+  // per-lane LDS addresses within a tile.  Row read of k-step ks: row c32 (+ 32 t), chunk 2 ks + g.
+  int rm_addr[8];
+  {
+    const int f = ((c32 & 3) << 2) | ((c32 >> 2) & 3);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) rm_addr[ks] = c32 * 256 + (((2 * ks + g) ^ f) << 4);
+  }
+  // Transposing read (dt, kq): in each 16-lane group lane 4 e + r reads 8 bytes of row 4 g + e (+ 32 t + 16 u
+  // + 8 kq), columns 32 dt + 16 cg + 4 r ..; f(row) = (e << 2) | (2 kq + g)
+  int tr_addr[4][2];
+  {
+    const int cg = (lane >> 4) & 1, e = (lane >> 2) & 3, r = lane & 3;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int kq = 0; kq < 2; ++kq)
+        tr_addr[dt][kq] = (4 * g + e) * 256 + (((4 * dt + 2 * cg + (r >> 1)) ^ (e << 2) ^ g ^ (kq << 1)) << 4) + (r & 1) * 8;
+  }
+  // tile loads: one instruction fills 4 rows (1 KB); wave w loads rows 16 w .. 16 w + 15 of Q and of dO.
+  // Lane i: row 4 b + i / 16, stored chunk i % 16 = logical chunk ^ f(row), f = ((i / 16) << 2) | (b & 3).
+  unsigned voff_q[4], voff_do[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = 16 * wave + 4 * j + (lane >> 4);
+    const int chunk = (lane & 15) ^ (((lane >> 4) << 2) | j);
+    voff_q[j] = (unsigned)row * (unsigned)ld * 2u + (unsigned)chunk * 16u;
+    voff_do[j] = (unsigned)row * (unsigned)ldo * 2u + (unsigned)chunk * 16u;
+  }
+  auto make_desc = [](const void* p, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)p;
+    i32x4_t d;
+    d[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    d[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32) & 0xffff);
+    d[2] = (int)bytes;
+    d[3] = 0x00020000;
+    return d;
+  };
+  const i32x4_t rs_q = make_desc(base, (unsigned)seq * ld * 2u);
+  const i32x4_t rs_do = make_desc(dout + (size_t)b * seq * ldo, (unsigned)seq * ldo * 2u);
+  const i32x4_t rs_l = make_desc(lse + (size_t)b * n_q * seq, (unsigned)n_q * seq * 4u);
+  const i32x4_t rs_d = make_desc(delta + (size_t)b * n_q * seq, (unsigned)n_q * seq * 4u);
+  const unsigned lds0 = (unsigned)(size_t)(lds_void_t*)smem;
+
+  // V rows of this wave's 64 keys -> LDS (16 loads of 4 rows), same layout as the streamed tiles
+  const char* sV = smem + 2 * DKV_STAGE + wave * 16384;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int row = 4 * j + (lane >> 4);
+    const int chunk = (lane & 15) ^ (((lane >> 4) << 2) | (j & 3));
+    const unsigned vo = ((unsigned)(wave_first_k + row) * (unsigned)ld + (unsigned)(n_q + n_kv + kvh) * D) * 2u + (unsigned)chunk * 16u;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds0 + 2 * DKV_STAGE + wave * 16384 + j * 1024), "v"(vo), "s"(rs_q) : "memory", "m0");
+  }
+  const int rep = n_q / n_kv;
+  const int qb0 = k0 / 64, nqb = (seq + 63) / 64 - qb0;       // query blocks at or after the first key
+  const int iters = rep * nqb;
+  // All offsets go through the lane offset, which is what the range check sees: rows at or past seq read zero.
+  auto issue_block = [&](int it, int stage) {
+    const int a = kvh * rep + it / nqb;
+    const int r0 = 64 * (qb0 + it % nqb);
+    const unsigned oq = ((unsigned)r0 * (unsigned)ld + (unsigned)a * D) * 2u;
+    const unsigned od = ((unsigned)r0 * (unsigned)ldo + (unsigned)a * D) * 2u;
+    const unsigned dst = lds0 + stage * DKV_STAGE + (16 * wave) * 256;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      bf16x4_t r;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] = (bf16_t)(acc[dt][4 * j + i] * osc);
-      *reinterpret_cast<bf16x4_t*>(orow + 32 * dt + 8 * j + 4 * g) = r;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst + j * 1024), "v"(voff_q[j] + oq), "s"(rs_q) : "memory", "m0");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst + 16384 + j * 1024), "v"(voff_do[j] + od), "s"(rs_do) : "memory", "m0");
     }
+    if (wave < 2) {                            // wave 0: lse of the 64 queries, wave 1: D
+      const unsigned vo = ((unsigned)a * (unsigned)seq + (unsigned)min(r0 + lane, seq - 1)) * 4u;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                   :: "s"(lds0 + stage * DKV_STAGE + 32768 + wave * 256), "v"(vo), "s"(wave == 0 ? rs_l : rs_d) : "memory", "m0");
+    }
+  };
+  typedef short i16x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) i16x4_t lds_i16x4_t;
+  auto tr_frag = [&](const char* tile, int dt, int t, int u) {
+    const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t*)(tile + (32 * t + 16 * u) * 256 + tr_addr[dt][0]));
+    const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t*)(tile + (32 * t + 16 * u + 8) * 256 + tr_addr[dt][1]));
+    return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto rm_frag = [&](const char* tile, int t, int ks) {
+    return *reinterpret_cast<const bf16x8_t*>(tile + t * 8192 + rm_addr[ks]);
+  };
+
+#define OPTSTAGE_SB() __builtin_amdgcn_sched_barrier(0)
+  // VGPR-result MFMA in assembly: the compiler would place the score tiles in accumulator registers, all 256
+  // of which hold dK, dV.  Readers of the result keep >= 2 MFMAs (or an s_nop) behind the last write.
+#define OPTSTAGE_MFMA_V(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+  auto block = [&](int it, int stage) {
+    const int r0 = 64 * (qb0 + it % nqb);
+    if (r0 + 63 < wave_first_k) return;                          // all queries precede this wave's keys
+    const char* sQ = smem + stage * DKV_STAGE;
+    const char* sDO = sQ + 16384;
+    const float* sL = reinterpret_cast<const float*>(sQ + 32768);
+    const float* sD = sL + 64;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int q0 = r0 + 32 * t;
+      if (q0 + 31 < wave_first_k) continue;                      // wave-uniform
+      const bool edge = q0 < wave_first_k + 63 || q0 + 32 > seq;   // touches the diagonal or the ragged tail
+      // lane = key, registers = queries q0 + 8 (v / 4) + 4 g + v % 4
+      f32x16_t s[2], dp[2];
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { s[kk][v] = 0.f; dp[kk][v] = 0.f; }
+      f32x4_t nL[4], Dq[4];                                        // -lse * log2(e) and D of this lane's queries
+      bf16x8_t qf[2], df[2], vf[2][2];
+      // ---- S = Q K^T: fragment of k-step ks + 1 requested before the MFMAs of k-step ks
+      qf[0] = rm_frag(sQ, t, 0);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        OPTSTAGE_SB();
+        if (ks < 7) {
+          qf[(ks + 1) & 1] = rm_frag(sQ, t, ks + 1);
+        } else {
+          df[0] = rm_frag(sDO, t, 0);
+          vf[0][0] = rm_frag(sV, 0, 0);
+          vf[0][1] = rm_frag(sV, 1, 0);
+        }
+        if (ks < 4) nL[ks] = *reinterpret_cast<const f32x4_t*>(sL + 32 * t + 8 * ks + 4 * g);
+        else Dq[ks - 4] = *reinterpret_cast<const f32x4_t*>(sD + 32 * t + 8 * (ks - 4) + 4 * g);
+        OPTSTAGE_SB();
+        OPTSTAGE_MFMA_V(s[0], qf[ks & 1], Kf[0][ks]);
+        OPTSTAGE_MFMA_V(s[1], qf[ks & 1], Kf[1][ks]);
+        OPTSTAGE_SB();
+        if (ks >= 4) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) nL[ks - 4][i] *= -LOG2E;
+        }
+      }
+      // ---- dP = dO V^T, with the exponentials of S (2 registers x 2 key tiles per k-step) under its MFMAs
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        OPTSTAGE_SB();
+        if (ks < 7) {
+          df[(ks + 1) & 1] = rm_frag(sDO, t, ks + 1);
+          vf[(ks + 1) & 1][0] = rm_frag(sV, 0, ks + 1);
+          vf[(ks + 1) & 1][1] = rm_frag(sV, 1, ks + 1);
+        }
+        OPTSTAGE_SB();
+        OPTSTAGE_MFMA_V(dp[0], df[ks & 1], vf[ks & 1][0]);
+        OPTSTAGE_MFMA_V(dp[1], df[ks & 1], vf[ks & 1][1]);
+        OPTSTAGE_SB();
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int v = 2 * ks + e;
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) s[kk][v] = __builtin_amdgcn_exp2f(fmaf(s[kk][v], c, nL[v >> 2][v & 3]));
+        }
+      }
+      OPTSTAGE_SB();
+      if (edge) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int qg = q0 + 8 * (v >> 2) + 4 * g + (v & 3);
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk)
+            if (qg < wave_first_k + 32 * kk + c32 || qg >= seq) s[kk][v] = 0.f;
+        }
+      }
+      OPTSTAGE_SB();
+      // ---- dV^T += dO^T P, with dS = P (dP - D) under its MFMAs (the first two MFMAs cover the dP latency)
+      bf16x8_t trf[2];
+      trf[0] = tr_frag(sDO, 0, t, 0);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8_t p0 = pack8(s[0], u), p1 = pack8(s[1], u);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          const int n = u * 4 + dt;
+          OPTSTAGE_SB();
+          if (n < 7) trf[(n + 1) & 1] = tr_frag(sDO, (dt + 1) & 3, t, dt == 3 ? 1 : u);
+          else trf[0] = tr_frag(sQ, 0, t, 0);
+          OPTSTAGE_SB();
+          accV[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trf[n & 1], p0, accV[0][dt], 0, 0, 0);
+          accV[1][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trf[n & 1], p1, accV[1][dt], 0, 0, 0);
+          OPTSTAGE_SB();
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int v = 2 * n + e;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) dp[kk][v] = s[kk][v] * (dp[kk][v] - Dq[v >> 2][v & 3]);
+          }
+        }
+      }
+      // ---- dK^T += Q^T dS
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8_t d0 = pack8(dp[0], u), d1 = pack8(dp[1], u);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          const int n = u * 4 + dt;
+          OPTSTAGE_SB();
+          if (n < 7) trf[(n + 1) & 1] = tr_frag(sQ, (dt + 1) & 3, t, dt == 3 ? 1 : u);
+          OPTSTAGE_SB();
+          accK[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trf[n & 1], d0, accK[0][dt], 0, 0, 0);
+          accK[1][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trf[n & 1], d1, accK[1][dt], 0, 0, 0);
+        }
+      }
+      OPTSTAGE_SB();
+    }
+  };
+#undef OPTSTAGE_MFMA_V
+#undef OPTSTAGE_SB
+
+  if (iters > 0) issue_block(0, 0);
+  for (int it = 0; it < iters; it += 2) {
+    // block `it` has landed (this wave's part; the barrier covers the rest) and nobody still reads stage 1
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (it + 1 < iters) issue_block(it + 1, 1);
+    block(it, 0);
+    if (it + 1 < iters) {
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+      if (it + 2 < iters) issue_block(it + 2, 0);
+      block(it + 1, 1);
+    }
+  }
+
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    const int kglob = wave_first_k + 32 * kk + c32;
+    if (kglob >= seq) continue;
+    bf16_t* krow = dqkv + ((size_t)b * seq + kglob) * ld + (size_t)(n_q + kvh) * D;
+    bf16_t* vrow = dqkv + ((size_t)b * seq + kglob) * ld + (size_t)(n_q + n_kv + kvh) * D;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x4_t rk, rv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          rk[i] = (bf16_t)(accK[kk][dt][4 * j + i] * scale);
+          rv[i] = (bf16_t)accV[kk][dt][4 * j + i];
+        }
+        *reinterpret_cast<bf16x4_t*>(krow + 32 * dt + 8 * j + 4 * g) = rk;
+        *reinterpret_cast<bf16x4_t*>(vrow + 32 * dt + 8 * j + 4 * g) = rv;
+      }
+  }
 }
 
 }  // namespace
@@ -522,7 +664,7 @@ bool attn_mfma_applies(int dtype, int d, int seq, int n_q, int n_kv) {
 }
 
 hipError_t launch_attn_fwd_mfma(const void* qkv, void* o, float* lse, int seq, int batch, int n_q, int n_kv, hipStream_t s) {
-  hipLaunchKernelGGL(attn_fwd_mfma, dim3((seq + 127) / 128, n_q, batch), dim3(256), 0, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, n_q, n_kv);
+  hipLaunchKernelGGL(attn_fwd_mfma, dim3(n_q, batch, (seq + 127) / 128), dim3(256), 0, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, n_q, n_kv);
   return hipGetLastError();
 }
 
@@ -532,16 +674,15 @@ hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout
   hipLaunchKernelGGL(attn_bwd_delta, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, (const bf16_t*)o, (const bf16_t*)dout, ws, seq, n_q, batch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3((seq + 127) / 128, n_q, batch), dim3(256), 0, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
+  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 127) / 128), dim3(256), 0, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  constexpr int smem = 2 * 32768 + 65536 + 512;
   static bool attr_set = false;
   if (!attr_set) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_SMEM);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(attn_bwd_dkv_mfma, dim3((seq + 127) / 128, n_kv, batch), dim3(512), smem, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
+  hipLaunchKernelGGL(attn_bwd_dkv_mfma, dim3(n_kv, batch, (seq + 255) / 256), dim3(256), DKV_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
   return hipGetLastError();
 }
