@@ -262,27 +262,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16_t* __restrict
   if (g == 0) lse[((size_t)b * n_q + a) * seq + qglob] = m * scale + logf(lt);
 }
 
-// ---- backward, step 0: D_t = <dO_t, O_t> per query row and head ----------------------------------------
-__global__ void attn_bwd_delta(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, float* __restrict__ delta,
-                               int seq, int n_q, int batch) {
-  // one wave per (row, head): 64 lanes x 2 elements
-  const int lane = threadIdx.x & 63;
-  const size_t w = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  const size_t total = (size_t)batch * seq * n_q;
-  if (w >= total) return;
-  const size_t row = w / n_q;
-  const int a = w % n_q;
-  const size_t off = row * ((size_t)n_q * D) + (size_t)a * D + 2 * lane;
-  float s = (float)o[off] * (float)dout[off] + (float)o[off + 1] * (float)dout[off + 1];
-  s = wave_sum(s);
-  const int b = row / seq, t = row % seq;
-  if (lane == 0) delta[((size_t)b * n_q + a) * seq + t] = s;
-}
-
 // ---- backward, dQ: grid (n_q, batch, ceil(seq / 128)); 4 waves x 32 query rows; key blocks of 64 ---------
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
-                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16_t* __restrict__ dqkv, int seq, int n_q, int n_kv) {
+// Also produces D_t = <dO_t, O_t> per query row and head (each wave holds its 32 rows of dO in registers
+// anyway) and stores it for the dK/dV kernel, which runs after this one.
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+                                                           const bf16_t* __restrict__ dout, const float* __restrict__ lse,
+                                                           float* __restrict__ delta, bf16_t* __restrict__ dqkv, int seq,
+                                                           int n_q, int n_kv) {
   __shared__ __attribute__((aligned(16))) char smem[3 * 16384];
   char* sK = smem;
   char* sV = smem + 16384;
@@ -297,15 +283,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16_t* __restr
   const int qglob = q0 + 32 * wave + c32;
   const int qrow = min(qglob, seq - 1);
   const bf16_t* dop = dout + ((size_t)b * seq + qrow) * (n_q * D) + a * D;
+  const bf16_t* op = o + ((size_t)b * seq + qrow) * (n_q * D) + a * D;
   bf16x8_t qf[8], dof[8];
+  float dsum = 0.f;
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
     qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)qrow * ld + a * D + 16 * ks + 8 * g);
     dof[ks] = *reinterpret_cast<const bf16x8_t*>(dop + 16 * ks + 8 * g);
+    const bf16x8_t of = *reinterpret_cast<const bf16x8_t*>(op + 16 * ks + 8 * g);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dsum = fmaf((float)dof[ks][e], (float)of[e], dsum);
   }
   const float scale = rsqrtf((float)D), c = scale * LOG2E;
   const float Lc = lse[((size_t)b * n_q + a) * seq + qrow] * LOG2E;
-  const float Dq = delta[((size_t)b * n_q + a) * seq + qrow];
+  const float Dq = dsum + __shfl_xor(dsum, 32, 64);              // the two lanes of a row hold 64 columns each
+  if (g == 0 && qglob < seq) delta[((size_t)b * n_q + a) * seq + qglob] = Dq;
   f32x16_t acc[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -670,11 +662,8 @@ hipError_t launch_attn_fwd_mfma(const void* qkv, void* o, float* lse, int seq, i
 
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv, float* ws,
                                 int seq, int batch, int n_q, int n_kv, hipStream_t s) {
-  const size_t rows = (size_t)batch * seq * n_q;
-  hipLaunchKernelGGL(attn_bwd_delta, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, (const bf16_t*)o, (const bf16_t*)dout, ws, seq, n_q, batch);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 127) / 128), dim3(256), 0, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
+  hipError_t e;
+  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 127) / 128), dim3(256), 0, s, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   static bool attr_set = false;
