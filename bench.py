@@ -112,7 +112,7 @@ def build_schedule(cfg, budget=0):
     raise RuntimeError("no schedule fits the budget")
 
 
-def make_stage(cfg, events, budget, torch):
+def make_stage(cfg, events, budget, torch, duplex=False):
     from paper_2510_05186_amd import binding as B
     from paper_2510_05186_amd.stage import Stage
     _, _, peak, _ = B.plan(cfg, events, budget=0)
@@ -122,7 +122,7 @@ def make_stage(cfg, events, budget, torch):
         kb = B.query_sizes(cfg)[2]
         per_mb = sum(kb[k] for k in cfg.offload_kinds) * cfg.n_layers
         pool = per_mb * cfg.n_microbatches
-    st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=pool)
+    st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=pool, duplex=duplex)
     st.set_weights_device(device_weights(cfg, torch))
     for j in range(cfg.n_microbatches):
         x, dy = device_io(cfg, j, torch)
@@ -208,6 +208,8 @@ def main():
     ap.add_argument("--config", default="cfg2_llama_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offload-leg", action="store_true")
+    ap.add_argument("--duplex", action="store_true",
+                    help="reloads on a stream of their own instead of the single transfer channel (offload workloads)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a kernel of known traffic "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -239,7 +241,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    st, peak_plan = make_stage(cfg, events, budget, torch)
+    st, peak_plan = make_stage(cfg, events, budget, torch, args.duplex)
     wall, agg = time_steps(st, events, args.steps, args.warmup, torch)
     flops = schedule_flops(cfg) * cfg.n_microbatches
     ms_per_step = wall / args.steps * 1e3
@@ -280,7 +282,7 @@ def main():
         "roofline": roofline, "kernels": kernels,
     }
     if agg["off"]:
-        out["offload"] = {"bytes_per_step": agg["off"], "d2h_GBps": agg["off"] * args.steps / (agg["ms_ops"][3] * 1e-3) / 1e9,
+        out["offload"] = {"duplex": bool(args.duplex), "bytes_per_step": agg["off"], "d2h_GBps": agg["off"] * args.steps / (agg["ms_ops"][3] * 1e-3) / 1e9,
                           "h2d_GBps": agg["rel"] * args.steps / (agg["ms_ops"][5] * 1e-3) / 1e9}
     st.close()
     del st
@@ -291,7 +293,7 @@ def main():
         c3 = CFG.CFG3
         b3 = int(c3.budget_frac_of_peak * peak_plan)
         ev3, knobs3 = build_schedule(c3, b3)
-        st3, _ = make_stage(c3, ev3, b3, torch)
+        st3, _ = make_stage(c3, ev3, b3, torch, args.duplex)
         w3, a3 = time_steps(st3, ev3, 1, 1, torch, kernel_timing=False)
         comp_only = [e for e in ev3 if e[0] in ("F", "B", "W")]
         st3.close()
@@ -303,7 +305,7 @@ def main():
         del st3b
         torch.cuda.empty_cache()
         out["offload_leg"] = {
-            "workload": c3.name, "hbm_budget_bytes": b3, "peak_hbm_bytes": a3["peak"], "schedule_knobs": knobs3,
+            "workload": c3.name, "duplex": bool(args.duplex), "hbm_budget_bytes": b3, "peak_hbm_bytes": a3["peak"], "schedule_knobs": knobs3,
             "value": flops / w3 / 1e12, "unit": "TFLOP/s", "ms_per_step": w3 * 1e3,
             "ms_same_order_without_copies": w3b * 1e3, "overlap_cost": w3 / w3b,
             "bytes_offloaded": a3["off"], "bytes_reloaded": a3["rel"],

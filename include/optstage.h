@@ -17,11 +17,12 @@
  *  - Weights, gradient accumulators, stage inputs x[j], output gradients dy[j], stage outputs y[j] and
  *    input gradients dx[j] are caller-owned DEVICE buffers that must stay valid until
  *    optstage_synchronize() returns.
- *  - Compute ops are enqueued on desc.compute_stream, transfers on desc.copy_stream (both hipStream_t
- *    passed as void*).  Calls return after enqueueing; only optstage_synchronize() blocks.
- *  - The library orders its own two streams against each other and nothing else: work the caller has
+ *  - Compute ops are enqueued on desc.compute_stream, transfers on desc.copy_stream (reloads on
+ *    desc.reload_stream when one is given); all hipStream_t passed as void*.  Calls return after
+ *    enqueueing; only optstage_synchronize() blocks.
+ *  - The library orders its own streams against each other and nothing else: work the caller has
  *    queued on OTHER streams that produces a buffer the library will read (a weight, x[j], dy[j]) must
- *    have completed, or been made a dependency of both streams, before the call that reads it.
+ *    have completed, or been made a dependency of the library's streams, before the call that reads it.
  *  - A failing call changes no accounting state (validate, then commit).
  *  - A handle is not thread-safe; use one host thread per handle.
  */
@@ -84,6 +85,12 @@ typedef struct {
   void* workspace; uint64_t workspace_bytes;  /* DEVICE block for transients, >= optstage_query_sizes' figure */
   void* host_pool; uint64_t host_pool_bytes;  /* pinned HOST block for offloaded activations (may be null if no O) */
   void* compute_stream; void* copy_stream;    /* hipStream_t; at default priority */
+  void* reload_stream;                        /* hipStream_t for R events, or null: R shares copy_stream with O, the
+                                                 single serial transfer channel of the paper's model (Eq. 8-11).  A
+                                                 stream of its own lets reloads run while offloads are in flight (the
+                                                 host link is full duplex); ordering of an item's R after its O, of R
+                                                 after the compute ops listed before it and of B after its reloads is
+                                                 kept by events either way */
 } optstage_desc;
 
 typedef struct {

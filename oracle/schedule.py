@@ -230,12 +230,15 @@ class Timing:
     bubble: list = field(default_factory=list)   # per stage, 1 - busy / makespan_global
 
 
-def simulate(schedules, t_op, t_comm=0.0, t_copy=None):
+def simulate(schedules, t_op, t_comm=0.0, t_copy=None, duplex=False):
     """ASAP timing of p stages.
 
     schedules[i]  event list of stage i
     t_op[i]       {"F": T_F, "B": T_B, "W": T_W} for stage i
     t_copy        callable (stage, event) -> duration of that O or R event
+    duplex        False: one serial transfer channel per stage, as the paper models it (Eq. 8-11);
+                  True: offloads and reloads each have their own serial channel (a full-duplex host
+                  link), so Eq. 8-11 hold within a direction only
     """
     p = len(schedules)
     t_copy = t_copy or (lambda i, ev: 0.0)
@@ -243,7 +246,8 @@ def simulate(schedules, t_op, t_comm=0.0, t_copy=None):
     end = [[None] * len(s) for s in schedules]
     ptr = [0] * p
     compute_free = [0.0] * p        # end of the last compute op issued on stage i
-    copy_free = [0.0] * p           # end of the last transfer on stage i's channel
+    copy_free = [[0.0, 0.0] for _ in range(p)]   # end of the last transfer per channel: [offload, reload]
+    ch_r = 1 if duplex else 0
     gate = [0.0] * p                # compute ops listed from here on start no earlier (OWAIT)
     end_F = [dict() for _ in range(p)]
     end_B = [dict() for _ in range(p)]
@@ -275,19 +279,19 @@ def simulate(schedules, t_op, t_comm=0.0, t_copy=None):
                     elif op == "B":
                         end_B[i][j] = e
                 elif op == "O":
-                    s = max(copy_free[i], end_F[i][j])                         # after its F ended
+                    s = max(copy_free[i][0], end_F[i][j])                      # after its F ended
                     e = s + t_copy(i, ev)
-                    copy_free[i] = e
+                    copy_free[i][0] = e
                     for k in ev[3]:
                         end_O[i][(j, ev[2], k)] = e
                 elif op == "OWAIT":
                     s = e = None
                     gate[i] = max([gate[i]] + [end_O[i][(j, ev[2], k)] for k in ev[3]])   # Eq. 12
                 elif op == "R":
-                    s = max([copy_free[i], compute_free[i]] +                  # Eq. 14, single channel
+                    s = max([copy_free[i][ch_r], compute_free[i]] +            # Eq. 14; its channel is free
                             [end_O[i][(j, ev[2], k)] for k in ev[3]])
                     e = s + t_copy(i, ev)
-                    copy_free[i] = e
+                    copy_free[i][ch_r] = e
                     end_R[i][j] = max(end_R[i].get(j, 0.0), e)
                 else:
                     raise ValueError(op)

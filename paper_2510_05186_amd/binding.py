@@ -32,7 +32,8 @@ class Desc(C.Structure):
                 ("n_microbatches", C.c_uint32), ("norm_eps", C.c_float), ("rope_base", C.c_float),
                 ("hbm_budget_bytes", C.c_uint64), ("arena", C.c_void_p), ("arena_bytes", C.c_uint64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64), ("host_pool", C.c_void_p),
-                ("host_pool_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
+                ("host_pool_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
+                ("reload_stream", C.c_void_p)]
 
 
 class Event(C.Structure):
@@ -132,7 +133,7 @@ def make_events(events) -> "C.Array":
 
 
 def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_bytes=0, host_pool=0,
-              host_pool_bytes=0, compute_stream=0, copy_stream=0) -> Desc:
+              host_pool_bytes=0, compute_stream=0, copy_stream=0, reload_stream=0) -> Desc:
     d = Desc()
     d.struct_size = C.sizeof(Desc)
     d.family, d.dtype = cfg.family, cfg.dtype
@@ -145,6 +146,7 @@ def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_byte
     d.workspace, d.workspace_bytes = workspace, workspace_bytes
     d.host_pool, d.host_pool_bytes = host_pool, host_pool_bytes
     d.compute_stream, d.copy_stream = compute_stream, copy_stream
+    d.reload_stream = reload_stream
     return d
 
 

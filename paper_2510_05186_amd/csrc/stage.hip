@@ -159,12 +159,13 @@ struct optstage {
   WorkspaceLayout ws;
   uint64_t raw[NK];
   Logical lg;
-  hipStream_t cs, xs;   // compute, copy
+  hipStream_t cs, xs, rs;   // compute, copy (offloads), reloads (= xs unless the caller gave a stream of its own)
   std::vector<const void*> w;          // [layer][which]
   std::vector<float*> gw;              // [layer][which]
   std::vector<const void*> x_in, dy_out;
   std::vector<void*> y_out, dx_in;
   std::vector<hipEvent_t> ev_f, ev_o, ev_r, ev_pos;   // [mb], [mb][layer] x3
+  hipEvent_t last_r = nullptr;   // event of the most recent reload (separate reload stream only)
   std::vector<hipEvent_t> tpool;
   size_t tnext = 0;
   std::vector<TimedSpan> spans;
@@ -522,6 +523,9 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
     case OPTSTAGE_O: {
       // the offload starts after the F that produced the data has ended
       HIP_TRY(hipStreamWaitEvent(st->xs, st->ev_f[j], 0));
+      // a pinned slot released by a reload listed earlier may be handed to this offload: with a reload stream
+      // of its own that reload must have drained first (on a shared channel stream order already says so)
+      if (st->rs != st->xs && st->last_r) HIP_TRY(hipStreamWaitEvent(st->xs, st->last_r, 0));
       if ((rc = span_begin(st, ev.op, st->xs, &sp)) != OPTSTAGE_OK) return rc;
       for (int k = 0; k < NFK; ++k)
         if (ev.kind_mask & (1u << k)) {
@@ -541,16 +545,19 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
       // the reload starts after the compute ops listed before it have ended
       hipEvent_t pos = st->ev_pos[(size_t)j * L + ev.layer];
       HIP_TRY(hipEventRecord(pos, st->cs));
-      HIP_TRY(hipStreamWaitEvent(st->xs, pos, 0));
-      if ((rc = span_begin(st, ev.op, st->xs, &sp)) != OPTSTAGE_OK) return rc;
+      HIP_TRY(hipStreamWaitEvent(st->rs, pos, 0));
+      // ... and after the offload that filled the host slot (implied by stream order on a shared channel)
+      if (st->rs != st->xs) HIP_TRY(hipStreamWaitEvent(st->rs, st->ev_o[(size_t)j * L + ev.layer], 0));
+      if ((rc = span_begin(st, ev.op, st->rs, &sp)) != OPTSTAGE_OK) return rc;
       for (int k = 0; k < NFK; ++k)
         if (ev.kind_mask & (1u << k)) {
           size_t i = (size_t)ev.layer * NK + k;
-          HIP_TRY(hipMemcpyAsync(st->arena() + ob.dev[i], (char*)st->desc.host_pool + ob.host[i], st->raw[k], hipMemcpyHostToDevice, st->xs));
+          HIP_TRY(hipMemcpyAsync(st->arena() + ob.dev[i], (char*)st->desc.host_pool + ob.host[i], st->raw[k], hipMemcpyHostToDevice, st->rs));
           st->stats.bytes_reloaded += st->raw[k];
         }
-      if ((rc = span_end(st, st->xs, sp)) != OPTSTAGE_OK) return rc;
-      HIP_TRY(hipEventRecord(st->ev_r[(size_t)j * L + ev.layer], st->xs));
+      if ((rc = span_end(st, st->rs, sp)) != OPTSTAGE_OK) return rc;
+      HIP_TRY(hipEventRecord(st->ev_r[(size_t)j * L + ev.layer], st->rs));
+      st->last_r = st->ev_r[(size_t)j * L + ev.layer];
       break;
     }
   }
@@ -656,6 +663,7 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
   }
   st->cs = (hipStream_t)desc->compute_stream;
   st->xs = (hipStream_t)desc->copy_stream;
+  st->rs = desc->reload_stream ? (hipStream_t)desc->reload_stream : st->xs;
   const size_t m = desc->n_microbatches, L = s.L;
   st->w.assign(L * OPTSTAGE_N_WEIGHTS, nullptr);
   st->gw.assign(L * OPTSTAGE_N_WEIGHTS, nullptr);
@@ -794,6 +802,7 @@ optstage_status optstage_synchronize(optstage_t* st) {
   if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
   HIP_TRY(hipStreamSynchronize(st->cs));
   HIP_TRY(hipStreamSynchronize(st->xs));
+  if (st->rs != st->xs) HIP_TRY(hipStreamSynchronize(st->rs));
   for (const TimedSpan& sp : st->spans) {
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
@@ -809,6 +818,7 @@ optstage_status optstage_reset(optstage_t* st) {
   if (!st->spans.empty()) return fail(OPTSTAGE_E_STATE, "reset with work in flight: call optstage_synchronize first");
   reset_logical(st);
   memset(&st->stats, 0, sizeof st->stats);
+  st->last_r = nullptr;
   return OPTSTAGE_OK;
 }
 
@@ -833,6 +843,7 @@ optstage_status optstage_debug_checksum(optstage_t* st, uint32_t mb, uint32_t la
   const BufRec& b = st->lg.buf(mb, layer, kind);
   HIP_TRY(hipStreamSynchronize(st->cs));
   HIP_TRY(hipStreamSynchronize(st->xs));
+  if (st->rs != st->xs) HIP_TRY(hipStreamSynchronize(st->rs));
   if (where == 0) {
     if (b.state != B_DEV && b.state != B_OFFLOADING && b.state != B_RELOADED) return fail(OPTSTAGE_E_STATE, "buffer has no device copy");
     uint64_t* dev = (uint64_t*)(st->wsp() + st->ws.csum);

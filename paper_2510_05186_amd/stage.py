@@ -11,13 +11,13 @@ import torch
 from . import binding as B
 
 _TORCH_DT = {0: torch.float32, 1: torch.bfloat16}
-_STREAMS = []   # one (compute, copy) pair per process: every Stage shares it, so the two streams keep the
-                # distinct hardware queues they were given when created and copies overlap compute
+_STREAMS = []   # one (compute, offload, reload) triple per process: every Stage shares it, so the streams keep
+                # the distinct hardware queues they were given when created and copies overlap compute
 
 
 def _streams():
     if not _STREAMS:
-        _STREAMS.extend([torch.cuda.Stream(), torch.cuda.Stream()])
+        _STREAMS.extend([torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()])
     return _STREAMS
 
 
@@ -32,7 +32,9 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 
 
 class Stage:
-    def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0):
+    def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0,
+                 duplex: bool = False):
+        """duplex: reloads get a stream of their own instead of sharing the offloads' (single channel)."""
         if not torch.cuda.is_available():
             raise RuntimeError("optstage needs a GPU: there is no CPU path")
         self.cfg = cfg
@@ -44,13 +46,14 @@ class Stage:
         self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         self.host_pool = torch.empty(host_pool_bytes, dtype=torch.uint8, pin_memory=True) if host_pool_bytes else None
-        self.compute_stream, self.copy_stream = _streams()
+        self.compute_stream, self.copy_stream, self.reload_stream = _streams()
         self.desc = B.make_desc(
             cfg, budget=budget, arena=self.arena.data_ptr(), arena_bytes=arena_bytes,
             workspace=self.workspace.data_ptr(), workspace_bytes=ws_bytes,
             host_pool=self.host_pool.data_ptr() if self.host_pool is not None else 0,
             host_pool_bytes=host_pool_bytes, compute_stream=self.compute_stream.cuda_stream,
-            copy_stream=self.copy_stream.cuda_stream)
+            copy_stream=self.copy_stream.cuda_stream,
+            reload_stream=self.reload_stream.cuda_stream if duplex else 0)
         h = C.c_void_p()
         B.check(self.lib.optstage_create(C.byref(self.desc), C.byref(h)))
         self.h = h
@@ -124,6 +127,7 @@ class Stage:
         cur = torch.cuda.current_stream()
         self.compute_stream.wait_stream(cur)
         self.copy_stream.wait_stream(cur)
+        self.reload_stream.wait_stream(cur)
 
     # ---- execution
     def validate(self, events):

@@ -160,6 +160,91 @@ def test_offload_under_budget_is_bit_exact_and_schedule_independent():
     ref_st.close()
 
 
+def test_duplex_reload_stream_changes_no_bit():
+    """Reloads on a stream of their own (full-duplex host link) instead of the single transfer channel of the
+    paper's model (Eq. 8-11): same bytes, same accounting, bitwise the same results."""
+    cfg = SMALL2
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    comp = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches, cap_of_stage=lambda i: 3)[cfg.stage_index]
+    events = G.add_offload(comp, cfg.n_layers, ("X_IN", "QKV", "X_MID"), min_gap=1, lead=2, wait_delay=2)
+    assert sum(1 for e in events if e[0] == "O") >= 4
+    S.check_order(events, cfg.n_microbatches, cfg.n_layers)
+    # pool smaller than the total offloaded bytes: pinned slots are reused while other transfers are in flight
+    per_mb = sum(t[k] for k in ("X_IN", "QKV", "X_MID")) * cfg.n_layers
+    runs = []
+    for duplex in (False, True):
+        st = Stage(cfg, host_pool_bytes=3 * per_mb, duplex=duplex)
+        st.set_weights(ws)
+        for j in range(cfg.n_microbatches):
+            st.bind(j, T.stage_input(cfg, j), T.output_grad(cfg, j))
+        for _ in range(2):                      # twice: the second pass reuses every slot again
+            st.reset()
+            st.zero_grads()
+            st.run(events)
+            st.synchronize()
+        check_accounting(cfg, st, events)
+        s = st.stats()
+        assert s.bytes_offloaded == s.bytes_reloaded > 0
+        runs.append(st)
+    a, b = runs
+    for j in range(cfg.n_microbatches):
+        assert torch.equal(a.y[j], b.y[j]) and torch.equal(a.dx[j], b.dx[j])
+    for l in range(cfg.n_layers):
+        for name in a.grads[l]:
+            assert torch.equal(a.grads[l][name], b.grads[l][name]), (l, name)
+    compare(cfg, b, oracle_run(cfg, ws))
+    a.close()
+    b.close()
+
+
+def test_online_schedule_swap_on_one_handle():
+    """A different event list every iteration on the same handle (no re-creation): results stay bitwise the
+    same, accounting follows the list that ran (the paper swaps in better schedules while training runs,
+    Sec. 4.3, online scheduling)."""
+    cfg = SMALL2
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    lists = [
+        G.one_f_one_b(cfg.n_stages, cfg.n_microbatches, cfg.stage_index),
+        G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches)[cfg.stage_index],
+        G.add_offload(G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches, cap_of_stage=lambda i: 2)[cfg.stage_index],
+                      cfg.n_layers, ("X_IN", "QKV", "X_MID"), min_gap=1, lead=1),
+    ]
+    assert any(e[0] == "O" for e in lists[2])
+    pool = sum(t[k] for k in ("X_IN", "QKV", "X_MID")) * cfg.n_layers * cfg.n_microbatches
+    st = Stage(cfg, host_pool_bytes=pool)
+    st.set_weights(ws)
+    for j in range(cfg.n_microbatches):
+        st.bind(j, T.stage_input(cfg, j), T.output_grad(cfg, j))
+    ref = None
+    peaks = []
+    for it, which in enumerate((0, 1, 2, 0, 2, 1)):
+        events = lists[which]
+        S.check_order(events, cfg.n_microbatches, cfg.n_layers)
+        st.reset()
+        st.zero_grads()
+        st.run(events)
+        st.synchronize()
+        check_accounting(cfg, st, events)
+        peaks.append(st.stats().peak_bytes)
+        snap = ([st.y[j].clone() for j in range(cfg.n_microbatches)], [st.dx[j].clone() for j in range(cfg.n_microbatches)],
+                [{k: g.clone() for k, g in gl.items()} for gl in st.grads])
+        if ref is None:
+            ref = snap
+            compare(cfg, st, oracle_run(cfg, ws))
+        else:
+            for j in range(cfg.n_microbatches):
+                assert torch.equal(snap[0][j], ref[0][j]) and torch.equal(snap[1][j], ref[1][j]), (it, j)
+            for l in range(cfg.n_layers):
+                for name in snap[2][l]:
+                    assert torch.equal(snap[2][l][name], ref[2][l][name]), (it, l, name)
+    # the three lists have different peaks, and a list's peak is the same whenever it runs
+    assert peaks[0] == peaks[3] and peaks[1] == peaks[5] and peaks[2] == peaks[4]
+    assert len({peaks[0], peaks[1], peaks[2]}) >= 2
+    st.close()
+
+
 def test_failing_calls_change_nothing():
     cfg = SMALL2
     ws = T.stage_weights(cfg)

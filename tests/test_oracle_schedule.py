@@ -13,13 +13,14 @@ L = 2
 
 
 # ------------------------------------------------------------------ independent re-implementations
-def tick_sim(lists, t_op, t_comm, t_copy):
-    """Integer time-stepped polling simulator (nothing shared with S.simulate)."""
+def tick_sim(lists, t_op, t_comm, t_copy, duplex=False):
+    """Integer time-stepped polling simulator (nothing shared with S.simulate).  duplex: offloads and
+    reloads are polled as two independent serial queues instead of one."""
     p = len(lists)
     fin = [dict() for _ in range(p)]          # event index -> finish tick
     begun = [dict() for _ in range(p)]
     busy_c = [0] * p
-    busy_x = [0] * p
+    busy_x = [[0, 0] for _ in range(p)]
     t = 0
     total = sum(len(l) for l in lists)
 
@@ -65,8 +66,9 @@ def tick_sim(lists, t_op, t_comm, t_copy):
                     begun[i][n] = t
                     fin[i][n] = t + t_op[i][op]
                     busy_c[i] = fin[i][n]
-            xfer = [n for n, ev in enumerate(lists[i]) if ev[0] in ("O", "R") and n not in begun[i]]
-            if xfer and busy_x[i] <= t:
+            for kinds, lane in ((("O",), 0), (("R",), 1)) if duplex else ((("O", "R"), 0),):
+              xfer = [n for n, ev in enumerate(lists[i]) if ev[0] in kinds and n not in begun[i]]
+              if xfer and busy_x[i][lane] <= t:
                 n = xfer[0]
                 ev = lists[i][n]
                 ok = True
@@ -81,7 +83,7 @@ def tick_sim(lists, t_op, t_comm, t_copy):
                 if ok:
                     begun[i][n] = t
                     fin[i][n] = t + t_copy
-                    busy_x[i] = fin[i][n]
+                    busy_x[i][lane] = fin[i][n]
         t += 1
         assert t < 400, "tick simulator stuck"
     comp_ends = [fin[i][n] for i in range(p) for n, ev in enumerate(lists[i]) if ev[0] in "FBW"]
@@ -126,8 +128,8 @@ def liveset_peak(events, n_layers, table):
     return peak
 
 
-def check_constraints(lists, tm, t_op, t_comm, t_copy):
-    """Every paper constraint, checked directly on a timed schedule."""
+def check_constraints(lists, tm, t_op, t_comm, t_copy, duplex=False):
+    """Every paper constraint, checked directly on a timed schedule (duplex: Eq. 8-11 per direction)."""
     eps = 1e-9
     p = len(lists)
     for i in range(p):
@@ -138,6 +140,8 @@ def check_constraints(lists, tm, t_op, t_comm, t_copy):
         for a, b in itertools.combinations(comp, 2):                 # Eq. 5: no overlap
             assert en[a] <= st[b] + eps or en[b] <= st[a] + eps
         for a, b in itertools.combinations(xfer, 2):                 # Eq. 8-11: one transfer at a time
+            if duplex and ev[a][0] != ev[b][0]:
+                continue
             assert en[a] <= st[b] + eps or en[b] <= st[a] + eps
         idx = {(e[0], e[1]): n for n, e in enumerate(ev) if e[0] in "FBW"}
         for (op, j), n in idx.items():
@@ -327,6 +331,47 @@ def test_bruteforce_with_offload_equal_times_capacity_three():
                 best["b"] = min(best.get("b", 10**9), tm.makespan_global)
             count += 1
     assert count > 20 and best["a"] == best["b"]
+
+
+def two_item_variants(order, m):
+    """Offload micro-batch 0 and micro-batch 1 (layer 0, X_IN): every placement in which a reload of one may
+    be listed while the offload of the other is still in flight."""
+    out = []
+    for v0 in offload_variants(order, 0):
+        for v1 in offload_variants(v0, 1):
+            out.append(v1)
+    return out
+
+
+def test_bruteforce_duplex_channels():
+    # two offloaded items, copy time longer than an op: with one channel the second item's offload can delay
+    # the first item's reload; with two channels it cannot.  Both simulators must agree in both modes, every
+    # timing must satisfy the constraints (Eq. 8-11 per direction in duplex mode), duplex is never slower,
+    # and it is strictly faster for at least one enumerated schedule.
+    m = 3
+    t_op = [{"F": 1, "B": 1, "W": 1}] * 2
+    l1 = G.one_f_one_b(2, m, 1)
+    faster = 0
+    count = 0
+    for l0 in all_orders(m)[::7]:
+        for v in two_item_variants(l0, m)[::5]:
+            try:
+                S.check_order(v, m, L)
+                one = S.simulate([v, l1], t_op, t_comm=0, t_copy=lambda i, ev: 2)
+                two = S.simulate([v, l1], t_op, t_comm=0, t_copy=lambda i, ev: 2, duplex=True)
+            except S.ScheduleError:
+                continue
+            for tm, dup in ((one, False), (two, True)):
+                span, begun, fin = tick_sim([v, l1], t_op, 0, 2, duplex=dup)
+                assert span == tm.makespan_global, (v, dup, span, tm.makespan_global)
+                for n, ev in enumerate(v):
+                    if ev[0] != "OWAIT":
+                        assert begun[0][n] == tm.start[0][n], (v, dup, n)
+                check_constraints([v, l1], tm, t_op, 0, 2, duplex=dup)
+            assert two.makespan_global <= one.makespan_global
+            faster += two.makespan_global < one.makespan_global
+            count += 1
+    assert count > 30 and faster > 0, (count, faster)
 
 
 def test_offload_lowers_peak_monotonically():
