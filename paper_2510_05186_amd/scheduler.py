@@ -1,0 +1,487 @@
+"""Host-side schedule generation for the stage executor.
+
+Two generators of per-stage event lists (the input of optstage_run):
+
+* ``adaoffload``  the dense-fill initial schedule of the paper's appendix "AdaOffload" (Alg. 1): as many
+  forward ops before the first backward op of a stage as its start estimate, a tolerance and the memory
+  capacity allow, every forward activation offloaded, the rest of the list by PipeOffload-style rules
+  (backward as soon as it can run, weight gradients in the gaps, reloads one op ahead of their consumer).
+* ``milp_schedule``  the mixed-integer program of the paper's appendix "Mathematical Models" (Eq. 2-17) for
+  small instances, solved with HiGHS through scipy.optimize.milp, with the fixed micro-batch order, the
+  one-direction precedence variables and the triangle cuts of Sec. 4.1.
+
+Both work on the paper's abstract instance (p stages, m identical micro-batches, one offloadable item per
+forward op) and return lists in the executor's vocabulary: ("F"|"B"|"W", j) and ("O"|"OWAIT"|"R", j, layer,
+kinds).  List order carries the paper's precedence binaries: an op listed after OWAIT(x) is credited x's
+memory (M = 1, Eq. 12), an op listed after R(x) is charged it (N = 1, Eq. 13) and R(x) starts after the ops
+listed before it (N = 0, Eq. 14).
+
+Readings where the appendix is silent or inconsistent (the same ones the executor follows): Eq. 5 holds for
+every pair of distinct ops of a stage; Eq. 12 bounds the start of the credited op (E - T, not E - T_comm); an
+offload starts after its forward op ended, its reload after the offload ended, and the backward op of the
+same micro-batch after the reload ended; only forward activations are offloaded; offloads, like reloads,
+run in micro-batch order (identical micro-batches, forward and backward ops already in that order), so K and
+L are constants and only H is decided.
+"""
+from __future__ import annotations
+
+import itertools
+from dataclasses import dataclass, field
+
+import numpy as np
+
+OPS = ("F", "B", "W")
+
+
+@dataclass
+class Instance:
+    """The paper's parameters for one pipeline (identical micro-batches)."""
+    p: int                       # stages
+    m: int                       # micro-batches
+    t_op: list                   # per stage {"F": T_F, "B": T_B, "W": T_W}
+    t_comm: float = 0.0
+    t_off: list | None = None    # per stage: duration of one offload (= one reload), T_offload
+    delta: list | None = None    # per stage {"F": Delta_F, "B": Delta_B, "W": Delta_W} (Eq. 7)
+    gamma: list | None = None    # per stage: bytes of the offloadable item, Gamma
+    own_peak: list | None = None  # per stage {"F","B","W"}: most bytes an op holds beyond the level before it
+                                  # while it runs.  None = Eq. 7 as printed: the op's own term is its net Delta,
+                                  # which credits the release of a B or W op before it has run; a device holds
+                                  # those bytes until the op ends (own term 0 for W, B's transient peak for B)
+    limit: list | None = None    # per stage: M_limit (None entry = unlimited)
+    offload_stages: tuple = ()   # stages that may offload
+    offload_mbs: tuple | None = None   # micro-batches that may offload (None = all)
+    item: tuple = (0, ("X_IN",))  # (layer, kinds) the O / OWAIT / R events name
+
+    def __post_init__(self):
+        self.t_off = self.t_off or [0.0] * self.p
+        self.delta = self.delta or [{"F": 0, "B": 0, "W": 0}] * self.p
+        self.gamma = self.gamma or [0] * self.p
+        self.limit = self.limit or [None] * self.p
+
+
+@dataclass
+class Solution:
+    lists: list                  # per stage event list
+    makespan: float              # Eq. 17
+    start: dict = field(default_factory=dict)    # (i, j, c) -> start time
+    offloaded: dict = field(default_factory=dict)  # (i, j) -> bool
+    status: str = ""
+
+
+# ----------------------------------------------------------------------------------------------- MILP
+
+def _fixed_precedence(u, v):
+    """Order of two ops of one stage fixed by the model (Eq. 6, fixed micro-batch order and what follows
+    from them by transitivity): +1 u before v, -1 v before u, 0 free."""
+    (ju, cu), (jv, cv) = u, v
+    ru, rv = OPS.index(cu), OPS.index(cv)
+    if ju <= jv and ru <= rv:
+        return 1
+    if jv <= ju and rv <= ru:
+        return -1
+    return 0
+
+
+def milp_schedule(inst: Instance, time_limit: float = 60.0, cutoff: float | None = None,
+                  triangle_cuts: bool = True, strict_eq13: bool = True) -> Solution:
+    """Solves Eq. 2-17 to optimality (small instances).  cutoff: a known makespan (e.g. AdaOffload's), added
+    as C <= cutoff; scipy's interface takes no starting point, so this is how an initial solution helps.
+    strict_eq13: Eq. 13 as printed makes an op that is charged a reload's memory start no earlier than that
+    reload; the stage executor charges by list position and lets the compute stream run on while the reload
+    waits for the transfer channel, which is the model without Eq. 13 (False).  A tiny secondary cost keeps N
+    at 0 wherever Eq. 14 does not force it, so that the extracted list charges no op needlessly."""
+    from scipy.optimize import Bounds, LinearConstraint, milp
+    from scipy.sparse import lil_matrix
+
+    p, m = inst.p, inst.m
+    ops = [(j, c) for j in range(m) for c in OPS]
+    names = []
+    lo, hi, integ = [], [], []
+
+    def var(name, lb, ub, integer):
+        names.append(name)
+        lo.append(lb)
+        hi.append(ub)
+        integ.append(1 if integer else 0)
+        return len(names) - 1
+
+    big = sum(sum(inst.t_op[i].values()) for i in range(p)) * m + (2 * p) * inst.t_comm + \
+        2 * m * sum(inst.t_off[i] for i in range(p)) + 1.0
+    C = var("C", 0, big, False)
+    E = {(i, u): var(f"E{i}{u}", 0, big, False) for i in range(p) for u in ops}
+    P = {}
+    for i in range(p):
+        for u, v in itertools.combinations(ops, 2):
+            if _fixed_precedence(u, v) == 0:
+                P[(i, u, v)] = var(f"P{i}{u}{v}", 0, 1, True)
+    off = [i for i in range(p) if i in inst.offload_stages and inst.gamma[i] > 0]
+    Wv, Ov, Rv, Hv, Mv, Nv = {}, {}, {}, {}, {}, {}
+    for i in off:
+        for j in range(m):
+            may = inst.offload_mbs is None or j in inst.offload_mbs
+            Wv[(i, j)] = var(f"w{i},{j}", 0, 1 if may else 0, True)
+            Ov[(i, j)] = var(f"O{i},{j}", 0, big, False)
+            Rv[(i, j)] = var(f"R{i},{j}", 0, big, False)
+            for v in ops:
+                Mv[(i, j, v)] = var(f"M{i},{j}{v}", 0, 1, True)
+                Nv[(i, j, v)] = var(f"N{i},{j}{v}", 0, 1, True)
+        for j, j2 in itertools.permutations(range(m), 2):
+            Hv[(i, j, j2)] = var(f"H{i},{j},{j2}", 0, 1, True)      # offload j starts before reload j2
+
+    rows = []           # (coefficients {var: a}, lb, ub)
+
+    def ge(coef, rhs):
+        rows.append((coef, rhs, np.inf))
+
+    def le(coef, rhs):
+        rows.append((coef, -np.inf, rhs))
+
+    def before(i, u, v):
+        """Linear expression (coefficients, constant) of the 0/1 value 'u before v'."""
+        f = _fixed_precedence(u, v)
+        if f:
+            return {}, 1.0 if f > 0 else 0.0
+        if (i, u, v) in P:
+            return {P[(i, u, v)]: 1.0}, 0.0
+        return {P[(i, v, u)]: -1.0}, 1.0
+
+    for i in range(p):
+        T = inst.t_op[i]
+        for u in ops:
+            ge({E[(i, u)]: 1.0}, T[u[1]])                                   # starts at or after 0
+        ge({E[(0, (0, "F"))]: -1.0}, -inst.t_op[0]["F"])                    # first op starts at 0
+        for j in range(m):
+            if i > 0:                                                        # Eq. 3
+                ge({E[(i, (j, "F"))]: 1.0, E[(i - 1, (j, "F"))]: -1.0}, inst.t_comm + T["F"])
+            if i < p - 1:                                                    # Eq. 4
+                ge({E[(i, (j, "B"))]: 1.0, E[(i + 1, (j, "B"))]: -1.0}, inst.t_comm + T["B"])
+            ge({C: 1.0, E[(i, (j, "W"))]: -1.0}, 0.0)                        # Eq. 17 with the first start at 0
+        for u, v in itertools.combinations(ops, 2):                          # Eq. 5 for every pair
+            coef, const = before(i, u, v)
+            # u before v: E_v >= E_u + T_v - big (1 - b)
+            c1 = {E[(i, v)]: 1.0, E[(i, u)]: -1.0}
+            for k, a in coef.items():
+                c1[k] = c1.get(k, 0.0) - big * a
+            ge(c1, T[v[1]] - big + big * const)
+            # v before u: E_u >= E_v + T_u - big b
+            c2 = {E[(i, u)]: 1.0, E[(i, v)]: -1.0}
+            for k, a in coef.items():
+                c2[k] = c2.get(k, 0.0) + big * a
+            ge(c2, T[u[1]] - big * const)
+        if triangle_cuts:                                                     # Sec. 4.1, triangle inequality cuts
+            for a, b, c in itertools.permutations(ops, 3):
+                ca, ka = before(i, a, b)
+                cb, kb = before(i, b, c)
+                cc, kc = before(i, a, c)
+                if not (ca or cb or cc):
+                    continue
+                coef = dict(cc)
+                for k, x in ca.items():
+                    coef[k] = coef.get(k, 0.0) - x
+                for k, x in cb.items():
+                    coef[k] = coef.get(k, 0.0) - x
+                ge(coef, ka + kb - 1.0 - kc)
+        # Eq. 7 for every op of the stage
+        if inst.limit[i] is not None:
+            D, G = inst.delta[i], inst.gamma[i]
+            for v in ops:
+                coef, const = {}, float(D[v[1]] if inst.own_peak is None else inst.own_peak[i][v[1]])
+                for u in ops:
+                    if u == v:
+                        continue
+                    cu, ku = before(i, u, v)
+                    const += D[u[1]] * ku
+                    for k, a in cu.items():
+                        coef[k] = coef.get(k, 0.0) + D[u[1]] * a
+                if i in off:
+                    for j in range(m):
+                        coef[Mv[(i, j, v)]] = coef.get(Mv[(i, j, v)], 0.0) - G
+                        coef[Nv[(i, j, v)]] = coef.get(Nv[(i, j, v)], 0.0) + G
+                le(coef, inst.limit[i] - const)
+    for i in off:
+        T, to = inst.t_op[i], inst.t_off[i]
+        for j in range(m):
+            w, o, r = Wv[(i, j)], Ov[(i, j)], Rv[(i, j)]
+            ge({o: 1.0, E[(i, (j, "F"))]: -1.0, w: -big}, -big)               # offload after its forward op
+            ge({r: 1.0, o: -1.0, w: -big}, to - big)                          # reload after its offload
+            ge({E[(i, (j, "B"))]: 1.0, r: -1.0, w: -big}, T["B"] + to - big)  # consumer after the reload
+            for j2 in range(j + 1, m):                                        # Eq. 8, 9 with K, L in micro-batch order
+                w2 = Wv[(i, j2)]
+                ge({Ov[(i, j2)]: 1.0, o: -1.0, w: -big, w2: -big}, to - 2 * big)
+                ge({Rv[(i, j2)]: 1.0, r: -1.0, w: -big, w2: -big}, to - 2 * big)
+            for j2 in range(m):
+                if j2 == j:
+                    continue
+                h, w2 = Hv[(i, j, j2)], Wv[(i, j2)]
+                ge({Rv[(i, j2)]: 1.0, o: -1.0, h: -big, w: -big, w2: -big}, to - 3 * big)   # Eq. 10
+                ge({o: 1.0, Rv[(i, j2)]: -1.0, h: big, w: -big, w2: -big}, to - 2 * big)    # Eq. 11
+            for v in ops:
+                M_, N_ = Mv[(i, j, v)], Nv[(i, j, v)]
+                le({M_: 1.0, w: -1.0}, 0.0)                                   # Eq. 15
+                le({N_: 1.0, w: -1.0}, 0.0)
+                st = {E[(i, v)]: 1.0}
+                ge({**st, o: -1.0, M_: -big}, T[v[1]] + to - big)             # Eq. 12 (start of v)
+                if strict_eq13:
+                    ge({**st, r: -1.0, N_: -big}, T[v[1]] - big)              # Eq. 13
+                ge({r: 1.0, E[(i, v)]: -1.0, N_: big, w: -big}, -big)         # Eq. 14
+    if cutoff is not None:
+        le({C: 1.0}, cutoff + 1e-6)
+
+    A = lil_matrix((len(rows), len(names)))
+    lb = np.empty(len(rows))
+    ub = np.empty(len(rows))
+    for r, (coef, a, b) in enumerate(rows):
+        for k, x in coef.items():
+            A[r, k] = x
+        lb[r], ub[r] = a, b
+    cost = np.zeros(len(names))
+    cost[C] = 1.0
+    for k in Nv.values():
+        cost[k] = 1e-7
+    res = milp(cost, constraints=LinearConstraint(A.tocsr(), lb, ub), integrality=np.array(integ),
+               bounds=Bounds(np.array(lo, dtype=float), np.array(hi, dtype=float)),
+               options={"time_limit": time_limit, "mip_rel_gap": 0.0})
+    if res.x is None:
+        return Solution(lists=[], makespan=float("inf"), status=res.message)
+    x = res.x
+    sol = Solution(lists=[], makespan=float(x[C]), status=res.message)
+    for i in range(p):
+        for u in ops:
+            sol.start[(i, u[0], u[1])] = float(x[E[(i, u)]] - inst.t_op[i][u[1]])
+        for j in range(m):
+            sol.offloaded[(i, j)] = bool(i in off and x[Wv[(i, j)]] > 0.5)
+    for i in range(p):
+        st = {u: float(x[E[(i, u)]] - inst.t_op[i][u[1]]) for u in ops}
+        items = {}
+        for j in range(m):
+            if sol.offloaded[(i, j)]:
+                items[j] = (float(x[Ov[(i, j)]]), float(x[Rv[(i, j)]]),
+                            [u for u in ops if x[Mv[(i, j, u)]] > 0.5], [u for u in ops if x[Nv[(i, j, u)]] > 0.5])
+        sol.lists.append(_list_from_times(st, items, inst.item))
+    sol.makespan = float(x[C])
+    return sol
+
+
+def _list_from_times(start, items, item):
+    """Event list of one stage from the solver's values.  Compute ops by start time; O at its start time
+    (hence after its forward op); OWAIT just before the first op credited with the memory (M = 1); R at its
+    start time but never after an op charged with it (N = 1), never before its OWAIT."""
+    layer, kinds = item
+    kinds = tuple(kinds)
+    rank = {"OWAIT": 0, "R": 1, "F": 2, "B": 2, "W": 2, "O": 3}
+    ev = [(t, rank[u[1]], OPS.index(u[1]), u[0], (u[1], u[0])) for u, t in start.items()]
+    for j, (o_t, r_t, cred, chg) in items.items():
+        ev.append((o_t, rank["O"], 0, j, ("O", j, layer, kinds)))
+        r_key = min([r_t] + [start[u] for u in chg])
+        w_key = min([r_key] + [start[u] for u in cred])
+        ev.append((w_key, rank["OWAIT"], 0, j, ("OWAIT", j, layer, kinds)))
+        ev.append((r_key, rank["R"], 0, j, ("R", j, layer, kinds)))
+    ev.sort(key=lambda e: (round(e[0], 9), e[1], e[2], e[3]))
+    return [e[4] for e in ev]
+
+
+# ----------------------------------------------------------------------------------------- AdaOffload
+
+def est_start_first_backward(inst: Instance):
+    """EstStart(B_{s,0}) of Alg. 1, step 1 (the algorithm only names it): the time the first micro-batch
+    needs to run forward through every stage and backward down to stage s, with nothing else in its way."""
+    p = inst.p
+    t = 0.0
+    for s in range(p):
+        t += inst.t_op[s]["F"] + (inst.t_comm if s < p - 1 else 0.0)
+    est = [0.0] * p
+    for s in reversed(range(p)):
+        est[s] = t
+        t += inst.t_op[s]["B"] + inst.t_comm
+    return est
+
+
+def adaoffload(inst: Instance, tolerance: float = 0.0, lead: int = 1) -> Solution:
+    """Alg. 1, in bytes: a forward activation costs Delta_F while on the device and Delta_F - Gamma once its
+    offload has ended (Gamma < Delta_F when only some tensor kinds are offloaded); a stage without a limit
+    holds everything.
+      Step 1  EstStart(B_{s,0}) per stage (est_start_first_backward).
+      Step 2  forward ops are placed back to back, each followed by its offload, until the next one would end
+              after EstStart + tolerance or would not fit even with the offloads that have completed by then.
+              That count is the stage's fill; when the same fill fits without offloading, nothing is offloaded.
+      Step 3  PipeOffload-style rules for the rest, built by list scheduling over all stages: a backward op
+              runs as soon as its inputs are there, else a forward op if it fits (Gamma is kept free for the
+              reload of the next backward op), else a weight-gradient op; a weight-gradient op that ends before
+              anything else could start goes first.  Reloads are listed `lead` compute ops ahead of their
+              consumer, the credit of an offload (OWAIT) as late as possible: right before the op that needs
+              the bytes.
+    Returns the lists and this construction's own makespan estimate (it ignores the reloads' share of the
+    transfer channel; time the lists with a simulator)."""
+    p, m = inst.p, inst.m
+    est = est_start_first_backward(inst)
+    layer, kinds = inst.item
+    kinds = tuple(kinds)
+    dF = [inst.delta[s]["F"] for s in range(p)]
+    can_off = [s in inst.offload_stages and inst.gamma[s] > 0 and inst.limit[s] is not None for s in range(p)]
+
+    def fits(s, n_on_device, n_away, offloading):
+        if inst.limit[s] is None:
+            return True
+        reserve = inst.gamma[s] if offloading else 0
+        return n_on_device * dF[s] + n_away * (dF[s] - inst.gamma[s]) + dF[s] + reserve <= inst.limit[s]
+
+    def fill_of(s, offloading):
+        T, to = inst.t_op[s], inst.t_off[s]
+        t = sum(inst.t_op[k]["F"] + inst.t_comm for k in range(s))      # arrival of micro-batch 0
+        n, chan, freed_at = 0, 0.0, []
+        while n < m:
+            if n >= 1 and t + T["F"] > est[s] + tolerance:
+                break
+            away = sum(1 for f in freed_at if f <= t) if offloading else 0
+            if not fits(s, n - away, away, offloading):
+                break
+            t += T["F"]
+            n += 1
+            if offloading:
+                chan = max(chan, t) + to
+                freed_at.append(chan)
+        return max(1, n)
+
+    fill, offloading = [], []
+    for s in range(p):
+        plain = fill_of(s, False)
+        dense = fill_of(s, True) if can_off[s] else plain
+        offloading.append(dense > plain)
+        fill.append(max(plain, dense))
+
+    # ---- compute order of every stage by list scheduling (times are this construction's own estimate)
+    end = {}
+    t_free = [0.0] * p
+    chan = [0.0] * p
+    nf, nb, nw = [0] * p, [0] * p, [0] * p
+    o_end = [dict() for _ in range(p)]
+    order = [[] for _ in range(p)]
+
+    def room_at(s, t):
+        """Earliest time >= t at which one more forward activation fits on stage s (None: not before another
+        op of the stage finishes): an offloaded activation shrinks when its offload ends, except the item of
+        the next backward op, which is kept or already reloaded."""
+        live = list(range(nw[s], nf[s]))
+        if not offloading[s]:
+            return t if fits(s, len(live), 0, False) else None
+        stay = sum(1 for j in live if j <= nb[s])
+        away = sorted(o_end[s][j] for j in live if j > nb[s])
+        for k in range(len(away) + 1):                                # k offloads have ended
+            if fits(s, stay + len(away) - k, k, True):
+                return t if k == 0 else max(t, away[k - 1])
+        return None
+
+    remaining = 3 * p * m
+    while remaining:
+        best = None
+        for s in range(p):
+            T = inst.t_op[s]
+            cands = []
+            jb, jf = nb[s], nf[s]
+            if jb < m and jb < nf[s]:
+                dep = end.get((s + 1, jb, "B")) if s < p - 1 else end.get((s, jb, "F"))
+                if dep is not None:
+                    ready = dep + (inst.t_comm if s < p - 1 else 0.0)
+                    if offloading[s] and jb in o_end[s]:
+                        ready = max(ready, o_end[s][jb] + inst.t_off[s])      # offload ended, reload done
+                    cands.append((max(t_free[s], ready), 0, "B", jb))
+            if jf < m:
+                dep = end.get((s - 1, jf, "F")) if s > 0 else 0.0
+                if dep is not None:
+                    ready = max(t_free[s], dep + (inst.t_comm if s > 0 else 0.0))
+                    # before the first backward op only `fill` forward ops; afterwards memory alone decides
+                    when = room_at(s, ready)
+                    if (nb[s] > 0 or nf[s] < fill[s]) and when is not None:
+                        cands.append((when, 1, "F", jf))
+            if nw[s] < nb[s]:
+                cands.append((max(t_free[s], end[(s, nw[s], "B")]), 2, "W", nw[s]))
+            if not cands:
+                continue
+            # the op that can start first; among those that start together backward > forward > weight gradient.
+            # A weight-gradient op that ends before the earliest other candidate starts goes first.
+            cands.sort()
+            pick = cands[0]
+            for c in cands:
+                if c[2] == "W" and c[0] + T["W"] <= pick[0] + 1e-12:
+                    pick = c
+                    break
+            if best is None or (pick[0], s) < (best[1][0], best[0]):
+                best = (s, pick)
+        if best is None:
+            raise RuntimeError("AdaOffload construction stalled: the limit holds no forward activation")
+        s, (st, _, c, j) = best
+        en = st + inst.t_op[s][c]
+        end[(s, j, c)] = en
+        t_free[s] = en
+        order[s].append((c, j))
+        if c == "F":
+            nf[s] += 1
+            if offloading[s]:
+                chan[s] = max(chan[s], en) + inst.t_off[s]
+                o_end[s][j] = chan[s]
+        elif c == "B":
+            nb[s] += 1
+        else:
+            nw[s] += 1
+        remaining -= 1
+
+    lists = [_with_transfers(order[s], offloading[s], inst.limit[s], dF[s], inst.gamma[s], lead, layer, kinds)
+             for s in range(p)]
+    return Solution(lists=lists, makespan=max(end[(s, m - 1, "W")] for s in range(p)),
+                    start={k: v - inst.t_op[k[0]][k[2]] for k, v in end.items()},
+                    offloaded={(s, j): bool(offloading[s]) for s in range(p) for j in range(m)}, status="adaoffload")
+
+
+def _with_transfers(order, offloading, limit, d_f, gamma, lead, layer, kinds):
+    """Inserts O / OWAIT / R into one stage's compute order: O right after every forward op; R `lead` compute ops
+    ahead of its backward op (never before its own forward op); OWAIT as late as possible, i.e. right before the
+    forward op or reload that would not fit otherwise (oldest offload first), or right before its own reload."""
+    if not offloading:
+        return list(order)
+    pos = {op: n for n, op in enumerate(order)}
+    r_before = {}                               # compute index -> micro-batches whose reload goes before it
+    for (c, j), n in pos.items():
+        if c == "B":
+            r_before.setdefault(max(n - lead, pos[("F", j)] + 1), []).append(j)
+    out, used, pending, credited = [], 0, [], set()
+
+    def make_room(need):
+        nonlocal used
+        while used + need > limit and pending:
+            jj = pending.pop(0)
+            out.append(("OWAIT", jj, layer, kinds))
+            credited.add(jj)
+            used -= gamma
+
+    for n, (c, j) in enumerate(order):
+        for jj in sorted(r_before.get(n, [])):
+            if jj not in credited:
+                pending.remove(jj)
+                out.append(("OWAIT", jj, layer, kinds))
+                credited.add(jj)
+                used -= gamma
+            make_room(gamma)
+            out.append(("R", jj, layer, kinds))
+            used += gamma
+        if c == "F":
+            make_room(d_f)
+            used += d_f
+        elif c == "W":
+            used -= d_f
+        out.append((c, j))
+        if c == "F":
+            out.append(("O", j, layer, kinds))
+            pending.append(j)
+    return out
+
+
+def expand_items(events, n_layers, kinds):
+    """Whole-activation offload of the paper (one item per forward op) written out for the executor's finer
+    granularity: the item's O / OWAIT / R become one event per layer over the given kinds, in layer order."""
+    out = []
+    for e in events:
+        if e[0] in ("O", "OWAIT", "R"):
+            out.extend((e[0], e[1], l, tuple(kinds)) for l in range(n_layers))
+        else:
+            out.append(e)
+    return out

@@ -160,6 +160,75 @@ def test_offload_under_budget_is_bit_exact_and_schedule_independent():
     ref_st.close()
 
 
+def test_adaoffload_and_milp_lists_run_on_the_stage():
+    """Lists from the host-side generators (AdaOffload, Alg. 1; the MILP of Eq. 2-17 on a tiny instance) are
+    accepted by the library's planner under the budget they were built for and change no bit of the result."""
+    from paper_2510_05186_amd import scheduler as SC
+    cfg = SMALL2
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    kinds = tuple(S.F_KINDS)                                # the paper's granularity: the whole forward activation
+    base = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches)[cfg.stage_index]
+    ref_st = gpu_run(cfg, ws, base)
+    peak0, _ = S.account_memory(base, cfg.n_layers, t)
+    delta = {c: S.op_delta(c, cfg.n_layers, t) for c in "FBW"}
+    gamma = sum(t[k] for k in kinds) * cfg.n_layers
+    slack = t["DY"] + t["DX_MID"] * 2                       # what B holds on top of the forward activations
+    pool = gamma * cfg.n_microbatches
+    p, m = cfg.n_stages, cfg.n_microbatches
+    t_op = [{"F": 1.0, "B": 1.3, "W": 0.9}] * p
+
+    # room for 3.3 forward activations where 1F1B would hold min(p - i, m) = 6: AdaOffload fills deeper by offloading
+    budget = int(3.3 * delta["F"]) + slack
+    assert budget < peak0
+    inst = SC.Instance(p=p, m=m, t_op=t_op, t_comm=0.02, t_off=[0.8] * p, delta=[delta] * p, gamma=[gamma] * p,
+                       limit=[budget - slack] * p, offload_stages=tuple(range(p)), item=(0, kinds))
+    ada = SC.adaoffload(inst, tolerance=0.5)
+    ev_ada = SC.expand_items(ada.lists[cfg.stage_index], cfg.n_layers, kinds)
+    assert any(e[0] == "O" for e in ev_ada)
+
+    # a 3-stage, 3-micro-batch instance small enough for the exact solver: stage 0 may hold two activations, and
+    # the optimum offloads to keep three in flight (makespan 11 instead of 14); stage 0's list runs on the GPU
+    from dataclasses import replace
+    cfg_m = replace(CFG.shrunken(CFG.CFG2, hidden=512, n_q=4, n_kv=4, ffn=1376, seq=512, n_layers=2, n_microbatches=3,
+                                 name="cfg2_milp"), n_stages=3, stage_index=0)
+    budget_m = 2 * delta["F"] + slack
+    unit = [{"F": 1, "B": 1, "W": 1}] * 3
+    own = {}                                                # what an op holds, while it runs, beyond the level before it
+    for c in "FBW":
+        level = top = 0
+        for sgn, _, k in S.op_memory_steps(c, cfg.n_layers):
+            level += sgn * t[k]
+            top = max(top, level)
+        own[c] = top
+    common = dict(p=3, m=3, t_op=unit, t_off=[0.5] * 3, delta=[delta] * 3, gamma=[gamma] * 3, own_peak=[own] * 3,
+                  limit=[budget_m, None, None], item=(0, kinds))
+    sol = SC.milp_schedule(SC.Instance(**common, offload_stages=(0,)), strict_eq13=False)
+    plain = SC.milp_schedule(SC.Instance(**common))
+    assert abs(sol.makespan - 11) < 1e-6 and abs(plain.makespan - 14) < 1e-6
+    ev_milp = SC.expand_items(sol.lists[0], cfg_m.n_layers, kinds)
+    assert any(e[0] == "O" for e in ev_milp)
+
+    for c, events, bud, ref in ((cfg, ev_ada, budget, ref_st), (cfg_m, ev_milp, budget_m, None)):
+        S.check_order(events, c.n_microbatches, c.n_layers)
+        pk, _ = S.account_memory(events, c.n_layers, t, limit=bud)
+        code, bad, peak, _ = B.plan(c, events, budget=bud)
+        assert code == B.OK and peak == pk <= bud, (code, bad, peak, pk, bud)
+        st = gpu_run(c, ws, events, budget=bud, host_pool_bytes=pool, arena_bytes=2 * bud)
+        check_accounting(c, st, events)
+        if ref is None:
+            ref = gpu_run(c, ws, G.one_f_one_b(3, 3, 0))
+        for j in range(c.n_microbatches):
+            assert torch.equal(st.y[j], ref.y[j]) and torch.equal(st.dx[j], ref.dx[j])
+        for l in range(c.n_layers):
+            for name in st.grads[l]:
+                assert torch.equal(st.grads[l][name], ref.grads[l][name]), (l, name)
+        st.close()
+        if ref is not ref_st:
+            ref.close()
+    ref_st.close()
+
+
 def test_duplex_reload_stream_changes_no_bit():
     """Reloads on a stream of their own (full-duplex host link) instead of the single transfer channel of the
     paper's model (Eq. 8-11): same bytes, same accounting, bitwise the same results."""

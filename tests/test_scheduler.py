@@ -1,0 +1,198 @@
+"""Host-side schedule generators (paper_2510_05186_amd/scheduler.py) against the oracle: the MILP optimum
+equals the brute-force optimum over every valid per-stage order (and every placement of O / OWAIT / R) on
+tiny instances, every list it returns is valid, fits the memory limit and reproduces the solver's makespan
+in the oracle simulator; AdaOffload returns valid, feasible, denser-than-1F1B lists whose makespan bounds
+the optimum from above."""
+import itertools
+
+import pytest
+
+from oracle import schedule as S
+from paper_2510_05186_amd import scheduler as SC
+from stage_inputs import schedules as G
+from test_oracle_schedule import L, TABLE, all_orders, check_constraints, offload_variants
+
+ITEM = (0, ("X_IN",))
+DELTA = {c: S.op_delta(c, L, TABLE) for c in "FBW"}
+GAMMA = TABLE["X_IN"]
+
+
+def eq7_peak(events):
+    return max(u for _, u in S.eq7_usage(events, L, TABLE))
+
+
+def own_peak(table, n_layers):
+    """Most bytes each op type holds beyond the level before it, from the oracle's allocation steps."""
+    out = {}
+    for c in "FBW":
+        level = top = 0
+        for sgn, _, k in S.op_memory_steps(c, n_layers):
+            level += sgn * table[k]
+            top = max(top, level)
+        out[c] = top
+    return out
+
+
+def brute_optimum(p, m, t_op, t_comm, t_off, limit0, offload_mbs, physical=False):
+    """Minimum Eq. 17 makespan over every pair of valid stage orders (p = 2), with every placement of the
+    transfers of any subset of `offload_mbs` on stage 0, subject to Eq. 7 on stage 0 (physical: subject to the
+    executor's list-order accounting instead, which holds what B and W release until they have run)."""
+    assert p == 2
+    orders = all_orders(m)
+    best = None
+    for l0 in orders:
+        cands = [l0]
+        for j in offload_mbs:
+            cands = cands + [v for c in cands for v in offload_variants(c, j)]
+        for v0 in cands:
+            if limit0 is not None and (S.account_memory(v0, L, TABLE)[0] if physical else eq7_peak(v0)) > limit0:
+                continue
+            for l1 in orders:
+                try:
+                    tm = S.simulate([v0, l1], t_op, t_comm=t_comm, t_copy=lambda i, ev: t_off)
+                except S.ScheduleError:
+                    continue
+                if best is None or tm.makespan_global < best - 1e-12:
+                    best = tm.makespan_global
+    return best
+
+
+def check_solution(inst, sol, t_off):
+    for i, lst in enumerate(sol.lists):
+        S.check_order(lst, inst.m, L)
+        if inst.limit[i] is not None:
+            assert eq7_peak(lst) <= inst.limit[i]
+    tm = S.simulate(sol.lists, inst.t_op, t_comm=inst.t_comm, t_copy=lambda i, ev: t_off)
+    check_constraints(sol.lists, tm, inst.t_op, inst.t_comm, t_off)
+    return tm
+
+
+@pytest.mark.parametrize("m,t_op,t_comm", [
+    (2, [{"F": 1, "B": 2, "W": 1}, {"F": 2, "B": 1, "W": 1}], 1),
+    (3, [{"F": 1, "B": 1, "W": 1}, {"F": 1, "B": 1, "W": 1}], 0),
+    (3, [{"F": 2, "B": 3, "W": 1}, {"F": 1, "B": 2, "W": 2}], 1),
+])
+def test_milp_without_offload_matches_bruteforce(m, t_op, t_comm):
+    inst = SC.Instance(p=2, m=m, t_op=t_op, t_comm=t_comm)
+    sol = SC.milp_schedule(inst)
+    ref = brute_optimum(2, m, t_op, t_comm, 0, None, ())
+    assert abs(sol.makespan - ref) < 1e-6, (sol.makespan, ref)
+    tm = check_solution(inst, sol, 0)
+    assert abs(tm.makespan_global - ref) < 1e-6
+
+
+def test_milp_memory_limit_without_offload_matches_bruteforce():
+    # a limit of two forward activations (+ what B allocates) forbids the deep fill
+    m = 3
+    t_op = [{"F": 1, "B": 1, "W": 1}] * 2
+    limit = 2 * DELTA["F"] + TABLE["DY"] + TABLE["DX_MID"]
+    inst = SC.Instance(p=2, m=m, t_op=t_op, delta=[DELTA, DELTA], gamma=[GAMMA, GAMMA], limit=[limit, None])
+    sol = SC.milp_schedule(inst)
+    ref = brute_optimum(2, m, t_op, 0, 0, limit, ())
+    free = brute_optimum(2, m, t_op, 0, 0, None, ())
+    assert abs(sol.makespan - ref) < 1e-6 and ref >= free
+    check_solution(inst, sol, 0)
+
+
+@pytest.mark.parametrize("t_off", [1, 2])
+def test_milp_with_offload_matches_bruteforce(t_off):
+    # stage 0 may offload the item of micro-batches 0 and 1; the limit leaves room for two activations plus
+    # the item-sized slack, so offloading buys a denser fill
+    m = 3
+    t_op = [{"F": 1, "B": 1, "W": 1}] * 2
+    limit = 2 * DELTA["F"] + TABLE["DY"] + TABLE["DX_MID"] + (DELTA["F"] - GAMMA)
+    inst = SC.Instance(p=2, m=m, t_op=t_op, t_off=[t_off, t_off], delta=[DELTA, DELTA], gamma=[GAMMA, GAMMA],
+                       limit=[limit, None], offload_stages=(0,), offload_mbs=(0, 1), item=ITEM)
+    relaxed = SC.milp_schedule(inst, strict_eq13=False)
+    ref = brute_optimum(2, m, t_op, 0, t_off, limit, (0, 1))
+    assert abs(relaxed.makespan - ref) < 1e-5, (relaxed.makespan, ref)
+    tm = check_solution(inst, relaxed, t_off)
+    assert tm.makespan_global <= relaxed.makespan + 1e-5
+    # Eq. 13 as printed only removes schedules: never better than the executor's model, never better than no limit
+    strict = SC.milp_schedule(inst, strict_eq13=True)
+    assert strict.makespan >= relaxed.makespan - 1e-6
+    tm = check_solution(inst, strict, t_off)
+    for i, lst in enumerate(strict.lists):              # Eq. 13 on the extracted timing
+        for n, ev in enumerate(lst):
+            if ev[0] == "R":
+                for k in range(n + 1, len(lst)):
+                    if lst[k][0] in "FBW":
+                        assert tm.start[i][k] + 1e-9 >= tm.start[i][n]
+
+
+def test_milp_with_physical_accounting_matches_bruteforce_on_the_executors_peak():
+    # own term of Eq. 7 = what the op really holds while it runs: the lists then fit the executor's accounting
+    m = 3
+    t_op = [{"F": 1, "B": 1, "W": 1}] * 2
+    limit = 2 * DELTA["F"] + TABLE["DY"] + TABLE["DX_MID"] + (DELTA["F"] - GAMMA)
+    pk = own_peak(TABLE, L)
+    assert pk["F"] == DELTA["F"] and pk["W"] == 0 and pk["B"] > 0
+    inst = SC.Instance(p=2, m=m, t_op=t_op, t_off=[1, 1], delta=[DELTA, DELTA], gamma=[GAMMA, GAMMA], own_peak=[pk, pk],
+                       limit=[limit, None], offload_stages=(0,), offload_mbs=(0, 1), item=ITEM)
+    sol = SC.milp_schedule(inst, strict_eq13=False)
+    ref = brute_optimum(2, m, t_op, 0, 1, limit, (0, 1), physical=True)
+    assert abs(sol.makespan - ref) < 1e-5, (sol.makespan, ref)
+    check_solution(inst, sol, 1)
+    assert S.account_memory(sol.lists[0], L, TABLE)[0] <= limit
+    paper = SC.milp_schedule(SC.Instance(p=2, m=m, t_op=t_op, t_off=[1, 1], delta=[DELTA, DELTA], gamma=[GAMMA, GAMMA],
+                                         limit=[limit, None], offload_stages=(0,), offload_mbs=(0, 1), item=ITEM),
+                             strict_eq13=False)
+    assert paper.makespan <= sol.makespan + 1e-6        # Eq. 7 as printed admits more schedules
+
+
+def test_milp_offload_beats_no_offload_under_the_same_limit():
+    m = 3
+    t_op = [{"F": 1, "B": 1, "W": 1}] * 2
+    limit = 2 * DELTA["F"] + TABLE["DY"] + TABLE["DX_MID"] + (DELTA["F"] - GAMMA)
+    base = dict(p=2, m=m, t_op=t_op, t_off=[1, 1], delta=[DELTA, DELTA], gamma=[GAMMA, GAMMA], limit=[limit, None], item=ITEM)
+    without = SC.milp_schedule(SC.Instance(**base))
+    with_off = SC.milp_schedule(SC.Instance(**base, offload_stages=(0,)), strict_eq13=False)
+    assert with_off.makespan <= without.makespan + 1e-6
+
+
+def test_triangle_cuts_and_cutoff_do_not_change_the_optimum():
+    t_op = [{"F": 2, "B": 3, "W": 1}, {"F": 1, "B": 2, "W": 2}]
+    inst = SC.Instance(p=2, m=3, t_op=t_op, t_comm=1)
+    a = SC.milp_schedule(inst, triangle_cuts=True)
+    b = SC.milp_schedule(inst, triangle_cuts=False)
+    ada = SC.adaoffload(inst)
+    c = SC.milp_schedule(inst, cutoff=ada.makespan)
+    assert abs(a.makespan - b.makespan) < 1e-6 and abs(a.makespan - c.makespan) < 1e-6
+    assert ada.makespan >= a.makespan - 1e-6
+
+
+@pytest.mark.parametrize("p,m", [(2, 3), (4, 8), (8, 16)])
+def test_adaoffload_lists_are_valid_and_dense(p, m):
+    t_op = [{"F": 1.0, "B": 1.2, "W": 0.8}] * p
+    # room for three activations per stage; the whole forward activation (every kind, both layers) is the
+    # offloadable item, 0.5 per activation = 0.25 per layer event
+    limit = 3 * DELTA["F"] + TABLE["DY"] + TABLE["DX_MID"]
+    inst = SC.Instance(p=p, m=m, t_op=t_op, t_comm=0.05, t_off=[0.5] * p, delta=[DELTA] * p, gamma=[DELTA["F"]] * p,
+                       limit=[limit] * p, offload_stages=tuple(range(p)), item=(0, tuple(S.F_KINDS)))
+    sol = SC.adaoffload(inst, tolerance=0.5)
+    lists = [SC.expand_items(lst, L, S.F_KINDS) for lst in sol.lists]
+    for i, lst in enumerate(lists):
+        S.check_order(lst, m, L)
+    tm = S.simulate(lists, t_op, t_comm=0.05, t_copy=lambda i, ev: 0.25)
+    check_constraints(lists, tm, t_op, 0.05, 0.25)
+    # every list fits its limit in the oracle's accounting (Eq. 7 usage and the executor's running sum), and
+    # stages that offload fill deeper than the three activations they can hold
+    for i, lst in enumerate(lists):
+        first_b = next(n for n, e in enumerate(lst) if e[0] == "B")
+        n_fill = sum(1 for e in lst[:first_b] if e[0] == "F")
+        assert n_fill >= 1
+        assert eq7_peak(lst) <= limit, (i, eq7_peak(lst), limit)
+        peak, _ = S.account_memory(lst, L, TABLE)
+        assert peak <= limit, (i, peak, limit)
+        if any(e[0] == "O" for e in lst):
+            assert n_fill > 3 or n_fill == m
+    # beats the capacity-respecting greedy list without offload whenever the capacity binds
+    capped = G.split_bw_greedy(p, m, cap_of_stage=lambda s: min(3, p - s))
+    tz = S.simulate(capped, t_op, t_comm=0.05)
+    assert tm.makespan_global <= tz.makespan_global + 1e-9
+    if p >= 4:
+        assert tm.makespan_global < 0.9 * tz.makespan_global
+    # the optimum bounds it from below on the instance small enough to solve exactly
+    if (p, m) == (2, 3):
+        opt = SC.milp_schedule(inst, strict_eq13=False, cutoff=sol.makespan)
+        assert opt.makespan <= tm.makespan_global + 1e-6
