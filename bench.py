@@ -83,13 +83,48 @@ def device_io(cfg, mb, torch):
     return x.contiguous(), dy.contiguous()
 
 
-def build_schedule(cfg, budget=0):
+def adaoffload_instance(cfg, budget, tflops=900.0, link_gbps=56.0):
+    """The paper's abstract instance for this workload (all p stages alike): op times from the flop counts at a
+    nominal rate, transfer time from the offloadable bytes at the measured host-link rate, Eq. 7's parameters
+    from the library's memory table."""
+    from paper_2510_05186_amd import binding as B
+    from paper_2510_05186_amd import scheduler as SC
+    s, h, f = cfg.seq * cfg.micro_batch, cfg.hidden, cfg.ffn
+    gemm = 2 * s * (cfg.qkv_width * h + h * cfg.n_q_heads * cfg.head_dim + cfg.up_width * h + h * f)
+    att = cfg.micro_batch * cfg.seq * cfg.seq * cfg.n_q_heads * cfg.head_dim
+    ms = lambda fl: cfg.n_layers * fl / (tflops * 1e9)
+    t_op = {"F": ms(gemm + 2 * att), "B": ms(gemm + 5 * att), "W": ms(gemm)}
+    _, act_per_mb, kb = B.query_sizes(cfg)
+    gamma = sum(kb[k] for k in cfg.offload_kinds) * cfg.n_layers
+    slack = 2 * (kb["DY"] + kb["DX_MID"])                 # what B holds beyond the forward activations
+    p = cfg.n_stages
+    return SC.Instance(p=p, m=cfg.n_microbatches, t_op=[t_op] * p, t_comm=0.0, t_off=[gamma / (link_gbps * 1e6)] * p,
+                       delta=[{"F": act_per_mb, "B": 0, "W": -act_per_mb}] * p, gamma=[gamma] * p,
+                       limit=[max(budget - slack, act_per_mb)] * p, offload_stages=tuple(range(p)),
+                       item=(0, tuple(cfg.offload_kinds)))
+
+
+def build_schedule(cfg, budget=0, generator="greedy"):
     """Event list of this stage for the configuration's schedule family; with a budget the generator's
     knobs (in-flight cap, which micro-batches to offload, how long copies may overlap) are searched with the
-    library's own planner until the list fits."""
+    library's own planner until the list fits.  generator "adaoffload": the dense-fill list of the paper's
+    Alg. 1 for the whole pipeline, this stage's part, repaired against the planner if it does not fit as is."""
     from paper_2510_05186_amd import binding as B
     from stage_inputs import schedules as G
     p, m, i = cfg.n_stages, cfg.n_microbatches, cfg.stage_index
+    if budget and generator == "adaoffload":
+        from paper_2510_05186_amd import scheduler as SC
+        inst = adaoffload_instance(cfg, budget)
+        sol = SC.adaoffload(inst, tolerance=0.5 * inst.t_op[0]["F"])
+        ev = SC.expand_items(sol.lists[i], cfg.n_layers, cfg.offload_kinds)
+        fits = lambda e: (lambda r: (r[0] == B.OK, r[1]))(B.plan(cfg, e, budget=budget))
+        knobs = {"generator": "adaoffload", "offload": any(e[0] == "O" for e in ev), "placement": "as generated"}
+        build_schedule.all_stages = [SC.expand_items(l, cfg.n_layers, cfg.offload_kinds) for l in sol.lists]
+        if not fits(ev)[0]:
+            ev = G.repair_to_fit(ev, fits)
+            knobs["placement"] = "repaired"
+        if ev is not None:
+            return ev, knobs
     if cfg.schedule == "1f1b":
         return G.one_f_one_b(p, m, i), {}
     if not budget:
@@ -164,7 +199,7 @@ def time_steps(st, events, steps, warmup, torch, kernel_timing=True):
     return wall, agg
 
 
-def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event):
+def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event, duplex=False):
     """CPU baseline: the fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample
     (ONE layer of the workload's stage, one micro-batch, F + B + W at full shape), and the oracle's
     pipeline simulator fed with the measured op times (all p stages assumed identical to this one)."""
@@ -194,7 +229,7 @@ def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event):
                       f"({fl / 1e12:.2f} TFLOP fp64 in {dt:.1f} s)", "host_cpus": os.cpu_count()}
     p = cfg.n_stages
     t_op = [{"F": t_op_ms[0], "B": t_op_ms[1], "W": t_op_ms[2]}] * p
-    tm = S.simulate(events_all_stages, t_op, t_comm=0.0, t_copy=lambda i, ev: copy_ms_per_event)
+    tm = S.simulate(events_all_stages, t_op, t_comm=0.0, t_copy=lambda i, ev: copy_ms_per_event, duplex=duplex)
     model = {"stage_bubble_frac": tm.bubble[cfg.stage_index], "makespan_ms": tm.makespan_global,
              "assumption": "p identical stages with this stage's measured mean T_F/T_B/T_W, T_comm = 0"}
     return base, model
@@ -208,6 +243,8 @@ def main():
     ap.add_argument("--config", default="cfg2_llama_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-offload-leg", action="store_true")
+    ap.add_argument("--generator", default="greedy", choices=("greedy", "adaoffload"),
+                    help="how the event list of a budgeted workload is produced")
     ap.add_argument("--duplex", action="store_true",
                     help="reloads on a stream of their own instead of the single transfer channel (offload workloads)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -234,7 +271,7 @@ def main():
     elif cfg.budget_frac_of_peak:
         base_ev, _ = build_schedule(CFG.CFG2)
         budget = int(cfg.budget_frac_of_peak * B.plan(CFG.CFG2, base_ev)[2])
-    events, knobs = build_schedule(cfg, budget)
+    events, knobs = build_schedule(cfg, budget, args.generator)
     if args.calibration_copy_mib:
         src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -292,7 +329,7 @@ def main():
         # same shapes under 40 % of this run's activation peak, with offload of (attention input, QKV, MLP input)
         c3 = CFG.CFG3
         b3 = int(c3.budget_frac_of_peak * peak_plan)
-        ev3, knobs3 = build_schedule(c3, b3)
+        ev3, knobs3 = build_schedule(c3, b3, args.generator)
         st3, _ = make_stage(c3, ev3, b3, torch, args.duplex)
         w3, a3 = time_steps(st3, ev3, 1, 1, torch, kernel_timing=False)
         comp_only = [e for e in ev3 if e[0] in ("F", "B", "W")]
@@ -315,7 +352,14 @@ def main():
     if not args.no_cpu_baseline:
         lists = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches) if cfg.schedule != "1f1b" else \
             [G.one_f_one_b(cfg.n_stages, cfg.n_microbatches, i) for i in range(cfg.n_stages)]
-        base, model = oracle_leg(cfg, t_op_ms, lists, 0.0)
+        copy_ms = 0.0
+        if args.generator == "adaoffload" and getattr(build_schedule, "all_stages", None) and budget:
+            # the generator's lists for every stage, transfers included, with this stage's measured mean copy time
+            lists = build_schedule.all_stages
+            n_x = agg["k_n"] and sum(1 for e in events if e[0] in ("O", "R"))
+            copy_ms = (agg["ms_ops"][3] + agg["ms_ops"][5]) / args.steps / n_x if n_x else 0.0
+        base, model = oracle_leg(cfg, t_op_ms, lists, copy_ms, args.duplex)
+        model["lists"] = "adaoffload, all stages, transfers included" if copy_ms else "compute ops only"
         out["cpu_baseline"] = base
         out["pipeline_model"] = model
     print(json.dumps(out))
