@@ -27,6 +27,14 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
                                  void* C, const void* R, uint32_t M, uint32_t N, uint32_t K, uint32_t lda,
                                  uint32_t ldb, uint32_t ldc, void* stream);
 
+/* n (1..16) independent bf16 products of the same layout, epilogue and K in ONE launch (the weight-gradient GEMMs
+ * of a W op, dW = dY^T X for every linear of every layer, do not depend on one another: Sec. 2.2).  problems is a
+ * HOST array; pointers inside are DEVICE.  Each problem must satisfy optstage_op_gemm's alignment rules, K % 64
+ * must be 0 and the set must hold at least 128 tiles of 256 x 256; otherwise OPTSTAGE_E_ARG and nothing runs. */
+typedef struct { const void* A; const void* B; void* C; const void* R; uint32_t M, N, lda, ldb, ldc; } optstage_gemm_problem;
+optstage_status optstage_op_gemm_grouped(uint32_t layout, uint32_t epilogue, uint32_t n,
+                                         const optstage_gemm_problem* problems, uint32_t K, void* stream);
+
 /* family LLAMA: RMSNorm, stats[rows] = rstd.  family GPT: LayerNorm, stats[2*row] = mean, [2*row+1] = rstd. */
 optstage_status optstage_op_norm_fwd(uint32_t dtype, uint32_t family, const void* x, const void* gamma,
                                      const void* beta, void* out, float* stats, uint32_t rows, uint32_t hidden,

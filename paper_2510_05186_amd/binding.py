@@ -36,6 +36,11 @@ class Desc(C.Structure):
                 ("reload_stream", C.c_void_p)]
 
 
+class GemmProblem(C.Structure):
+    _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("C", C.c_void_p), ("R", C.c_void_p),
+                ("M", C.c_uint32), ("N", C.c_uint32), ("lda", C.c_uint32), ("ldb", C.c_uint32), ("ldc", C.c_uint32)]
+
+
 class Event(C.Structure):
     _fields_ = [("op", C.c_uint32), ("microbatch", C.c_uint32), ("layer", C.c_uint32), ("kind_mask", C.c_uint32)]
 
@@ -77,6 +82,7 @@ _SIGS = {
     "optstage_debug_read": [_vp, _u32, _u32, _u32, _vp, _u64],
     "optstage_plan": [C.POINTER(Desc), C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(_u64), C.POINTER(_u64)],
     "optstage_op_gemm": [_u32, _u32, _u32, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _u32, _vp],
+    "optstage_op_gemm_grouped": [_u32, _u32, _u32, _vp, _u32, _vp],
     "optstage_op_norm_fwd": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _f32, _vp],
     "optstage_op_norm_bwd": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _vp],
     "optstage_op_act_fwd": [_u32, _u32, _vp, _vp, _u32, _u32, _vp],

@@ -449,22 +449,20 @@ __device__ __forceinline__ void epilogue_bf16_rows(f32x16_t (&acc)[4][4], char* 
   }
 }
 
-// TNL = false: A(m, k) at A[m * lda + k], B(n, k) at B[n * ldb + k].  TNL = true: A[k * lda + m], B[k * ldb + n].
+// One output tile.  TNL = false: A(m, k) at A[m * lda + k], B(n, k) at B[n * ldb + k].  TNL = true: A[k * lda + m],
+// B[k * ldb + n].  pid = position of the tile in the problem's tile sequence (groups of 8 tile rows, walked
+// column by column).
 template <bool TNL, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                                               void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N,
-                                                               int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n,
-                                                               unsigned a_bytes, unsigned b_bytes) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+__device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                            void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N, int K, int lda,
+                                            int ldb, int ldc, int tiles_m, int tiles_n, unsigned a_bytes, unsigned b_bytes,
+                                            int pid) {
   constexpr int BM = 256, BN = 256, WM = 2, WN = 2, TM = 4, TN = 4;
   constexpr int OPB = 32768;                    // one operand of one stage
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
-  int pid = blockIdx.x;
-  const int nblk = tiles_m * tiles_n;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
   constexpr int GM = 8;
   const int grp = pid / (GM * tiles_n);
   const int first_m = grp * GM;
@@ -650,6 +648,42 @@ __global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(const bf16_t* __r
                             n0 + wn * (BN / WN));
 }
 
+// Consecutive hardware workgroup ids go to different XCDs: give every XCD one contiguous range of the sequence
+__device__ __forceinline__ int xcd_remap(int id, int n) { return (n & 7) == 0 ? (id & 7) * (n >> 3) + (id >> 3) : id; }
+
+template <bool TNL, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                               void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N,
+                                                               int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n,
+                                                               unsigned a_bytes, unsigned b_bytes) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  direct_tile<TNL, EPI>(smem, A, B, Cv, R, M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes,
+                        xcd_remap(blockIdx.x, tiles_m * tiles_n));
+}
+
+// Several independent products with the same K in one launch (the weight-gradient GEMMs of a W op: four per
+// layer, none depending on another): their tiles form one sequence, so the partly filled last round of
+// workgroups that every product would leave behind on its own happens once.
+constexpr int MAX_GROUP = 16;
+struct GroupedProblem {
+  const bf16_t* A; const bf16_t* B; void* C; const bf16_t* R;
+  int M, N, lda, ldb, ldc, tiles_m, tiles_n, first_tile;
+  unsigned a_bytes, b_bytes;
+};
+struct GroupedArgs { int n, K, total; GroupedProblem p[MAX_GROUP]; };
+
+template <bool TNL, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_direct_grouped_kernel(const GroupedArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int id = xcd_remap(blockIdx.x, g.total);
+  int q = 0;
+  for (int i = 1; i < g.n; ++i)
+    if (id >= g.p[i].first_tile) q = i;
+  const GroupedProblem& pr = g.p[q];
+  direct_tile<TNL, EPI>(smem, pr.A, pr.B, pr.C, pr.R, pr.M, pr.N, g.K, pr.lda, pr.ldb, pr.ldc, pr.tiles_m, pr.tiles_n,
+                        pr.a_bytes, pr.b_bytes, id - pr.first_tile);
+}
+
 template <bool TNL, int EPI>
 hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
                          int ldc, hipStream_t s) {
@@ -678,6 +712,36 @@ bool direct_applies(bool tnl, int M, int N, int K, int lda, int ldb) {
   if (tnl) return ((unsigned long long)K * lda * 2 < lim) && ((unsigned long long)K * ldb * 2 < lim);
   return ((unsigned long long)(M + 256) * lda * 2 < lim) && ((unsigned long long)(N + 256) * ldb * 2 < lim);
 }
+template <bool TNL, int EPI>
+hipError_t launch_direct_grouped(int n, const GemmProblem* pr, int K, hipStream_t s) {
+  auto kern = gemm_bf16_direct_grouped_kernel<TNL, EPI>;
+  constexpr int smem = 131072;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  GroupedArgs g;
+  g.n = n;
+  g.K = K;
+  int total = 0;
+  for (int i = 0; i < n; ++i) {
+    GroupedProblem& q = g.p[i];
+    q.A = (const bf16_t*)pr[i].A; q.B = (const bf16_t*)pr[i].B; q.C = pr[i].C; q.R = (const bf16_t*)pr[i].R;
+    q.M = pr[i].M; q.N = pr[i].N; q.lda = pr[i].lda; q.ldb = pr[i].ldb; q.ldc = pr[i].ldc;
+    q.tiles_m = (q.M + 255) / 256;
+    q.tiles_n = (q.N + 255) / 256;
+    q.first_tile = total;
+    total += q.tiles_m * q.tiles_n;
+    q.a_bytes = (unsigned)(TNL ? ((size_t)(K - 1) * q.lda + q.M) * 2 : ((size_t)(q.M - 1) * q.lda + K) * 2);
+    q.b_bytes = (unsigned)(TNL ? ((size_t)(K - 1) * q.ldb + q.N) * 2 : ((size_t)(q.N - 1) * q.ldb + K) * 2);
+  }
+  g.total = total;
+  hipLaunchKernelGGL(kern, dim3(total), dim3(256), smem, s, g);
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int WM, int WN, bool A_RC, bool B_RC, int EPI>
 hipError_t launch_cfg(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
                       int ldc, hipStream_t s) {
@@ -728,5 +792,30 @@ hipError_t launch_gemm_bf16(int layout, int epi, const void* A, const void* B, v
     if (epi == EPI_STORE) return launch_layout<true, EPI_STORE>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
     if (epi == EPI_ACCUM) return launch_layout<true, EPI_ACCUM>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
   }
+  return hipErrorInvalidValue;
+}
+
+// n independent products sharing layout, epilogue and K in one launch: whether the set qualifies (every product
+// on the direct path, operands aligned as the kernels need, at least half a round of tiles in total)
+bool gemm_bf16_grouped_applies(int layout, int n, const GemmProblem* pr, int K) {
+  if (n <= 0 || n > MAX_GROUP || K <= 0 || (K % 64)) return false;
+  long tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    const GemmProblem& q = pr[i];
+    if (q.M <= 0 || q.N <= 0) return false;
+    if ((q.lda & 7) || (q.ldb & 7) || (q.ldc & 3) || (q.N & 3)) return false;
+    if (layout == GEMM_TN && ((q.M & 7) || (q.N & 7))) return false;
+    if (!direct_applies(layout == GEMM_TN, q.M, q.N, K, q.lda, q.ldb)) return false;
+    tiles += (long)((q.M + 255) / 256) * ((q.N + 255) / 256);
+  }
+  return tiles >= 128;
+}
+
+hipError_t launch_gemm_bf16_grouped(int layout, int epi, int n, const GemmProblem* pr, int K, hipStream_t s) {
+  if (!gemm_bf16_grouped_applies(layout, n, pr, K)) return hipErrorInvalidValue;
+  if (layout == GEMM_TN && epi == EPI_ACCUM) return launch_direct_grouped<true, EPI_ACCUM>(n, pr, K, s);
+  if (layout == GEMM_TN && epi == EPI_STORE) return launch_direct_grouped<true, EPI_STORE>(n, pr, K, s);
+  if (layout == GEMM_NT && epi == EPI_STORE) return launch_direct_grouped<false, EPI_STORE>(n, pr, K, s);
+  if (layout == GEMM_NT && epi == EPI_ACCUM) return launch_direct_grouped<false, EPI_ACCUM>(n, pr, K, s);
   return hipErrorInvalidValue;
 }

@@ -63,6 +63,24 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
   return wrap(e, "gemm");
 }
 
+optstage_status optstage_op_gemm_grouped(uint32_t layout, uint32_t epilogue, uint32_t n,
+                                         const optstage_gemm_problem* problems, uint32_t K, void* stream) {
+  REQ(problems && n >= 1 && n <= 16 && layout <= 1 && (epilogue == 0 || epilogue == 2), "gemm_grouped: bad argument");
+  GemmProblem pr[16];
+  for (uint32_t i = 0; i < n; ++i) {
+    const optstage_gemm_problem& q = problems[i];
+    REQ(q.A && q.B && q.C, "gemm_grouped: null operand");
+    REQ(aligned16(q.A) && aligned16(q.B) && aligned16(q.C), "gemm_grouped: operands must be 16-byte aligned");
+    REQ(q.M && q.N && q.M < (1u << 30) && q.N < (1u << 30) && K && K < (1u << 30), "gemm_grouped: bad extent");
+    if (layout == 0) { REQ(q.lda >= K && q.ldb >= K, "gemm_grouped: leading dimension smaller than K"); }
+    else { REQ(q.lda >= q.M && q.ldb >= q.N, "gemm_grouped: leading dimension smaller than the row length"); }
+    REQ(q.ldc >= q.N, "gemm_grouped: ldc smaller than N");
+    pr[i] = {q.A, q.B, q.C, q.R, (int)q.M, (int)q.N, (int)q.lda, (int)q.ldb, (int)q.ldc};
+  }
+  REQ(gemm_bf16_grouped_applies((int)layout, (int)n, pr, (int)K), "gemm_grouped: the set does not qualify (K % 64, alignment, fewer than 128 tiles)");
+  return wrap(launch_gemm_bf16_grouped((int)layout, (int)epilogue, (int)n, pr, (int)K, (hipStream_t)stream), "gemm_grouped");
+}
+
 optstage_status optstage_op_norm_fwd(uint32_t dtype, uint32_t family, const void* x, const void* gamma,
                                      const void* beta, void* out, float* stats, uint32_t rows, uint32_t hidden,
                                      float eps, void* stream) {

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -377,6 +378,12 @@ optstage_status k_gemm(optstage* st, int layout, int epi, const void* A, const v
   KT(cls, 2.0 * M * N * K, gemm(st->sh, layout, epi, A, B, C, R, M, N, K, lda, ldb, ldc, st->cs));
   return OPTSTAGE_OK;
 }
+optstage_status k_gemm_grouped(optstage* st, int layout, int epi, int n, const GemmProblem* pr, int K) {
+  double flops = 0;
+  for (int i = 0; i < n; ++i) flops += 2.0 * pr[i].M * pr[i].N * K;
+  KT(OPTSTAGE_KC_GEMM_TN_ACCUM, flops, launch_gemm_bf16_grouped(layout, epi, n, pr, K, st->cs));
+  return OPTSTAGE_OK;
+}
 optstage_status k_norm_fwd(optstage* st, const void* x, const void* g, const void* b, void* out, float* stats) {
   const Shape& s = st->sh;
   KT(OPTSTAGE_KC_NORM_FWD, 2.0 * s.e * s.tokens * s.h, launch_norm_fwd(s.dtype, s.family, x, g, b, out, stats, s.tokens, s.h, st->desc.norm_eps, st->cs));
@@ -487,12 +494,25 @@ optstage_status exec_backward_weight(optstage* st, int j, const OpBufs& ob) {
   hipStream_t cs = st->cs;
   const int T = s.tokens;
   auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
+  // dW += dY^T X for the four linears of every layer (fp32 accumulators).  None of these products depends on
+  // another: bf16 stages hand them to one grouped launch per 16, so that only the last launch leaves a partly
+  // filled round of workgroups; anything the grouped path does not take runs product by product.
+  std::vector<GemmProblem> pr;
   for (int l = 0; l < s.L; ++l) {
-    // dW += dY^T X for the four linears (fp32 accumulators)
-    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DY), P(l, OPTSTAGE_K_A), GW(st, l, OPTSTAGE_W_D), nullptr, s.h, s.f, T, s.h, s.f, s.f));
-    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_N2), GW(st, l, OPTSTAGE_W_GU), nullptr, s.up_w, s.h, T, s.up_w, s.h, s.h));
-    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_DX_MID), P(l, OPTSTAGE_K_O), GW(st, l, OPTSTAGE_W_O), nullptr, s.h, s.nq * s.d, T, s.h, s.nq * s.d, s.nq * s.d));
-    TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_N1), GW(st, l, OPTSTAGE_W_QKV), nullptr, s.qkv_w, s.h, T, s.qkv_w, s.h, s.h));
+    pr.push_back({P(l, OPTSTAGE_K_DY), P(l, OPTSTAGE_K_A), GW(st, l, OPTSTAGE_W_D), nullptr, s.h, s.f, s.h, s.f, s.f});
+    pr.push_back({P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_N2), GW(st, l, OPTSTAGE_W_GU), nullptr, s.up_w, s.h, s.up_w, s.h, s.h});
+    pr.push_back({P(l, OPTSTAGE_K_DX_MID), P(l, OPTSTAGE_K_O), GW(st, l, OPTSTAGE_W_O), nullptr, s.h, s.nq * s.d, s.h, s.nq * s.d, s.nq * s.d});
+    pr.push_back({P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_N1), GW(st, l, OPTSTAGE_W_QKV), nullptr, s.qkv_w, s.h, s.qkv_w, s.h, s.h});
+  }
+  for (size_t i0 = 0; i0 < pr.size(); i0 += 16) {
+    const int n = (int)std::min<size_t>(16, pr.size() - i0);
+    const bool grouped = s.dtype == OPTSTAGE_BF16 && gemm_bf16_grouped_applies(GEMM_TN, n, &pr[i0], T);
+    if (grouped) TRY(k_gemm_grouped(st, GEMM_TN, EPI_ACCUM, n, &pr[i0], T));
+    if (!grouped)
+      for (int i = 0; i < n; ++i) {
+        const GemmProblem& q = pr[i0 + i];
+        TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, q.A, q.B, q.C, nullptr, q.M, q.N, T, q.lda, q.ldb, q.ldc));
+      }
   }
   return OPTSTAGE_OK;
 }

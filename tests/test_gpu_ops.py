@@ -63,6 +63,36 @@ def test_gemm_tn_accumulate(dtype, M, N, K):
     assert rel_err(host(C), ref) < (1e-5 if dtype == FP32 else 1e-4)    # fp32 accumulators: no bf16 rounding of C
 
 
+def test_gemm_grouped_equals_one_by_one_and_the_oracle():
+    """The weight-gradient products of a W op in one launch (shapes of the Llama stage's four linears at a
+    shorter token count, including a ragged 200-row edge tile): bitwise the same as launching each on its
+    own, and within tolerance of dY^T X from the oracle on sampled rows."""
+    import ctypes as C
+    K = 768
+    shapes = [(1024, 2752), (5504, 1024), (1024, 1024), (3072, 1024), (200, 1024)]
+    probs = (B.GemmProblem * len(shapes))()
+    keep = []
+    for i, (M, N) in enumerate(shapes):
+        dy = q(RNG.standard_normal((K, M)), BF16)
+        x = q(RNG.standard_normal((K, N)), BF16)
+        c0 = torch.from_numpy(RNG.standard_normal((M, N)).astype(np.float32)).cuda()
+        DY, X = dev(dy, BF16), dev(x, BF16)
+        grouped, single = c0.clone(), c0.clone()
+        ok(lib().optstage_op_gemm(BF16, B.GEMM_TN, B.EPI_ACCUM, DY.data_ptr(), X.data_ptr(), single.data_ptr(), 0, M, N, K, M, N, N, stream()))
+        probs[i].A, probs[i].B, probs[i].C, probs[i].R = DY.data_ptr(), X.data_ptr(), grouped.data_ptr(), 0
+        probs[i].M, probs[i].N, probs[i].lda, probs[i].ldb, probs[i].ldc = M, N, M, N, N
+        keep.append((dy, x, c0, DY, X, grouped, single))
+    ok(lib().optstage_op_gemm_grouped(B.GEMM_TN, B.EPI_ACCUM, len(shapes), C.cast(probs, C.c_void_p), K, stream()))
+    torch.cuda.synchronize()
+    for dy, x, c0, DY, X, grouped, single in keep:
+        assert torch.equal(grouped, single)
+        rows = RNG.choice(dy.shape[1], size=min(16, dy.shape[1]), replace=False)
+        ref = host(c0)[rows] + dy[:, rows].T.astype(np.float64) @ x.astype(np.float64)
+        assert rel_err(host(grouped)[rows], ref) < 1e-4
+    # a set that does not qualify (K not a multiple of 64) is refused and nothing runs
+    assert lib().optstage_op_gemm_grouped(B.GEMM_TN, B.EPI_ACCUM, len(shapes), C.cast(probs, C.c_void_p), 72, stream()) == B.E_ARG
+
+
 def test_gemm_rejects_bad_shapes():
     A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
     f = lib().optstage_op_gemm
