@@ -262,101 +262,244 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16_t* __restrict
   if (g == 0) lse[((size_t)b * n_q + a) * seq + qglob] = m * scale + logf(lt);
 }
 
-// ---- backward, dQ: grid (n_q, batch, ceil(seq / 128)); 4 waves x 32 query rows; key blocks of 64 ---------
-// Also produces D_t = <dO_t, O_t> per query row and head (each wave holds its 32 rows of dO in registers
-// anyway) and stores it for the dK/dV kernel, which runs after this one.
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
-                                                           const bf16_t* __restrict__ dout, const float* __restrict__ lse,
-                                                           float* __restrict__ delta, bf16_t* __restrict__ dqkv, int seq,
-                                                           int n_q, int n_kv) {
-  __shared__ __attribute__((aligned(16))) char smem[3 * 16384];
-  char* sK = smem;
-  char* sV = smem + 16384;
-  char* sKt = smem + 32768;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c32 = lane & 31;
-  const FragAddr fr(c32, g);
-  const int nqb = (seq + 127) / 128;
-  const int q0 = (nqb - 1 - (int)blockIdx.z) * 128;
+// ---- backward, dQ: grid (n_q, batch, ceil(seq / 256)); 4 waves (one per SIMD) -----------------------------
+// Mirror image of the dK/dV kernel below.  Wave w owns queries q0 + 64 w .. + 63 as two 32-query tiles: their Q
+// and dO operand fragments stay in registers (128) and dQ^T ([d 128][64 queries]) in accumulator registers, so
+// every K / V fragment read from LDS feeds two MFMAs.  Key blocks of 64 (K and V rows) stream through a
+// two-stage LDS ring loaded straight from global memory; one copy of the K tile serves S^T = K Q^T (16-byte row
+// reads) and dQ^T += K^T dS^T (transposing reads), through the same chunk swizzle as in the dK/dV kernel.
+// Also produces D_t = <dO_t, O_t> per query row and head (from the dO fragments it holds anyway) and stores it
+// for the dK/dV kernel, which runs after this one.
+constexpr int DQ_STAGE = 32768;              // K tile, V tile of 64 keys
+constexpr int DQ_SMEM = 2 * DQ_STAGE;
+
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+                                                        const bf16_t* __restrict__ dout, const float* __restrict__ lse,
+                                                        float* __restrict__ delta, bf16_t* __restrict__ dqkv, int seq,
+                                                        int n_q, int n_kv) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nqb = (seq + 255) / 256;
+  const int q0 = (nqb - 1 - (int)blockIdx.z) * 256;          // longest rows are dispatched first, for every head
   const int a = blockIdx.x, b = blockIdx.y, kvh = a * n_kv / n_q;
-  const int ld = (n_q + 2 * n_kv) * D;
+  const int ld = (n_q + 2 * n_kv) * D, ldo = n_q * D;
   const bf16_t* base = qkv + (size_t)b * seq * ld;
-  const int qglob = q0 + 32 * wave + c32;
-  const int qrow = min(qglob, seq - 1);
-  const bf16_t* dop = dout + ((size_t)b * seq + qrow) * (n_q * D) + a * D;
-  const bf16_t* op = o + ((size_t)b * seq + qrow) * (n_q * D) + a * D;
-  bf16x8_t qf[8], dof[8];
-  float dsum = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)qrow * ld + a * D + 16 * ks + 8 * g);
-    dof[ks] = *reinterpret_cast<const bf16x8_t*>(dop + 16 * ks + 8 * g);
-    const bf16x8_t of = *reinterpret_cast<const bf16x8_t*>(op + 16 * ks + 8 * g);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) dsum = fmaf((float)dof[ks][e], (float)of[e], dsum);
-  }
+  const int wave_first_q = q0 + 64 * wave, wave_last_q = wave_first_q + 63;
   const float scale = rsqrtf((float)D), c = scale * LOG2E;
-  const float Lc = lse[((size_t)b * n_q + a) * seq + qrow] * LOG2E;
-  const float Dq = dsum + __shfl_xor(dsum, 32, 64);              // the two lanes of a row hold 64 columns each
-  if (g == 0 && qglob < seq) delta[((size_t)b * n_q + a) * seq + qglob] = Dq;
-  f32x16_t acc[4];
+
+  // Q, dO operand fragments of this wave's queries (rows past the end are clamped: their results are not stored),
+  // lse * log2(e) and D per query
+  bf16x8_t Qf[2][8], dOf[2][8];
+  float Lc[2], Dq[2];
+  int qglob[2];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int qt = 0; qt < 2; ++qt) {
+    qglob[qt] = wave_first_q + 32 * qt + c32;
+    const int qrow = min(qglob[qt], seq - 1);
+    const bf16_t* qp = base + (size_t)qrow * ld + (size_t)a * D + 8 * g;
+    const bf16_t* dop = dout + ((size_t)b * seq + qrow) * ldo + (size_t)a * D + 8 * g;
+    const bf16_t* op = o + ((size_t)b * seq + qrow) * ldo + (size_t)a * D + 8 * g;
+    float dsum = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
-  const int nkb = min((q0 + 127) / 64 + 1, (seq + 63) / 64);
-  const int wave_last_q = q0 + 32 * wave + 31;
-  uint4 kreg[4], vreg[4];
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, (unsigned)seq * ld * 2u);
-  const unsigned lane_off = tile_lane_offset(ld, tid);
-  const unsigned k_off = (unsigned)(n_q + kvh) * D * 2u, v_off = (unsigned)(n_q + n_kv + kvh) * D * 2u;
-  tile_load(kreg, rs, lane_off, k_off, ld);
-  tile_load(vreg, rs, lane_off, v_off, ld);
-  for (int kb = 0; kb < nkb; ++kb) {
-    __syncthreads();
-    tile_store_rowmajor(sK, kreg, tid);
-    tile_store_rowmajor(sV, vreg, tid);
-    tile_store_transposed(sKt, kreg, tid);
-    __syncthreads();
-    if (kb + 1 < nkb) {
-      const unsigned row_off = (unsigned)(64 * (kb + 1)) * ld * 2u;
-      tile_load(kreg, rs, lane_off, row_off + k_off, ld);
-      tile_load(vreg, rs, lane_off, row_off + v_off, ld);
+    for (int ks = 0; ks < 8; ++ks) {
+      Qf[qt][ks] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * ks);
+      dOf[qt][ks] = *reinterpret_cast<const bf16x8_t*>(dop + 16 * ks);
+      const bf16x8_t of = *reinterpret_cast<const bf16x8_t*>(op + 16 * ks);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dsum = fmaf((float)dOf[qt][ks][e], (float)of[e], dsum);
     }
-    if (64 * kb > wave_last_q) continue;
-    const bool diag = 64 * kb + 63 > q0 + 32 * wave;              // block touches the diagonal: mask
-    // the two 32-key halves of the block one after the other, so only one S / dP tile is live at a time
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      f32x16_t s, dp;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
-      score_tiles<true, true, false>(fr, sK, sV, t, nullptr, nullptr, 0, nullptr, nullptr, qf, dof, s, dp);
-      if (diag) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int key = 64 * kb + 32 * t + 8 * (v >> 2) + 4 * g + (v & 3);
-          float p = __builtin_amdgcn_exp2f(fmaf(s[v], c, -Lc));
-          if (key > qglob) p = 0.f;
-          s[v] = p * (dp[v] - Dq);                                // dS^T
-        }
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c, -Lc)) * (dp[v] - Dq);
-      }
-      accumulate_transposed(fr, sKt, t, s, acc);
-    }
+    Lc[qt] = -lse[((size_t)b * n_q + a) * seq + qrow] * LOG2E;
+    Dq[qt] = dsum + __shfl_xor(dsum, 32, 64);                  // the two lanes of a row hold 64 columns each
+    if (g == 0 && qglob[qt] < seq) delta[((size_t)b * n_q + a) * seq + qglob[qt]] = Dq[qt];
   }
-  if (qglob >= seq) return;
-  bf16_t* dq = dqkv + ((size_t)b * seq + qglob) * ld + a * D;
+  f32x16_t acc[2][4];                          // [query tile][d tile]: lane = query, registers = d
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[qt][dt][v] = 0.f;
+
+  int rm_addr[8];
+  {
+    const int f = ((c32 & 3) << 2) | ((c32 >> 2) & 3);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) rm_addr[ks] = c32 * 256 + (((2 * ks + g) ^ f) << 4);
+  }
+  int tr_addr[4][2];
+  {
+    const int cg = (lane >> 4) & 1, e = (lane >> 2) & 3, r = lane & 3;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int kq = 0; kq < 2; ++kq)
+        tr_addr[dt][kq] = (4 * g + e) * 256 + (((4 * dt + 2 * cg + (r >> 1)) ^ (e << 2) ^ g ^ (kq << 1)) << 4) + (r & 1) * 8;
+  }
+  // tile loads: one instruction fills 4 rows (1 KB); wave w loads rows 16 w .. 16 w + 15 of the K and of the V tile
+  unsigned voff[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = 16 * wave + 4 * j + (lane >> 4);
+    const int chunk = (lane & 15) ^ (((lane >> 4) << 2) | j);
+    voff[j] = (unsigned)row * (unsigned)ld * 2u + (unsigned)chunk * 16u;
+  }
+  auto make_desc = [](const void* p, unsigned bytes) {
+    const unsigned long long ad = (unsigned long long)p;
+    i32x4_t d;
+    d[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)ad);
+    d[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)(ad >> 32) & 0xffff);
+    d[2] = (int)bytes;
+    d[3] = 0x00020000;
+    return d;
+  };
+  const i32x4_t rs = make_desc(base, (unsigned)seq * ld * 2u);
+  const unsigned lds0 = (unsigned)(size_t)(lds_void_t*)smem;
+  const unsigned k_off = (unsigned)(n_q + kvh) * D * 2u, v_off = (unsigned)(n_q + n_kv + kvh) * D * 2u;
+  // All offsets go through the lane offset, which is what the range check sees: rows at or past seq read zero.
+  auto issue_block = [&](int kb, int stage) {
+    const unsigned rowoff = (unsigned)(64 * kb) * (unsigned)ld * 2u;
+    const unsigned dst = lds0 + stage * DQ_STAGE + (16 * wave) * 256;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      bf16x4_t r;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] = (bf16_t)(acc[dt][4 * j + i] * scale);
-      *reinterpret_cast<bf16x4_t*>(dq + 32 * dt + 8 * j + 4 * g) = r;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst + j * 1024), "v"(voff[j] + rowoff + k_off), "s"(rs) : "memory", "m0");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst + 16384 + j * 1024), "v"(voff[j] + rowoff + v_off), "s"(rs) : "memory", "m0");
     }
+  };
+  typedef short i16x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) i16x4_t lds_i16x4_t;
+  auto tr_frag = [&](const char* tile, int dt, int t, int u) {
+    const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t*)(tile + (32 * t + 16 * u) * 256 + tr_addr[dt][0]));
+    const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t*)(tile + (32 * t + 16 * u + 8) * 256 + tr_addr[dt][1]));
+    return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto rm_frag = [&](const char* tile, int t, int ks) {
+    return *reinterpret_cast<const bf16x8_t*>(tile + t * 8192 + rm_addr[ks]);
+  };
+
+#define OPTSTAGE_SB() __builtin_amdgcn_sched_barrier(0)
+#define OPTSTAGE_MFMA_V(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+  auto block = [&](int kb, int stage) {
+    if (64 * kb > wave_last_q) return;                           // block above this wave's diagonal
+    const char* sK = smem + stage * DQ_STAGE;
+    const char* sV = sK + 16384;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int key0 = 64 * kb + 32 * t;
+      if (key0 > wave_last_q) continue;                          // wave-uniform
+      const bool edge = key0 + 31 > wave_first_q;                // touches the diagonal (keys past seq are masked by it)
+      // lane = query, registers = keys key0 + 8 (v / 4) + 4 g + v % 4
+      f32x16_t s[2], dp[2];
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { s[qt][v] = 0.f; dp[qt][v] = 0.f; }
+      bf16x8_t kf[2], vf[2];
+      // ---- S^T = K Q^T
+      kf[0] = rm_frag(sK, t, 0);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        OPTSTAGE_SB();
+        if (ks < 7) kf[(ks + 1) & 1] = rm_frag(sK, t, ks + 1);
+        else vf[0] = rm_frag(sV, t, 0);
+        OPTSTAGE_SB();
+        OPTSTAGE_MFMA_V(s[0], kf[ks & 1], Qf[0][ks]);
+        OPTSTAGE_MFMA_V(s[1], kf[ks & 1], Qf[1][ks]);
+      }
+      // ---- dP^T = V dO^T, with the exponentials of S^T under its MFMAs
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        OPTSTAGE_SB();
+        if (ks < 7) vf[(ks + 1) & 1] = rm_frag(sV, t, ks + 1);
+        OPTSTAGE_SB();
+        OPTSTAGE_MFMA_V(dp[0], vf[ks & 1], dOf[0][ks]);
+        OPTSTAGE_MFMA_V(dp[1], vf[ks & 1], dOf[1][ks]);
+        OPTSTAGE_SB();
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int v = 2 * ks + e;
+#pragma unroll
+          for (int qt = 0; qt < 2; ++qt) s[qt][v] = __builtin_amdgcn_exp2f(fmaf(s[qt][v], c, Lc[qt]));
+        }
+      }
+      OPTSTAGE_SB();
+      if (edge) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = key0 + 8 * (v >> 2) + 4 * g + (v & 3);
+#pragma unroll
+          for (int qt = 0; qt < 2; ++qt)
+            if (key > qglob[qt]) s[qt][v] = 0.f;
+        }
+      }
+      // results of the matrix unit may be read by the vector unit only some cycles after the last pass
+      asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+      OPTSTAGE_SB();
+      // ---- dQ^T += K^T dS^T; dS^T = P^T (dP^T - D) of the second half runs under the MFMAs of the first
+      bf16x8_t trf[2];
+      trf[0] = tr_frag(sK, 0, t, 0);
+#pragma unroll
+      for (int v = 0; v < 8; ++v)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) dp[qt][v] = s[qt][v] * (dp[qt][v] - Dq[qt]);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8_t d0 = pack8(dp[0], u), d1 = pack8(dp[1], u);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          const int n = u * 4 + dt;
+          OPTSTAGE_SB();
+          if (n < 7) trf[(n + 1) & 1] = tr_frag(sK, (dt + 1) & 3, t, dt == 3 ? 1 : u);
+          OPTSTAGE_SB();
+          acc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trf[n & 1], d0, acc[0][dt], 0, 0, 0);
+          acc[1][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trf[n & 1], d1, acc[1][dt], 0, 0, 0);
+          OPTSTAGE_SB();
+          if (u == 0) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              const int v = 8 + 2 * dt + e;
+#pragma unroll
+              for (int qt = 0; qt < 2; ++qt) dp[qt][v] = s[qt][v] * (dp[qt][v] - Dq[qt]);
+            }
+          }
+        }
+      }
+      OPTSTAGE_SB();
+    }
+  };
+#undef OPTSTAGE_MFMA_V
+#undef OPTSTAGE_SB
+
+  const int nkb = min((q0 + 255) / 64 + 1, (seq + 63) / 64);
+  issue_block(0, 0);
+  for (int kb = 0; kb < nkb; kb += 2) {
+    // block kb has landed (this wave's part; the barrier covers the rest) and nobody still reads stage 1
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (kb + 1 < nkb) issue_block(kb + 1, 1);
+    block(kb, 0);
+    if (kb + 1 < nkb) {
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+      if (kb + 2 < nkb) issue_block(kb + 2, 0);
+      block(kb + 1, 1);
+    }
+  }
+
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    if (qglob[qt] >= seq) continue;
+    bf16_t* dq = dqkv + ((size_t)b * seq + qglob[qt]) * ld + (size_t)a * D;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x4_t r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (bf16_t)(acc[qt][dt][4 * j + i] * scale);
+        *reinterpret_cast<bf16x4_t*>(dq + 32 * dt + 8 * j + 4 * g) = r;
+      }
+  }
 }
 
 // ---- backward, dK / dV: grid (n_kv, batch, ceil(seq / 256)); 4 waves (one per SIMD) ----------------------
@@ -663,7 +806,13 @@ hipError_t launch_attn_fwd_mfma(const void* qkv, void* o, float* lse, int seq, i
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv, float* ws,
                                 int seq, int batch, int n_q, int n_kv, hipStream_t s) {
   hipError_t e;
-  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 127) / 128), dim3(256), 0, s, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
+  static bool dq_attr_set = false;
+  if (!dq_attr_set) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, DQ_SMEM);
+    if (e != hipSuccess) return e;
+    dq_attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 255) / 256), dim3(256), DQ_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   static bool attr_set = false;
