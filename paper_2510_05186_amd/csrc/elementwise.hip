@@ -93,22 +93,33 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, 
 #pragma unroll
     for (int e = 0; e < V::N; ++e) { pg[c][e] = 0.f; pb[c][e] = 0.f; }
   }
+  // two register sets: the loads of the next row are in flight while the current one is reduced and written
+  V xv[2][MAXC], dv[2][MAXC], rv[2][MAXC];
+  float mean_[2], r_[2];
+  auto load_row = [&](int buf, int row) {
+    if (LN) { mean_[buf] = stats[2 * row]; r_[buf] = stats[2 * row + 1]; } else { mean_[buf] = 0.f; r_[buf] = stats[row]; }
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = tid + c * NT;
+      if (ci < nvec) {
+        xv[buf][c] = *reinterpret_cast<const V*>(x + (size_t)row * h + ci * V::N);
+        dv[buf][c] = *reinterpret_cast<const V*>(dn + (size_t)row * h + ci * V::N);
+        if (dres) rv[buf][c] = *reinterpret_cast<const V*>(dres + (size_t)row * h + ci * V::N);
+      }
+    }
+  };
   int it = 0;
-  for (int row = blockIdx.x; row < rows; row += gridDim.x, ++it) {
-    float mean = 0.f, r;
-    if (LN) { mean = stats[2 * row]; r = stats[2 * row + 1]; } else r = stats[row];
-    V xv[MAXC], dv[MAXC];
+  auto process = [&](int buf, int row) {
+    const float mean = mean_[buf], r = r_[buf];
     float sg = 0.f, sgx = 0.f;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
       int ci = tid + c * NT;
       if (ci < nvec) {
-        xv[c] = *reinterpret_cast<const V*>(x + (size_t)row * h + ci * V::N);
-        dv[c] = *reinterpret_cast<const V*>(dn + (size_t)row * h + ci * V::N);
 #pragma unroll
         for (int e = 0; e < V::N; ++e) {
-          float xh = (xv[c].get(e) - mean) * r;
-          float d = dv[c].get(e);
+          float xh = (xv[buf][c].get(e) - mean) * r;
+          float d = dv[buf][c].get(e);
           float g = d * gv[c].get(e);
           sg += g;
           sgx += g * xh;
@@ -118,6 +129,7 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, 
       }
     }
     const int par = (it & 1) * 2;
+    ++it;
     // two reductions share one barrier: pack both partials before the sync
     sgx = wave_sum(sgx);
     sg = wave_sum(sg);
@@ -130,18 +142,29 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, 
     for (int c = 0; c < MAXC; ++c) {
       int ci = tid + c * NT;
       if (ci < nvec) {
-        V o, rs;
-        if (dres) rs = *reinterpret_cast<const V*>(dres + (size_t)row * h + ci * V::N);
+        V o;
 #pragma unroll
         for (int e = 0; e < V::N; ++e) {
-          float xh = (xv[c].get(e) - mean) * r;
-          float g = dv[c].get(e) * gv[c].get(e);
+          float xh = (xv[buf][c].get(e) - mean) * r;
+          float g = dv[buf][c].get(e) * gv[c].get(e);
           float d = r * (g - mg - xh * mgx);
-          if (dres) d += rs.get(e);
+          if (dres) d += rv[buf][c].get(e);
           o.set(e, d);
         }
         *reinterpret_cast<V*>(dx + (size_t)row * h + ci * V::N) = o;
       }
+    }
+  };
+  const int gd = gridDim.x;
+  int row = blockIdx.x;
+  if (row < rows) load_row(0, row);
+  for (; row < rows; row += 2 * gd) {
+    const int r1 = row + gd, r2 = row + 2 * gd;
+    if (r1 < rows) load_row(1, r1);
+    process(0, row);
+    if (r1 < rows) {
+      if (r2 < rows) load_row(0, r2);
+      process(1, r1);
     }
   }
   float* pgo = partial + (size_t)blockIdx.x * h;
@@ -166,10 +189,19 @@ __global__ __launch_bounds__(256) void norm_bwd_reduce_kernel(const float* __res
   const int cx = threadIdx.x & 31, rg = threadIdx.x >> 5;
   const int col = blockIdx.x * 32 + cx;
   const float* p = partial + (size_t)blockIdx.y * nb * h;
-  float s = 0.f;
-  if (col < h)
-    for (int b = rg; b < nb; b += 8) s += p[(size_t)b * h + col];
-  red[rg][cx] = s;
+  // four independent partial sums keep four loads in flight per lane; fixed combination order
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (col < h) {
+    int b = rg;
+    for (; b + 24 < nb; b += 32) {
+      s0 += p[(size_t)b * h + col];
+      s1 += p[(size_t)(b + 8) * h + col];
+      s2 += p[(size_t)(b + 16) * h + col];
+      s3 += p[(size_t)(b + 24) * h + col];
+    }
+    for (; b < nb; b += 8) s0 += p[(size_t)b * h + col];
+  }
+  red[rg][cx] = (s0 + s1) + (s2 + s3);
   __syncthreads();
   if (rg == 0 && col < h) {
     float t = 0.f;
