@@ -517,14 +517,19 @@ constexpr int DKV_STAGE = 32768 + 512;       // Q tile, dO tile, 64 lse, 64 D
 constexpr int DKV_VTILE = 256 * 256;         // V rows of the workgroup's keys, behind the two stages
 constexpr int DKV_SMEM = 2 * DKV_STAGE + DKV_VTILE;
 
+// With grouped-query attention a kv head's gradient sums over n_q / n_kv query heads and the grid has only
+// n_kv * batch * ceil(seq / 256) workgroups; `split` > 1 deals the query heads of a group to that many
+// workgroups, each writing an fp32 partial ([part][batch][seq][kv head][K|V][128]) that attn_bwd_dkv_reduce sums
+// in a fixed order.
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16_t* __restrict__ dqkv, int seq, int n_q, int n_kv) {
+                                                         bf16_t* __restrict__ dqkv, float* __restrict__ partial, int split,
+                                                         int seq, int n_q, int n_kv) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int k0 = blockIdx.z * 256;               // first key blocks (most queries) are dispatched first, for every head
-  const int kvh = blockIdx.x, b = blockIdx.y;
+  const int kvh = blockIdx.x / split, part = blockIdx.x % split, b = blockIdx.y;
   const int ld = (n_q + 2 * n_kv) * D, ldo = n_q * D;
   const bf16_t* base = qkv + (size_t)b * seq * ld;
   const int wave_first_k = k0 + 64 * wave;
@@ -600,12 +605,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds0 + 2 * DKV_STAGE + wave * 16384 + j * 1024), "v"(vo), "s"(rs_q) : "memory", "m0");
   }
-  const int rep = n_q / n_kv;
+  const int rep = n_q / n_kv / split;                          // query heads of the group handled here
   const int qb0 = k0 / 64, nqb = (seq + 63) / 64 - qb0;       // query blocks at or after the first key
   const int iters = rep * nqb;
   // All offsets go through the lane offset, which is what the range check sees: rows at or past seq read zero.
   auto issue_block = [&](int it, int stage) {
-    const int a = kvh * rep + it / nqb;
+    const int a = (kvh * split + part) * rep + it / nqb;
     const int r0 = 64 * (qb0 + it % nqb);
     const unsigned oq = ((unsigned)r0 * (unsigned)ld + (unsigned)a * D) * 2u;
     const unsigned od = ((unsigned)r0 * (unsigned)ldo + (unsigned)a * D) * 2u;
@@ -773,6 +778,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
   for (int kk = 0; kk < 2; ++kk) {
     const int kglob = wave_first_k + 32 * kk + c32;
     if (kglob >= seq) continue;
+    if (split > 1) {
+      float* prow = partial + ((((size_t)part * gridDim.y + b) * seq + kglob) * n_kv + kvh) * 2 * D;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          f32x4_t rk, rv;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { rk[i] = accK[kk][dt][4 * j + i]; rv[i] = accV[kk][dt][4 * j + i]; }
+          *reinterpret_cast<f32x4_t*>(prow + 32 * dt + 8 * j + 4 * g) = rk;
+          *reinterpret_cast<f32x4_t*>(prow + D + 32 * dt + 8 * j + 4 * g) = rv;
+        }
+      continue;
+    }
     bf16_t* krow = dqkv + ((size_t)b * seq + kglob) * ld + (size_t)(n_q + kvh) * D;
     bf16_t* vrow = dqkv + ((size_t)b * seq + kglob) * ld + (size_t)(n_q + n_kv + kvh) * D;
 #pragma unroll
@@ -791,7 +810,41 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
   }
 }
 
+// sums the `split` partials of dK, dV (fixed order), scales dK by 1 / sqrt(d) and stores bf16 into the packed
+// gradient rows: one thread per 4 columns of one (token, kv head, K|V)
+__global__ void attn_bwd_dkv_reduce(const float* __restrict__ partial, bf16_t* __restrict__ dqkv, int split, int rows,
+                                    int n_q, int n_kv) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t per_part = (size_t)rows * n_kv * 2 * D;
+  if (idx * 4 >= per_part) return;
+  const size_t e = idx * 4;
+  const int col = (int)(e % D);
+  const int kv = (int)((e / D) % 2);
+  const int h = (int)((e / (2 * D)) % n_kv);
+  const size_t row = e / ((size_t)2 * D * n_kv);
+  f32x4_t acc = *reinterpret_cast<const f32x4_t*>(partial + e);
+  for (int p = 1; p < split; ++p) {
+    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(partial + p * per_part + e);
+    acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+  }
+  const float sc = kv == 0 ? rsqrtf((float)D) : 1.f;
+  bf16x4_t o;
+  o[0] = (bf16_t)(acc[0] * sc); o[1] = (bf16_t)(acc[1] * sc); o[2] = (bf16_t)(acc[2] * sc); o[3] = (bf16_t)(acc[3] * sc);
+  const int ld = (n_q + 2 * n_kv) * D;
+  *reinterpret_cast<bf16x4_t*>(dqkv + row * ld + (size_t)(n_q + kv * n_kv + h) * D + col) = o;
+}
+
 }  // namespace
+
+// how many workgroups share the query heads of one kv head in the dK/dV kernel: enough to give every compute
+// unit about two workgroups, a divisor of n_q / n_kv
+int attn_dkv_split(int seq, int batch, int n_q, int n_kv) {
+  const int rep = n_q / n_kv;
+  const long wgs = (long)n_kv * batch * ((seq + 255) / 256);
+  int split = 1;
+  while (split < rep && wgs * split < 448 && rep % (split * 2) == 0) split *= 2;
+  return split;
+}
 
 // bf16, head_dim 128, and per-sequence tensors addressable with 32-bit byte offsets (buffer loads)
 bool attn_mfma_applies(int dtype, int d, int seq, int n_q, int n_kv) {
@@ -821,6 +874,14 @@ hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(attn_bwd_dkv_mfma, dim3(n_kv, batch, (seq + 255) / 256), dim3(256), DKV_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
+  const int split = attn_dkv_split(seq, batch, n_q, n_kv);
+  float* partial = ws + (size_t)batch * n_q * seq;            // behind the D array
+  hipLaunchKernelGGL(attn_bwd_dkv_mfma, dim3(n_kv * split, batch, (seq + 255) / 256), dim3(256), DKV_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, partial, split, seq, n_q, n_kv);
+  if (split > 1) {
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t quads = (size_t)batch * seq * n_kv * 2 * D / 4;
+    hipLaunchKernelGGL(attn_bwd_dkv_reduce, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, partial, (bf16_t*)dqkv, split, batch * seq, n_q, n_kv);
+  }
   return hipGetLastError();
 }

@@ -53,6 +53,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // launchers implemented in the .hip files; all return hipError_t from the launch
+int attn_dkv_split(int seq, int batch, int n_q, int n_kv);
 struct GemmProblem { const void* A; const void* B; void* C; const void* R; int M, N, lda, ldb, ldc; };
 bool gemm_bf16_grouped_applies(int layout, int n, const GemmProblem* problems, int K);
 hipError_t launch_gemm_bf16_grouped(int layout, int epi, int n, const GemmProblem* problems, int K, hipStream_t s);

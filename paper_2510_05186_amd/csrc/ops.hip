@@ -29,8 +29,14 @@ hipError_t launch_attn_bwd(int dtype, const void* qkv, const void* o, const void
 }
 
 uint64_t attn_bwd_ws_floats(int seq, int batch, int n_q, int n_kv, int d) {
-  (void)n_kv; (void)d;
-  return (uint64_t)batch * n_q * seq;   // D_t = <dO_t, O_t> per query row and head
+  // D_t = <dO_t, O_t> per query row and head, then (grouped-query attention on the MFMA path only) the fp32
+  // partials of dK, dV of the workgroups that share a kv head
+  uint64_t n = (uint64_t)batch * n_q * seq;
+  if (d == 128 && n_kv > 0 && n_q % n_kv == 0) {
+    const int split = attn_dkv_split(seq, batch, n_q, n_kv);
+    if (split > 1) n += (uint64_t)split * batch * seq * n_kv * 2 * d;
+  }
+  return n;
 }
 
 namespace {
