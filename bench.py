@@ -83,6 +83,9 @@ def device_io(cfg, mb, torch):
     return x.contiguous(), dy.contiguous()
 
 
+RECOMPUTE = 0   # --recompute: the memory-table variant in which F keeps no norm outputs and no MLP activation output
+
+
 def adaoffload_instance(cfg, budget, tflops=900.0, link_gbps=56.0):
     """The paper's abstract instance for this workload (all p stages alike): op times from the flop counts at a
     nominal rate, transfer time from the offloadable bytes at the measured host-link rate, Eq. 7's parameters
@@ -94,12 +97,13 @@ def adaoffload_instance(cfg, budget, tflops=900.0, link_gbps=56.0):
     att = cfg.micro_batch * cfg.seq * cfg.seq * cfg.n_q_heads * cfg.head_dim
     ms = lambda fl: cfg.n_layers * fl / (tflops * 1e9)
     t_op = {"F": ms(gemm + 2 * att), "B": ms(gemm + 5 * att), "W": ms(gemm)}
-    _, act_per_mb, kb = B.query_sizes(cfg)
+    _, act_per_mb, kb = B.query_sizes(cfg, recompute=RECOMPUTE)
     gamma = sum(kb[k] for k in cfg.offload_kinds) * cfg.n_layers
     slack = 2 * (kb["DY"] + kb["DX_MID"])                 # what B holds beyond the forward activations
+    rebuilt = RECOMPUTE * cfg.n_layers * (kb["N1"] + kb["N2"] + kb["A"])    # B makes them, W releases them
     p = cfg.n_stages
     return SC.Instance(p=p, m=cfg.n_microbatches, t_op=[t_op] * p, t_comm=0.0, t_off=[gamma / (link_gbps * 1e6)] * p,
-                       delta=[{"F": act_per_mb, "B": 0, "W": -act_per_mb}] * p, gamma=[gamma] * p,
+                       delta=[{"F": act_per_mb, "B": rebuilt, "W": -act_per_mb - rebuilt}] * p, gamma=[gamma] * p,
                        limit=[max(budget - slack, act_per_mb)] * p, offload_stages=tuple(range(p)),
                        item=(0, tuple(cfg.offload_kinds)))
 
@@ -117,7 +121,7 @@ def build_schedule(cfg, budget=0, generator="greedy"):
         inst = adaoffload_instance(cfg, budget)
         sol = SC.adaoffload(inst, tolerance=0.5 * inst.t_op[0]["F"])
         ev = SC.expand_items(sol.lists[i], cfg.n_layers, cfg.offload_kinds)
-        fits = lambda e: (lambda r: (r[0] == B.OK, r[1]))(B.plan(cfg, e, budget=budget))
+        fits = lambda e: (lambda r: (r[0] == B.OK, r[1]))(B.plan(cfg, e, budget=budget, recompute=RECOMPUTE))
         knobs = {"generator": "adaoffload", "offload": any(e[0] == "O" for e in ev), "placement": "as generated"}
         build_schedule.all_stages = [SC.expand_items(l, cfg.n_layers, cfg.offload_kinds) for l in sol.lists]
         if not fits(ev)[0]:
@@ -131,10 +135,10 @@ def build_schedule(cfg, budget=0, generator="greedy"):
         return G.split_bw_greedy(p, m)[i], {}
     for cap in range(p - i, 0, -1):
         comp = G.split_bw_greedy(p, m, cap_of_stage=lambda s, c=cap: c)[i]
-        if B.plan(cfg, comp, budget=budget)[0] == B.OK:
+        if B.plan(cfg, comp, budget=budget, recompute=RECOMPUTE)[0] == B.OK:
             return comp, {"in_flight_cap": cap, "offload": False}
         def fits(ev):
-            st, bad, _, _ = B.plan(cfg, ev, budget=budget)
+            st, bad, _, _ = B.plan(cfg, ev, budget=budget, recompute=RECOMPUTE)
             return st == B.OK, bad
         for lead in (2, 1):
             # optimistic placement (copies overlap neighbouring ops), then repaired against the planner
@@ -150,14 +154,15 @@ def build_schedule(cfg, budget=0, generator="greedy"):
 def make_stage(cfg, events, budget, torch, duplex=False):
     from paper_2510_05186_amd import binding as B
     from paper_2510_05186_amd.stage import Stage
-    _, _, peak, _ = B.plan(cfg, events, budget=0)
+    _, _, peak, _ = B.plan(cfg, events, budget=0, recompute=RECOMPUTE)
     n_off = sum(1 for e in events if e[0] == "O")
     pool = 0
     if n_off:
         kb = B.query_sizes(cfg)[2]
         per_mb = sum(kb[k] for k in cfg.offload_kinds) * cfg.n_layers
         pool = per_mb * cfg.n_microbatches
-    st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=pool, duplex=duplex)
+    st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=pool, duplex=duplex,
+               recompute=bool(RECOMPUTE))
     st.set_weights_device(device_weights(cfg, torch))
     for j in range(cfg.n_microbatches):
         x, dy = device_io(cfg, j, torch)
@@ -247,6 +252,8 @@ def main():
                     help="how the event list of a budgeted workload is produced")
     ap.add_argument("--duplex", action="store_true",
                     help="reloads on a stream of their own instead of the single transfer channel (offload workloads)")
+    ap.add_argument("--recompute", action="store_true",
+                    help="memory-table variant: F keeps no norm outputs and no MLP activation output, B rebuilds them")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a kernel of known traffic "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -265,6 +272,8 @@ def main():
         print("bench.py: no GPU visible; the stage has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = CFG.CONFIGS[args.config]
+    global RECOMPUTE
+    RECOMPUTE = int(args.recompute)
     budget = 0
     if cfg.budget_bytes:
         budget = cfg.budget_bytes
@@ -310,7 +319,7 @@ def main():
                    "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim, "ffn": cfg.ffn, "seq": cfg.seq,
                    "micro_batch": cfg.micro_batch, "stage": cfg.stage_index, "p": cfg.n_stages,
                    "m": cfg.n_microbatches, "schedule": cfg.schedule, "schedule_knobs": knobs,
-                   "events": len(events)},
+                   "events": len(events), "memory_table": "recompute n1, n2, a in B" if RECOMPUTE else "store all"},
         "frac_of_bf16_peak": value / peak_tf,
         "stage_busy_frac": busy_ms / ms_per_step,
         "stage_idle_frac": 1.0 - busy_ms / ms_per_step,

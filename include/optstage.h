@@ -80,6 +80,12 @@ typedef struct {
   uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, seq, micro_batch;
   uint32_t stage_index, n_stages, n_microbatches;   /* i, p, m */
   float norm_eps, rope_base;
+  uint32_t recompute;                   /* memory-table variant.  0: F keeps every kind it produces.  1: F keeps no
+                                           N1, N2, A (norm outputs and MLP activation output live in transients);
+                                           B rebuilds them from X_IN, X_MID, GU, bit for bit, and holds them for W.
+                                           Delta_F shrinks and Delta_B grows by their bytes; they cannot be
+                                           offloaded */
+  uint32_t reserved;                    /* 0 */
   uint64_t hbm_budget_bytes;            /* M_limit_i for activations (Eq. 7); 0 = unlimited */
   void* arena; uint64_t arena_bytes;          /* DEVICE block for activations, 256-byte aligned */
   void* workspace; uint64_t workspace_bytes;  /* DEVICE block for transients, >= optstage_query_sizes' figure */
@@ -125,8 +131,8 @@ typedef struct {
 
 /* The memory table (the parameters Delta and Gamma of Eq. 7): bytes of each activation kind for one
  * layer of one micro-batch (each rounded up to 256), written to bytes_per_kind[OPTSTAGE_N_KINDS] (HOST);
- * *act_bytes_per_mb = Delta_F = sum of the F kinds over all layers; *min_workspace = required
- * workspace_bytes.  Only the shape fields of desc are read.  Any out pointer may be null. */
+ * *act_bytes_per_mb = Delta_F = sum over all layers of the kinds F keeps (desc.recompute decides which);
+ * *min_workspace = required workspace_bytes.  Only the shape fields and recompute are read.  Any out pointer may be null. */
 optstage_status optstage_query_sizes(const optstage_desc* desc, uint64_t* min_workspace,
                                      uint64_t* act_bytes_per_mb, uint64_t* bytes_per_kind);
 

@@ -46,6 +46,7 @@ LLAMA = 1
 F_KINDS = ("X_IN", "N1", "QKV", "O", "LSE", "X_MID", "N2", "GU", "A", "STATS")
 B_KINDS = ("DY", "DX_MID")
 W_FREED = ("N1", "QKV", "O", "DX_MID", "N2", "GU", "A", "DY")
+RECOMPUTED = ("N1", "N2", "A")     # cheap functions of X_IN, X_MID, GU: the recompute variant does not keep them in F
 ALIGN = 256
 
 
@@ -71,23 +72,34 @@ def memory_table(family, hidden, n_q_heads, n_kv_heads, head_dim, ffn, tokens, e
     return {k: _round_up(v) for k, v in raw.items()}
 
 
-def op_memory_steps(op, n_layers):
+def op_memory_steps(op, n_layers, recompute=False):
     """Ordered (+1/-1, layer, kind) steps a compute op performs on the activation
     arena.  F keeps everything it produces.  B walks layers last to first: it
     creates the layer's output-gradient buffer DY (kept for W) and DX_MID (kept
     for W), and releases X_MID, LSE, X_IN, STATS once their last reader is done.
-    W releases everything still held."""
+    W releases everything still held.
+
+    recompute: the memory-table variant in which F keeps no N1, N2, A and B
+    rebuilds them for W (A and N2 before the MLP part of the layer is
+    differentiated, N1 before the attention part's norm), so Delta_F shrinks and
+    Delta_B grows by the same bytes while W is unchanged."""
     steps = []
     if op == "F":
         for l in range(n_layers):
             for k in F_KINDS:
-                steps.append((+1, l, k))
+                if not (recompute and k in RECOMPUTED):
+                    steps.append((+1, l, k))
     elif op == "B":
         steps.append((+1, n_layers - 1, "DY"))
         for l in reversed(range(n_layers)):
+            if recompute:
+                steps.append((+1, l, "A"))
+                steps.append((+1, l, "N2"))
             steps.append((+1, l, "DX_MID"))
             steps.append((-1, l, "X_MID"))
             steps.append((-1, l, "LSE"))
+            if recompute:
+                steps.append((+1, l, "N1"))
             if l > 0:
                 steps.append((+1, l - 1, "DY"))
             steps.append((-1, l, "X_IN"))
@@ -101,9 +113,9 @@ def op_memory_steps(op, n_layers):
     return steps
 
 
-def op_delta(op, n_layers, table):
+def op_delta(op, n_layers, table, recompute=False):
     """Net memory change Delta of a compute op (the parameter of Eq. 7)."""
-    return sum(sgn * table[k] for sgn, _, k in op_memory_steps(op, n_layers))
+    return sum(sgn * table[k] for sgn, _, k in op_memory_steps(op, n_layers, recompute))
 
 
 class ScheduleError(Exception):
@@ -112,8 +124,9 @@ class ScheduleError(Exception):
         self.index = index
 
 
-def check_order(events, n_microbatches, n_layers):
-    """Validity of one stage's list (raises ScheduleError naming the first bad event)."""
+def check_order(events, n_microbatches, n_layers, recompute=False):
+    """Validity of one stage's list (raises ScheduleError naming the first bad event).
+    In the recompute variant the kinds F does not keep cannot be offloaded."""
     done = {"F": set(), "B": set(), "W": set()}
     nxt = {"F": 0, "B": 0, "W": 0}
     state = {}                      # (j, layer, kind) -> "O" | "OWAIT" | "R"
@@ -141,7 +154,7 @@ def check_order(events, n_microbatches, n_layers):
             if not (0 <= layer < n_layers) or len(kinds) == 0:
                 raise ScheduleError(idx, "bad layer or empty kind set")
             for k in kinds:
-                if k not in F_KINDS:
+                if k not in F_KINDS or (recompute and k in RECOMPUTED):
                     raise ScheduleError(idx, f"kind {k} cannot be offloaded")
                 key = (j, layer, k)
                 st = state.get(key)
@@ -169,7 +182,7 @@ def check_order(events, n_microbatches, n_layers):
             raise ScheduleError(len(events), f"{key} never reloaded")
 
 
-def account_memory(events, n_layers, table, limit=None):
+def account_memory(events, n_layers, table, limit=None, recompute=False):
     """List-order logical accounting.  Returns (peak, trace) where trace[i] is the
     bytes in use after event i; raises ScheduleError at the first allocation
     that would exceed `limit` (checked before committing it)."""
@@ -179,7 +192,7 @@ def account_memory(events, n_layers, table, limit=None):
     for idx, ev in enumerate(events):
         op = ev[0]
         if op in ("F", "B", "W"):
-            steps = [(sgn, table[k]) for sgn, _, k in op_memory_steps(op, n_layers)]
+            steps = [(sgn, table[k]) for sgn, _, k in op_memory_steps(op, n_layers, recompute)]
         elif op == "OWAIT":
             steps = [(-1, table[k]) for k in ev[3]]
         elif op == "R":
@@ -200,7 +213,7 @@ def account_memory(events, n_layers, table, limit=None):
     return peak, trace
 
 
-def eq7_usage(events, n_layers, table):
+def eq7_usage(events, n_layers, table, recompute=False):
     """Memory in use during each compute op exactly as Eq. 7 counts it: the op's own
     Delta, plus Delta of every compute op ordered before it, minus Gamma of every
     offload completed before it, plus Gamma of every reload started before it."""
@@ -208,10 +221,10 @@ def eq7_usage(events, n_layers, table):
     for idx, ev in enumerate(events):
         if ev[0] not in ("F", "B", "W"):
             continue
-        use = op_delta(ev[0], n_layers, table)
+        use = op_delta(ev[0], n_layers, table, recompute)
         for prev in events[:idx]:
             if prev[0] in ("F", "B", "W"):
-                use += op_delta(prev[0], n_layers, table)
+                use += op_delta(prev[0], n_layers, table, recompute)
             elif prev[0] == "OWAIT":
                 use -= sum(table[k] for k in prev[3])
             elif prev[0] == "R":

@@ -30,6 +30,7 @@ class Desc(C.Structure):
                 ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32), ("ffn", C.c_uint32), ("seq", C.c_uint32),
                 ("micro_batch", C.c_uint32), ("stage_index", C.c_uint32), ("n_stages", C.c_uint32),
                 ("n_microbatches", C.c_uint32), ("norm_eps", C.c_float), ("rope_base", C.c_float),
+                ("recompute", C.c_uint32), ("reserved", C.c_uint32),
                 ("hbm_budget_bytes", C.c_uint64), ("arena", C.c_void_p), ("arena_bytes", C.c_uint64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64), ("host_pool", C.c_void_p),
                 ("host_pool_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
@@ -139,7 +140,7 @@ def make_events(events) -> "C.Array":
 
 
 def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_bytes=0, host_pool=0,
-              host_pool_bytes=0, compute_stream=0, copy_stream=0, reload_stream=0) -> Desc:
+              host_pool_bytes=0, compute_stream=0, copy_stream=0, reload_stream=0, recompute=0) -> Desc:
     d = Desc()
     d.struct_size = C.sizeof(Desc)
     d.family, d.dtype = cfg.family, cfg.dtype
@@ -153,21 +154,22 @@ def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_byte
     d.host_pool, d.host_pool_bytes = host_pool, host_pool_bytes
     d.compute_stream, d.copy_stream = compute_stream, copy_stream
     d.reload_stream = reload_stream
+    d.recompute = int(recompute)
     return d
 
 
-def query_sizes(cfg):
+def query_sizes(cfg, recompute=0):
     """-> (min_workspace, act_bytes_per_mb, {kind: bytes})"""
-    d = make_desc(cfg)
+    d = make_desc(cfg, recompute=recompute)
     ws, act = _u64(), _u64()
     kinds = (_u64 * N_KINDS)()
     check(lib().optstage_query_sizes(C.byref(d), C.byref(ws), C.byref(act), kinds))
     return ws.value, act.value, {k: kinds[i] for i, k in enumerate(KINDS)}
 
 
-def plan(cfg, events, budget=0):
+def plan(cfg, events, budget=0, recompute=0):
     """Pure-host validation + accounting.  -> (status, first_bad, peak_bytes, live_after list)."""
-    d = make_desc(cfg, budget=budget)
+    d = make_desc(cfg, budget=budget, recompute=recompute)
     arr = make_events(events)
     n = len(list(events)) if not isinstance(events, list) else len(events)
     bad = C.c_size_t(0)

@@ -44,6 +44,8 @@ namespace {
 constexpr uint64_t ALIGN = 256;
 constexpr int NK = OPTSTAGE_N_KINDS;
 constexpr int NFK = OPTSTAGE_N_F_KINDS;
+// kinds that are cheap functions of kinds F keeps anyway (norm outputs, MLP activation output)
+inline bool recomputable(int k) { return k == OPTSTAGE_K_N1 || k == OPTSTAGE_K_N2 || k == OPTSTAGE_K_A; }
 uint64_t round_up(uint64_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Shape {
@@ -53,7 +55,7 @@ struct Shape {
 optstage_status shape_from_desc(const optstage_desc* d, Shape* s) {
   if (!d) return fail(OPTSTAGE_E_ARG, "desc is null");
   if (d->struct_size != sizeof(optstage_desc)) return fail(OPTSTAGE_E_ARG, "desc.struct_size mismatch");
-  if (d->family > 1 || d->dtype > 1) return fail(OPTSTAGE_E_ARG, "bad family or dtype");
+  if (d->family > 1 || d->dtype > 1 || d->recompute > 1) return fail(OPTSTAGE_E_ARG, "bad family, dtype or recompute");
   if (!d->n_layers || !d->hidden || !d->n_q_heads || !d->n_kv_heads || !d->ffn || !d->seq || !d->micro_batch || !d->n_microbatches)
     return fail(OPTSTAGE_E_ARG, "zero-sized shape field");
   if (d->head_dim != 64 && d->head_dim != 128) return fail(OPTSTAGE_E_ARG, "head_dim must be 64 or 128");
@@ -138,6 +140,7 @@ struct MbState {
 // Pure host, copyable: everything the validator needs.
 struct Logical {
   int L = 0, m = 0;
+  bool recompute = false;   // F keeps no N1 / N2 / A; B rebuilds them for W
   uint64_t bytes[NK] = {}, budget = 0, live = 0, peak = 0;
   int next_f = 0, next_b = 0, next_w = 0;
   std::vector<MbState> mbs;
@@ -216,6 +219,7 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
       if (j != lg.next_f) return fail(OPTSTAGE_E_ORDER, "F ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_f, j);
       for (int l = 0; l < L; ++l)
         for (int k = 0; k < NFK; ++k) {
+          if (lg.recompute && recomputable(k)) continue;
           if ((st = alloc_dev(lg, j, l, k)) != OPTSTAGE_OK) return st;
           lg.buf(j, l, k).state = B_DEV;
           note(l, k);
@@ -230,6 +234,7 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
       if (j != lg.next_b) return fail(OPTSTAGE_E_ORDER, "B ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_b, j);
       for (int l = 0; l < L; ++l)
         for (int k = 0; k < NFK; ++k) {
+          if (lg.recompute && recomputable(k)) continue;
           uint8_t s = lg.buf(j, l, k).state;
           if (s != B_DEV && s != B_RELOADED)
             return fail(OPTSTAGE_E_ORDER, "B %d while layer %d kind %d is offloaded and not reloaded", j, l, k);
@@ -242,10 +247,17 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
       };
       auto drop = [&](int l, int k) { free_dev(lg, j, l, k); lg.buf(j, l, k).state = B_NONE; };
       if ((st = make(L - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
+      // every buffer is made before the kernel that first writes it and dropped after its last reader, in the
+      // order B enqueues its kernels: a region released here may be handed out again within the same op
       for (int l = L - 1; l >= 0; --l) {
+        if (lg.recompute) {
+          if ((st = make(l, OPTSTAGE_K_A)) != OPTSTAGE_OK) return st;
+          if ((st = make(l, OPTSTAGE_K_N2)) != OPTSTAGE_OK) return st;
+        }
         if ((st = make(l, OPTSTAGE_K_DX_MID)) != OPTSTAGE_OK) return st;
         drop(l, OPTSTAGE_K_X_MID);
         drop(l, OPTSTAGE_K_LSE);
+        if (lg.recompute && (st = make(l, OPTSTAGE_K_N1)) != OPTSTAGE_OK) return st;
         if (l > 0 && (st = make(l - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
         drop(l, OPTSTAGE_K_X_IN);
         drop(l, OPTSTAGE_K_STATS);
@@ -438,20 +450,25 @@ optstage_status exec_forward(optstage* st, int j, const OpBufs& ob) {
   auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
   HIP_TRY(hipMemcpyAsync(P(0, OPTSTAGE_K_X_IN), st->x_in[j], st->raw[OPTSTAGE_K_X_IN], hipMemcpyDeviceToDevice, cs));
   const int nstat = s.family == OPTSTAGE_LLAMA ? 1 : 2;
+  const bool rc = st->lg.recompute;
   for (int l = 0; l < s.L; ++l) {
     void* x = P(l, OPTSTAGE_K_X_IN);
     float* stats = (float*)P(l, OPTSTAGE_K_STATS);
-    TRY(k_norm_fwd(st, x, W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats));
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N1), W(st, l, OPTSTAGE_W_QKV), P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
+    // not kept: the norm outputs and the MLP activation output live in B's transient buffers, idle during F
+    void* n1 = rc ? (void*)(st->wsp() + st->ws.dn) : P(l, OPTSTAGE_K_N1);
+    void* n2 = rc ? (void*)(st->wsp() + st->ws.dn) : P(l, OPTSTAGE_K_N2);
+    void* a = rc ? (void*)(st->wsp() + st->ws.da) : P(l, OPTSTAGE_K_A);
+    TRY(k_norm_fwd(st, x, W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), n1, stats));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, n1, W(st, l, OPTSTAGE_W_QKV), P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
     if (s.family == OPTSTAGE_LLAMA)
       TRY(k_rope(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), 0));
     TRY(k_attn_fwd(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), (float*)P(l, OPTSTAGE_K_LSE)));
     TRY(k_gemm(st, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_O), W(st, l, OPTSTAGE_W_O), P(l, OPTSTAGE_K_X_MID), x, T, s.h, s.nq * s.d, s.nq * s.d, s.nq * s.d, s.h));
-    TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T));
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_N2), W(st, l, OPTSTAGE_W_GU), P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
-    TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_A)));
+    TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), n2, stats + (size_t)nstat * T));
+    TRY(k_gemm(st, GEMM_NT, EPI_STORE, n2, W(st, l, OPTSTAGE_W_GU), P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
+    TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), a));
     void* y = l + 1 < s.L ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[j];
-    TRY(k_gemm(st, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_A), W(st, l, OPTSTAGE_W_D), y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
+    TRY(k_gemm(st, GEMM_NT, EPI_RESID, a, W(st, l, OPTSTAGE_W_D), y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
   }
   return OPTSTAGE_OK;
 }
@@ -464,14 +481,17 @@ optstage_status exec_backward_input(optstage* st, int j, const OpBufs& ob) {
   char* ws = st->wsp();
   void *da = ws + st->ws.da, *dn = ws + st->ws.dn, *dout = ws + st->ws.dout, *dqkv = ws + st->ws.dqkv;
   const int nstat = s.family == OPTSTAGE_LLAMA ? 1 : 2;
+  const bool rc = st->lg.recompute;
   HIP_TRY(hipMemcpyAsync(P(s.L - 1, OPTSTAGE_K_DY), st->dy_out[j], st->raw[OPTSTAGE_K_DY], hipMemcpyDeviceToDevice, cs));
   for (int l = s.L - 1; l >= 0; --l) {
     void* dy = P(l, OPTSTAGE_K_DY);
     float* stats = (float*)P(l, OPTSTAGE_K_STATS);
     // da = dy W_d ; dgu = act'(gu) da (over gu) ; dn2 = dgu W_gu
     TRY(k_gemm(st, GEMM_NT, EPI_STORE, dy, WT(st, l, OPTSTAGE_W_D), da, nullptr, T, s.f, s.h, s.h, s.h, s.f));
+    if (rc) TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_A)));   // W's operand, before gu is overwritten
     TRY(k_act_bwd(st, da, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_GU)));
     TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_GU), WT(st, l, OPTSTAGE_W_GU), dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h));
+    if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T));
     // dx_mid = dy + norm2'(dn2)
     TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2)));
     // do = dx_mid W_o ; attention backward ; rotary backward into the qkv buffer
@@ -483,6 +503,7 @@ optstage_status exec_backward_input(optstage* st, int j, const OpBufs& ob) {
       HIP_TRY(hipMemcpyAsync(P(l, OPTSTAGE_K_QKV), dqkv, st->raw[OPTSTAGE_K_QKV], hipMemcpyDeviceToDevice, cs));
     // dn1 = dqkv W_qkv ; dx_in = dx_mid + norm1'(dn1)
     TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_QKV), WT(st, l, OPTSTAGE_W_QKV), dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h));
+    if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_IN), W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats));
     void* dx = l > 0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[j];
     TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1)));
   }
@@ -628,6 +649,7 @@ void reset_logical(optstage* st) {
   lg.L = st->sh.L;
   lg.m = st->desc.n_microbatches;
   lg.budget = st->desc.hbm_budget_bytes;
+  lg.recompute = st->desc.recompute != 0;
   lg.live = lg.peak = 0;
   lg.next_f = lg.next_b = lg.next_w = 0;
   lg.mbs.assign(lg.m, MbState());
@@ -652,7 +674,7 @@ optstage_status optstage_query_sizes(const optstage_desc* desc, uint64_t* min_wo
   uint64_t per_layer = 0;
   for (int k = 0; k < NK; ++k) {
     if (bytes_per_kind) bytes_per_kind[k] = round_up(raw[k]);
-    if (k < NFK) per_layer += round_up(raw[k]);
+    if (k < NFK && !(desc->recompute && recomputable(k))) per_layer += round_up(raw[k]);
   }
   if (act_bytes_per_mb) *act_bytes_per_mb = per_layer * s.L;
   if (min_workspace) *min_workspace = workspace_layout(s).total;
@@ -750,6 +772,7 @@ optstage_status optstage_validate(const optstage_t* st, const optstage_event* ev
   lg.L = st->sh.L;
   lg.m = st->desc.n_microbatches;
   lg.budget = st->desc.hbm_budget_bytes;
+  lg.recompute = st->desc.recompute != 0;
   memcpy(lg.bytes, st->lg.bytes, sizeof lg.bytes);
   lg.mbs.assign(lg.m, MbState());
   lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());
@@ -782,6 +805,7 @@ optstage_status optstage_plan(const optstage_desc* desc, const optstage_event* e
   lg.L = s.L;
   lg.m = desc->n_microbatches;
   lg.budget = desc->hbm_budget_bytes;
+  lg.recompute = desc->recompute != 0;
   for (int k = 0; k < NK; ++k) lg.bytes[k] = round_up(raw[k]);
   lg.mbs.assign(lg.m, MbState());
   lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());

@@ -299,7 +299,9 @@ def est_start_first_backward(inst: Instance):
 def adaoffload(inst: Instance, tolerance: float = 0.0, lead: int = 1) -> Solution:
     """Alg. 1, in bytes: a forward activation costs Delta_F while on the device and Delta_F - Gamma once its
     offload has ended (Gamma < Delta_F when only some tensor kinds are offloaded); a stage without a limit
-    holds everything.
+    holds everything.  Where Delta_B > 0 (a memory table in which B rebuilds tensors that F did not keep) a
+    micro-batch between its B and its W costs Delta_F + Delta_B, and room for the next B's growth is kept free
+    the way Gamma is kept free for the next reload.
       Step 1  EstStart(B_{s,0}) per stage (est_start_first_backward).
       Step 2  forward ops are placed back to back, each followed by its offload, until the next one would end
               after EstStart + tolerance or would not fit even with the offloads that have completed by then.
@@ -317,13 +319,17 @@ def adaoffload(inst: Instance, tolerance: float = 0.0, lead: int = 1) -> Solutio
     layer, kinds = inst.item
     kinds = tuple(kinds)
     dF = [inst.delta[s]["F"] for s in range(p)]
+    dB = [max(0, inst.delta[s]["B"]) for s in range(p)]
     can_off = [s in inst.offload_stages and inst.gamma[s] > 0 and inst.limit[s] is not None for s in range(p)]
 
-    def fits(s, n_on_device, n_away, offloading):
+    def held(s, n_on_device, n_away, n_after_b):
+        return n_on_device * dF[s] + n_away * (dF[s] - inst.gamma[s]) + n_after_b * dB[s]
+
+    def fits(s, n_on_device, n_away, offloading, n_after_b=0):
         if inst.limit[s] is None:
             return True
-        reserve = inst.gamma[s] if offloading else 0
-        return n_on_device * dF[s] + n_away * (dF[s] - inst.gamma[s]) + dF[s] + reserve <= inst.limit[s]
+        reserve = (inst.gamma[s] if offloading else 0) + dB[s]
+        return held(s, n_on_device, n_away, n_after_b) + dF[s] + reserve <= inst.limit[s]
 
     def fill_of(s, offloading):
         T, to = inst.t_op[s], inst.t_off[s]
@@ -362,12 +368,13 @@ def adaoffload(inst: Instance, tolerance: float = 0.0, lead: int = 1) -> Solutio
         op of the stage finishes): an offloaded activation shrinks when its offload ends, except the item of
         the next backward op, which is kept or already reloaded."""
         live = list(range(nw[s], nf[s]))
+        after_b = nb[s] - nw[s]
         if not offloading[s]:
-            return t if fits(s, len(live), 0, False) else None
+            return t if fits(s, len(live), 0, False, after_b) else None
         stay = sum(1 for j in live if j <= nb[s])
         away = sorted(o_end[s][j] for j in live if j > nb[s])
         for k in range(len(away) + 1):                                # k offloads have ended
-            if fits(s, stay + len(away) - k, k, True):
+            if fits(s, stay + len(away) - k, k, True, after_b):
                 return t if k == 0 else max(t, away[k - 1])
         return None
 
@@ -384,7 +391,11 @@ def adaoffload(inst: Instance, tolerance: float = 0.0, lead: int = 1) -> Solutio
                     ready = dep + (inst.t_comm if s < p - 1 else 0.0)
                     if offloading[s] and jb in o_end[s]:
                         ready = max(ready, o_end[s][jb] + inst.t_off[s])      # offload ended, reload done
-                    cands.append((max(t_free[s], ready), 0, "B", jb))
+                    # B's own growth must fit; if it does not, a pending weight-gradient op releases memory first
+                    n_live = nf[s] - nw[s]
+                    grows = dB[s] and inst.limit[s] is not None
+                    if not grows or nw[s] == nb[s] or held(s, n_live, 0, nb[s] - nw[s]) + dB[s] <= inst.limit[s]:
+                        cands.append((max(t_free[s], ready), 0, "B", jb))
             if jf < m:
                 dep = end.get((s - 1, jf, "F")) if s > 0 else 0.0
                 if dep is not None:
@@ -425,14 +436,14 @@ def adaoffload(inst: Instance, tolerance: float = 0.0, lead: int = 1) -> Solutio
             nw[s] += 1
         remaining -= 1
 
-    lists = [_with_transfers(order[s], offloading[s], inst.limit[s], dF[s], inst.gamma[s], lead, layer, kinds)
+    lists = [_with_transfers(order[s], offloading[s], inst.limit[s], dF[s], inst.gamma[s], lead, layer, kinds, dB[s])
              for s in range(p)]
     return Solution(lists=lists, makespan=max(end[(s, m - 1, "W")] for s in range(p)),
                     start={k: v - inst.t_op[k[0]][k[2]] for k, v in end.items()},
                     offloaded={(s, j): bool(offloading[s]) for s in range(p) for j in range(m)}, status="adaoffload")
 
 
-def _with_transfers(order, offloading, limit, d_f, gamma, lead, layer, kinds):
+def _with_transfers(order, offloading, limit, d_f, gamma, lead, layer, kinds, d_b=0):
     """Inserts O / OWAIT / R into one stage's compute order: O right after every forward op; R `lead` compute ops
     ahead of its backward op (never before its own forward op); OWAIT as late as possible, i.e. right before the
     forward op or reload that would not fit otherwise (oldest offload first), or right before its own reload."""
@@ -466,8 +477,11 @@ def _with_transfers(order, offloading, limit, d_f, gamma, lead, layer, kinds):
         if c == "F":
             make_room(d_f)
             used += d_f
+        elif c == "B" and d_b:
+            make_room(d_b)
+            used += d_b
         elif c == "W":
-            used -= d_f
+            used -= d_f + d_b
         out.append((c, j))
         if c == "F":
             out.append(("O", j, layer, kinds))

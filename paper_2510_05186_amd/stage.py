@@ -33,16 +33,19 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 
 class Stage:
     def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0,
-                 duplex: bool = False):
-        """duplex: reloads get a stream of their own instead of sharing the offloads' (single channel)."""
+                 duplex: bool = False, recompute: bool = False):
+        """duplex: reloads get a stream of their own instead of sharing the offloads' (single channel).
+        recompute: F keeps no norm outputs and no MLP activation output; B rebuilds them for W."""
         if not torch.cuda.is_available():
             raise RuntimeError("optstage needs a GPU: there is no CPU path")
         self.cfg = cfg
         self.lib = B.lib()
-        ws_bytes, act_per_mb, self.kind_bytes = B.query_sizes(cfg)
+        self.recompute = bool(recompute)
+        ws_bytes, act_per_mb, self.kind_bytes = B.query_sizes(cfg, recompute=int(recompute))
         self.act_bytes_per_mb = act_per_mb
         if arena_bytes is None:
-            arena_bytes = int((budget if budget else act_per_mb * cfg.n_microbatches) * 1.25) + (64 << 20)
+            full = act_per_mb if not recompute else B.query_sizes(cfg)[1]   # B and W hold the rebuilt kinds too
+            arena_bytes = int((budget if budget else full * cfg.n_microbatches) * 1.25) + (64 << 20)
         self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         self.host_pool = torch.empty(host_pool_bytes, dtype=torch.uint8, pin_memory=True) if host_pool_bytes else None
@@ -53,7 +56,7 @@ class Stage:
             host_pool=self.host_pool.data_ptr() if self.host_pool is not None else 0,
             host_pool_bytes=host_pool_bytes, compute_stream=self.compute_stream.cuda_stream,
             copy_stream=self.copy_stream.cuda_stream,
-            reload_stream=self.reload_stream.cuda_stream if duplex else 0)
+            reload_stream=self.reload_stream.cuda_stream if duplex else 0, recompute=int(recompute))
         h = C.c_void_p()
         B.check(self.lib.optstage_create(C.byref(self.desc), C.byref(h)))
         self.h = h

@@ -47,6 +47,40 @@ def test_memory_table_matches_oracle(cfg):
     assert ws > 0
 
 
+@pytest.mark.parametrize("cfg", [CFG.CFG1, CFG.CFG2, CFG.CFG4], ids=lambda c: c.name)
+def test_recompute_memory_table_matches_oracle(cfg):
+    _, act, kinds = B.query_sizes(cfg, recompute=1)
+    t = oracle_table(cfg)
+    assert kinds == t
+    assert act == S.op_delta("F", cfg.n_layers, t, recompute=True) < S.op_delta("F", cfg.n_layers, t)
+
+
+def test_recompute_plan_matches_oracle_accounting():
+    cfg = small_cfg()
+    t = oracle_table(cfg)
+    p, m, L = 4, cfg.n_microbatches, cfg.n_layers
+    lists = [G.one_f_one_b(p, m, i) for i in range(p)] + G.split_bw_greedy(p, m)
+    more = [G.add_offload(base, L, ("X_IN", "QKV", "X_MID", "GU"), min_gap=gap, lead=1) for base in lists for gap in (1, 3)]
+    for ev in lists + more:
+        S.check_order(ev, m, L, recompute=True)
+        peak, trace = S.account_memory(ev, L, t, recompute=True)
+        st, bad, lib_peak, live = B.plan(cfg, ev, recompute=1)
+        assert st == B.OK, B.lib().optstage_last_error()
+        assert lib_peak == peak and live == trace
+        assert peak < S.account_memory(ev, L, t)[0]
+        st, bad, _, _ = B.plan(cfg, ev, budget=peak - 1, recompute=1)
+        assert st == B.E_BUDGET
+        with pytest.raises(S.ScheduleError) as ei:
+            S.account_memory(ev, L, t, limit=peak - 1, recompute=True)
+        assert ei.value.index == bad
+    # a kind F does not keep cannot be offloaded: same event rejected on both sides
+    ev = G.add_offload(lists[0], L, ("N2",), min_gap=1)
+    with pytest.raises(S.ScheduleError) as ei:
+        S.check_order(ev, m, L, recompute=True)
+    st, bad, _, _ = B.plan(cfg, ev, recompute=1)
+    assert st == B.E_ORDER and bad == ei.value.index
+
+
 def small_cfg(m=6, L=3):
     return CFG.shrunken(CFG.CFG4, hidden=256, n_q=4, n_kv=2, ffn=384, seq=192, n_layers=L, n_microbatches=m)
 

@@ -267,6 +267,55 @@ def test_duplex_reload_stream_changes_no_bit():
     b.close()
 
 
+@pytest.mark.parametrize("cfg", [SMALL2, SMALL4, SMALLG], ids=lambda c: c.name)
+def test_recompute_variant_changes_no_bit_and_accounts_like_the_oracle(cfg):
+    """Memory-table variant: F keeps no norm outputs and no MLP activation output, B rebuilds them for W.  Same
+    kernels on the same inputs, so every result is bitwise the store-all one; the accounting follows the
+    oracle's variant table; a budget between the two peaks admits only the variant."""
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    base = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches)[cfg.stage_index]
+    events = G.add_offload(base, cfg.n_layers, ("QKV", "GU", "X_MID"), min_gap=1, lead=1)
+    assert any(e[0] == "O" for e in events)
+    S.check_order(events, cfg.n_microbatches, cfg.n_layers, recompute=True)
+    peak_full, _ = S.account_memory(events, cfg.n_layers, t)
+    peak_var, trace = S.account_memory(events, cfg.n_layers, t, recompute=True)
+    assert peak_var < peak_full
+    budget = (peak_var + peak_full) // 2
+    pool = sum(t[k] for k in ("QKV", "GU", "X_MID")) * cfg.n_layers * cfg.n_microbatches
+
+    ref_st = gpu_run(cfg, ws, base)                      # store-all, no offload, no budget
+    full = Stage(cfg, budget=budget, host_pool_bytes=pool, arena_bytes=2 * peak_full)
+    assert full.validate(events)[0] == B.E_BUDGET
+    full.close()
+
+    st = Stage(cfg, budget=budget, host_pool_bytes=pool, arena_bytes=2 * peak_full, recompute=True)
+    assert st.act_bytes_per_mb == S.op_delta("F", cfg.n_layers, t, recompute=True)
+    st.set_weights(ws)
+    for j in range(cfg.n_microbatches):
+        st.bind(j, T.stage_input(cfg, j), T.output_grad(cfg, j))
+    assert st.validate(events)[0] == B.OK, B.lib().optstage_last_error()
+    for it in range(2):                                  # second iteration on the same handle after a reset
+        st.run(events)
+        st.synchronize()
+        s = st.stats()
+        assert s.peak_bytes == peak_var <= budget and s.live_bytes == trace[-1] == 0
+        for j in range(cfg.n_microbatches):
+            assert torch.equal(st.y[j], ref_st.y[j]) and torch.equal(st.dx[j], ref_st.dx[j])
+        for l in range(cfg.n_layers):
+            for name in st.grads[l]:
+                assert torch.equal(st.grads[l][name], ref_st.grads[l][name]), (it, l, name)
+        st.reset()
+        st.zero_grads()
+    # the kinds F does not keep are not there to offload
+    bad = G.add_offload(base, cfg.n_layers, ("N1",), min_gap=1)
+    code, idx = st.validate(bad)
+    assert code == B.E_ORDER and bad[idx][0] == "O"
+    compare(cfg, ref_st, oracle_run(cfg, ws))
+    st.close()
+    ref_st.close()
+
+
 def test_online_schedule_swap_on_one_handle():
     """A different event list every iteration on the same handle (no re-creation): results stay bitwise the
     same, accounting follows the list that ran (the paper swaps in better schedules while training runs,

@@ -231,6 +231,49 @@ def test_memory_table_values():
     assert t["X_IN"] == 256 and t["STATS"] == 256 and t["GU"] == 256
 
 
+def test_recompute_variant_of_the_memory_table():
+    """F keeps no norm outputs and no MLP activation output; B rebuilds them for W.  The figures are worked out
+    by hand from the shapes, not through the table code."""
+    # llama 7B layer, per token in bf16: kept by F in the store-all table 16 h + 6 f + 4 n_q + 8 bytes
+    # (x_in, n1, x_mid, n2, o: 2 h each; qkv 6 h; gu 4 f; a 2 f; lse 4 n_q; rstd x2 8); the variant drops 4 h + 2 f
+    h, f, nq, tok = 4096, 11008, 32, 8192
+    t = S.memory_table(S.LLAMA, h, nq, nq, 128, f, tok, 2)
+    full, var = S.op_delta("F", 1, t), S.op_delta("F", 1, t, recompute=True)
+    assert full == tok * (16 * h + 6 * f + 4 * nq + 8)
+    assert full - var == tok * (4 * h + 2 * f)
+    assert abs((full - var) / full - 0.2915) < 1e-4
+    for Ln in (1, 3):
+        d0 = [S.op_delta(c, Ln, TABLE) for c in "FBW"]
+        d1 = [S.op_delta(c, Ln, TABLE, recompute=True) for c in "FBW"]
+        moved = Ln * (TABLE["N1"] + TABLE["N2"] + TABLE["A"])
+        assert d1 == [d0[0] - moved, d0[1] + moved, d0[2]] and sum(d1) == 0
+    # one layer, one micro-batch, by hand: B holds dy, then a, n2, dx_mid on top of what F kept, drops x_mid and
+    # lse, adds n1, drops x_in and stats
+    T1 = TABLE
+    kept = sum(T1[k] for k in S.F_KINDS if k not in ("N1", "N2", "A"))
+    ev = [("F", 0), ("B", 0), ("W", 0)]
+    peak, trace = S.account_memory(ev, 1, T1, recompute=True)
+    in_b = kept + T1["DY"] + T1["A"] + T1["N2"] + T1["DX_MID"]
+    assert trace[0] == kept and peak == max(in_b, in_b - T1["X_MID"] - T1["LSE"] + T1["N1"])
+    assert trace[1] == in_b - T1["X_MID"] - T1["LSE"] + T1["N1"] - T1["X_IN"] - T1["STATS"] and trace[2] == 0
+    # same list, store-all: after B the two variants hold the same bytes (W's operands)
+    assert S.account_memory(ev, 1, T1)[1][1] == trace[1]
+    # every F ahead of every B: the peak falls inside B 0, where the variant holds a subset of the store-all
+    # buffers of micro-batch 0 and none of the three kinds for the m - 1 micro-batches still waiting for B
+    m = 5
+    ev = [("F", j) for j in range(m)] + [(c, j) for j in range(m) for c in "BW"]
+    p0, _ = S.account_memory(ev, L, TABLE)
+    p1, _ = S.account_memory(ev, L, TABLE, recompute=True)
+    moved = L * (TABLE["N1"] + TABLE["N2"] + TABLE["A"])
+    assert (m - 1) * moved <= p0 - p1 <= m * moved
+    # the kinds F does not keep cannot be offloaded
+    bad = [("F", 0), ("O", 0, 0, ("N1",)), ("OWAIT", 0, 0, ("N1",)), ("R", 0, 0, ("N1",)), ("B", 0), ("W", 0)]
+    S.check_order(bad, 1, 1)
+    with pytest.raises(S.ScheduleError) as ei:
+        S.check_order(bad, 1, 1, recompute=True)
+    assert ei.value.index == 1
+
+
 # ------------------------------------------------------------------ brute force
 def all_orders(m):
     ops = [(c, j) for j in range(m) for c in "FBW"]

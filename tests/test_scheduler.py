@@ -196,3 +196,32 @@ def test_adaoffload_lists_are_valid_and_dense(p, m):
     if (p, m) == (2, 3):
         opt = SC.milp_schedule(inst, strict_eq13=False, cutoff=sol.makespan)
         assert opt.makespan <= tm.makespan_global + 1e-6
+
+
+@pytest.mark.parametrize("p,m", [(2, 4), (4, 8)])
+def test_adaoffload_with_a_memory_table_in_which_b_grows(p, m):
+    """Recompute variant of the table: Delta_F is smaller and Delta_B > 0 (B rebuilds what W reads).  The lists
+    must fit the limit in the oracle's accounting of that variant, and hold more forward activations before
+    the first B than the store-all table allows under the same limit."""
+    t_op = [{"F": 1.0, "B": 1.3, "W": 0.8}] * p
+    kinds = tuple(k for k in S.F_KINDS if k not in S.RECOMPUTED)
+    d_var = {c: S.op_delta(c, L, TABLE, recompute=True) for c in "FBW"}
+    assert d_var["B"] > 0
+    slack = 2 * (TABLE["DY"] + TABLE["DX_MID"])          # B's transients inside the op
+    limit = 3 * DELTA["F"] + slack
+    fills = {}
+    for name, delta, rc in (("store_all", DELTA, False), ("recompute", d_var, True)):
+        inst = SC.Instance(p=p, m=m, t_op=t_op, t_comm=0.05, t_off=[0.4] * p, delta=[delta] * p,
+                           gamma=[sum(TABLE[k] for k in kinds) * L] * p, limit=[limit - slack] * p,
+                           offload_stages=tuple(range(p)), item=(0, kinds))
+        sol = SC.adaoffload(inst, tolerance=0.5)
+        lists = [SC.expand_items(lst, L, kinds) for lst in sol.lists]
+        for lst in lists:
+            S.check_order(lst, m, L, recompute=rc)
+            peak, _ = S.account_memory(lst, L, TABLE, recompute=rc)
+            assert peak <= limit, (name, peak, limit)
+        S.simulate(lists, t_op, t_comm=0.05, t_copy=lambda i, ev: 0.4 / L)
+        lst = lists[0]
+        first_b = next(n for n, e in enumerate(lst) if e[0] == "B")
+        fills[name] = sum(1 for e in lst[:first_b] if e[0] == "F")
+    assert fills["recompute"] >= fills["store_all"]
