@@ -256,6 +256,15 @@ def _merge_qkv(q, k, v):
     return np.concatenate([q.reshape(s, -1), k.reshape(s, -1), v.reshape(s, -1)], axis=1)
 
 
+def _sequences(sh: StageShape, rows: int):
+    """Row ranges of the sequences of one micro-batch: a micro-batch of size b holds b
+    sequences of sh.seq tokens, stored one after the other; attention and rotary
+    positions are per sequence."""
+    if rows % sh.seq:
+        raise ValueError(f"{rows} rows are not a whole number of sequences of {sh.seq} tokens")
+    return [slice(b * sh.seq, (b + 1) * sh.seq) for b in range(rows // sh.seq)]
+
+
 def layer_forward(sh: StageShape, w: dict, x, attn_chunk=None):
     """Returns (y, saved).  saved holds every tensor the store-all inventory keeps:
     x_in, n1, qkv (after rotary), o, lse, x_mid, n2, gu, a and the norm statistics."""
@@ -268,11 +277,14 @@ def layer_forward(sh: StageShape, w: dict, x, attn_chunk=None):
         sv["mu1"], sv["r1"] = mu1, r1
     qkv = linear_fwd(n1, w["wqkv"])
     q, k, v = _split_qkv(sh, qkv)
+    seqs = _sequences(sh, x.shape[0])
     if sh.family == LLAMA:
-        q = rope_apply(q, sh.rope_base)
-        k = rope_apply(k, sh.rope_base)
+        q = np.concatenate([rope_apply(q[sl], sh.rope_base) for sl in seqs], axis=0)
+        k = np.concatenate([rope_apply(k[sl], sh.rope_base) for sl in seqs], axis=0)
         qkv = _merge_qkv(q, k, v)
-    o, lse = attention_fwd(q, k, v, attn_chunk)
+    per_seq = [attention_fwd(q[sl], k[sl], v[sl], attn_chunk) for sl in seqs]
+    o = np.concatenate([o_b for o_b, _ in per_seq], axis=0)
+    lse = np.stack([l_b for _, l_b in per_seq], axis=0)          # [sequence, head, position]
     o = o.reshape(x.shape[0], -1)
     x_mid = x + linear_fwd(o, w["wo"])
     if sh.family == LLAMA:
@@ -306,11 +318,15 @@ def layer_backward_input(sh: StageShape, w: dict, sv: dict, dy, attn_chunk=None)
     do = linear_bwd_input(dx_mid, w["wo"])
     q, k, v = _split_qkv(sh, sv["qkv"])
     nq, d = sh.n_q_heads, sh.head_dim
-    dq, dk, dv = attention_bwd(q, k, v, sv["o"].reshape(s, nq, d), do.reshape(s, nq, d), attn_chunk)
-    if sh.family == LLAMA:
-        dq = rope_apply(dq, sh.rope_base, sign=-1.0)
-        dk = rope_apply(dk, sh.rope_base, sign=-1.0)
-    dqkv = _merge_qkv(dq, dk, dv)
+    o3, do3 = sv["o"].reshape(s, nq, d), do.reshape(s, nq, d)
+    parts = []
+    for sl in _sequences(sh, s):
+        dq, dk, dv = attention_bwd(q[sl], k[sl], v[sl], o3[sl], do3[sl], attn_chunk)
+        if sh.family == LLAMA:
+            dq = rope_apply(dq, sh.rope_base, sign=-1.0)
+            dk = rope_apply(dk, sh.rope_base, sign=-1.0)
+        parts.append(_merge_qkv(dq, dk, dv))
+    dqkv = np.concatenate(parts, axis=0)
     dn1 = linear_bwd_input(dqkv, w["wqkv"])
     if sh.family == LLAMA:
         dxi, dnorm["g1"] = rmsnorm_bwd(dn1, sv["x_in"], sv["r1"], w["g1"])

@@ -66,7 +66,12 @@ CFG5 = StageConfig("cfg5_longseq_bf16", LLAMA, BF16, 4, 5120, 40, 40, 128, 13824
                    schedule="zb_offload", budget_bytes=64 * 10**9,
                    offload_kinds=("X_IN", "QKV", "X_MID"))
 
-CONFIGS = {c.name: c for c in (CFG1, CFG2, CFG3, CFG4, CFG5)}
+# second workload: a GPT-style stage at sequence length 1024 with grouped-query attention (hidden 2048, 16 heads in
+# 8 groups, MLP 4096), 8 of 128 layers on stage 2 of p = 16, micro-batch size 8
+CFG6 = StageConfig("cfg6_gpt_seq1024_bf16", GPT, BF16, 8, 2048, 16, 8, 128, 4096, 1024, 8, 2, 16, 16,
+                   schedule="zb")
+
+CONFIGS = {c.name: c for c in (CFG1, CFG2, CFG3, CFG4, CFG5, CFG6)}
 
 
 def shrunken(cfg: StageConfig, hidden: int, n_q: int, n_kv: int, ffn: int, seq: int,

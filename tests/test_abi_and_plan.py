@@ -38,7 +38,7 @@ def oracle_table(cfg):
                           cfg.seq * cfg.micro_batch, cfg.elem_size)
 
 
-@pytest.mark.parametrize("cfg", [CFG.CFG1, CFG.CFG2, CFG.CFG4, CFG.CFG5], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [CFG.CFG1, CFG.CFG2, CFG.CFG4, CFG.CFG5, CFG.CFG6], ids=lambda c: c.name)
 def test_memory_table_matches_oracle(cfg):
     ws, act, kinds = B.query_sizes(cfg)
     t = oracle_table(cfg)

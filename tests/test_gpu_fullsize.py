@@ -106,8 +106,9 @@ def test_attention_full_size_whole_heads(seq, nq, nkv, heads):
     assert rel_err(host(DQKV[:, (nq + nkv + g) * d:(nq + nkv + g + 1) * d]), dv[:, 0]) < TOL[BF16]
 
 
-def test_one_whole_layer_at_full_shape_against_oracle():
-    cfg = replace(CFG.CFG2, name="cfg2_one_layer", n_layers=1, n_microbatches=1)
+@pytest.mark.parametrize("base", [CFG.CFG2, CFG.CFG6], ids=lambda c: c.name)
+def test_one_whole_layer_at_full_shape_against_oracle(base):
+    cfg = replace(base, name=base.name + "_one_layer", n_layers=1, n_microbatches=1)
     ws = T.stage_weights(cfg)
     st = Stage(cfg)
     st.set_weights(ws)
@@ -120,7 +121,7 @@ def test_one_whole_layer_at_full_shape_against_oracle():
     assert rel_err(host(st.y[0]), y) < tol and rel_err(host(st.dx[0]), dx) < tol
     for name in ("wqkv", "wo", "wgu", "wd"):
         assert rel_err(host(st.grads[0][name]), dW[0][name]) < tol, name
-    for name in ("g1", "g2"):
+    for name in dn[0]:                     # norm gains (and biases for LayerNorm)
         assert rel_err(host(st.grads[0][name]), dn[0][name]) < tol, name
     assert st.stats().live_bytes == 0
     st.close()

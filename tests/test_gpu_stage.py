@@ -1,6 +1,7 @@
 """Whole-schedule parity of the HIP stage against the fp64 oracle, through the C-ABI:
 outputs and gradients within tolerance, offload -> reload bit-exact, accounting bit-exact."""
 import ctypes as C
+from dataclasses import replace
 
 import numpy as np
 import pytest
@@ -91,7 +92,14 @@ SMALL4 = CFG.shrunken(CFG.CFG4, hidden=1024, n_q=8, n_kv=2, ffn=1792, seq=320, n
 SMALLG = CFG.shrunken(CFG.CFG1, hidden=256, n_q=4, n_kv=4, ffn=1024, seq=200, n_layers=2, n_microbatches=3, dtype=CFG.BF16, name="gpt_bf16_small")
 
 
-@pytest.mark.parametrize("cfg", [SMALL2, SMALL4, SMALLG], ids=lambda c: c.name)
+# micro-batches of several sequences (the second workload's shape class): GPT with grouped-query attention at
+# head_dim 128, and a Llama twin; sequence lengths that are not a multiple of any tile
+SMALL6 = replace(CFG.shrunken(CFG.CFG6, hidden=512, n_q=4, n_kv=2, ffn=1024, seq=200, n_layers=2, n_microbatches=3, name="cfg6_small"),
+                 micro_batch=3)
+SMALL2B = replace(SMALL2, name="cfg2_small_mb2", seq=192, micro_batch=2, n_microbatches=3)
+
+
+@pytest.mark.parametrize("cfg", [SMALL2, SMALL4, SMALLG, SMALL6, SMALL2B], ids=lambda c: c.name)
 def test_split_bw_schedule_parity(cfg):
     ws = T.stage_weights(cfg)
     events = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches)[cfg.stage_index]

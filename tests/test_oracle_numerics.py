@@ -164,6 +164,43 @@ def test_w_is_order_independent_and_sums_over_microbatches():
             np.testing.assert_allclose(tot_a[l][name], tw[l][name].grad.numpy(), rtol=1e-10, atol=1e-12)
 
 
+@pytest.mark.parametrize("family", [O.GPT, O.LLAMA])
+def test_micro_batch_of_several_sequences_is_the_sequences_side_by_side(family):
+    """A micro-batch of size b is b sequences stored one after the other: nothing couples them (attention is
+    causal within a sequence, rotary positions restart), so y and dx are the per-sequence results stacked and
+    every parameter gradient is the sum over the sequences.  torch autograd on the stacked loss agrees."""
+    sh = tiny_shape(family, 4, 2)
+    ws = rand_weights(sh)
+    b = 3
+    x = RNG.standard_normal((b * sh.seq, sh.hidden))
+    dy = RNG.standard_normal((b * sh.seq, sh.hidden))
+    y, dx, dW, dn = O.stage_fbw(sh, ws, x, dy)
+    parts = [O.stage_fbw(sh, ws, x[i * sh.seq:(i + 1) * sh.seq], dy[i * sh.seq:(i + 1) * sh.seq]) for i in range(b)]
+    np.testing.assert_allclose(y, np.concatenate([p[0] for p in parts]), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dx, np.concatenate([p[1] for p in parts]), rtol=1e-12, atol=1e-13)
+    for l in range(sh.n_layers):
+        for name in dW[l]:
+            np.testing.assert_allclose(dW[l][name], sum(p[2][l][name] for p in parts), rtol=1e-11, atol=1e-12)
+        for name in dn[l]:
+            np.testing.assert_allclose(dn[l][name], sum(p[3][l][name] for p in parts), rtol=1e-11, atol=1e-12)
+    # coupling test: changing the last sequence leaves the first one's output alone, changing the first token of a
+    # sequence changes the rest of that sequence
+    x2 = x.copy()
+    x2[2 * sh.seq] += 1.0
+    y2 = O.stage_forward(sh, ws, x2)[0]
+    assert np.array_equal(y2[:2 * sh.seq], y[:2 * sh.seq])
+    assert np.all(np.abs(y2[2 * sh.seq:] - y[2 * sh.seq:]).max(axis=1) > 0)
+    tw = [{k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in w.items()} for w in ws]
+    loss = sum((torch_stage(sh, tw, torch.tensor(x[i * sh.seq:(i + 1) * sh.seq])) * torch.tensor(dy[i * sh.seq:(i + 1) * sh.seq])).sum()
+               for i in range(b))
+    loss.backward()
+    for l in range(sh.n_layers):
+        for name in ("wqkv", "wo", "wgu", "wd"):
+            np.testing.assert_allclose(dW[l][name], tw[l][name].grad.numpy(), rtol=1e-10, atol=1e-12)
+    with pytest.raises(ValueError):
+        O.stage_forward(sh, ws, x[:sh.seq + 1])
+
+
 # ---------------------------------------------------------------- attention invariants
 def test_attention_invariants():
     s, nq, nkv, d = 12, 4, 2, 8
