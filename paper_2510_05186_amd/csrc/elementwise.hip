@@ -181,6 +181,108 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, 
   }
 }
 
+// Narrow rows (at most 64 * MAXC 16-byte chunks): one row per WAVE, so the two row sums need no barrier and a
+// workgroup has four rows in flight; the four waves' column partials are added through LDS at the end, in wave
+// order, into the workgroup's one row of partial sums.
+template <typename T, bool LN>
+__global__ __launch_bounds__(NT) void norm_bwd_wave_kernel(const T* __restrict__ dn, const T* __restrict__ x,
+                                                           const float* __restrict__ stats, const T* __restrict__ gamma,
+                                                           const T* __restrict__ dres, T* __restrict__ dx,
+                                                           float* __restrict__ partial, int rows, int h) {
+  typedef Vec16<T> V;
+  constexpr int MAXH = 64 * MAXC * V::N;
+  __shared__ float comb[4 * MAXH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nvec = h / V::N;
+  float pg[MAXC][V::N], pb[MAXC][V::N];
+  V gv[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    int ci = lane + c * 64;
+    if (ci < nvec) gv[c] = *reinterpret_cast<const V*>(gamma + ci * V::N);
+#pragma unroll
+    for (int e = 0; e < V::N; ++e) { pg[c][e] = 0.f; pb[c][e] = 0.f; }
+  }
+  V xv[2][MAXC], dv[2][MAXC], rv[2][MAXC];
+  float mean_[2], r_[2];
+  auto load_row = [&](int buf, int row) {
+    if (LN) { mean_[buf] = stats[2 * row]; r_[buf] = stats[2 * row + 1]; } else { mean_[buf] = 0.f; r_[buf] = stats[row]; }
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = lane + c * 64;
+      if (ci < nvec) {
+        xv[buf][c] = *reinterpret_cast<const V*>(x + (size_t)row * h + ci * V::N);
+        dv[buf][c] = *reinterpret_cast<const V*>(dn + (size_t)row * h + ci * V::N);
+        if (dres) rv[buf][c] = *reinterpret_cast<const V*>(dres + (size_t)row * h + ci * V::N);
+      }
+    }
+  };
+  auto process = [&](int buf, int row) {
+    const float mean = mean_[buf], r = r_[buf];
+    float sg = 0.f, sgx = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = lane + c * 64;
+      if (ci < nvec) {
+#pragma unroll
+        for (int e = 0; e < V::N; ++e) {
+          float xh = (xv[buf][c].get(e) - mean) * r;
+          float d = dv[buf][c].get(e);
+          float g = d * gv[c].get(e);
+          sg += g;
+          sgx += g * xh;
+          pg[c][e] += d * xh;
+          pb[c][e] += d;
+        }
+      }
+    }
+    const float mgx = wave_sum(sgx) / h;
+    const float mg = LN ? wave_sum(sg) / h : 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = lane + c * 64;
+      if (ci < nvec) {
+        V o;
+#pragma unroll
+        for (int e = 0; e < V::N; ++e) {
+          float xh = (xv[buf][c].get(e) - mean) * r;
+          float g = dv[buf][c].get(e) * gv[c].get(e);
+          float d = r * (g - mg - xh * mgx);
+          if (dres) d += rv[buf][c].get(e);
+          o.set(e, d);
+        }
+        *reinterpret_cast<V*>(dx + (size_t)row * h + ci * V::N) = o;
+      }
+    }
+  };
+  const int gd = gridDim.x * 4;
+  int row = blockIdx.x * 4 + wave;
+  if (row < rows) load_row(0, row);
+  for (; row < rows; row += 2 * gd) {
+    const int r1 = row + gd, r2 = row + 2 * gd;
+    if (r1 < rows) load_row(1, r1);
+    process(0, row);
+    if (r1 < rows) {
+      if (r2 < rows) load_row(0, r2);
+      process(1, r1);
+    }
+  }
+  for (int pass = 0; pass < (LN ? 2 : 1); ++pass) {
+    if (pass) __syncthreads();
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      int ci = lane + c * 64;
+      if (ci < nvec)
+#pragma unroll
+        for (int e = 0; e < V::N; ++e) comb[wave * MAXH + ci * V::N + e] = pass ? pb[c][e] : pg[c][e];
+    }
+    __syncthreads();
+    float* out = partial + (size_t)(pass * gridDim.x + blockIdx.x) * h;
+    for (int col = tid; col < h; col += NT)
+      out[col] = ((comb[col] + comb[MAXH + col]) + comb[2 * MAXH + col]) + comb[3 * MAXH + col];
+  }
+}
+
 // sums the per-workgroup partials column-wise and adds them into the caller's fp32 accumulators:
 // workgroup = 32 columns x 8 row groups, fixed summation order (deterministic)
 __global__ __launch_bounds__(256) void norm_bwd_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dgamma,
@@ -385,11 +487,17 @@ hipError_t launch_norm_bwd(int dtype, int family, const void* dn, const void* x,
   const int nb = norm_bwd_partial_rows(rows);
   if (dtype == DT_BF16) {
     if (!norm_shape_ok<bf16_t>(h)) return hipErrorInvalidValue;
-    if (ln) hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    const bool narrow = h / 8 <= 64 * MAXC && rows >= 4 * nb;   // one row per wave
+    if (ln && narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    else if (narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<bf16_t, false>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    else if (ln) hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
     else hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, false>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
   } else {
     if (!norm_shape_ok<float>(h)) return hipErrorInvalidValue;
-    if (ln) hipLaunchKernelGGL((norm_bwd_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    const bool narrow = h / 4 <= 64 * MAXC && rows >= 4 * nb;
+    if (ln && narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    else if (narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<float, false>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    else if (ln) hipLaunchKernelGGL((norm_bwd_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
     else hipLaunchKernelGGL((norm_bwd_kernel<float, false>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
   }
   hipError_t e = hipGetLastError();

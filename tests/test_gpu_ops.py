@@ -108,7 +108,7 @@ def test_gemm_rejects_bad_shapes():
 # ------------------------------------------------------------------ norms
 @pytest.mark.parametrize("dtype,family,rows,h", [
     (BF16, O.LLAMA, 300, 4096), (BF16, O.LLAMA, 37, 520), (BF16, O.GPT, 64, 1024), (BF16, O.LLAMA, 700, 8192),
-    (FP32, O.GPT, 128, 256), (FP32, O.LLAMA, 130, 1000),
+    (FP32, O.GPT, 128, 256), (FP32, O.LLAMA, 130, 1000), (BF16, O.GPT, 2100, 2048), (FP32, O.GPT, 8200, 256), (BF16, O.LLAMA, 2500, 1024),
 ])
 def test_norm_fwd_bwd(dtype, family, rows, h):
     eps = 1e-5
