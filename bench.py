@@ -83,6 +83,7 @@ def device_io(cfg, mb, torch):
     return x.contiguous(), dy.contiguous()
 
 
+CHUNKS = 1      # --chunks: model chunks on the stage (interleaved 1F1B instead of the configuration's schedule)
 RECOMPUTE = 0   # --recompute: the memory-table variant in which F keeps no norm outputs and no MLP activation output
 
 
@@ -116,6 +117,10 @@ def build_schedule(cfg, budget=0, generator="greedy"):
     from paper_2510_05186_amd import binding as B
     from stage_inputs import schedules as G
     p, m, i = cfg.n_stages, cfg.n_microbatches, cfg.stage_index
+    if CHUNKS > 1:
+        if budget:
+            raise RuntimeError("--chunks runs the interleaved list without a budget search")
+        return G.interleaved_one_f_one_b(p, m, i, CHUNKS), {"schedule": "interleaved 1F1B", "chunks": CHUNKS}
     if budget and generator == "adaoffload":
         from paper_2510_05186_amd import scheduler as SC
         inst = adaoffload_instance(cfg, budget)
@@ -154,7 +159,7 @@ def build_schedule(cfg, budget=0, generator="greedy"):
 def make_stage(cfg, events, budget, torch, duplex=False):
     from paper_2510_05186_amd import binding as B
     from paper_2510_05186_amd.stage import Stage
-    _, _, peak, _ = B.plan(cfg, events, budget=0, recompute=RECOMPUTE)
+    _, _, peak, _ = B.plan(cfg, events, budget=0, recompute=RECOMPUTE, n_chunks=CHUNKS)
     n_off = sum(1 for e in events if e[0] == "O")
     pool = 0
     if n_off:
@@ -162,11 +167,12 @@ def make_stage(cfg, events, budget, torch, duplex=False):
         per_mb = sum(kb[k] for k in cfg.offload_kinds) * cfg.n_layers
         pool = per_mb * cfg.n_microbatches
     st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=pool, duplex=duplex,
-               recompute=bool(RECOMPUTE))
+               recompute=bool(RECOMPUTE), n_chunks=CHUNKS)
     st.set_weights_device(device_weights(cfg, torch))
-    for j in range(cfg.n_microbatches):
-        x, dy = device_io(cfg, j, torch)
-        st.bind(j, x, dy)
+    for c in range(CHUNKS):
+        for j in range(cfg.n_microbatches):
+            x, dy = device_io(cfg, c * cfg.n_microbatches + j, torch)
+            st.bind(j, x, dy, chunk=c)
     return st, peak
 
 
@@ -204,7 +210,7 @@ def time_steps(st, events, steps, warmup, torch, kernel_timing=True):
     return wall, agg
 
 
-def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event, duplex=False):
+def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event, duplex=False, n_chunks=1):
     """CPU baseline: the fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample
     (ONE layer of the workload's stage, one micro-batch, F + B + W at full shape), and the oracle's
     pipeline simulator fed with the measured op times (all p stages assumed identical to this one)."""
@@ -234,7 +240,8 @@ def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event, duplex=False)
                       f"({fl / 1e12:.2f} TFLOP fp64 in {dt:.1f} s)", "host_cpus": os.cpu_count()}
     p = cfg.n_stages
     t_op = [{"F": t_op_ms[0], "B": t_op_ms[1], "W": t_op_ms[2]}] * p
-    tm = S.simulate(events_all_stages, t_op, t_comm=0.0, t_copy=lambda i, ev: copy_ms_per_event, duplex=duplex)
+    tm = S.simulate(events_all_stages, t_op, t_comm=0.0, t_copy=lambda i, ev: copy_ms_per_event, duplex=duplex,
+                    n_chunks=n_chunks, layers_per_chunk=cfg.n_layers // n_chunks)
     model = {"stage_bubble_frac": tm.bubble[cfg.stage_index], "makespan_ms": tm.makespan_global,
              "assumption": "p identical stages with this stage's measured mean T_F/T_B/T_W, T_comm = 0"}
     return base, model
@@ -252,6 +259,8 @@ def main():
                     help="how the event list of a budgeted workload is produced")
     ap.add_argument("--duplex", action="store_true",
                     help="reloads on a stream of their own instead of the single transfer channel (offload workloads)")
+    ap.add_argument("--chunks", type=int, default=1,
+                    help="model chunks on the stage: runs interleaved 1F1B over them (layers split evenly)")
     ap.add_argument("--recompute", action="store_true",
                     help="memory-table variant: F keeps no norm outputs and no MLP activation output, B rebuilds them")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -272,8 +281,9 @@ def main():
         print("bench.py: no GPU visible; the stage has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = CFG.CONFIGS[args.config]
-    global RECOMPUTE
+    global RECOMPUTE, CHUNKS
     RECOMPUTE = int(args.recompute)
+    CHUNKS = max(1, args.chunks)
     budget = 0
     if cfg.budget_bytes:
         budget = cfg.budget_bytes
@@ -308,7 +318,7 @@ def main():
                 "avg_launch_ms": dom.get("avg_ms"), "launches_per_step": dom.get("launches_per_step"),
                 "algorithmic_bytes": nt_store_algorithmic_bytes(cfg), "traffic": measured_traffic(cfg)}
     busy_ms = sum(agg["ms_ops"][:3]) / args.steps
-    n_f = cfg.n_microbatches
+    n_f = cfg.n_microbatches * CHUNKS
     t_op_ms = [agg["ms_ops"][k] / args.steps / n_f for k in range(3)]
     out = {
         "metric": "stage TFLOP/s (F+B+W) + bubble % under HBM budget; MFMA util vs bf16 peak",
@@ -334,7 +344,7 @@ def main():
     del st
     torch.cuda.empty_cache()
 
-    if not args.no_offload_leg and cfg.name == "cfg2_llama_bf16":
+    if not args.no_offload_leg and cfg.name == "cfg2_llama_bf16" and CHUNKS == 1:
         # same shapes under 40 % of this run's activation peak, with offload of (attention input, QKV, MLP input):
         # on the single transfer channel of the paper's model and with reloads on a stream of their own
         c3 = CFG.CFG3
@@ -366,13 +376,15 @@ def main():
     if not args.no_cpu_baseline:
         lists = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches) if cfg.schedule != "1f1b" else \
             [G.one_f_one_b(cfg.n_stages, cfg.n_microbatches, i) for i in range(cfg.n_stages)]
+        if CHUNKS > 1:
+            lists = [G.interleaved_one_f_one_b(cfg.n_stages, cfg.n_microbatches, i, CHUNKS) for i in range(cfg.n_stages)]
         copy_ms = 0.0
         if args.generator == "adaoffload" and getattr(build_schedule, "all_stages", None) and budget:
             # the generator's lists for every stage, transfers included, with this stage's measured mean copy time
             lists = build_schedule.all_stages
             n_x = agg["k_n"] and sum(1 for e in events if e[0] in ("O", "R"))
             copy_ms = (agg["ms_ops"][3] + agg["ms_ops"][5]) / args.steps / n_x if n_x else 0.0
-        base, model = oracle_leg(cfg, t_op_ms, lists, copy_ms, args.duplex)
+        base, model = oracle_leg(cfg, t_op_ms, lists, copy_ms, args.duplex, CHUNKS)
         model["lists"] = "adaoffload, all stages, transfers included" if copy_ms else "compute ops only"
         out["cpu_baseline"] = base
         out["pipeline_model"] = model

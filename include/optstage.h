@@ -85,7 +85,12 @@ typedef struct {
                                            B rebuilds them from X_IN, X_MID, GU, bit for bit, and holds them for W.
                                            Delta_F shrinks and Delta_B grows by their bytes; they cannot be
                                            offloaded */
-  uint32_t reserved;                    /* 0 */
+  uint32_t n_chunks;                    /* model chunks held by this stage (interleaved and V-shaped schedules
+                                           of the comparison methods in Sec. 5 place more than one on a stage);
+                                           0 or 1 = one.  n_layers counts all of them and must divide evenly:
+                                           chunk c is layers c * n_layers / n_chunks onwards.  Every chunk has its
+                                           own F / B / W per micro-batch and its own boundary tensors; arena,
+                                           budget and transfer channel are shared */
   uint64_t hbm_budget_bytes;            /* M_limit_i for activations (Eq. 7); 0 = unlimited */
   void* arena; uint64_t arena_bytes;          /* DEVICE block for activations, 256-byte aligned */
   void* workspace; uint64_t workspace_bytes;  /* DEVICE block for transients, >= optstage_query_sizes' figure */
@@ -102,7 +107,8 @@ typedef struct {
 typedef struct {
   uint32_t op;          /* optstage_op */
   uint32_t microbatch;  /* j */
-  uint32_t layer;       /* O / OWAIT / R only */
+  uint32_t layer;       /* O / OWAIT / R: layer index on the stage (over all chunks).  F / B / W: model chunk
+                           (0 on a stage with one chunk) */
   uint32_t kind_mask;   /* O / OWAIT / R only: bit k set = activation kind k (k < OPTSTAGE_N_F_KINDS) */
 } optstage_event;
 
@@ -152,6 +158,11 @@ optstage_status optstage_set_weight(optstage_t* st, uint32_t layer, uint32_t whi
  * x_in (read by F), dy_out (read by B), y_out (written by F), dx_in (written by B). */
 optstage_status optstage_bind_io(optstage_t* st, uint32_t mb, const void* x_in, const void* dy_out,
                                  void* y_out, void* dx_in);
+/* The same for model chunk `chunk` of a stage that holds several (optstage_bind_io is chunk 0): the fixed
+ * micro-batch order and Eq. 6 apply per chunk, each chunk's first layer reads its own x_in and its last
+ * layer its own dy_out. */
+optstage_status optstage_bind_io_chunk(optstage_t* st, uint32_t chunk, uint32_t mb, const void* x_in,
+                                       const void* dy_out, void* y_out, void* dx_in);
 
 /* Checks a whole list against the ordering rules and the budget without running anything, starting
  * from an empty stage.  events is HOST memory.  On failure *first_bad (may be null) is the index of the

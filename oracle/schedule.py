@@ -29,7 +29,12 @@ the same item's offload ends and ends before B of its micro-batch starts.
 A stage schedule is ONE ordered list of events
     ("F", j) ("B", j) ("W", j) ("O", j, layer, kinds) ("OWAIT", j, layer, kinds)
     ("R", j, layer, kinds)
-where kinds is a tuple of activation kind names.  List order is the order
+where kinds is a tuple of activation kind names.  A stage that holds several
+model chunks (the interleaved and V-shaped schedules of the comparison methods,
+Sec. 5) writes its compute ops ("F", j, chunk); its n_layers layers are split
+evenly over the chunks in order, transfers name the layer on the stage, and
+every rule above applies per chunk (Eq. 6, the fixed micro-batch order), with
+Eq. 3 / Eq. 4 following the chunk's position in the model (`virtual_stage`).  List order is the order
 relation of the paper's precedence binaries: compute ops run in list order; the
 copy channel serves O and R in list order; a compute op listed after OWAIT(x)
 starts after offload x ended and x's bytes are credited from that position; an
@@ -72,7 +77,30 @@ def memory_table(family, hidden, n_q_heads, n_kv_heads, head_dim, ffn, tokens, e
     return {k: _round_up(v) for k, v in raw.items()}
 
 
-def op_memory_steps(op, n_layers, recompute=False):
+def chunk_of(ev):
+    """Model chunk of a compute event: ("F", j) is chunk 0, ("F", j, c) chunk c."""
+    return ev[2] if len(ev) > 2 else 0
+
+
+def virtual_stage(i, c, p, placement="interleaved"):
+    """Position of chunk c of stage i in the model's order of p * n_chunks pieces.
+    "interleaved": chunk c holds pieces c p .. c p + p - 1 in stage order (1F1B-I);
+    "v": odd chunks run through the stages in reverse (ZB-V: stage 0 holds the first
+    and the last piece)."""
+    if placement == "interleaved" or c % 2 == 0:
+        return c * p + i
+    if placement == "v":
+        return c * p + (p - 1 - i)
+    raise ValueError(placement)
+
+
+def _holder(v, p, placement):
+    c = v // p
+    i = v % p if (placement == "interleaved" or c % 2 == 0) else p - 1 - v % p
+    return i, c
+
+
+def op_memory_steps(op, n_layers, recompute=False, first_layer=0):
     """Ordered (+1/-1, layer, kind) steps a compute op performs on the activation
     arena.  F keeps everything it produces.  B walks layers last to first: it
     creates the layer's output-gradient buffer DY (kept for W) and DX_MID (kept
@@ -82,7 +110,17 @@ def op_memory_steps(op, n_layers, recompute=False):
     recompute: the memory-table variant in which F keeps no N1, N2, A and B
     rebuilds them for W (A and N2 before the MLP part of the layer is
     differentiated, N1 before the attention part's norm), so Delta_F shrinks and
-    Delta_B grows by the same bytes while W is unchanged."""
+    Delta_B grows by the same bytes while W is unchanged.
+
+    first_layer: the op covers layers first_layer .. first_layer + n_layers - 1 of
+    the stage (a model chunk)."""
+    steps = []
+    for sgn, l, k in _op_memory_steps(op, n_layers, recompute):
+        steps.append((sgn, l + first_layer, k))
+    return steps
+
+
+def _op_memory_steps(op, n_layers, recompute):
     steps = []
     if op == "F":
         for l in range(n_layers):
@@ -124,42 +162,50 @@ class ScheduleError(Exception):
         self.index = index
 
 
-def check_order(events, n_microbatches, n_layers, recompute=False):
+def check_order(events, n_microbatches, n_layers, recompute=False, n_chunks=1):
     """Validity of one stage's list (raises ScheduleError naming the first bad event).
-    In the recompute variant the kinds F does not keep cannot be offloaded."""
-    done = {"F": set(), "B": set(), "W": set()}
-    nxt = {"F": 0, "B": 0, "W": 0}
+    In the recompute variant the kinds F does not keep cannot be offloaded.  With
+    several model chunks (n_layers counts all of them) the rules hold per chunk."""
+    if n_layers % n_chunks:
+        raise ValueError("n_layers must be a multiple of n_chunks")
+    per_chunk = n_layers // n_chunks
+    done = {"F": set(), "B": set(), "W": set()}     # (chunk, j)
+    nxt = {(op, c): 0 for op in "FBW" for c in range(n_chunks)}
     state = {}                      # (j, layer, kind) -> "O" | "OWAIT" | "R"
     for idx, ev in enumerate(events):
         op, j = ev[0], ev[1]
         if not (0 <= j < n_microbatches):
             raise ScheduleError(idx, "micro-batch index out of range")
         if op in ("F", "B", "W"):
-            if j in done[op]:
+            c = chunk_of(ev)
+            if not (0 <= c < n_chunks):
+                raise ScheduleError(idx, "chunk out of range")
+            if (c, j) in done[op]:
                 raise ScheduleError(idx, f"{op} {j} listed twice")
-            if j != nxt[op]:
+            if j != nxt[(op, c)]:
                 raise ScheduleError(idx, f"{op} ops must run in increasing micro-batch order")
-            if op == "B" and j not in done["F"]:
+            if op == "B" and (c, j) not in done["F"]:
                 raise ScheduleError(idx, "B before F")
-            if op == "W" and j not in done["B"]:
+            if op == "W" and (c, j) not in done["B"]:
                 raise ScheduleError(idx, "W before B")
             if op == "B":
                 for key, st in state.items():
-                    if key[0] == j and st != "R":
+                    if key[0] == j and key[1] // per_chunk == c and st != "R":
                         raise ScheduleError(idx, f"B {j} while {key} is offloaded and not reloaded")
-            done[op].add(j)
-            nxt[op] += 1
+            done[op].add((c, j))
+            nxt[(op, c)] += 1
         elif op in ("O", "OWAIT", "R"):
             layer, kinds = ev[2], ev[3]
             if not (0 <= layer < n_layers) or len(kinds) == 0:
                 raise ScheduleError(idx, "bad layer or empty kind set")
+            c = layer // per_chunk
             for k in kinds:
                 if k not in F_KINDS or (recompute and k in RECOMPUTED):
                     raise ScheduleError(idx, f"kind {k} cannot be offloaded")
                 key = (j, layer, k)
                 st = state.get(key)
                 if op == "O":
-                    if j not in done["F"] or j in done["B"]:
+                    if (c, j) not in done["F"] or (c, j) in done["B"]:
                         raise ScheduleError(idx, "offload outside the F..B window of its micro-batch")
                     if st is not None:
                         raise ScheduleError(idx, f"{key} offloaded twice")
@@ -175,14 +221,14 @@ def check_order(events, n_microbatches, n_layers, recompute=False):
         else:
             raise ScheduleError(idx, f"unknown op {op}")
     for op in ("F", "B", "W"):
-        if len(done[op]) != n_microbatches:
+        if len(done[op]) != n_microbatches * n_chunks:
             raise ScheduleError(len(events), f"missing {op} ops")
     for key, st in state.items():
         if st != "R":
             raise ScheduleError(len(events), f"{key} never reloaded")
 
 
-def account_memory(events, n_layers, table, limit=None, recompute=False):
+def account_memory(events, n_layers, table, limit=None, recompute=False, n_chunks=1):
     """List-order logical accounting.  Returns (peak, trace) where trace[i] is the
     bytes in use after event i; raises ScheduleError at the first allocation
     that would exceed `limit` (checked before committing it)."""
@@ -192,7 +238,7 @@ def account_memory(events, n_layers, table, limit=None, recompute=False):
     for idx, ev in enumerate(events):
         op = ev[0]
         if op in ("F", "B", "W"):
-            steps = [(sgn, table[k]) for sgn, _, k in op_memory_steps(op, n_layers, recompute)]
+            steps = [(sgn, table[k]) for sgn, _, k in op_memory_steps(op, n_layers // n_chunks, recompute)]
         elif op == "OWAIT":
             steps = [(-1, table[k]) for k in ev[3]]
         elif op == "R":
@@ -243,11 +289,16 @@ class Timing:
     bubble: list = field(default_factory=list)   # per stage, 1 - busy / makespan_global
 
 
-def simulate(schedules, t_op, t_comm=0.0, t_copy=None, duplex=False):
+def simulate(schedules, t_op, t_comm=0.0, t_copy=None, duplex=False, n_chunks=1, placement="interleaved",
+             layers_per_chunk=None):
     """ASAP timing of p stages.
 
     schedules[i]  event list of stage i
-    t_op[i]       {"F": T_F, "B": T_B, "W": T_W} for stage i
+    t_op[i]       {"F": T_F, "B": T_B, "W": T_W} for stage i (of ONE chunk's op when the stage holds several)
+    n_chunks, placement   model chunks per stage and where they sit in the model (`virtual_stage`): the F of a
+                  chunk waits for the F of the piece before it (Eq. 3), the B for the B of the piece after
+                  it (Eq. 4); t_comm applies when that piece is on another stage
+    layers_per_chunk      needed with transfers on a multi-chunk stage: maps an event's layer to its chunk
     t_copy        callable (stage, event) -> duration of that O or R event
     duplex        False: one serial transfer channel per stage, as the paper models it (Eq. 8-11);
                   True: offloads and reloads each have their own serial channel (a full-duplex host
@@ -265,7 +316,16 @@ def simulate(schedules, t_op, t_comm=0.0, t_copy=None, duplex=False):
     end_F = [dict() for _ in range(p)]
     end_B = [dict() for _ in range(p)]
     end_O = [dict() for _ in range(p)]          # (j, layer, kind) -> end
-    end_R = [dict() for _ in range(p)]          # j -> latest reload end
+    end_R = [dict() for _ in range(p)]          # (j, chunk) -> latest reload end
+    n_virtual = p * n_chunks
+
+    def chunk_of_layer(layer):
+        if n_chunks == 1:
+            return 0
+        if layers_per_chunk is None:
+            raise ValueError("layers_per_chunk is needed for transfers on a multi-chunk stage")
+        return layer // layers_per_chunk
+
     progress = True
     while progress:
         progress = False
@@ -274,25 +334,29 @@ def simulate(schedules, t_op, t_comm=0.0, t_copy=None, duplex=False):
                 ev = schedules[i][ptr[i]]
                 op, j = ev[0], ev[1]
                 if op in ("F", "B", "W"):
+                    c = chunk_of(ev)
+                    v = virtual_stage(i, c, p, placement)
                     ready = max(compute_free[i], gate[i])
-                    if op == "F" and i > 0:
-                        if j not in end_F[i - 1]:
+                    if op == "F" and v > 0:
+                        i2, c2 = _holder(v - 1, p, placement)
+                        if (j, c2) not in end_F[i2]:
                             break
-                        ready = max(ready, end_F[i - 1][j] + t_comm)           # Eq. 3
+                        ready = max(ready, end_F[i2][(j, c2)] + (t_comm if i2 != i else 0.0))      # Eq. 3
                     if op == "B":
-                        if i < p - 1:
-                            if j not in end_B[i + 1]:
+                        if v < n_virtual - 1:
+                            i2, c2 = _holder(v + 1, p, placement)
+                            if (j, c2) not in end_B[i2]:
                                 break
-                            ready = max(ready, end_B[i + 1][j] + t_comm)       # Eq. 4
-                        ready = max(ready, end_R[i].get(j, 0.0))               # reload completes first
+                            ready = max(ready, end_B[i2][(j, c2)] + (t_comm if i2 != i else 0.0))  # Eq. 4
+                        ready = max(ready, end_R[i].get((j, c), 0.0))          # reload completes first
                     s, e = ready, ready + t_op[i][op]
                     compute_free[i] = e
                     if op == "F":
-                        end_F[i][j] = e
+                        end_F[i][(j, c)] = e
                     elif op == "B":
-                        end_B[i][j] = e
+                        end_B[i][(j, c)] = e
                 elif op == "O":
-                    s = max(copy_free[i][0], end_F[i][j])                      # after its F ended
+                    s = max(copy_free[i][0], end_F[i][(j, chunk_of_layer(ev[2]))])   # after its F ended
                     e = s + t_copy(i, ev)
                     copy_free[i][0] = e
                     for k in ev[3]:
@@ -305,7 +369,8 @@ def simulate(schedules, t_op, t_comm=0.0, t_copy=None, duplex=False):
                             [end_O[i][(j, ev[2], k)] for k in ev[3]])
                     e = s + t_copy(i, ev)
                     copy_free[i][ch_r] = e
-                    end_R[i][j] = max(end_R[i].get(j, 0.0), e)
+                    key = (j, chunk_of_layer(ev[2]))
+                    end_R[i][key] = max(end_R[i].get(key, 0.0), e)
                 else:
                     raise ValueError(op)
                 start[i][ptr[i]], end[i][ptr[i]] = s, e

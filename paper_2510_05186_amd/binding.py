@@ -30,7 +30,7 @@ class Desc(C.Structure):
                 ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32), ("ffn", C.c_uint32), ("seq", C.c_uint32),
                 ("micro_batch", C.c_uint32), ("stage_index", C.c_uint32), ("n_stages", C.c_uint32),
                 ("n_microbatches", C.c_uint32), ("norm_eps", C.c_float), ("rope_base", C.c_float),
-                ("recompute", C.c_uint32), ("reserved", C.c_uint32),
+                ("recompute", C.c_uint32), ("n_chunks", C.c_uint32),
                 ("hbm_budget_bytes", C.c_uint64), ("arena", C.c_void_p), ("arena_bytes", C.c_uint64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64), ("host_pool", C.c_void_p),
                 ("host_pool_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
@@ -67,6 +67,7 @@ _SIGS = {
     "optstage_create": [C.POINTER(Desc), C.POINTER(_vp)],
     "optstage_set_weight": [_vp, _u32, _u32, _vp, _vp],
     "optstage_bind_io": [_vp, _u32, _vp, _vp, _vp, _vp],
+    "optstage_bind_io_chunk": [_vp, _u32, _u32, _vp, _vp, _vp, _vp],
     "optstage_validate": [_vp, C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t)],
     "optstage_run": [_vp, C.POINTER(Event), C.c_size_t],
     "optstage_forward": [_vp, _u32],
@@ -124,13 +125,15 @@ def check(status):
 
 
 def make_events(events) -> "C.Array":
-    """events: iterable of ("F", j) / ("O", j, layer, kinds) tuples (kinds = names or ids)."""
+    """events: iterable of ("F", j) / ("F", j, chunk) / ("O", j, layer, kinds) tuples (kinds = names or ids)."""
     events = list(events)
     arr = (Event * max(1, len(events)))()
     for n, ev in enumerate(events):
         arr[n].op = OP_CODE[ev[0]] if isinstance(ev[0], str) else int(ev[0])
         arr[n].microbatch = ev[1]
-        if len(ev) > 2:
+        if len(ev) == 3:
+            arr[n].layer = ev[2]                       # compute op of a model chunk
+        elif len(ev) > 3:
             arr[n].layer = ev[2]
             mask = 0
             for k in ev[3]:
@@ -140,7 +143,7 @@ def make_events(events) -> "C.Array":
 
 
 def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_bytes=0, host_pool=0,
-              host_pool_bytes=0, compute_stream=0, copy_stream=0, reload_stream=0, recompute=0) -> Desc:
+              host_pool_bytes=0, compute_stream=0, copy_stream=0, reload_stream=0, recompute=0, n_chunks=1) -> Desc:
     d = Desc()
     d.struct_size = C.sizeof(Desc)
     d.family, d.dtype = cfg.family, cfg.dtype
@@ -155,6 +158,7 @@ def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_byte
     d.compute_stream, d.copy_stream = compute_stream, copy_stream
     d.reload_stream = reload_stream
     d.recompute = int(recompute)
+    d.n_chunks = int(n_chunks)
     return d
 
 
@@ -167,9 +171,9 @@ def query_sizes(cfg, recompute=0):
     return ws.value, act.value, {k: kinds[i] for i, k in enumerate(KINDS)}
 
 
-def plan(cfg, events, budget=0, recompute=0):
+def plan(cfg, events, budget=0, recompute=0, n_chunks=1):
     """Pure-host validation + accounting.  -> (status, first_bad, peak_bytes, live_after list)."""
-    d = make_desc(cfg, budget=budget, recompute=recompute)
+    d = make_desc(cfg, budget=budget, recompute=recompute, n_chunks=n_chunks)
     arr = make_events(events)
     n = len(list(events)) if not isinstance(events, list) else len(events)
     bad = C.c_size_t(0)

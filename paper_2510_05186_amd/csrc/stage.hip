@@ -50,6 +50,7 @@ uint64_t round_up(uint64_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Shape {
   int family, dtype, L, h, nq, nkv, d, f, seq, mb, tokens, qkv_w, up_w, e;
+  int chunks, Lc;   // model chunks on this stage and layers per chunk (L = chunks * Lc)
 };
 
 optstage_status shape_from_desc(const optstage_desc* d, Shape* s) {
@@ -70,6 +71,9 @@ optstage_status shape_from_desc(const optstage_desc* d, Shape* s) {
   s->qkv_w = (s->nq + 2 * s->nkv) * s->d;
   s->up_w = s->family == OPTSTAGE_LLAMA ? 2 * s->f : s->f;
   s->e = s->dtype == OPTSTAGE_BF16 ? 2 : 4;
+  s->chunks = d->n_chunks ? (int)d->n_chunks : 1;
+  if (s->L % s->chunks) return fail(OPTSTAGE_E_ARG, "n_layers must be a multiple of n_chunks");
+  s->Lc = s->L / s->chunks;
   return OPTSTAGE_OK;
 }
 
@@ -139,11 +143,11 @@ struct MbState {
 
 // Pure host, copyable: everything the validator needs.
 struct Logical {
-  int L = 0, m = 0;
+  int L = 0, m = 0, chunks = 1, Lc = 0;
   bool recompute = false;   // F keeps no N1 / N2 / A; B rebuilds them for W
   uint64_t bytes[NK] = {}, budget = 0, live = 0, peak = 0;
-  int next_f = 0, next_b = 0, next_w = 0;
-  std::vector<MbState> mbs;
+  std::vector<int> next_f, next_b, next_w;   // [chunk]
+  std::vector<MbState> mbs;                  // [chunk][mb]
   std::vector<BufRec> bufs;   // [mb][layer][kind]
   BlockArena arena, host;
   BufRec& buf(int j, int l, int k) { return bufs[((size_t)j * L + l) * NK + k]; }
@@ -211,13 +215,19 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
   if (ev.microbatch >= (uint32_t)lg.m) return fail(OPTSTAGE_E_ARG, "micro-batch %u out of range", ev.microbatch);
   if (out) { out->dev.assign((size_t)L * NK, UINT64_MAX); out->host.assign((size_t)L * NK, UINT64_MAX); }
   auto note = [&](int l, int k) { if (out) out->dev[(size_t)l * NK + k] = lg.buf(j, l, k).dev_off; };
-  MbState& mb = lg.mbs[j];
+  // F / B / W: the event's layer field is the model chunk; O / OWAIT / R: the chunk that holds the layer
+  const bool compute = ev.op <= OPTSTAGE_W;
+  if (compute && ev.layer >= (uint32_t)lg.chunks) return fail(OPTSTAGE_E_ARG, "chunk %u out of range", ev.layer);
+  if (!compute && ev.op <= OPTSTAGE_R && ev.layer >= (uint32_t)L) return fail(OPTSTAGE_E_ARG, "layer %u out of range", ev.layer);
+  const int c = compute ? (int)ev.layer : (ev.op <= OPTSTAGE_R ? (int)ev.layer / lg.Lc : 0);
+  const int l0 = c * lg.Lc, l1 = l0 + lg.Lc;      // the chunk's layers
+  MbState& mb = lg.mbs[(size_t)c * lg.m + j];
   optstage_status st;
   switch (ev.op) {
     case OPTSTAGE_F: {
       if (mb.f) return fail(OPTSTAGE_E_ORDER, "F %d listed twice", j);
-      if (j != lg.next_f) return fail(OPTSTAGE_E_ORDER, "F ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_f, j);
-      for (int l = 0; l < L; ++l)
+      if (j != lg.next_f[c]) return fail(OPTSTAGE_E_ORDER, "F ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_f[c], j);
+      for (int l = l0; l < l1; ++l)
         for (int k = 0; k < NFK; ++k) {
           if (lg.recompute && recomputable(k)) continue;
           if ((st = alloc_dev(lg, j, l, k)) != OPTSTAGE_OK) return st;
@@ -225,14 +235,14 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
           note(l, k);
         }
       mb.f = true;
-      lg.next_f++;
+      lg.next_f[c]++;
       return OPTSTAGE_OK;
     }
     case OPTSTAGE_B: {
       if (mb.b) return fail(OPTSTAGE_E_ORDER, "B %d listed twice", j);
       if (!mb.f) return fail(OPTSTAGE_E_ORDER, "B %d before F %d", j, j);
-      if (j != lg.next_b) return fail(OPTSTAGE_E_ORDER, "B ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_b, j);
-      for (int l = 0; l < L; ++l)
+      if (j != lg.next_b[c]) return fail(OPTSTAGE_E_ORDER, "B ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_b[c], j);
+      for (int l = l0; l < l1; ++l)
         for (int k = 0; k < NFK; ++k) {
           if (lg.recompute && recomputable(k)) continue;
           uint8_t s = lg.buf(j, l, k).state;
@@ -246,10 +256,10 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
         return s2;
       };
       auto drop = [&](int l, int k) { free_dev(lg, j, l, k); lg.buf(j, l, k).state = B_NONE; };
-      if ((st = make(L - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
+      if ((st = make(l1 - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
       // every buffer is made before the kernel that first writes it and dropped after its last reader, in the
       // order B enqueues its kernels: a region released here may be handed out again within the same op
-      for (int l = L - 1; l >= 0; --l) {
+      for (int l = l1 - 1; l >= l0; --l) {
         if (lg.recompute) {
           if ((st = make(l, OPTSTAGE_K_A)) != OPTSTAGE_OK) return st;
           if ((st = make(l, OPTSTAGE_K_N2)) != OPTSTAGE_OK) return st;
@@ -258,34 +268,33 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
         drop(l, OPTSTAGE_K_X_MID);
         drop(l, OPTSTAGE_K_LSE);
         if (lg.recompute && (st = make(l, OPTSTAGE_K_N1)) != OPTSTAGE_OK) return st;
-        if (l > 0 && (st = make(l - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
+        if (l > l0 && (st = make(l - 1, OPTSTAGE_K_DY)) != OPTSTAGE_OK) return st;
         drop(l, OPTSTAGE_K_X_IN);
         drop(l, OPTSTAGE_K_STATS);
       }
       mb.b = true;
-      lg.next_b++;
+      lg.next_b[c]++;
       return OPTSTAGE_OK;
     }
     case OPTSTAGE_W: {
       if (mb.w) return fail(OPTSTAGE_E_ORDER, "W %d listed twice", j);
       if (!mb.b) return fail(OPTSTAGE_E_ORDER, "W %d before B %d", j, j);
-      if (j != lg.next_w) return fail(OPTSTAGE_E_ORDER, "W ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_w, j);
+      if (j != lg.next_w[c]) return fail(OPTSTAGE_E_ORDER, "W ops must run in increasing micro-batch order (expected %d, got %d)", lg.next_w[c], j);
       static const int freed[] = {OPTSTAGE_K_N1, OPTSTAGE_K_QKV, OPTSTAGE_K_O, OPTSTAGE_K_DX_MID,
                                   OPTSTAGE_K_N2, OPTSTAGE_K_GU, OPTSTAGE_K_A, OPTSTAGE_K_DY};
-      for (int l = 0; l < L; ++l)
+      for (int l = l0; l < l1; ++l)
         for (int k : freed) {
           note(l, k);
           free_dev(lg, j, l, k);
           lg.buf(j, l, k).state = B_NONE;
         }
       mb.w = true;
-      lg.next_w++;
+      lg.next_w[c]++;
       return OPTSTAGE_OK;
     }
     case OPTSTAGE_O:
     case OPTSTAGE_OWAIT:
     case OPTSTAGE_R: {
-      if (ev.layer >= (uint32_t)L) return fail(OPTSTAGE_E_ARG, "layer %u out of range", ev.layer);
       if (!ev.kind_mask || (ev.kind_mask >> NFK)) return fail(OPTSTAGE_E_ARG, "kind_mask 0x%x names no offloadable kind or a non-offloadable one", ev.kind_mask);
       const int l = (int)ev.layer;
       for (int k = 0; k < NFK; ++k) {
@@ -322,8 +331,9 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
 }
 
 optstage_status check_complete(const Logical& lg) {
-  for (int j = 0; j < lg.m; ++j)
-    if (!lg.mbs[j].f || !lg.mbs[j].b || !lg.mbs[j].w) return fail(OPTSTAGE_E_ORDER, "micro-batch %d is missing F, B or W", j);
+  for (size_t i = 0; i < lg.mbs.size(); ++i)
+    if (!lg.mbs[i].f || !lg.mbs[i].b || !lg.mbs[i].w)
+      return fail(OPTSTAGE_E_ORDER, "micro-batch %d of chunk %d is missing F, B or W", (int)(i % lg.m), (int)(i / lg.m));
   return OPTSTAGE_OK;
 }
 
@@ -443,15 +453,17 @@ optstage_status check_weights(optstage* st, bool need_grads) {
   return OPTSTAGE_OK;
 }
 
-optstage_status exec_forward(optstage* st, int j, const OpBufs& ob) {
+optstage_status exec_forward(optstage* st, int j, int c, const OpBufs& ob) {
   const Shape& s = st->sh;
   hipStream_t cs = st->cs;
   const int T = s.tokens;
   auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
-  HIP_TRY(hipMemcpyAsync(P(0, OPTSTAGE_K_X_IN), st->x_in[j], st->raw[OPTSTAGE_K_X_IN], hipMemcpyDeviceToDevice, cs));
+  const int l0 = c * s.Lc, l1 = l0 + s.Lc;
+  const size_t io = (size_t)c * st->desc.n_microbatches + j;
+  HIP_TRY(hipMemcpyAsync(P(l0, OPTSTAGE_K_X_IN), st->x_in[io], st->raw[OPTSTAGE_K_X_IN], hipMemcpyDeviceToDevice, cs));
   const int nstat = s.family == OPTSTAGE_LLAMA ? 1 : 2;
   const bool rc = st->lg.recompute;
-  for (int l = 0; l < s.L; ++l) {
+  for (int l = l0; l < l1; ++l) {
     void* x = P(l, OPTSTAGE_K_X_IN);
     float* stats = (float*)P(l, OPTSTAGE_K_STATS);
     // not kept: the norm outputs and the MLP activation output live in B's transient buffers, idle during F
@@ -467,13 +479,13 @@ optstage_status exec_forward(optstage* st, int j, const OpBufs& ob) {
     TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), n2, stats + (size_t)nstat * T));
     TRY(k_gemm(st, GEMM_NT, EPI_STORE, n2, W(st, l, OPTSTAGE_W_GU), P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
     TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), a));
-    void* y = l + 1 < s.L ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[j];
+    void* y = l + 1 < l1 ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[io];
     TRY(k_gemm(st, GEMM_NT, EPI_RESID, a, W(st, l, OPTSTAGE_W_D), y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
   }
   return OPTSTAGE_OK;
 }
 
-optstage_status exec_backward_input(optstage* st, int j, const OpBufs& ob) {
+optstage_status exec_backward_input(optstage* st, int j, int c, const OpBufs& ob) {
   const Shape& s = st->sh;
   hipStream_t cs = st->cs;
   const int T = s.tokens;
@@ -482,8 +494,10 @@ optstage_status exec_backward_input(optstage* st, int j, const OpBufs& ob) {
   void *da = ws + st->ws.da, *dn = ws + st->ws.dn, *dout = ws + st->ws.dout, *dqkv = ws + st->ws.dqkv;
   const int nstat = s.family == OPTSTAGE_LLAMA ? 1 : 2;
   const bool rc = st->lg.recompute;
-  HIP_TRY(hipMemcpyAsync(P(s.L - 1, OPTSTAGE_K_DY), st->dy_out[j], st->raw[OPTSTAGE_K_DY], hipMemcpyDeviceToDevice, cs));
-  for (int l = s.L - 1; l >= 0; --l) {
+  const int l0 = c * s.Lc, l1 = l0 + s.Lc;
+  const size_t io = (size_t)c * st->desc.n_microbatches + j;
+  HIP_TRY(hipMemcpyAsync(P(l1 - 1, OPTSTAGE_K_DY), st->dy_out[io], st->raw[OPTSTAGE_K_DY], hipMemcpyDeviceToDevice, cs));
+  for (int l = l1 - 1; l >= l0; --l) {
     void* dy = P(l, OPTSTAGE_K_DY);
     float* stats = (float*)P(l, OPTSTAGE_K_STATS);
     // da = dy W_d ; dgu = act'(gu) da (over gu) ; dn2 = dgu W_gu
@@ -504,13 +518,13 @@ optstage_status exec_backward_input(optstage* st, int j, const OpBufs& ob) {
     // dn1 = dqkv W_qkv ; dx_in = dx_mid + norm1'(dn1)
     TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_QKV), WT(st, l, OPTSTAGE_W_QKV), dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h));
     if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_IN), W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats));
-    void* dx = l > 0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[j];
+    void* dx = l > l0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[io];
     TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1)));
   }
   return OPTSTAGE_OK;
 }
 
-optstage_status exec_backward_weight(optstage* st, int j, const OpBufs& ob) {
+optstage_status exec_backward_weight(optstage* st, int j, int c, const OpBufs& ob) {
   const Shape& s = st->sh;
   hipStream_t cs = st->cs;
   const int T = s.tokens;
@@ -519,7 +533,7 @@ optstage_status exec_backward_weight(optstage* st, int j, const OpBufs& ob) {
   // another: bf16 stages hand them to one grouped launch per 16, so that only the last launch leaves a partly
   // filled round of workgroups; anything the grouped path does not take runs product by product.
   std::vector<GemmProblem> pr;
-  for (int l = 0; l < s.L; ++l) {
+  for (int l = c * s.Lc; l < (c + 1) * s.Lc; ++l) {
     pr.push_back({P(l, OPTSTAGE_K_DY), P(l, OPTSTAGE_K_A), GW(st, l, OPTSTAGE_W_D), nullptr, s.h, s.f, s.h, s.f, s.f});
     pr.push_back({P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_N2), GW(st, l, OPTSTAGE_W_GU), nullptr, s.up_w, s.h, s.up_w, s.h, s.h});
     pr.push_back({P(l, OPTSTAGE_K_DX_MID), P(l, OPTSTAGE_K_O), GW(st, l, OPTSTAGE_W_O), nullptr, s.h, s.nq * s.d, s.h, s.nq * s.d, s.nq * s.d});
@@ -539,31 +553,34 @@ optstage_status exec_backward_weight(optstage* st, int j, const OpBufs& ob) {
 }
 
 optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs& ob) {
-  const int j = ev.microbatch, L = st->sh.L;
+  const int j = ev.microbatch, L = st->sh.L, m = st->desc.n_microbatches;
+  // F / B / W carry their chunk in the layer field; a transfer belongs to the chunk that holds its layer
+  const int c = ev.op <= OPTSTAGE_W ? (int)ev.layer : (int)ev.layer / st->sh.Lc;
+  hipEvent_t ev_f = st->ev_f[(size_t)c * m + j];
   TimedSpan sp;
   optstage_status rc;
   switch (ev.op) {
     case OPTSTAGE_F:
       if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
-      if ((rc = exec_forward(st, j, ob)) != OPTSTAGE_OK) return rc;
+      if ((rc = exec_forward(st, j, c, ob)) != OPTSTAGE_OK) return rc;
       if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
-      HIP_TRY(hipEventRecord(st->ev_f[j], st->cs));
+      HIP_TRY(hipEventRecord(ev_f, st->cs));
       break;
     case OPTSTAGE_B:
       // every reload of this micro-batch must have completed (the reload ends before its consumer starts)
-      for (int l = 0; l < L; ++l) HIP_TRY(hipStreamWaitEvent(st->cs, st->ev_r[(size_t)j * L + l], 0));
+      for (int l = c * st->sh.Lc; l < (c + 1) * st->sh.Lc; ++l) HIP_TRY(hipStreamWaitEvent(st->cs, st->ev_r[(size_t)j * L + l], 0));
       if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
-      if ((rc = exec_backward_input(st, j, ob)) != OPTSTAGE_OK) return rc;
+      if ((rc = exec_backward_input(st, j, c, ob)) != OPTSTAGE_OK) return rc;
       if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
       break;
     case OPTSTAGE_W:
       if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
-      if ((rc = exec_backward_weight(st, j, ob)) != OPTSTAGE_OK) return rc;
+      if ((rc = exec_backward_weight(st, j, c, ob)) != OPTSTAGE_OK) return rc;
       if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
       break;
     case OPTSTAGE_O: {
       // the offload starts after the F that produced the data has ended
-      HIP_TRY(hipStreamWaitEvent(st->xs, st->ev_f[j], 0));
+      HIP_TRY(hipStreamWaitEvent(st->xs, ev_f, 0));
       // a pinned slot released by a reload listed earlier may be handed to this offload: with a reload stream
       // of its own that reload must have drained first (on a shared channel stream order already says so)
       if (st->rs != st->xs && st->last_r) HIP_TRY(hipStreamWaitEvent(st->xs, st->last_r, 0));
@@ -613,8 +630,11 @@ optstage_status precheck(optstage* st, const optstage_event* events, size_t n) {
     if (ev.op > OPTSTAGE_R) return fail(OPTSTAGE_E_ARG, "event %zu: unknown op %u", i, ev.op);
     if (ev.microbatch >= st->desc.n_microbatches) return fail(OPTSTAGE_E_ARG, "event %zu: micro-batch out of range", i);
     const int j = ev.microbatch;
-    if (ev.op == OPTSTAGE_F && (!st->x_in[j] || !st->y_out[j])) return fail(OPTSTAGE_E_STATE, "event %zu: x_in / y_out of micro-batch %d not bound", i, j);
-    if (ev.op == OPTSTAGE_B && (!st->dy_out[j] || !st->dx_in[j])) return fail(OPTSTAGE_E_STATE, "event %zu: dy_out / dx_in of micro-batch %d not bound", i, j);
+    if (ev.op <= OPTSTAGE_W && ev.layer >= (uint32_t)st->sh.chunks) return fail(OPTSTAGE_E_ARG, "event %zu: chunk %u out of range", i, ev.layer);
+    if (ev.op > OPTSTAGE_W && ev.layer >= (uint32_t)st->sh.L) return fail(OPTSTAGE_E_ARG, "event %zu: layer %u out of range", i, ev.layer);
+    const size_t io = ev.op <= OPTSTAGE_W ? (size_t)ev.layer * st->desc.n_microbatches + j : 0;
+    if (ev.op == OPTSTAGE_F && (!st->x_in[io] || !st->y_out[io])) return fail(OPTSTAGE_E_STATE, "event %zu: x_in / y_out of micro-batch %d not bound", i, j);
+    if (ev.op == OPTSTAGE_B && (!st->dy_out[io] || !st->dx_in[io])) return fail(OPTSTAGE_E_STATE, "event %zu: dy_out / dx_in of micro-batch %d not bound", i, j);
     if (ev.op == OPTSTAGE_O) needs_host = true;
   }
   if (needs_host && !st->desc.host_pool) return fail(OPTSTAGE_E_HOSTPOOL, "offload requested but no pinned host pool was given");
@@ -644,18 +664,27 @@ optstage_status run_list(optstage* st, const optstage_event* events, size_t n) {
   return OPTSTAGE_OK;
 }
 
-void reset_logical(optstage* st) {
-  Logical& lg = st->lg;
-  lg.L = st->sh.L;
-  lg.m = st->desc.n_microbatches;
-  lg.budget = st->desc.hbm_budget_bytes;
-  lg.recompute = st->desc.recompute != 0;
+// empty accounting state for one iteration; lg.bytes is left alone
+void init_logical(Logical& lg, const Shape& s, const optstage_desc& d, uint64_t arena_cap, uint64_t host_cap) {
+  lg.L = s.L;
+  lg.chunks = s.chunks;
+  lg.Lc = s.Lc;
+  lg.m = d.n_microbatches;
+  lg.budget = d.hbm_budget_bytes;
+  lg.recompute = d.recompute != 0;
   lg.live = lg.peak = 0;
-  lg.next_f = lg.next_b = lg.next_w = 0;
-  lg.mbs.assign(lg.m, MbState());
+  lg.next_f.assign(s.chunks, 0);
+  lg.next_b.assign(s.chunks, 0);
+  lg.next_w.assign(s.chunks, 0);
+  lg.mbs.assign((size_t)lg.m * s.chunks, MbState());
   lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());
-  lg.arena.reset(st->desc.arena_bytes / ALIGN * ALIGN);
-  lg.host.reset(st->desc.host_pool ? st->desc.host_pool_bytes / ALIGN * ALIGN : 0);
+  lg.arena.reset(arena_cap);
+  lg.host.reset(host_cap);
+}
+
+void reset_logical(optstage* st) {
+  init_logical(st->lg, st->sh, st->desc, st->desc.arena_bytes / ALIGN * ALIGN,
+               st->desc.host_pool ? st->desc.host_pool_bytes / ALIGN * ALIGN : 0);
 }
 
 }  // namespace
@@ -709,7 +738,8 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
   const size_t m = desc->n_microbatches, L = s.L;
   st->w.assign(L * OPTSTAGE_N_WEIGHTS, nullptr);
   st->gw.assign(L * OPTSTAGE_N_WEIGHTS, nullptr);
-  st->x_in.assign(m, nullptr); st->dy_out.assign(m, nullptr); st->y_out.assign(m, nullptr); st->dx_in.assign(m, nullptr);
+  const size_t nio = m * s.chunks;   // [chunk][mb]
+  st->x_in.assign(nio, nullptr); st->dy_out.assign(nio, nullptr); st->y_out.assign(nio, nullptr); st->dx_in.assign(nio, nullptr);
   memset(&st->stats, 0, sizeof st->stats);
   reset_logical(st);
   auto mk = [&](std::vector<hipEvent_t>& v, size_t n) -> bool {
@@ -718,7 +748,7 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
       if (hipEventCreateWithFlags(&v[i], hipEventDisableTiming) != hipSuccess) return false;
     return true;
   };
-  if (!mk(st->ev_f, m) || !mk(st->ev_o, m * L) || !mk(st->ev_r, m * L) || !mk(st->ev_pos, m * L)) {
+  if (!mk(st->ev_f, nio) || !mk(st->ev_o, m * L) || !mk(st->ev_r, m * L) || !mk(st->ev_pos, m * L)) {
     optstage_destroy(st);
     return fail(OPTSTAGE_E_HIP, "hipEventCreateWithFlags failed");
   }
@@ -758,26 +788,27 @@ optstage_status optstage_set_weight(optstage_t* st, uint32_t layer, uint32_t whi
   return OPTSTAGE_OK;
 }
 
-optstage_status optstage_bind_io(optstage_t* st, uint32_t mb, const void* x_in, const void* dy_out, void* y_out, void* dx_in) {
+optstage_status optstage_bind_io_chunk(optstage_t* st, uint32_t chunk, uint32_t mb, const void* x_in, const void* dy_out,
+                                       void* y_out, void* dx_in) {
   if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
+  if (chunk >= (uint32_t)st->sh.chunks) return fail(OPTSTAGE_E_ARG, "chunk out of range");
   if (mb >= st->desc.n_microbatches) return fail(OPTSTAGE_E_ARG, "micro-batch out of range");
   if (((uintptr_t)x_in | (uintptr_t)dy_out | (uintptr_t)y_out | (uintptr_t)dx_in) & 15) return fail(OPTSTAGE_E_ARG, "io tensors must be 16-byte aligned");
-  st->x_in[mb] = x_in; st->dy_out[mb] = dy_out; st->y_out[mb] = y_out; st->dx_in[mb] = dx_in;
+  const size_t io = (size_t)chunk * st->desc.n_microbatches + mb;
+  st->x_in[io] = x_in; st->dy_out[io] = dy_out; st->y_out[io] = y_out; st->dx_in[io] = dx_in;
   return OPTSTAGE_OK;
+}
+
+optstage_status optstage_bind_io(optstage_t* st, uint32_t mb, const void* x_in, const void* dy_out, void* y_out, void* dx_in) {
+  return optstage_bind_io_chunk(st, 0, mb, x_in, dy_out, y_out, dx_in);
 }
 
 optstage_status optstage_validate(const optstage_t* st, const optstage_event* events, size_t n, size_t* first_bad) {
   if (!st || (!events && n)) return fail(OPTSTAGE_E_ARG, "null argument");
   Logical lg;
-  lg.L = st->sh.L;
-  lg.m = st->desc.n_microbatches;
-  lg.budget = st->desc.hbm_budget_bytes;
-  lg.recompute = st->desc.recompute != 0;
   memcpy(lg.bytes, st->lg.bytes, sizeof lg.bytes);
-  lg.mbs.assign(lg.m, MbState());
-  lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());
-  lg.arena.reset(st->desc.arena_bytes / ALIGN * ALIGN);
-  lg.host.reset(st->desc.host_pool ? st->desc.host_pool_bytes / ALIGN * ALIGN : 0);
+  init_logical(lg, st->sh, st->desc, st->desc.arena_bytes / ALIGN * ALIGN,
+               st->desc.host_pool ? st->desc.host_pool_bytes / ALIGN * ALIGN : 0);
   for (size_t i = 0; i < n; ++i) {
     optstage_status rc = apply_event(lg, events[i], nullptr);
     if (rc != OPTSTAGE_OK) {
@@ -802,15 +833,9 @@ optstage_status optstage_plan(const optstage_desc* desc, const optstage_event* e
   uint64_t raw[NK];
   kind_raw_bytes(s, raw);
   Logical lg;
-  lg.L = s.L;
-  lg.m = desc->n_microbatches;
-  lg.budget = desc->hbm_budget_bytes;
-  lg.recompute = desc->recompute != 0;
   for (int k = 0; k < NK; ++k) lg.bytes[k] = round_up(raw[k]);
-  lg.mbs.assign(lg.m, MbState());
-  lg.bufs.assign((size_t)lg.m * lg.L * NK, BufRec());
-  lg.arena.reset(UINT64_MAX / 2 / ALIGN * ALIGN);   // logical accounting only: unbounded placement space
-  lg.host.reset(UINT64_MAX / 2 / ALIGN * ALIGN);
+  // logical accounting only: unbounded placement space
+  init_logical(lg, s, *desc, UINT64_MAX / 2 / ALIGN * ALIGN, UINT64_MAX / 2 / ALIGN * ALIGN);
   if (peak_bytes) *peak_bytes = 0;
   for (size_t i = 0; i < n; ++i) {
     rc = apply_event(lg, events[i], nullptr);

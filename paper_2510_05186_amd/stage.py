@@ -33,9 +33,10 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 
 class Stage:
     def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0,
-                 duplex: bool = False, recompute: bool = False):
+                 duplex: bool = False, recompute: bool = False, n_chunks: int = 1):
         """duplex: reloads get a stream of their own instead of sharing the offloads' (single channel).
-        recompute: F keeps no norm outputs and no MLP activation output; B rebuilds them for W."""
+        recompute: F keeps no norm outputs and no MLP activation output; B rebuilds them for W.
+        n_chunks: model chunks on this stage (cfg.n_layers counts all of them)."""
         if not torch.cuda.is_available():
             raise RuntimeError("optstage needs a GPU: there is no CPU path")
         self.cfg = cfg
@@ -46,6 +47,7 @@ class Stage:
         if arena_bytes is None:
             full = act_per_mb if not recompute else B.query_sizes(cfg)[1]   # B and W hold the rebuilt kinds too
             arena_bytes = int((budget if budget else full * cfg.n_microbatches) * 1.25) + (64 << 20)
+        self.n_chunks = int(n_chunks)
         self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         self.host_pool = torch.empty(host_pool_bytes, dtype=torch.uint8, pin_memory=True) if host_pool_bytes else None
@@ -56,7 +58,8 @@ class Stage:
             host_pool=self.host_pool.data_ptr() if self.host_pool is not None else 0,
             host_pool_bytes=host_pool_bytes, compute_stream=self.compute_stream.cuda_stream,
             copy_stream=self.copy_stream.cuda_stream,
-            reload_stream=self.reload_stream.cuda_stream if duplex else 0, recompute=int(recompute))
+            reload_stream=self.reload_stream.cuda_stream if duplex else 0, recompute=int(recompute),
+            n_chunks=self.n_chunks)
         h = C.c_void_p()
         B.check(self.lib.optstage_create(C.byref(self.desc), C.byref(h)))
         self.h = h
@@ -115,14 +118,17 @@ class Stage:
                 t.zero_()
         torch.cuda.synchronize()
 
-    def bind(self, mb: int, x: np.ndarray | torch.Tensor, dy: np.ndarray | torch.Tensor):
+    def bind(self, mb: int, x: np.ndarray | torch.Tensor, dy: np.ndarray | torch.Tensor, chunk: int = 0):
+        """Boundary tensors of micro-batch mb (of model chunk `chunk`); the dicts x, dy, y, dx are keyed by mb for
+        chunk 0 and by (chunk, mb) otherwise."""
         dt = self.cfg.dtype
-        self.x[mb] = x if isinstance(x, torch.Tensor) else to_device(x, dt)
-        self.dy[mb] = dy if isinstance(dy, torch.Tensor) else to_device(dy, dt)
-        self.y[mb] = torch.empty_like(self.x[mb])
-        self.dx[mb] = torch.empty_like(self.x[mb])
-        B.check(self.lib.optstage_bind_io(self.h, mb, self.x[mb].data_ptr(), self.dy[mb].data_ptr(),
-                                          self.y[mb].data_ptr(), self.dx[mb].data_ptr()))
+        key = mb if chunk == 0 else (chunk, mb)
+        self.x[key] = x if isinstance(x, torch.Tensor) else to_device(x, dt)
+        self.dy[key] = dy if isinstance(dy, torch.Tensor) else to_device(dy, dt)
+        self.y[key] = torch.empty_like(self.x[key])
+        self.dx[key] = torch.empty_like(self.x[key])
+        B.check(self.lib.optstage_bind_io_chunk(self.h, chunk, mb, self.x[key].data_ptr(), self.dy[key].data_ptr(),
+                                                self.y[key].data_ptr(), self.dx[key].data_ptr()))
 
     def _order_after_torch(self):
         """The library's streams know nothing of torch's: work torch has queued on its current stream (tensor

@@ -6,7 +6,7 @@ whoever consumes it (the library's validator, or the oracle's accounting), so
 the offload generator exposes its policy knobs and the caller searches them.
 
 Event tuples: ("F", j) ("B", j) ("W", j) ("O", j, layer, kinds) ("OWAIT", j, layer, kinds)
-("R", j, layer, kinds).
+("R", j, layer, kinds); compute events of model chunk c on a stage that holds several: (op, j, c).
 """
 from __future__ import annotations
 
@@ -22,6 +22,36 @@ def one_f_one_b(p: int, m: int, i: int) -> list:
             ev.append(("F", f))
             f += 1
         ev += [("B", b), ("W", b)]
+        b += 1
+    return ev
+
+
+def interleaved_one_f_one_b(p: int, m: int, i: int, n_chunks: int) -> list:
+    """1F1B with n_chunks model chunks per stage (chunk c of stage i is piece c p + i of the model), for stage
+    i of p; m must be a multiple of p.  Forward chunk-ops come in rounds of p micro-batches per chunk; the k-th
+    forward op is chunk (k mod p n_chunks) div p of micro-batch (k div p n_chunks) p + k mod p, the k-th
+    backward op the same with the chunks in reverse.  Warm-up: 2 (p - i - 1) + (n_chunks - 1) p forward ops,
+    then one forward / one backward, then the remaining backward ops; W runs right after its B.
+    Compute events of chunk c are written (op, j, c)."""
+    if m % p:
+        raise ValueError("interleaved 1F1B needs the micro-batch count to be a multiple of the stage count")
+    total = m * n_chunks
+
+    def fwd(k):
+        return ("F", (k // (p * n_chunks)) * p + k % p, (k % (p * n_chunks)) // p)
+
+    def bwd(k):
+        return ((k // (p * n_chunks)) * p + k % p, n_chunks - 1 - (k % (p * n_chunks)) // p)
+
+    warm = min(2 * (p - i - 1) + (n_chunks - 1) * p, total)
+    ev = [fwd(k) for k in range(warm)]
+    f, b = warm, 0
+    while b < total:
+        if f < total:
+            ev.append(fwd(f))
+            f += 1
+        j, c = bwd(b)
+        ev += [("B", j, c), ("W", j, c)]
         b += 1
     return ev
 
@@ -84,21 +114,26 @@ def add_offload(compute_list: list, n_layers: int, kinds: tuple, min_gap: int = 
     next op waits for the copy); the R events sit `lead` compute ops ahead of B j so the
     reload overlaps them (0 = B j waits for the whole reload)."""
     comp = [e for e in compute_list]
-    pos_f = {e[1]: n for n, e in enumerate(comp) if e[0] == "F"}
-    pos_b = {e[1]: n for n, e in enumerate(comp) if e[0] == "B"}
+    chunk = lambda e: e[2] if len(e) > 2 else 0
+    n_chunks = 1 + max(chunk(e) for e in comp)
+    per_chunk = n_layers // n_chunks                    # n_layers counts the layers of all chunks of the stage
+    pos_f = {(chunk(e), e[1]): n for n, e in enumerate(comp) if e[0] == "F"}
+    pos_b = {(chunk(e), e[1]): n for n, e in enumerate(comp) if e[0] == "B"}
     before = {n: [] for n in range(len(comp) + 1)}      # events to emit before compute op n
-    for j in sorted(pos_f):
-        gap = pos_b[j] - pos_f[j] - 1
+    for key in sorted(pos_f, key=lambda k: pos_f[k]):
+        c, j = key
+        gap = pos_b[key] - pos_f[key] - 1
         if gap < max(1, min_gap):
             continue
-        o_at = pos_f[j] + 1
-        wait_at = min(pos_f[j] + 1 + wait_delay, pos_b[j])
-        r_at = max(wait_at, pos_b[j] - lead)
-        for l in range(n_layers):
+        o_at = pos_f[key] + 1
+        wait_at = min(pos_f[key] + 1 + wait_delay, pos_b[key])
+        r_at = max(wait_at, pos_b[key] - lead)
+        layers = range(c * per_chunk, (c + 1) * per_chunk)
+        for l in layers:
             before[o_at].append((1, ("O", j, l, tuple(kinds))))
-        for l in range(n_layers):
+        for l in layers:
             before[wait_at].append((2 if wait_at == o_at else 0, ("OWAIT", j, l, tuple(kinds))))
-        for l in reversed(range(n_layers)):             # B consumes the last layer first
+        for l in reversed(layers):                      # B consumes the last layer first
             before[r_at].append((3, ("R", j, l, tuple(kinds))))
     out = []
     for n in range(len(comp) + 1):

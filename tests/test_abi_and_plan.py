@@ -81,6 +81,41 @@ def test_recompute_plan_matches_oracle_accounting():
     assert st == B.E_ORDER and bad == ei.value.index
 
 
+def test_plan_with_model_chunks_matches_oracle():
+    """A stage that holds two model chunks: the planner's order rules and accounting are the oracle's."""
+    cfg = small_cfg(m=4, L=4)
+    t = oracle_table(cfg)
+    m, L, v = cfg.n_microbatches, cfg.n_layers, 2
+    for i in range(2):
+        base = G.interleaved_one_f_one_b(2, m, i, v)
+        for ev in (base, G.add_offload(base, L, ("X_IN", "QKV", "GU"), min_gap=2, lead=1)):
+            S.check_order(ev, m, L, n_chunks=v)
+            peak, trace = S.account_memory(ev, L, t, n_chunks=v)
+            st, bad, lib_peak, live = B.plan(cfg, ev, n_chunks=v)
+            assert st == B.OK, B.lib().optstage_last_error()
+            assert lib_peak == peak and live == trace
+            st, bad, _, _ = B.plan(cfg, ev, budget=peak - 1, n_chunks=v)
+            assert st == B.E_BUDGET
+            with pytest.raises(S.ScheduleError) as ei:
+                S.account_memory(ev, L, t, limit=peak - 1, n_chunks=v)
+            assert ei.value.index == bad
+    kinds = ("QKV",)
+    bad_lists = [
+        [("F", 0, 0), ("B", 0, 1)],                                            # B of a chunk before its F
+        [("F", 1, 1)],                                                         # chunk 1 starts at micro-batch 0
+        [("F", 0, 0), ("F", 0, 1), ("O", 0, 3, kinds), ("OWAIT", 0, 3, kinds), ("B", 0, 1)],   # not reloaded
+        [("F", 0, 0), ("O", 0, 2, kinds)],                                     # layer 2 belongs to chunk 1
+    ]
+    for ev in bad_lists:
+        with pytest.raises(S.ScheduleError) as ei:
+            S.check_order(ev, m, L, n_chunks=v)
+        st, bad, _, _ = B.plan(cfg, ev, n_chunks=v)
+        assert st == B.E_ORDER and bad == ei.value.index, (ev, st, bad, ei.value.index)
+    assert B.plan(cfg, [("F", 0, 2)], n_chunks=v)[0] == B.E_ARG               # no such chunk
+    d = B.make_desc(cfg, n_chunks=3)                                           # 4 layers do not split in three
+    assert B.lib().optstage_query_sizes(d, None, None, None) == B.E_ARG
+
+
 def small_cfg(m=6, L=3):
     return CFG.shrunken(CFG.CFG4, hidden=256, n_q=4, n_kv=2, ffn=384, seq=192, n_layers=L, n_microbatches=m)
 

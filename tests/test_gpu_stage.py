@@ -324,6 +324,76 @@ def test_recompute_variant_changes_no_bit_and_accounts_like_the_oracle(cfg):
     ref_st.close()
 
 
+def test_two_model_chunks_on_one_stage():
+    """A stage holding two model chunks (interleaved 1F1B, stage 0 of p = 2) with offload under one shared
+    budget: every chunk's outputs and gradients are bitwise those of that chunk run as a stage of its own,
+    they match the oracle, and the accounting is the oracle's."""
+    v, m = 2, 4
+    cfg = replace(SMALL2, name="cfg2_small_two_chunks", n_layers=4, n_microbatches=m, n_stages=2, stage_index=0)
+    Lc = cfg.n_layers // v
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    base = G.interleaved_one_f_one_b(cfg.n_stages, m, cfg.stage_index, v)
+    events = G.add_offload(base, cfg.n_layers, ("X_IN", "QKV", "X_MID"), min_gap=3, lead=1)
+    assert any(e[0] == "O" for e in events)
+    S.check_order(events, m, cfg.n_layers, n_chunks=v)
+    peak, trace = S.account_memory(events, cfg.n_layers, t, n_chunks=v)
+    assert peak < S.account_memory(base, cfg.n_layers, t, n_chunks=v)[0]
+    io = {(c, j): (T.stage_input(cfg, c * m + j), T.output_grad(cfg, c * m + j)) for c in range(v) for j in range(m)}
+
+    pool = sum(t[k] for k in ("X_IN", "QKV", "X_MID")) * cfg.n_layers * m
+    st = Stage(cfg, budget=peak, host_pool_bytes=pool, arena_bytes=2 * peak, n_chunks=v)
+    st.set_weights(ws)
+    for (c, j), (x, dy) in io.items():
+        st.bind(j, x, dy, chunk=c)
+    code, bad = st.validate(events)
+    assert code == B.OK, (code, bad, B.lib().optstage_last_error())
+    st.run(events)
+    st.synchronize()
+    s = st.stats()
+    assert s.peak_bytes == peak and s.live_bytes == trace[-1] == 0
+    assert s.n_ops[B.OP_F] == s.n_ops[B.OP_B] == s.n_ops[B.OP_W] == v * m and s.bytes_offloaded == s.bytes_reloaded > 0
+
+    tol = TOL[cfg.dtype]
+    for c in range(v):
+        sub = replace(cfg, name=f"chunk{c}", n_layers=Lc)
+        wsc = ws[c * Lc:(c + 1) * Lc]
+        one = Stage(sub)
+        one.set_weights(wsc)
+        for j in range(m):
+            one.bind(j, *io[(c, j)])
+        one.run([e for j in range(m) for e in (("F", j), ("B", j), ("W", j))])
+        one.synchronize()
+        key = lambda j: j if c == 0 else (c, j)
+        for j in range(m):
+            assert torch.equal(st.y[key(j)], one.y[j]) and torch.equal(st.dx[key(j)], one.dx[j]), (c, j)
+        for l in range(Lc):
+            for name in one.grads[l]:
+                assert torch.equal(st.grads[c * Lc + l][name], one.grads[l][name]), (c, l, name)
+        # the chunk against the oracle
+        sh, ow = oracle_shape(sub), oracle_weights(wsc)
+        tot = None
+        for j in range(m):
+            y, dx, dW, dn = O.stage_fbw(sh, ow, io[(c, j)][0].astype(np.float64), io[(c, j)][1].astype(np.float64))
+            assert rel_err(host(st.y[key(j)]), y) < tol and rel_err(host(st.dx[key(j)]), dx) < tol
+            g = [{**dW[l], **dn[l]} for l in range(Lc)]
+            tot = g if tot is None else [{k: tot[l][k] + g[l][k] for k in g[l]} for l in range(Lc)]
+        for l in range(Lc):
+            for name, g in tot[l].items():
+                assert rel_err(host(st.grads[c * Lc + l][name]), g) < tol, (c, l, name)
+        one.close()
+    # a compute event for a chunk the stage does not have, and io never bound for a chunk
+    assert st.validate([("F", 0, 2)])[0] == B.E_ARG
+    st.close()
+    lone = Stage(cfg, n_chunks=v)
+    lone.set_weights(ws)
+    lone.bind(0, *io[(0, 0)])
+    with pytest.raises(B.OptstageError) as ei:
+        lone.run([("F", 0, 1)])
+    assert ei.value.status == B.E_STATE
+    lone.close()
+
+
 def test_online_schedule_swap_on_one_handle():
     """A different event list every iteration on the same handle (no re-creation): results stay bitwise the
     same, accounting follows the list that ran (the paper swaps in better schedules while training runs,

@@ -274,6 +274,139 @@ def test_recompute_variant_of_the_memory_table():
     assert ei.value.index == 1
 
 
+# ------------------------------------------------------------------ several model chunks per stage
+def tick_sim_chunks(lists, t_op, t_comm, before_of):
+    """Integer time-stepped simulator for compute-only lists with model chunks.  before_of(i, c) names the
+    (stage, chunk) holding the previous piece of the model, or None for the first piece; it is written out by
+    the caller, not computed from the oracle's placement code."""
+    p = len(lists)
+    pieces = {(i, e[2] if len(e) > 2 else 0) for i in range(p) for e in lists[i]}
+    after_of = {before_of(i, c): (i, c) for (i, c) in pieces if before_of(i, c) is not None}
+    fin = [dict() for _ in range(p)]
+    begun = [dict() for _ in range(p)]
+    busy = [0] * p
+
+    def end_of(i, op, j, c):
+        for n, e in enumerate(lists[i]):
+            if e[0] == op and e[1] == j and (e[2] if len(e) > 2 else 0) == c:
+                return fin[i].get(n)
+        raise AssertionError("missing op")
+
+    t = 0
+    while sum(len(f) for f in fin) < sum(len(l) for l in lists):
+        for i in range(p):
+            todo = [n for n in range(len(lists[i])) if n not in begun[i]]
+            if not todo or busy[i] > t:
+                continue
+            n = todo[0]
+            e = lists[i][n]
+            op, j, c = e[0], e[1], (e[2] if len(e) > 2 else 0)
+            ok = True
+            if op == "F" and before_of(i, c) is not None:
+                i2, c2 = before_of(i, c)
+                u = end_of(i2, "F", j, c2)
+                ok = u is not None and u + (t_comm if i2 != i else 0) <= t
+            if op == "B" and (i, c) in after_of:
+                i2, c2 = after_of[(i, c)]
+                u = end_of(i2, "B", j, c2)
+                ok = u is not None and u + (t_comm if i2 != i else 0) <= t
+            if ok:
+                begun[i][n] = t
+                fin[i][n] = t + t_op[i][op]
+                busy[i] = fin[i][n]
+        t += 1
+        assert t < 2000, "tick simulator stuck"
+    return max(max(f.values()) for f in fin) - min(min(b.values()) for b in begun), begun, fin
+
+
+@pytest.mark.parametrize("p,m,v", [(2, 2, 2), (4, 8, 2), (4, 4, 3), (8, 16, 2)])
+def test_interleaved_1f1b_bubble_closed_form(p, m, v):
+    """1F1B with v model chunks per stage idles (p - 1) / (v m + p - 1) of the time when a chunk's backward
+    costs twice its forward and transfers between stages are free: the warm-up and cool-down ramps are those
+    of plain 1F1B on pieces v times shorter."""
+    lists = [G.interleaved_one_f_one_b(p, m, i, v) for i in range(p)]
+    for lst in lists:
+        S.check_order(lst, m, v, n_chunks=v)
+    t_op = [{"F": 1.0, "B": 2.0, "W": 0.0}] * p
+    tm = S.simulate(lists, t_op, n_chunks=v)
+    assert abs(tm.makespan_global - (3.0 * m * v + 3.0 * (p - 1))) < 1e-12
+    assert all(abs(b - (p - 1) / (v * m + p - 1)) < 1e-12 for b in tm.bubble)
+    # one chunk per stage: the makespan of plain 1F1B (its warm-up is twice as deep, which costs memory, not time)
+    one = S.simulate([G.interleaved_one_f_one_b(p, m, i, 1) for i in range(p)], t_op)
+    assert abs(one.makespan_global - S.simulate([G.one_f_one_b(p, m, i) for i in range(p)], t_op).makespan_global) < 1e-12
+    # integer tick simulator with the placement written out by hand: chunk c of stage i follows chunk c of stage
+    # i - 1, and chunk c of stage 0 follows chunk c - 1 of the last stage
+    before = lambda i, c: (i - 1, c) if i > 0 else ((p - 1, c - 1) if c > 0 else None)
+    ti = [{"F": 1, "B": 2, "W": 1}] * p
+    span, begun, fin = tick_sim_chunks(lists, ti, 1, before)
+    tm = S.simulate(lists, ti, t_comm=1, n_chunks=v)
+    assert span == tm.makespan_global
+    for i in range(p):
+        for n in range(len(lists[i])):
+            assert begun[i][n] == tm.start[i][n] and fin[i][n] == tm.end[i][n]
+
+
+def test_v_shaped_placement_by_hand():
+    """Two stages, two chunks, V shape: the model runs stage 0 chunk 0, stage 1 chunk 0, stage 1 chunk 1, stage 0
+    chunk 1.  One micro-batch is a serial chain; times worked out by hand with T_F = 1, T_B = 2, T_W = 1 and a
+    transfer of 0.5 between stages (none where consecutive pieces share a stage)."""
+    s0 = [("F", 0, 0), ("F", 0, 1), ("B", 0, 1), ("W", 0, 1), ("B", 0, 0), ("W", 0, 0)]
+    s1 = [("F", 0, 0), ("F", 0, 1), ("B", 0, 1), ("B", 0, 0), ("W", 0, 1), ("W", 0, 0)]
+    t_op = [{"F": 1.0, "B": 2.0, "W": 1.0}] * 2
+    tm = S.simulate([s0, s1], t_op, t_comm=0.5, n_chunks=2, placement="v")
+    # stage 0: F c0 0..1; stage 1: F c0 1.5..2.5, F c1 2.5..3.5; stage 0: F c1 4..5, B c1 5..7, W c1 7..8;
+    # stage 1: B c1 7.5..9.5, B c0 9.5..11.5, W 11.5..12.5, W 12.5..13.5; stage 0: B c0 12..14, W c0 14..15
+    assert tm.start[0] == [0.0, 4.0, 5.0, 7.0, 12.0, 14.0]
+    assert tm.start[1] == [1.5, 2.5, 7.5, 9.5, 11.5, 12.5]
+    assert tm.makespan_global == 15.0
+    assert [S.virtual_stage(i, c, 2, "v") for i, c in ((0, 0), (1, 0), (1, 1), (0, 1))] == [0, 1, 2, 3]
+    # the same lists read as interleaved (stage 0 chunk 1 would follow stage 1 chunk 0... and stage 1 chunk 1 stage
+    # 0 chunk 1) deadlock on stage 1, which lists F of chunk 1 before stage 0 has run it
+    span, begun, fin = tick_sim_chunks([s0, s1], [{"F": 2, "B": 4, "W": 2}] * 2, 1,
+                                       lambda i, c: {(0, 0): None, (1, 0): (0, 0), (1, 1): (1, 0), (0, 1): (1, 1)}[(i, c)])
+    tm2 = S.simulate([s0, s1], [{"F": 2, "B": 4, "W": 2}] * 2, t_comm=1, n_chunks=2, placement="v")
+    assert span == tm2.makespan_global == 30
+
+
+def test_chunked_lists_order_rules_and_accounting():
+    Lc, v, m = 2, 2, 4
+    lst = G.interleaved_one_f_one_b(2, m, 0, v)
+    S.check_order(lst, m, Lc * v, n_chunks=v)
+    # per chunk: B needs that chunk's F, W that chunk's B, micro-batches in order per chunk
+    bad = [("F", 0, 0), ("B", 0, 1)]
+    with pytest.raises(S.ScheduleError) as ei:
+        S.check_order(bad + [("W", 0, 1)], 1, 2, n_chunks=2)
+    assert ei.value.index == 1
+    with pytest.raises(S.ScheduleError):
+        S.check_order([("F", 0, 0), ("F", 1, 1)], 2, 2, n_chunks=2)          # chunk 1 starts at micro-batch 0
+    with pytest.raises(S.ScheduleError):
+        S.check_order([("F", 0, 2)], 1, 2, n_chunks=2)                        # no such chunk
+    S.check_order([("F", 0, 1), ("F", 0, 0), ("B", 0, 0), ("B", 0, 1), ("W", 0, 1), ("W", 0, 0)], 1, 2, n_chunks=2)
+    # a chunk op moves the bytes of the chunk's layers only: the same totals as a one-chunk stage with
+    # n_layers / n_chunks layers on which every (chunk, micro-batch) pair is a micro-batch of its own
+    relabelled = [(e[0], e[2] * m + e[1]) for e in lst]
+    pk, tr = S.account_memory(lst, Lc * v, TABLE, n_chunks=v)
+    pk1, tr1 = S.account_memory(relabelled, Lc, TABLE)
+    assert pk == pk1 and tr == tr1 and tr[-1] == 0
+    # stage 0 of p = 2: 2 (p - 1) + (v - 1) p = 4 warm-up forward chunk-ops and the first steady-state one
+    # precede its first backward
+    dF = S.op_delta("F", Lc, TABLE)
+    first_b = next(n for n, e in enumerate(lst) if e[0] == "B")
+    assert tr[first_b - 1] == 5 * dF
+    # transfers name the layer on the stage; B of a chunk needs the reloads of that chunk's layers only
+    kinds = ("QKV",)
+    ev = [("F", 0, 0), ("O", 0, 1, kinds), ("F", 0, 1), ("OWAIT", 0, 1, kinds), ("B", 0, 1), ("W", 0, 1),
+          ("R", 0, 1, kinds), ("B", 0, 0), ("W", 0, 0)]
+    S.check_order(ev, 1, 4, n_chunks=2)
+    with pytest.raises(S.ScheduleError) as ei:
+        S.check_order([("F", 0, 0), ("F", 0, 1), ("O", 0, 3, kinds), ("OWAIT", 0, 3, kinds), ("B", 0, 1)], 1, 4, n_chunks=2)
+    assert ei.value.index == 4
+    tm = S.simulate([ev], [{"F": 1.0, "B": 2.0, "W": 1.0}], t_copy=lambda i, e: 0.5, n_chunks=2, layers_per_chunk=2)
+    # F c0 0..1, F c1 1..2, B c1 2..4, W c1 4..5: the offload starts when F of chunk 0 ends, the reload when W of
+    # chunk 1 ends, and B of chunk 0 when the reload (0.5) is in
+    assert tm.start[0][1] == 1.0 and tm.start[0][6] == 5.0 and tm.start[0][7] == 5.5
+
+
 # ------------------------------------------------------------------ brute force
 def all_orders(m):
     ops = [(c, j) for j in range(m) for c in "FBW"]
