@@ -8,9 +8,9 @@
 // next product's 8-element operand, so probabilities never move between lanes:
 //   forward / dQ:  S^T = K Q^T (lane = query, registers = keys)  ->  O^T += V^T P^T,  dQ^T += K^T dS^T
 //   dK/dV:         S   = Q K^T (lane = key,   registers = queries) -> dV^T += dO^T P,  dK^T += Q^T dS
-// Operands that are contracted over their row index (V^T, K^T, dO^T, Q^T) are transposed in registers on
-// the way into LDS (4 x 8 patches, 8-byte stores); all LDS tiles are XOR-swizzled so that operand reads
-// and tile writes are bank-conflict free.
+// Tiles go from global memory straight into LDS, row-major; operands that are contracted over their row
+// index (V^T, K^T, dO^T, Q^T) come out of the same tile through transposing LDS reads.  All LDS tiles are
+// XOR-swizzled so that both kinds of operand reads are bank-conflict free.
 #include "common.h"
 
 namespace {
@@ -18,81 +18,9 @@ namespace {
 constexpr int D = 128;
 constexpr float LOG2E = 1.4426950408889634f;
 
-// LDS swizzles.  The LDS serves 16-byte reads 16 lanes at a time and 8-byte reads 32 lanes at a time over
-// 64 four-byte banks (256 B), writes in 128-byte passes; each access pattern below touches every bank once.
-// [rows][128] bf16 tile, 256 B per row: 16-byte chunk c of row r is stored at chunk c ^ (r & 15), so the
-// 16 lanes that read one chunk of 16 consecutive rows hit 16 different chunks.
-__device__ __forceinline__ int rowmajor_off(int r, int c) { return r * 256 + ((c ^ (r & 15)) << 4); }
-// [128][64] bf16 transposed tile, 128 B per row: 8-byte granule q of row r is stored at granule
-// q ^ (((r >> 3) ^ ((r & 7) << 1)) & 15): distinct over 16 consecutive rows, over (row parity, granule) of
-// 32 consecutive rows (operand reads), and over rows 8 apart (the 16 lanes of one transposing store).
-__device__ __forceinline__ int transposed_off(int r, int q) { return r * 128 + ((q ^ (((r >> 3) ^ ((r & 7) << 1)) & 15)) << 3); }
-
-// Per-lane constants of the operand reads: every LDS address is (lane base) + (compile-time tile offset) +
-// ((lane swizzle term) ^ (compile-time chunk term)), i.e. one xor-add per read.
-struct FragAddr {
-  int rm_base, rm_x, tr_base, tr_x;
-  __device__ __forceinline__ FragAddr(int c32, int g) {
-    rm_base = c32 * 256;
-    rm_x = (g ^ (c32 & 15)) << 4;
-    tr_base = c32 * 128;
-    tr_x = ((((c32 >> 3) ^ ((c32 & 7) << 1)) & 15) ^ g) << 3;
-  }
-  // 16-byte operand of k-step ks (d = 16 ks + 8 g ..) from row 32 t + c32 of a row-major tile
-  __device__ __forceinline__ bf16x8_t rowmajor(const char* lds, int t, int ks) const {
-    return *reinterpret_cast<const bf16x8_t*>(lds + rm_base + 8192 * t + (rm_x ^ (ks << 5)));
-  }
-  // 8-element operand contracted over tile rows 32 t + 16 u + 4 g + {0..3} and + 8, column 32 dt + c32
-  __device__ __forceinline__ bf16x8_t transposed(const char* lds, int dt, int t, int u) const {
-    const int k = ((8 * t + 4 * u) ^ (4 * dt)) << 3;          // 4 dt enters the swizzle through row >> 3
-    uint2 lo = *reinterpret_cast<const uint2*>(lds + tr_base + 4096 * dt + (tr_x ^ k));
-    uint2 hi = *reinterpret_cast<const uint2*>(lds + tr_base + 4096 * dt + (tr_x ^ k ^ 16));
-    uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    return *reinterpret_cast<bf16x8_t*>(&v);
-  }
-};
-
-// cooperative load of a [64 rows][128] tile (rows row0.., zero beyond nrows): thread (kq = tid / 16,
-// dc = tid % 16) holds rows 4 kq .. 4 kq + 3 of 16-byte column chunk dc; the same registers feed both the
-// row-major and the transposed LDS store
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void_t;
-// Tiles are fetched with raw buffer loads: one 32-bit lane offset (row 4 kq, chunk dc) plus a scalar offset
-// for (first row + kk, head); rows at or past the end of the tensor fall outside the buffer range and read
-// as zero, so there is neither predication nor 64-bit address arithmetic in the loops.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ unsigned tile_lane_offset(int ld, int tid) { return (unsigned)((tid >> 4) * 4 * ld + (tid & 15) * 8) * 2u; }
-// byte_off: scalar byte offset of (row0, first column of the head) inside the buffer
-__device__ __forceinline__ void tile_load(uint4 reg[4], __amdgpu_buffer_rsrc_t rs, unsigned lane_off, unsigned byte_off, int ld) {
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    i32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, byte_off + (unsigned)(kk * ld * 2), 0);
-    reg[kk] = make_uint4((unsigned)v[0], (unsigned)v[1], (unsigned)v[2], (unsigned)v[3]);
-  }
-}
-__device__ __forceinline__ void tile_store_rowmajor(char* lds, const uint4 reg[4], int tid) {
-  const int kq = tid >> 4, dc = tid & 15;
-  const int base = kq * 1024, x = (dc ^ ((4 * kq) & 15)) << 4;      // row 4 kq + kk: (row & 15) = (4 kq & 15) ^ kk
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) *reinterpret_cast<uint4*>(lds + base + kk * 256 + (x ^ (kk << 4))) = reg[kk];
-}
-__device__ __forceinline__ void tile_store_transposed(char* lds, const uint4 reg[4], int tid) {
-  const int kq = tid >> 4, dc = tid & 15;
-  const uint32_t* w = reinterpret_cast<const uint32_t*>(reg);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    uint32_t o[2];
-#pragma unroll
-    for (int pr = 0; pr < 2; ++pr) {
-      uint32_t a = w[(2 * pr) * 4 + (i >> 1)], b = w[(2 * pr + 1) * 4 + (i >> 1)];
-      o[pr] = (i & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-    }
-    // row 8 dc + i: swizzle term ((row >> 3) ^ ((row & 7) << 1)) & 15 = dc ^ 2 i
-    *reinterpret_cast<uint2*>(lds + dc * 1024 + i * 128 + ((((kq ^ dc) & 15) << 3) ^ (i << 4))) = make_uint2(o[0], o[1]);
-  }
-}
+
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int u) {
   bf16x8_t r;
 #pragma unroll
@@ -100,167 +28,318 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int u) {
   return r;
 }
 
-
-// One 32 x 32 score tile (and optionally the matching dP tile) over the 8 k-steps of head_dim 128, with the
-// LDS operand reads of k-step ks + 1 issued before the MFMAs of k-step ks and scheduling fences in between,
-// so that at most two k-steps of operands are live (bounded registers, no spills); the second wave of the
-// SIMD covers what LDS latency remains.  LA / LB say whether an operand comes from an LDS tile (row
-// block ta / tb) or from the register-resident fragments ra / rb.
-template <bool TWO, bool LA, bool LB>
-__device__ __forceinline__ void score_tiles(const FragAddr& fr, const char* sA0, const char* sA1, int ta,
-                                            const char* sB0, const char* sB1, int tb, const bf16x8_t* ra0,
-                                            const bf16x8_t* ra1, const bf16x8_t* rb0, const bf16x8_t* rb1,
-                                            f32x16_t& s, f32x16_t& dp) {
-  bf16x8_t a0[2], b0[2], a1[2], b1[2];
-  auto fetch = [&](int buf, int ks) {
-    if (LA) { a0[buf] = fr.rowmajor(sA0, ta, ks); if (TWO) a1[buf] = fr.rowmajor(sA1, ta, ks); }
-    if (LB) { b0[buf] = fr.rowmajor(sB0, tb, ks); if (TWO) b1[buf] = fr.rowmajor(sB1, tb, ks); }
-  };
-  fetch(0, 0);
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    if (ks < 7) fetch((ks + 1) & 1, ks + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(LA ? a0[ks & 1] : ra0[ks], LB ? b0[ks & 1] : rb0[ks], s, 0, 0, 0);
-    if (TWO) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(LA ? a1[ks & 1] : ra1[ks], LB ? b1[ks & 1] : rb1[ks], dp, 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+// max over the two lanes 32 apart (the two halves of a score row), in both of them: v_permlane32_swap exchanges
+// the upper half of its first operand with the lower half of its second, so swapping x with itself gives
+// (x.low, x.low) and (x.high, x.high).  A vector instruction: no trip through the LDS crossbar.
+__device__ __forceinline__ float pair_max32(float x) {
+  const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
 }
 
-// acc[dt] += T^T-fragment(dt, t, u) x packed tile, for the 4 row tiles of head_dim 128 and both 16-wide
-// contraction halves u of one 32-wide tile t
-__device__ __forceinline__ void accumulate_transposed(const FragAddr& fr, const char* sT, int t, const f32x16_t& w,
-                                                      f32x16_t (&acc)[4]) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    bf16x8_t f[4];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) f[dt] = fr.transposed(sT, dt, t, u);
-    const bf16x8_t pw = pack8(w, u);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[dt], pw, acc[dt], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
+// ---- forward: grid (n_q, batch, ceil(seq / 256)); 4 waves (one per SIMD) ---------------------------------
+// Same frame as the dQ kernel below: wave w owns queries q0 + 64 w .. + 63 as two 32-query tiles, Q operand
+// fragments in registers, O^T ([d 128][64 queries]) in accumulator registers, key blocks of 64 (K and V rows)
+// streaming through an LDS ring filled straight from global memory (three stages: the scores of the next
+// block's first tile are issued before the current block's last tile is finished).  Per 32-key tile:
+//   S^T = K Q^T (16 MFMAs), p = exp2(c s - c m_ref) with row sums, O^T += V^T P^T (16 MFMAs, V^T through
+//   transposing LDS reads of the row-major V tile).
+// One wave per SIMD means nothing else hides the exponentials (v_exp_f32 runs at a quarter of the vector rate:
+// per tile they cost about half of what the 32 MFMAs cost), so the steps of consecutive tiles are interleaved by
+// hand: the exponentials of tile i run between the score MFMAs of tile i + 1, the row maxima of tile i + 1
+// between the O^T MFMAs of tile i.
+// The softmax reference m_ref is not the running maximum: it is raised (and O^T and the row sums rescaled)
+// only when some row of the wave finds a score more than FWD_TAU / c above it, so p <= 2^FWD_TAU and the
+// rescaling, which would sit between consecutive tiles' MFMAs on the same accumulators, is rare after the first
+// tiles.  softmax does not depend on the reference: o = (sum p v) / (sum p), lse = m_ref scale + log(sum p).
+constexpr int FWD_STAGE = 32768;             // K tile, V tile of 64 keys
+constexpr int FWD_SMEM = 3 * FWD_STAGE;
+constexpr float FWD_TAU = 8.f;
 
-// ---- forward ------------------------------------------------------------------------------------------
-// grid (n_q, batch, ceil(seq / 128)); 4 waves x 32 query rows; key blocks of 64
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
-                                                        float* __restrict__ lse, int seq, int n_q, int n_kv) {
-  __shared__ __attribute__((aligned(16))) char smem[2 * 16384];
-  char* sK = smem;
-  char* sV = smem + 16384;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, c32 = lane & 31;
-  const FragAddr fr(c32, g);
-  const int nqb = (seq + 127) / 128;
-  const int q0 = (nqb - 1 - (int)blockIdx.z) * 128;          // longest rows are dispatched first, for every head
+__global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+                                                     float* __restrict__ lse, int seq, int n_q, int n_kv) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nqb = (seq + 255) / 256;
+  const int q0 = (nqb - 1 - (int)blockIdx.z) * 256;          // longest rows are dispatched first, for every head
   const int a = blockIdx.x, b = blockIdx.y, kvh = a * n_kv / n_q;
-  const int ld = (n_q + 2 * n_kv) * D;
+  const int ld = (n_q + 2 * n_kv) * D, ldo = n_q * D;
   const bf16_t* base = qkv + (size_t)b * seq * ld;
-  const int qglob = q0 + 32 * wave + c32;
-  const int qrow = min(qglob, seq - 1);
-  bf16x8_t qf[8];
+  const int wave_first_q = q0 + 64 * wave, wave_last_q = wave_first_q + 63;
+  const float scale = rsqrtf((float)D), c = scale * LOG2E, thr = FWD_TAU / c;
+
+  bf16x8_t Qf[2][8];
+  int qglob[2];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(base + (size_t)qrow * ld + a * D + 16 * ks + 8 * g);
-  f32x16_t oacc[4];
+  for (int qt = 0; qt < 2; ++qt) {
+    qglob[qt] = wave_first_q + 32 * qt + c32;
+    const bf16_t* qp = base + (size_t)min(qglob[qt], seq - 1) * ld + (size_t)a * D + 8 * g;
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+    for (int ks = 0; ks < 8; ++ks) Qf[qt][ks] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * ks);
+  }
+  f32x16_t acc[2][4];                          // [query tile][d tile]: lane = query, registers = d
 #pragma unroll
-    for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
-  float m = -INFINITY, l = 0.f;
-  const float scale = rsqrtf((float)D), c = scale * LOG2E;
-  const int nkb = min((q0 + 127) / 64 + 1, (seq + 63) / 64);
-  const int wave_last_q = q0 + 32 * wave + 31;
-  uint4 kreg[4], vreg[4];
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, (unsigned)seq * ld * 2u);
-  const unsigned lane_off = tile_lane_offset(ld, tid);
-  const unsigned k_off = (unsigned)(n_q + kvh) * D * 2u, v_off = (unsigned)(n_q + n_kv + kvh) * D * 2u;
-  tile_load(kreg, rs, lane_off, k_off, ld);
-  tile_load(vreg, rs, lane_off, v_off, ld);
-  for (int kb = 0; kb < nkb; ++kb) {
-    __syncthreads();
-    tile_store_rowmajor(sK, kreg, tid);
-    tile_store_transposed(sV, vreg, tid);
-    __syncthreads();
-    if (kb + 1 < nkb) {
-      const unsigned row_off = (unsigned)(64 * (kb + 1)) * ld * 2u;
-      tile_load(kreg, rs, lane_off, row_off + k_off, ld);
-      tile_load(vreg, rs, lane_off, row_off + v_off, ld);
-    }
-    if (64 * kb > wave_last_q) continue;                       // wave-uniform: block above this wave's diagonal
-    f32x16_t s[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        bf16x8_t kf = fr.rowmajor(sK, t, ks);
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
-      }
-    if (64 * kb + 63 > q0 + 32 * wave) {                       // block touches the diagonal
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int key = 64 * kb + 32 * t + 8 * (v >> 2) + 4 * g + (v & 3);
-          if (key > qglob) s[t][v] = -INFINITY;
-        }
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[t][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m - mn) * c);
-    const float mc = mn * c;
-    float ls = 0.f;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float p = __builtin_amdgcn_exp2f(fmaf(s[t][v], c, -mc));
-        s[t][v] = p;
-        ls += p;
-      }
-    l = l * alpha + ls;
-    m = mn;
+  for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+      for (int v = 0; v < 16; ++v) acc[qt][dt][v] = 0.f;
+  float mref[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
+
+  // LDS addressing as in the dQ kernel: 64 rows x 256 B per tile, 16-byte chunk c of row r stored at chunk
+  // c ^ (((r & 3) << 2) | ((r >> 2) & 3))
+  int rm_addr[8];
+  {
+    const int f = ((c32 & 3) << 2) | ((c32 >> 2) & 3);
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        bf16x8_t pf = pack8(s[t], u);
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          bf16x8_t vf = fr.transposed(sV, dt, t, u);
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
-        }
-      }
+    for (int ks = 0; ks < 8; ++ks) rm_addr[ks] = c32 * 256 + (((2 * ks + g) ^ f) << 4);
   }
-  const float lt = l + __shfl_xor(l, 32, 64);
-  if (qglob >= seq) return;
-  const float inv = 1.f / lt;
-  bf16_t* orow = o + ((size_t)b * seq + qglob) * (n_q * D) + a * D;
+  int tr_addr[4][2];
+  {
+    const int cg = (lane >> 4) & 1, e = (lane >> 2) & 3, r = lane & 3;
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int kq = 0; kq < 2; ++kq)
+        tr_addr[dt][kq] = (4 * g + e) * 256 + (((4 * dt + 2 * cg + (r >> 1)) ^ (e << 2) ^ g ^ (kq << 1)) << 4) + (r & 1) * 8;
+  }
+  unsigned voff[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = 16 * wave + 4 * j + (lane >> 4);
+    const int chunk = (lane & 15) ^ (((lane >> 4) << 2) | j);
+    voff[j] = (unsigned)row * (unsigned)ld * 2u + (unsigned)chunk * 16u;
+  }
+  i32x4_t rs;
+  {
+    const unsigned long long ad = (unsigned long long)base;
+    rs[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)ad);
+    rs[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)(ad >> 32) & 0xffff);
+    rs[2] = (int)((unsigned)seq * ld * 2u);                   // rows at or past seq read zero
+    rs[3] = 0x00020000;
+  }
+  const unsigned lds0 = (unsigned)(size_t)(lds_void_t*)smem;
+  const unsigned k_off = (unsigned)(n_q + kvh) * D * 2u, v_off = (unsigned)(n_q + n_kv + kvh) * D * 2u;
+  auto issue_block = [&](int kb, int stage) {
+    const unsigned rowoff = (unsigned)(64 * kb) * (unsigned)ld * 2u;
+    const unsigned dst = lds0 + stage * FWD_STAGE + (16 * wave) * 256;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      bf16x4_t r;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] = (bf16_t)(oacc[dt][4 * j + i] * inv);
-      *reinterpret_cast<bf16x4_t*>(orow + 32 * dt + 8 * j + 4 * g) = r;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst + j * 1024), "v"(voff[j] + rowoff + k_off), "s"(rs) : "memory", "m0");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst + 16384 + j * 1024), "v"(voff[j] + rowoff + v_off), "s"(rs) : "memory", "m0");
     }
-  if (g == 0) lse[((size_t)b * n_q + a) * seq + qglob] = m * scale + logf(lt);
+  };
+  typedef short i16x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) i16x4_t lds_i16x4_t;
+  auto tr_frag = [&](const char* tile, int dt, int t, int u) {
+    const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t*)(tile + (32 * t + 16 * u) * 256 + tr_addr[dt][0]));
+    const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t*)(tile + (32 * t + 16 * u + 8) * 256 + tr_addr[dt][1]));
+    return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto rm_frag = [&](const char* tile, int t, int ks) {
+    return *reinterpret_cast<const bf16x8_t*>(tile + t * 8192 + rm_addr[ks]);
+  };
+
+  const int nkb = min((q0 + 255) / 64 + 1, (seq + 63) / 64);
+
+#define OPTSTAGE_SB() __builtin_amdgcn_sched_barrier(0)
+#define OPTSTAGE_MFMA_V(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+  // O^T and the Q fragments stay in the accumulation half of the register file (an MFMA takes its A / B operands
+  // from either half): the vector half holds two score tiles, the streaming operand fragments and addresses.  A
+  // compiler-chosen form would shuttle O^T between the halves at every tile.
+#define OPTSTAGE_MFMA_A(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b))
+  // Every wave runs every tile of the workgroup's 2 nkb, with no branch around a step: a tile above a wave's
+  // diagonal is masked entirely (p = 0 adds nothing), and its SIMD would wait for the workgroup's last wave
+  // anyway.  The scores issued in the very last step read a stage that holds no tile of this workgroup's; they
+  // are never used.
+  //
+  // scores of the next tile into nxt (K half t of the tile in `stage_k`), between them the exponentials of the
+  // current tile in cur
+  // The first operand fragment of every step is read during the step before it (kf_first, trf_first), so that no
+  // step starts with the matrix unit idle for an LDS round trip.
+  bf16x8_t kf_first, trf_first;
+  auto step_scores = [&](bool with_exp, int stage_k, int t, f32x16_t (&cur)[2], f32x16_t (&nxt)[2], int stage_v, int tv) {
+    const char* sK = smem + stage_k * FWD_STAGE;
+    bf16x8_t kf[2];
+    kf[0] = kf_first;
+    const float mc0 = mref[0] * c, mc1 = mref[1] * c;
+    float ls0 = 0.f, ls1 = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      OPTSTAGE_SB();
+      if (ks < 7) kf[(ks + 1) & 1] = rm_frag(sK, t, ks + 1);
+      else trf_first = tr_frag(smem + stage_v * FWD_STAGE + 16384, 0, tv, 0);
+      OPTSTAGE_SB();
+      // The compiler does not see into the MFMA statements, so it keeps no distance between a vector instruction
+      // that produces an operand (a copy, a read of an accumulation register that holds part of Q) and the MFMA
+      // that consumes it: have the operands in place, then two idle cycles
+      asm volatile("s_nop 1" :: "v"(kf[ks & 1]));
+      // One MFMA, then vector work for about as long as it occupies the matrix unit, then the next: a wave that
+      // reaches an MFMA while the unit is busy waits there and issues nothing else, so two MFMAs back to back
+      // followed by all of the vector work run one after the other instead of side by side.
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        if (ks == 0)                                             // the first k-step starts from C = 0
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(nxt[qt]) : "v"(kf[0]), "a"(Qf[qt][0]));
+        else
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(nxt[qt]) : "v"(kf[ks & 1]), "a"(Qf[qt][ks]));
+        OPTSTAGE_SB();
+        if (with_exp) {                                          // compile-time after inlining
+          const int v = 2 * ks + qt;
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(cur[0][v], c, -mc0));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(cur[1][v], c, -mc1));
+          cur[0][v] = p0; cur[1][v] = p1;
+          ls0 += p0; ls1 += p1;
+          // keeps these instructions here, between the MFMAs: without a use at this point the compiler sinks
+          // them to where the probabilities are packed
+          asm volatile("" : "+v"(cur[0][v]), "+v"(cur[1][v]), "+v"(ls0), "+v"(ls1));
+        }
+        OPTSTAGE_SB();
+      }
+    }
+    OPTSTAGE_SB();
+    lsum[0] += ls0; lsum[1] += ls1;
+  };
+  // scores above the diagonal (and keys past the sequence, which lie above every stored query) leave the softmax
+  auto mask_tile = [&](int i, f32x16_t (&sc)[2]) {
+    if (32 * i + 31 <= wave_first_q) return;                     // wave-uniform: the tile lies below the diagonal
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = 32 * i + 8 * (v >> 2) + 4 * g + (v & 3);
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+        if (key > qglob[qt]) sc[qt][v] = -INFINITY;
+    }
+  };
+  auto max_half = [&](int n, int qt, const f32x16_t (&sc)[2], float (&mx)[2]) {
+    mx[qt] = fmaxf(mx[qt], fmaxf(sc[qt][2 * n], sc[qt][2 * n + 1]));
+    asm volatile("" : "+v"(mx[qt]));                            // stays between the MFMAs it is written between
+  };
+  auto max_slice = [&](int n, const f32x16_t (&sc)[2], float (&mx)[2]) {
+    mx[0] = fmaxf(mx[0], fmaxf(sc[0][2 * n], sc[0][2 * n + 1]));
+    mx[1] = fmaxf(mx[1], fmaxf(sc[1][2 * n], sc[1][2 * n + 1]));
+    asm volatile("" : "+v"(mx[0]), "+v"(mx[1]));               // stays between the MFMAs it is written between
+  };
+  // the rare raise of m_ref, with O^T and the row sums rescaled
+  auto raise_reference = [&](float (&mx)[2]) {
+    mx[0] = pair_max32(mx[0]);                                  // the two lanes of a row hold 16 keys each
+    mx[1] = pair_max32(mx[1]);
+    if (__any((mx[0] > mref[0] + thr) | (mx[1] > mref[1] + thr))) {
+      asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");         // the last O^T MFMAs have left the matrix unit
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        const float mn = fmaxf(mref[qt], mx[qt]);
+        const float alpha = mn == mref[qt] ? 1.f : __builtin_amdgcn_exp2f((mref[qt] - mn) * c);
+        mref[qt] = mn;
+        lsum[qt] *= alpha;
+        // one accumulator tile at a time: they pass through vector registers for the multiplication
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          OPTSTAGE_SB();
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[qt][dt][v] *= alpha;
+        }
+        OPTSTAGE_SB();
+      }
+    }
+  };
+  // O^T += V^T P^T of the current tile (probabilities in cur, V half t of the tile in `stage_v`), between the MFMAs
+  // the row maxima of the next tile i1 (scores in nxt, already masked)
+  auto step_output = [&](int stage_v, int t, int i1, f32x16_t (&cur)[2], f32x16_t (&nxt)[2], int stage_k, int tk) {
+    const char* sV = smem + stage_v * FWD_STAGE + 16384;
+    mask_tile(i1, nxt);
+    float mx[2] = {-INFINITY, -INFINITY};
+    // fragment n + 2 is requested before the MFMAs of fragment n: one pair of MFMAs is shorter than an LDS round
+    // trip
+    bf16x8_t trf[3];
+    trf[0] = trf_first;
+    trf[1] = tr_frag(sV, 1, t, 0);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bf16x8_t p0 = pack8(cur[0], u), p1 = pack8(cur[1], u);
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const int n = u * 4 + dt, n2 = n + 2;
+        OPTSTAGE_SB();
+        if (n2 < 8) trf[n2 % 3] = tr_frag(sV, n2 & 3, t, n2 >> 2);
+        else if (n == 6) kf_first = rm_frag(smem + stage_k * FWD_STAGE, tk, 0);
+        if (dt == 0) asm volatile("s_nop 1" :: "v"(p0), "v"(p1) : "memory");   // packed operands settled
+        OPTSTAGE_SB();
+        OPTSTAGE_MFMA_A(acc[0][dt], trf[n % 3], p0);
+        OPTSTAGE_SB();
+        max_half(n, 0, nxt, mx);
+        OPTSTAGE_SB();
+        OPTSTAGE_MFMA_A(acc[1][dt], trf[n % 3], p1);
+        OPTSTAGE_SB();
+        max_half(n, 1, nxt, mx);
+      }
+    }
+    OPTSTAGE_SB();
+    raise_reference(mx);
+  };
+#define OPTSTAGE_BLOCK_SYNC() asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory")
+
+  f32x16_t sA[2], sB[2];
+  issue_block(0, 0);
+  OPTSTAGE_BLOCK_SYNC();
+  if (nkb > 1) issue_block(1, 1);
+  kf_first = rm_frag(smem, 0, 0);
+  step_scores(false, 0, 0, sB, sA, 0, 0);                      // scores of tile 0 into sA
+  {
+    // nothing to hide behind yet: results of the matrix unit may be read by the vector unit only some cycles
+    // after the last pass
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    mask_tile(0, sA);
+    float mx[2] = {-INFINITY, -INFINITY};
+#pragma unroll
+    for (int n = 0; n < 8; ++n) max_slice(n, sA, mx);
+    raise_reference(mx);
+    kf_first = rm_frag(smem, 1, 0);
+  }
+  int stage = 0;
+  for (int kb = 0; kb < nkb; ++kb) {
+    const int next = stage == 2 ? 0 : stage + 1, after = next == 2 ? 0 : next + 1;
+    step_scores(true, stage, 1, sA, sB, stage, 0);             // exponentials of tile 2 kb, scores of tile 2 kb + 1
+    // block kb + 1 has landed (this wave's part; the barrier covers the rest; it was requested a whole block
+    // ago) and nobody still reads the stage that block kb - 1 was in
+    OPTSTAGE_BLOCK_SYNC();
+    if (kb + 2 < nkb) issue_block(kb + 2, after);
+    step_output(stage, 0, 2 * kb + 1, sA, sB, next, 0);
+    step_scores(true, next, 0, sB, sA, stage, 1);              // exponentials of tile 2 kb + 1, scores of tile 2 kb + 2
+    step_output(stage, 1, 2 * kb + 2, sB, sA, next, 1);
+    stage = next;
+  }
+#undef OPTSTAGE_BLOCK_SYNC
+#undef OPTSTAGE_MFMA_V
+#undef OPTSTAGE_MFMA_A
+  asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+
+  float lt[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) lt[qt] = lsum[qt] + __shfl_xor(lsum[qt], 32, 64);
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    if (qglob[qt] >= seq) continue;
+    const float inv = 1.f / lt[qt];
+    bf16_t* orow = o + ((size_t)b * seq + qglob[qt]) * ldo + (size_t)a * D;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      OPTSTAGE_SB();
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x4_t r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (bf16_t)(acc[qt][dt][4 * j + i] * inv);
+        *reinterpret_cast<bf16x4_t*>(orow + 32 * dt + 8 * j + 4 * g) = r;
+      }
+    }
+    if (g == 0) lse[((size_t)b * n_q + a) * seq + qglob[qt]] = mref[qt] * scale + logf(lt[qt]);
+  }
+#undef OPTSTAGE_SB
 }
+
 
 // ---- backward, dQ: grid (n_q, batch, ceil(seq / 256)); 4 waves (one per SIMD) -----------------------------
 // Mirror image of the dK/dV kernel below.  Wave w owns queries q0 + 64 w .. + 63 as two 32-query tiles: their Q
@@ -852,7 +931,13 @@ bool attn_mfma_applies(int dtype, int d, int seq, int n_q, int n_kv) {
 }
 
 hipError_t launch_attn_fwd_mfma(const void* qkv, void* o, float* lse, int seq, int batch, int n_q, int n_kv, hipStream_t s) {
-  hipLaunchKernelGGL(attn_fwd_mfma, dim3(n_q, batch, (seq + 127) / 128), dim3(256), 0, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, n_q, n_kv);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, FWD_SMEM);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_fwd_mfma, dim3(n_q, batch, (seq + 255) / 256), dim3(256), FWD_SMEM, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, n_q, n_kv);
   return hipGetLastError();
 }
 
