@@ -392,6 +392,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
     Dq[qt] = dsum + __shfl_xor(dsum, 32, 64);                  // the two lanes of a row hold 64 columns each
     if (g == 0 && qglob[qt] < seq) delta[((size_t)b * n_q + a) * seq + qglob[qt]] = Dq[qt];
   }
+  // -D of this lane's two queries in every register of an accumulator-shaped tuple: the initial value of the dP^T
+  // MFMAs, which then deliver dP^T - D
+  f32x16_t negD[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negD[qt][v] = -Dq[qt];
+  // from here on the fragments are operands of MFMAs only: they move to the accumulation half of the register file
+  // for good (the empty statements are where the move happens)
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(Qf[qt][ks]), "+a"(dOf[qt][ks]));
   f32x16_t acc[2][4];                          // [query tile][d tile]: lane = query, registers = d
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt)
@@ -459,7 +472,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
   };
 
 #define OPTSTAGE_SB() __builtin_amdgcn_sched_barrier(0)
-#define OPTSTAGE_MFMA_V(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+  // the register-resident operands (Q, dO) sit in the accumulation half of the register file, next to dQ^T: an
+  // MFMA takes its A / B operands from either half, and the vector half is left to the score tiles, the streaming
+  // fragments and the addresses
+#define OPTSTAGE_MFMA_V(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b))
+#define OPTSTAGE_MFMA_0(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b))
   auto block = [&](int kb, int stage) {
     if (64 * kb > wave_last_q) return;                           // block above this wave's diagonal
     const char* sK = smem + stage * DQ_STAGE;
@@ -471,12 +488,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
       const bool edge = key0 + 31 > wave_first_q;                // touches the diagonal (keys past seq are masked by it)
       // lane = query, registers = keys key0 + 8 (v / 4) + 4 g + v % 4
       f32x16_t s[2], dp[2];
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { s[qt][v] = 0.f; dp[qt][v] = 0.f; }
       bf16x8_t kf[2], vf[2];
-      // ---- S^T = K Q^T
+      // ---- S^T = K Q^T (the first k-step starts from C = 0)
       kf[0] = rm_frag(sK, t, 0);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
@@ -484,8 +497,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
         if (ks < 7) kf[(ks + 1) & 1] = rm_frag(sK, t, ks + 1);
         else vf[0] = rm_frag(sV, t, 0);
         OPTSTAGE_SB();
-        OPTSTAGE_MFMA_V(s[0], kf[ks & 1], Qf[0][ks]);
-        OPTSTAGE_MFMA_V(s[1], kf[ks & 1], Qf[1][ks]);
+        if (ks == 0) {
+          OPTSTAGE_MFMA_0(s[0], kf[0], Qf[0][0]);
+          OPTSTAGE_MFMA_0(s[1], kf[0], Qf[1][0]);
+        } else {
+          OPTSTAGE_MFMA_V(s[0], kf[ks & 1], Qf[0][ks]);
+          OPTSTAGE_MFMA_V(s[1], kf[ks & 1], Qf[1][ks]);
+        }
       }
       // ---- dP^T = V dO^T, with the exponentials of S^T under its MFMAs
 #pragma unroll
@@ -493,8 +511,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
         OPTSTAGE_SB();
         if (ks < 7) vf[(ks + 1) & 1] = rm_frag(sV, t, ks + 1);
         OPTSTAGE_SB();
-        OPTSTAGE_MFMA_V(dp[0], vf[ks & 1], dOf[0][ks]);
-        OPTSTAGE_MFMA_V(dp[1], vf[ks & 1], dOf[1][ks]);
+        if (ks == 0) {                                             // dP^T - D: the first k-step starts from C = -D
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(dp[0]) : "v"(vf[0]), "a"(dOf[0][0]), "v"(negD[0]));
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(dp[1]) : "v"(vf[0]), "a"(dOf[1][0]), "v"(negD[1]));
+        } else {
+          OPTSTAGE_MFMA_V(dp[0], vf[ks & 1], dOf[0][ks]);
+          OPTSTAGE_MFMA_V(dp[1], vf[ks & 1], dOf[1][ks]);
+        }
         OPTSTAGE_SB();
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -505,6 +528,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
       }
       OPTSTAGE_SB();
       if (edge) {
+        asm volatile("" ::: "memory");                             // a real branch: only diagonal tiles pay for the mask
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = key0 + 8 * (v >> 2) + 4 * g + (v & 3);
@@ -516,13 +540,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
       // results of the matrix unit may be read by the vector unit only some cycles after the last pass
       asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
       OPTSTAGE_SB();
-      // ---- dQ^T += K^T dS^T; dS^T = P^T (dP^T - D) of the second half runs under the MFMAs of the first
+      // ---- dQ^T += K^T dS^T; dS^T = P^T (dP^T - D) of the second half runs under the MFMAs of the first (D is
+      // already subtracted: it was the accumulator's initial value)
       bf16x8_t trf[2];
       trf[0] = tr_frag(sK, 0, t, 0);
 #pragma unroll
       for (int v = 0; v < 8; ++v)
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) dp[qt][v] = s[qt][v] * (dp[qt][v] - Dq[qt]);
+        for (int qt = 0; qt < 2; ++qt) dp[qt][v] = s[qt][v] * dp[qt][v];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const bf16x8_t d0 = pack8(dp[0], u), d1 = pack8(dp[1], u);
@@ -540,7 +565,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
             for (int e = 0; e < 2; ++e) {
               const int v = 8 + 2 * dt + e;
 #pragma unroll
-              for (int qt = 0; qt < 2; ++qt) dp[qt][v] = s[qt][v] * (dp[qt][v] - Dq[qt]);
+              for (int qt = 0; qt < 2; ++qt) dp[qt][v] = s[qt][v] * dp[qt][v];
             }
           }
         }
@@ -549,6 +574,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
     }
   };
 #undef OPTSTAGE_MFMA_V
+#undef OPTSTAGE_MFMA_0
 #undef OPTSTAGE_SB
 
   const int nkb = min((q0 + 255) / 64 + 1, (seq + 63) / 64);
@@ -722,6 +748,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
   // VGPR-result MFMA in assembly: the compiler would place the score tiles in accumulator registers, all 256
   // of which hold dK, dV.  Readers of the result keep >= 2 MFMAs (or an s_nop) behind the last write.
 #define OPTSTAGE_MFMA_V(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b))
+#define OPTSTAGE_MFMA_0(acc, a, b) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b))
   auto block = [&](int it, int stage) {
     const int r0 = 64 * (qb0 + it % nqb);
     if (r0 + 63 < wave_first_k) return;                          // all queries precede this wave's keys
@@ -736,10 +763,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
       const bool edge = q0 < wave_first_k + 63 || q0 + 32 > seq;   // touches the diagonal or the ragged tail
       // lane = key, registers = queries q0 + 8 (v / 4) + 4 g + v % 4
       f32x16_t s[2], dp[2];
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { s[kk][v] = 0.f; dp[kk][v] = 0.f; }
       f32x4_t nL[4], Dq[4];                                        // -lse * log2(e) and D of this lane's queries
       bf16x8_t qf[2], df[2], vf[2][2];
       // ---- S = Q K^T: fragment of k-step ks + 1 requested before the MFMAs of k-step ks
@@ -757,8 +780,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
         if (ks < 4) nL[ks] = *reinterpret_cast<const f32x4_t*>(sL + 32 * t + 8 * ks + 4 * g);
         else Dq[ks - 4] = *reinterpret_cast<const f32x4_t*>(sD + 32 * t + 8 * (ks - 4) + 4 * g);
         OPTSTAGE_SB();
-        OPTSTAGE_MFMA_V(s[0], qf[ks & 1], Kf[0][ks]);
-        OPTSTAGE_MFMA_V(s[1], qf[ks & 1], Kf[1][ks]);
+        if (ks == 0) {                                             // the first k-step starts from C = 0
+          OPTSTAGE_MFMA_0(s[0], qf[0], Kf[0][0]);
+          OPTSTAGE_MFMA_0(s[1], qf[0], Kf[1][0]);
+        } else {
+          OPTSTAGE_MFMA_V(s[0], qf[ks & 1], Kf[0][ks]);
+          OPTSTAGE_MFMA_V(s[1], qf[ks & 1], Kf[1][ks]);
+        }
         OPTSTAGE_SB();
         if (ks >= 4) {
 #pragma unroll
@@ -775,8 +803,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
           vf[(ks + 1) & 1][1] = rm_frag(sV, 1, ks + 1);
         }
         OPTSTAGE_SB();
-        OPTSTAGE_MFMA_V(dp[0], df[ks & 1], vf[ks & 1][0]);
-        OPTSTAGE_MFMA_V(dp[1], df[ks & 1], vf[ks & 1][1]);
+        if (ks == 0) {
+          OPTSTAGE_MFMA_0(dp[0], df[0], vf[0][0]);
+          OPTSTAGE_MFMA_0(dp[1], df[0], vf[0][1]);
+        } else {
+          OPTSTAGE_MFMA_V(dp[0], df[ks & 1], vf[ks & 1][0]);
+          OPTSTAGE_MFMA_V(dp[1], df[ks & 1], vf[ks & 1][1]);
+        }
         OPTSTAGE_SB();
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -838,6 +871,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
     }
   };
 #undef OPTSTAGE_MFMA_V
+#undef OPTSTAGE_MFMA_0
 #undef OPTSTAGE_SB
 
   if (iters > 0) issue_block(0, 0);
