@@ -390,7 +390,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t* __restrict
     }
     Lc[qt] = -lse[((size_t)b * n_q + a) * seq + qrow] * LOG2E;
     Dq[qt] = dsum + __shfl_xor(dsum, 32, 64);                  // the two lanes of a row hold 64 columns each
-    if (g == 0 && qglob[qt] < seq) delta[((size_t)b * n_q + a) * seq + qglob[qt]] = Dq[qt];
+    // stored negated: both backward kernels use -D as the initial value of their dP accumulators
+    if (g == 0 && qglob[qt] < seq) delta[((size_t)b * n_q + a) * seq + qglob[qt]] = -Dq[qt];
   }
   // -D of this lane's two queries in every register of an accumulator-shaped tuple: the initial value of the dP^T
   // MFMAs, which then deliver dP^T - D
@@ -763,7 +764,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
       const bool edge = q0 < wave_first_k + 63 || q0 + 32 > seq;   // touches the diagonal or the ragged tail
       // lane = key, registers = queries q0 + 8 (v / 4) + 4 g + v % 4
       f32x16_t s[2], dp[2];
-      f32x4_t nL[4], Dq[4];                                        // -lse * log2(e) and D of this lane's queries
+      f32x4_t nL[4];                                               // -lse * log2(e) of this lane's queries
+      f32x16_t negD;                                               // -D of this lane's queries, in accumulator order
       bf16x8_t qf[2], df[2], vf[2][2];
       // ---- S = Q K^T: fragment of k-step ks + 1 requested before the MFMAs of k-step ks
       qf[0] = rm_frag(sQ, t, 0);
@@ -778,7 +780,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
           vf[0][1] = rm_frag(sV, 1, 0);
         }
         if (ks < 4) nL[ks] = *reinterpret_cast<const f32x4_t*>(sL + 32 * t + 8 * ks + 4 * g);
-        else Dq[ks - 4] = *reinterpret_cast<const f32x4_t*>(sD + 32 * t + 8 * (ks - 4) + 4 * g);
+        else {
+          const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(sD + 32 * t + 8 * (ks - 4) + 4 * g);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) negD[4 * (ks - 4) + i] = d4[i];
+        }
         OPTSTAGE_SB();
         if (ks == 0) {                                             // the first k-step starts from C = 0
           OPTSTAGE_MFMA_0(s[0], qf[0], Kf[0][0]);
@@ -803,9 +809,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
           vf[(ks + 1) & 1][1] = rm_frag(sV, 1, ks + 1);
         }
         OPTSTAGE_SB();
-        if (ks == 0) {
-          OPTSTAGE_MFMA_0(dp[0], df[0], vf[0][0]);
-          OPTSTAGE_MFMA_0(dp[1], df[0], vf[0][1]);
+        if (ks == 0) {                                             // dP - D: the first k-step starts from C = -D
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(dp[0]) : "v"(df[0]), "v"(vf[0][0]), "v"(negD));
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(dp[1]) : "v"(df[0]), "v"(vf[0][1]), "v"(negD));
         } else {
           OPTSTAGE_MFMA_V(dp[0], df[ks & 1], vf[ks & 1][0]);
           OPTSTAGE_MFMA_V(dp[1], df[ks & 1], vf[ks & 1][1]);
@@ -849,7 +855,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t* __restric
           for (int e = 0; e < 2; ++e) {
             const int v = 2 * n + e;
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) dp[kk][v] = s[kk][v] * (dp[kk][v] - Dq[v >> 2][v & 3]);
+            for (int kk = 0; kk < 2; ++kk) dp[kk][v] = s[kk][v] * dp[kk][v];
           }
         }
       }
