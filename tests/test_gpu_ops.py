@@ -231,6 +231,29 @@ def test_attention_fwd_bwd(dtype, seq, batch, nq, nkv, d):
             assert rel_err(dq_g[sl, lo:hi], ref[:, lo:hi]) < TOL[dtype], (lo, hi)
 
 
+@pytest.mark.parametrize("gain", [6.0, 0.05])
+def test_attention_forward_with_peaked_and_flat_scores(gain):
+    """Scores far larger than usual (the softmax reference has to be raised again and again, and most
+    probabilities underflow) and far smaller (the reference is set once and never raised)."""
+    seq, nq, nkv, d = 700, 2, 1, 128
+    w = (nq + 2 * nkv) * d
+    qkv = RNG.standard_normal((seq, w))
+    qkv[:, : (nq + nkv) * d] *= gain
+    qkv = q(qkv, BF16)
+    QKV = dev(qkv, BF16)
+    Ot = torch.empty(seq, nq * d, dtype=QKV.dtype, device="cuda")
+    LSE = torch.empty(nq * seq, dtype=torch.float32, device="cuda")
+    ok(lib().optstage_op_attn_fwd(BF16, QKV.data_ptr(), Ot.data_ptr(), LSE.data_ptr(), seq, 1, nq, nkv, d, stream()))
+    torch.cuda.synchronize()
+    qq = qkv[:, : nq * d].reshape(seq, nq, d)
+    kk = qkv[:, nq * d: (nq + nkv) * d].reshape(seq, nkv, d)
+    vv = qkv[:, (nq + nkv) * d:].reshape(seq, nkv, d)
+    o, lse = O.attention_fwd(qq, kk, vv)
+    assert np.isfinite(host(Ot)).all() and np.isfinite(host(LSE)).all()
+    assert rel_err(host(Ot), o.reshape(seq, -1)) < TOL[BF16]
+    assert np.max(np.abs(host(LSE).reshape(nq, seq) - lse) / np.maximum(1.0, np.abs(lse))) < 2e-2
+
+
 # ------------------------------------------------------------------ checksum
 def test_checksum_matches_host_arithmetic():
     for n in (0, 8, 4096, 1 << 20, (1 << 20) + 8):
