@@ -172,7 +172,8 @@ optstage_status optstage_validate(const optstage_t* st, const optstage_event* ev
 /* Validates (as above, but from the handle's current state) and enqueues the whole list. */
 optstage_status optstage_run(optstage_t* st, const optstage_event* events, size_t n);
 
-/* Step-wise equivalents: same semantics as one-event lists. */
+/* Step-wise equivalents: same semantics as one-event lists.  The three compute calls act on model chunk 0; a
+ * stage that holds several chunks reaches the others through event lists (the event's layer field). */
 optstage_status optstage_forward(optstage_t* st, uint32_t mb);
 optstage_status optstage_backward_input(optstage_t* st, uint32_t mb);
 optstage_status optstage_backward_weight(optstage_t* st, uint32_t mb);
