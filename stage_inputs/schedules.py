@@ -104,6 +104,85 @@ def split_bw_greedy(p: int, m: int, cap_of_stage=None) -> list:
     return lists
 
 
+def _piece(i: int, c: int, p: int, placement: str) -> int:
+    """Position in the model of chunk c of stage i: "interleaved" chunk c covers pieces c p .. c p + p - 1 in stage
+    order; "v" runs odd chunks through the stages in reverse (stage 0 holds the first and the last piece)."""
+    return c * p + (i if (placement == "interleaved" or c % 2 == 0) else p - 1 - i)
+
+
+def split_bw_greedy_chunks(p: int, m: int, n_chunks: int, placement: str = "v", cap_of_stage=None) -> list:
+    """Zero-bubble style lists for stages that hold n_chunks model chunks each (V-shaped or interleaved placement):
+    the unit-time lock-step sweep of split_bw_greedy over the p n_chunks pieces of the model.  An idle stage runs,
+    in this order of preference: a ready B (the piece nearest the loss first), a ready F (the deepest piece first,
+    so that micro-batches already under way finish before new ones start), where a new micro-batch is admitted
+    only while the chunk activations of the admitted ones (held, F done and W not done, or still to come) stay within
+    `cap_of_stage(i)` (default 2 p, every stage alike: what the V shape is for; at least n_chunks),
+    a ready W (oldest first).  Compute events are written (op, j, chunk)."""
+    cap_of_stage = cap_of_stage or (lambda i: 2 * p)
+    n_pieces = p * n_chunks
+    holder = {}
+    for i in range(p):
+        for c in range(n_chunks):
+            holder[_piece(i, c, p, placement)] = (i, c)
+    lists = [[] for _ in range(p)]
+    nf = {k: 0 for k in holder.values()}
+    nb = dict(nf)
+    nw = dict(nf)
+    done_f, done_b = {}, {}                     # (piece, j) -> finish tick
+    t = 0
+    total = 3 * m * n_pieces
+    placed = 0
+    while placed < total:
+        chosen = []
+        for i in range(p):
+            chunks = sorted(range(n_chunks), key=lambda c: -_piece(i, c, p, placement))    # deepest piece first
+            pick = None
+            for c in chunks:                                                             # B
+                v, j = _piece(i, c, p, placement), nb[(i, c)]
+                if j < m and j < nf[(i, c)] and done_f.get((v, j), t + 1) <= t and \
+                        (v == n_pieces - 1 or done_b.get((v + 1, j), t + 1) <= t):
+                    pick = ("B", j, c)
+                    break
+            if pick is None:                                                             # F
+                first = chunks[-1]                      # the chunk a micro-batch visits first on this stage
+                # a micro-batch admitted on its first chunk will need room for all its chunks here: the cap
+                # counts those to come as well, or the later chunks could find the stage full for good
+                committed = n_chunks * nf[(i, first)] - sum(nw[(i, c)] for c in range(n_chunks))
+                for c in chunks:
+                    v, j = _piece(i, c, p, placement), nf[(i, c)]
+                    if c == first and committed + n_chunks > cap_of_stage(i):
+                        continue
+                    if j < m and (v == 0 or done_f.get((v - 1, j), t + 1) <= t):
+                        pick = ("F", j, c)
+                        break
+            if pick is None:                                                             # W
+                cands = [(done_b[(_piece(i, c, p, placement), nw[(i, c)])], c) for c in range(n_chunks)
+                         if nw[(i, c)] < nb[(i, c)] and done_b[(_piece(i, c, p, placement), nw[(i, c)])] <= t]
+                if cands:
+                    c = min(cands)[1]
+                    pick = ("W", nw[(i, c)], c)
+            chosen.append(pick)
+        for i, pick in enumerate(chosen):
+            if pick is None:
+                continue
+            lists[i].append(pick)
+            op, j, c = pick
+            v = _piece(i, c, p, placement)
+            if op == "F":
+                nf[(i, c)] += 1
+                done_f[(v, j)] = t + 1
+            elif op == "B":
+                nb[(i, c)] += 1
+                done_b[(v, j)] = t + 1
+            else:
+                nw[(i, c)] += 1
+            placed += 1
+        t += 1
+        if t > 10 * (3 * m * n_chunks + 2 * n_pieces) + 100:
+            raise RuntimeError("generator did not terminate (in-flight cap too small for this shape?)")
+    return lists
+
+
 def add_offload(compute_list: list, n_layers: int, kinds: tuple, min_gap: int = 2, lead: int = 1,
                 wait_delay: int = 1) -> list:
     """Insert O / OWAIT / R events into a compute order.

@@ -324,16 +324,22 @@ def test_recompute_variant_changes_no_bit_and_accounts_like_the_oracle(cfg):
     ref_st.close()
 
 
-def test_two_model_chunks_on_one_stage():
-    """A stage holding two model chunks (interleaved 1F1B, stage 0 of p = 2) with offload under one shared
-    budget: every chunk's outputs and gradients are bitwise those of that chunk run as a stage of its own,
-    they match the oracle, and the accounting is the oracle's."""
+@pytest.mark.parametrize("family", ["interleaved_1f1b", "v_split_bw"])
+def test_two_model_chunks_on_one_stage(family):
+    """A stage holding two model chunks (interleaved 1F1B, stage 0 of p = 2; zero-bubble style list for the V
+    placement, stage 1 of p = 2) with offload under one shared budget: every chunk's outputs and gradients are
+    bitwise those of that chunk run as a stage of its own, they match the oracle, and the accounting is the
+    oracle's."""
     v, m = 2, 4
-    cfg = replace(SMALL2, name="cfg2_small_two_chunks", n_layers=4, n_microbatches=m, n_stages=2, stage_index=0)
+    cfg = replace(SMALL2, name="cfg2_small_two_chunks", n_layers=4, n_microbatches=m, n_stages=2,
+                  stage_index=0 if family == "interleaved_1f1b" else 1)
     Lc = cfg.n_layers // v
     ws = T.stage_weights(cfg)
     t = oracle_table(cfg)
-    base = G.interleaved_one_f_one_b(cfg.n_stages, m, cfg.stage_index, v)
+    if family == "interleaved_1f1b":
+        base = G.interleaved_one_f_one_b(cfg.n_stages, m, cfg.stage_index, v)
+    else:
+        base = G.split_bw_greedy_chunks(cfg.n_stages, m, v, "v")[cfg.stage_index]
     events = G.add_offload(base, cfg.n_layers, ("X_IN", "QKV", "X_MID"), min_gap=3, lead=1)
     assert any(e[0] == "O" for e in events)
     S.check_order(events, m, cfg.n_layers, n_chunks=v)

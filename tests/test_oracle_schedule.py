@@ -368,6 +368,39 @@ def test_v_shaped_placement_by_hand():
     assert span == tm2.makespan_global == 30
 
 
+@pytest.mark.parametrize("p,m,placement", [(2, 4, "v"), (4, 8, "v"), (4, 8, "interleaved"), (8, 16, "v")])
+def test_split_bw_lists_with_chunks(p, m, placement):
+    """Zero-bubble style lists over two chunks per stage: valid per chunk, consistent across stages (the simulator
+    finds no deadlock and agrees with the integer tick simulator whose placement is written out by hand), every
+    stage within its in-flight cap, and no slower than interleaved 1F1B, which has no freedom to move W."""
+    v = 2
+    lists = G.split_bw_greedy_chunks(p, m, v, placement)
+    for lst in lists:
+        S.check_order(lst, m, v, n_chunks=v)
+    t_op = [{"F": 1, "B": 1, "W": 1}] * p
+    tm = S.simulate(lists, t_op, t_comm=0, n_chunks=v, placement=placement)
+    if placement == "v":       # chunk 0 runs down the stages, chunk 1 back up; the turn is on the last stage
+        before = lambda i, c: ((i - 1, 0) if i > 0 else None) if c == 0 else ((i + 1, 1) if i < p - 1 else (p - 1, 0))
+    else:
+        before = lambda i, c: (i - 1, c) if i > 0 else ((p - 1, c - 1) if c > 0 else None)
+    span, begun, fin = tick_sim_chunks(lists, t_op, 0, before)
+    assert span == tm.makespan_global
+    ref = S.simulate([G.interleaved_one_f_one_b(p, m, i, v) for i in range(p)], t_op, n_chunks=v)
+    assert tm.makespan_global <= ref.makespan_global
+    dF = S.op_delta("F", 1, TABLE)
+    slack = TABLE["DY"] + TABLE["DX_MID"]
+    peaks = [S.account_memory(lst, v, TABLE, n_chunks=v)[0] for lst in lists]
+    assert all(pk <= 2 * p * dF + slack for pk in peaks)
+    if placement == "v":       # what the V shape is for: every stage holds the same (up to B's transients)
+        assert max(peaks) - min(peaks) <= slack
+    # a smaller cap is honoured too
+    tight = G.split_bw_greedy_chunks(p, m, v, placement, cap_of_stage=lambda i: p + 1)
+    for lst in tight:
+        S.check_order(lst, m, v, n_chunks=v)
+        assert S.account_memory(lst, v, TABLE, n_chunks=v)[0] <= (p + 1) * dF + slack
+    S.simulate(tight, t_op, n_chunks=v, placement=placement)
+
+
 def test_chunked_lists_order_rules_and_accounting():
     Lc, v, m = 2, 2, 4
     lst = G.interleaved_one_f_one_b(2, m, 0, v)
