@@ -21,6 +21,11 @@ extern "C" {
 /* C[M,N] = sum_k A(m,k) B(n,k).
  * layout 0 (NT): A is [M,K] (lda), B is [N,K] (ldb)  -- forward Y = X W^T and dX = dY (W^T)^T
  * layout 1 (TN): A is [K,M] (lda), B is [K,N] (ldb)  -- dW = dY^T X
+ * layout 2 (NT, B in slabs; bf16, epilogue 0 or 1): A as in layout 0; B(n,k) at element offset
+ *          ((n / 256) * (K / 64) + k / 64) * 16384 + (n % 256) * 64 + k % 64, i.e. the 256 rows x 64 columns that one
+ *          workgroup loads per step of the contraction are consecutive in memory (how the stage keeps its weight
+ *          copies); B spans ceil(N / 256) * (K / 64) slabs, rows past N are never used; ldb is ignored.  Needs
+ *          K % 64 == 0 and at least 128 output tiles of 256 x 256, else OPTSTAGE_E_ARG.
  * epilogue 0: C (stage dtype) = product; 1: C = product + R (R like C); 2: C (fp32) += product.
  * bf16 needs lda, ldb multiples of 8, N and ldc multiples of 4, K (NT) or M and N (TN) multiples of 8. */
 optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilogue, const void* A, const void* B,

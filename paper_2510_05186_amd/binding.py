@@ -20,7 +20,7 @@ WEIGHTS = ("g1", "b1", "wqkv", "wo", "g2", "b2", "wgu", "wd")
 WEIGHT_ID = {k: i for i, k in enumerate(WEIGHTS)}
 KERNEL_CLASSES = ("gemm_nt_store", "gemm_nt_resid", "gemm_tn_accum", "attn_fwd", "attn_bwd", "norm_fwd", "norm_bwd",
                   "act_fwd", "act_bwd", "rope")
-GEMM_NT, GEMM_TN = 0, 1
+GEMM_NT, GEMM_TN, GEMM_NT_SLAB = 0, 1, 2
 EPI_STORE, EPI_RESID, EPI_ACCUM = 0, 1, 2
 
 

@@ -15,7 +15,9 @@ enum { FAM_GPT = 0, FAM_LLAMA = 1 };
 // GEMM operand layouts: C[M,N] = sum_k A(m,k) * B(n,k)
 //   NT: A is [M,K] row-major, B is [N,K] row-major  (both contiguous along the contraction)
 //   TN: A is [K,M] row-major, B is [K,N] row-major  (both contiguous along their output index)
-enum { GEMM_NT = 0, GEMM_TN = 1 };
+// GEMM_NT_SLAB: C = A B^T with B stored in slabs of 256 rows x 64 columns, slab (n / 256, k / 64) at element offset
+// ((n / 256) * (K / 64) + k / 64) * 16384, row-major inside, rows padded to a multiple of 256
+enum { GEMM_NT = 0, GEMM_TN = 1, GEMM_NT_SLAB = 2 };
 // epilogues: store C (stage dtype); store C + R (R like C); C (fp32) += product
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_ACCUM = 2 };
 
@@ -74,6 +76,9 @@ hipError_t launch_rope_table(float* table, int seq, int d, float base, hipStream
 hipError_t launch_rope(int dtype, const void* src, void* dst, const float* table, int rows, int seq, int n_q, int n_kv,
                        int d, int backward, int do_rotate, hipStream_t s);
 hipError_t launch_transpose(int dtype, const void* src, void* dst, int rows, int cols, hipStream_t s);
+// bf16 weight into the slab layout of GEMM_NT_SLAB: B[n][k] = src[n * K + k], or src[k * N + n] when transposed
+hipError_t launch_slabs(const void* src, void* dst, int N, int K, int transposed, hipStream_t s);
+bool gemm_bf16_slab_applies(int M, int N, int K, int lda);
 hipError_t launch_checksum(const void* buf, uint64_t bytes, uint64_t* out_dev, hipStream_t s);
 hipError_t launch_attn_fwd(int dtype, const void* qkv, void* o, float* lse, int seq, int batch, int n_q, int n_kv,
                            int d, hipStream_t s);

@@ -416,6 +416,28 @@ __global__ void rope_kernel(const T* src, T* dst, const float2* __restrict__ tab
   }
 }
 
+// ---- weights into slabs (once per weight update): the GEMM's B operand B[n][k], n < N, k < K (K % 64 == 0), stored
+// so that the 256 rows x 64 columns a workgroup loads per k-tile are consecutive in memory: slab (n / 256, k / 64) at
+// element offset ((n / 256) * (K / 64) + k / 64) * 16384, row-major inside, rows past N zero.
+// TRANSPOSED = false: B[n][k] = src[n * K + k]; true: B[n][k] = src[k * N + n] (the transposed weight)
+template <bool TRANSPOSED>
+__global__ void slab_kernel(const unsigned short* __restrict__ src, unsigned short* __restrict__ dst, int N, int K) {
+  __shared__ unsigned short tile[64][65];
+  const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
+  for (int e = threadIdx.x; e < 64 * 64; e += blockDim.x) {
+    const int hi = e / 64, lo = e % 64;               // lo runs along the source's contiguous direction
+    const int nn = TRANSPOSED ? lo : hi, kk = TRANSPOSED ? hi : lo;
+    unsigned short v = 0;
+    if (n0 + nn < N) v = TRANSPOSED ? src[(size_t)(k0 + kk) * N + n0 + nn] : src[(size_t)(n0 + nn) * K + k0 + kk];
+    tile[nn][kk] = v;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * 64; e += blockDim.x) {
+    const int nn = e / 64, kk = e % 64, n = n0 + nn;
+    dst[((size_t)(n / 256) * (K / 64) + k0 / 64) * 16384 + (size_t)(n % 256) * 64 + kk] = tile[nn][kk];
+  }
+}
+
 // ---- transpose (weights, once per weight update) ------------------------------------------------------
 template <typename T>
 __global__ void transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int rows, int cols) {
@@ -559,6 +581,15 @@ hipError_t launch_rope(int dtype, const void* src, void* dst, const float* table
   float sign = backward ? -1.f : 1.f;
   if (dtype == DT_BF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(g), dim3(256), 0, s, (const bf16_t*)src, (bf16_t*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate);
   else hipLaunchKernelGGL(rope_kernel<float>, dim3(g), dim3(256), 0, s, (const float*)src, (float*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate);
+  return hipGetLastError();
+}
+
+hipError_t launch_slabs(const void* src, void* dst, int N, int K, int transposed, hipStream_t s) {
+  if (N <= 0 || K <= 0 || (K % 64)) return hipErrorInvalidValue;
+  const int n_pad = (N + 255) / 256 * 256;
+  dim3 grid(K / 64, n_pad / 64);
+  if (transposed) hipLaunchKernelGGL(slab_kernel<true>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, N, K);
+  else hipLaunchKernelGGL(slab_kernel<false>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, N, K);
   return hipGetLastError();
 }
 

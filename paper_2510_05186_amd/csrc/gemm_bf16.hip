@@ -456,7 +456,7 @@ template <bool TNL, int EPI>
 __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                             void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N, int K, int lda,
                                             int ldb, int ldc, int tiles_m, int tiles_n, unsigned a_bytes, unsigned b_bytes,
-                                            int pid) {
+                                            int pid, bool b_slab = false) {
   constexpr int BM = 256, BN = 256, WM = 2, WN = 2, TM = 4, TN = 4;
   constexpr int OPB = 32768;                    // one operand of one stage
   const int tid = threadIdx.x, lane = tid & 63;
@@ -517,9 +517,13 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
     for (int j = 0; j < 8; ++j) {
       const unsigned coff = (unsigned)((c0 ^ j) << 4);
       voff[2 * j] = (unsigned)(m0 + wave * 64 + j * 8 + lrow) * (unsigned)lda * 2u + coff;
-      voff[2 * j + 1] = (unsigned)(n0 + wave * 64 + j * 8 + lrow) * (unsigned)ldb * 2u + coff;
+      // B in slabs: the 256 rows x 64 columns of tile column tile_n and k-tile kt lie together (32 KB, row-major
+      // inside), so one load instruction covers 1 KB of consecutive memory instead of 128 bytes of 8 rows each
+      voff[2 * j + 1] = b_slab ? (unsigned)tile_n * (unsigned)(K / BK) * 32768u + (unsigned)(wave * 64 + j * 8 + lrow) * 128u + coff
+                               : (unsigned)(n0 + wave * 64 + j * 8 + lrow) * (unsigned)ldb * 2u + coff;
     }
-    a_tile = b_tile = BK * 2;
+    a_tile = BK * 2;
+    b_tile = b_slab ? 32768u : BK * 2;
   }
   auto make_desc = [](const void* p, unsigned bytes) {
     const unsigned long long a = (unsigned long long)p;
@@ -655,10 +659,10 @@ template <bool TNL, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n,
-                                                               unsigned a_bytes, unsigned b_bytes) {
+                                                               unsigned a_bytes, unsigned b_bytes, int b_slab) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   direct_tile<TNL, EPI>(smem, A, B, Cv, R, M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes,
-                        xcd_remap(blockIdx.x, tiles_m * tiles_n));
+                        xcd_remap(blockIdx.x, tiles_m * tiles_n), !TNL && b_slab != 0);
 }
 
 // Several independent products with the same K in one launch (the weight-gradient GEMMs of a W op: four per
@@ -686,7 +690,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_direct_grouped_kernel(const Gro
 
 template <bool TNL, int EPI>
 hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
-                         int ldc, hipStream_t s) {
+                         int ldc, hipStream_t s, bool b_slab = false) {
   auto kern = gemm_bf16_direct_kernel<TNL, EPI>;
   constexpr int smem = 131072;
   static bool attr_set = false;
@@ -698,9 +702,10 @@ hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, i
   const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
   // byte extent of each operand: whatever lies past it reads as zero
   const unsigned a_bytes = (unsigned)(TNL ? ((size_t)(K - 1) * lda + M) * 2 : ((size_t)(M - 1) * lda + K) * 2);
-  const unsigned b_bytes = (unsigned)(TNL ? ((size_t)(K - 1) * ldb + N) * 2 : ((size_t)(N - 1) * ldb + K) * 2);
+  const unsigned b_bytes = b_slab ? (unsigned)((size_t)tiles_n * (K / 64) * 32768)
+                                  : (unsigned)(TNL ? ((size_t)(K - 1) * ldb + N) * 2 : ((size_t)(N - 1) * ldb + K) * 2);
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, (const bf16_t*)A, (const bf16_t*)B, C, (const bf16_t*)R,
-                     M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes);
+                     M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes, b_slab ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -777,10 +782,24 @@ hipError_t launch_layout(const void* A, const void* B, void* C, const void* R, i
 
 }  // namespace
 
+// B in slabs is served by the direct kernel only: shapes that the dispatcher would send elsewhere do not qualify
+bool gemm_bf16_slab_applies(int M, int N, int K, int lda) {
+  if (M <= 0 || N <= 0 || K <= 0 || (K % 64) || (lda & 7) || (N & 3)) return false;
+  const long tiles_n = (N + 255) / 256, big_tiles = (long)((M + 255) / 256) * tiles_n;
+  if (big_tiles < 128 || (unsigned long long)tiles_n * (K / 64) * 32768ull >= 0xF0000000ull) return false;
+  return direct_applies(false, M, N, K, lda, 8);
+}
+
 hipError_t launch_gemm_bf16(int layout, int epi, const void* A, const void* B, void* C, const void* R, int M, int N,
                             int K, int lda, int ldb, int ldc, hipStream_t s) {
   // host-side shape checks: 16-byte vector accesses need these
   if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
+  if (layout == GEMM_NT_SLAB) {
+    if ((ldc & 3) || !gemm_bf16_slab_applies(M, N, K, lda)) return hipErrorInvalidValue;
+    if (epi == EPI_STORE) return launch_direct<false, EPI_STORE>(A, B, C, R, M, N, K, lda, 64, ldc, s, true);
+    if (epi == EPI_RESID) return launch_direct<false, EPI_RESID>(A, B, C, R, M, N, K, lda, 64, ldc, s, true);
+    return hipErrorInvalidValue;
+  }
   if ((lda & 7) || (ldb & 7) || (ldc & 3) || (N & 3)) return hipErrorInvalidValue;
   if (layout == GEMM_NT) {
     if (K & 7) return hipErrorInvalidValue;

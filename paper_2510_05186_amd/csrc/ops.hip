@@ -58,10 +58,11 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
                                  uint32_t ldb, uint32_t ldc, void* stream) {
   REQ(A && B && C && (epilogue != 1 || R), "gemm: null operand");
   REQ(aligned16(A) && aligned16(B) && aligned16(C) && aligned16(R), "gemm: operands must be 16-byte aligned");
-  REQ(dtype <= 1 && layout <= 1 && epilogue <= 2, "gemm: bad dtype / layout / epilogue");
+  REQ(dtype <= 1 && layout <= 2 && epilogue <= 2, "gemm: bad dtype / layout / epilogue");
   REQ(M && N && K && M < (1u << 30) && N < (1u << 30) && K < (1u << 30), "gemm: bad extent");
   if (layout == 0) { REQ(lda >= K && ldb >= K, "gemm: leading dimension smaller than K"); }
-  else { REQ(lda >= M && ldb >= N, "gemm: leading dimension smaller than the row length"); }
+  else if (layout == 1) { REQ(lda >= M && ldb >= N, "gemm: leading dimension smaller than the row length"); }
+  else { REQ(dtype == OPTSTAGE_BF16 && epilogue <= 1 && lda >= K, "gemm: the slab layout serves bf16 store / residual products"); }
   REQ(ldc >= N, "gemm: ldc smaller than N");
   hipError_t e = dtype == OPTSTAGE_BF16
                      ? launch_gemm_bf16(layout, epilogue, A, B, C, R, M, N, K, lda, ldb, ldc, (hipStream_t)stream)

@@ -95,7 +95,8 @@ void kind_raw_bytes(const Shape& s, uint64_t raw[NK]) {
 }
 
 struct WorkspaceLayout {
-  uint64_t rope, wt_base, wt[OPTSTAGE_N_WEIGHTS], wt_layer_stride, da, dn, dout, dqkv, attn, partial, csum, total;
+  uint64_t rope, wt_base, wt[OPTSTAGE_N_WEIGHTS], wf[OPTSTAGE_N_WEIGHTS], wt_layer_stride, da, dn, dout, dqkv, attn, partial,
+      csum, total;
 };
 
 uint64_t weight_elems(const Shape& s, int which) {
@@ -108,6 +109,28 @@ uint64_t weight_elems(const Shape& s, int which) {
   }
 }
 
+// rows (outputs) and columns (inputs) of a linear weight; false for the norm parameters
+bool weight_dims(const Shape& s, int which, int* rows, int* cols) {
+  switch (which) {
+    case OPTSTAGE_W_QKV: *rows = s.qkv_w; *cols = s.h; return true;
+    case OPTSTAGE_W_O: *rows = s.h; *cols = s.nq * s.d; return true;
+    case OPTSTAGE_W_GU: *rows = s.up_w; *cols = s.h; return true;
+    case OPTSTAGE_W_D: *rows = s.h; *cols = s.f; return true;
+    default: return false;
+  }
+}
+
+// Which of a weight's two GEMM operand copies are kept in the slab layout (256 rows x 64 columns per slab, what a
+// workgroup of the direct bf16 kernel loads per k-tile, consecutive in memory): the forward operand W (y = x W^T)
+// and the transposed one (dx = dy W).  A shape the direct kernel does not serve keeps the plain copies.
+void slab_modes(const Shape& s, int which, bool* fwd, bool* bwd) {
+  int rows = 0, cols = 0;
+  *fwd = *bwd = false;
+  if (s.dtype != OPTSTAGE_BF16 || !weight_dims(s, which, &rows, &cols)) return;
+  *fwd = gemm_bf16_slab_applies(s.tokens, rows, cols, cols);
+  *bwd = gemm_bf16_slab_applies(s.tokens, cols, rows, rows);
+}
+
 WorkspaceLayout workspace_layout(const Shape& s) {
   WorkspaceLayout w;
   memset(&w, 0, sizeof w);
@@ -116,7 +139,15 @@ WorkspaceLayout workspace_layout(const Shape& s) {
   w.rope = take(s.family == OPTSTAGE_LLAMA ? (uint64_t)s.seq * (s.d / 2) * 8 : 0);
   uint64_t lstart = off;
   w.wt_base = lstart;
-  for (int k : {OPTSTAGE_W_QKV, OPTSTAGE_W_O, OPTSTAGE_W_GU, OPTSTAGE_W_D}) w.wt[k] = take(weight_elems(s, k) * s.e) - lstart;
+  for (int k : {OPTSTAGE_W_QKV, OPTSTAGE_W_O, OPTSTAGE_W_GU, OPTSTAGE_W_D}) {
+    int rows = 0, cols = 0;
+    bool sf, sb;
+    weight_dims(s, k, &rows, &cols);
+    slab_modes(s, k, &sf, &sb);
+    // transposed copy [cols][rows] (slabs pad its rows to a multiple of 256); forward slab copy only where it is used
+    w.wt[k] = take((uint64_t)(sb ? (cols + 255) / 256 * 256 : cols) * rows * s.e) - lstart;
+    w.wf[k] = take(sf ? (uint64_t)((rows + 255) / 256 * 256) * cols * s.e : 0) - lstart;
+  }
   w.wt_layer_stride = off - lstart;
   off = lstart + w.wt_layer_stride * s.L;
   w.da = take((uint64_t)s.tokens * s.f * s.e);
@@ -386,6 +417,20 @@ optstage_status span_end(optstage* st, hipStream_t s, const TimedSpan& sp) {
 const void* W(optstage* st, int l, int which) { return st->w[(size_t)l * OPTSTAGE_N_WEIGHTS + which]; }
 float* GW(optstage* st, int l, int which) { return st->gw[(size_t)l * OPTSTAGE_N_WEIGHTS + which]; }
 const void* WT(optstage* st, int l, int which) { return st->wsp() + st->ws.wt_base + st->ws.wt_layer_stride * l + st->ws.wt[which]; }
+const void* WF(optstage* st, int l, int which) { return st->wsp() + st->ws.wt_base + st->ws.wt_layer_stride * l + st->ws.wf[which]; }
+// B operand and layout code of the forward (y = x W^T) and backward (dx = dy W) GEMM of a weight
+const void* fwd_operand(optstage* st, int l, int which, int* layout) {
+  bool sf, sb;
+  slab_modes(st->sh, which, &sf, &sb);
+  *layout = sf ? GEMM_NT_SLAB : GEMM_NT;
+  return sf ? WF(st, l, which) : W(st, l, which);
+}
+const void* bwd_operand(optstage* st, int l, int which, int* layout) {
+  bool sf, sb;
+  slab_modes(st->sh, which, &sf, &sb);
+  *layout = sb ? GEMM_NT_SLAB : GEMM_NT;
+  return WT(st, l, which);
+}
 
 
 #define TRY(x)                               \
@@ -471,16 +516,21 @@ optstage_status exec_forward(optstage* st, int j, int c, const OpBufs& ob) {
     void* n2 = rc ? (void*)(st->wsp() + st->ws.dn) : P(l, OPTSTAGE_K_N2);
     void* a = rc ? (void*)(st->wsp() + st->ws.da) : P(l, OPTSTAGE_K_A);
     TRY(k_norm_fwd(st, x, W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), n1, stats));
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, n1, W(st, l, OPTSTAGE_W_QKV), P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
+    int lay;
+    const void* wq = fwd_operand(st, l, OPTSTAGE_W_QKV, &lay);
+    TRY(k_gemm(st, lay, EPI_STORE, n1, wq, P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
     if (s.family == OPTSTAGE_LLAMA)
       TRY(k_rope(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), 0));
     TRY(k_attn_fwd(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), (float*)P(l, OPTSTAGE_K_LSE)));
-    TRY(k_gemm(st, GEMM_NT, EPI_RESID, P(l, OPTSTAGE_K_O), W(st, l, OPTSTAGE_W_O), P(l, OPTSTAGE_K_X_MID), x, T, s.h, s.nq * s.d, s.nq * s.d, s.nq * s.d, s.h));
+    const void* wo = fwd_operand(st, l, OPTSTAGE_W_O, &lay);
+    TRY(k_gemm(st, lay, EPI_RESID, P(l, OPTSTAGE_K_O), wo, P(l, OPTSTAGE_K_X_MID), x, T, s.h, s.nq * s.d, s.nq * s.d, s.nq * s.d, s.h));
     TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), n2, stats + (size_t)nstat * T));
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, n2, W(st, l, OPTSTAGE_W_GU), P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
+    const void* wgu = fwd_operand(st, l, OPTSTAGE_W_GU, &lay);
+    TRY(k_gemm(st, lay, EPI_STORE, n2, wgu, P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
     TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), a));
     void* y = l + 1 < l1 ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[io];
-    TRY(k_gemm(st, GEMM_NT, EPI_RESID, a, W(st, l, OPTSTAGE_W_D), y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
+    const void* wd = fwd_operand(st, l, OPTSTAGE_W_D, &lay);
+    TRY(k_gemm(st, lay, EPI_RESID, a, wd, y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
   }
   return OPTSTAGE_OK;
 }
@@ -501,22 +551,27 @@ optstage_status exec_backward_input(optstage* st, int j, int c, const OpBufs& ob
     void* dy = P(l, OPTSTAGE_K_DY);
     float* stats = (float*)P(l, OPTSTAGE_K_STATS);
     // da = dy W_d ; dgu = act'(gu) da (over gu) ; dn2 = dgu W_gu
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, dy, WT(st, l, OPTSTAGE_W_D), da, nullptr, T, s.f, s.h, s.h, s.h, s.f));
+    int lay;
+    const void* wd = bwd_operand(st, l, OPTSTAGE_W_D, &lay);
+    TRY(k_gemm(st, lay, EPI_STORE, dy, wd, da, nullptr, T, s.f, s.h, s.h, s.h, s.f));
     if (rc) TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_A)));   // W's operand, before gu is overwritten
     TRY(k_act_bwd(st, da, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_GU)));
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_GU), WT(st, l, OPTSTAGE_W_GU), dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h));
+    const void* wgu = bwd_operand(st, l, OPTSTAGE_W_GU, &lay);
+    TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_GU), wgu, dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h));
     if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T));
     // dx_mid = dy + norm2'(dn2)
     TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2)));
     // do = dx_mid W_o ; attention backward ; rotary backward into the qkv buffer
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_DX_MID), WT(st, l, OPTSTAGE_W_O), dout, nullptr, T, s.nq * s.d, s.h, s.h, s.h, s.nq * s.d));
+    const void* wo = bwd_operand(st, l, OPTSTAGE_W_O, &lay);
+    TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_DX_MID), wo, dout, nullptr, T, s.nq * s.d, s.h, s.h, s.h, s.nq * s.d));
     TRY(k_attn_bwd(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), dout, (const float*)P(l, OPTSTAGE_K_LSE), dqkv));
     if (s.family == OPTSTAGE_LLAMA)
       TRY(k_rope(st, dqkv, P(l, OPTSTAGE_K_QKV), 1));
     else
       HIP_TRY(hipMemcpyAsync(P(l, OPTSTAGE_K_QKV), dqkv, st->raw[OPTSTAGE_K_QKV], hipMemcpyDeviceToDevice, cs));
     // dn1 = dqkv W_qkv ; dx_in = dx_mid + norm1'(dn1)
-    TRY(k_gemm(st, GEMM_NT, EPI_STORE, P(l, OPTSTAGE_K_QKV), WT(st, l, OPTSTAGE_W_QKV), dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h));
+    const void* wq = bwd_operand(st, l, OPTSTAGE_W_QKV, &lay);
+    TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_QKV), wq, dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h));
     if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_IN), W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats));
     void* dx = l > l0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[io];
     TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1)));
@@ -777,14 +832,12 @@ optstage_status optstage_set_weight(optstage_t* st, uint32_t layer, uint32_t whi
   st->gw[(size_t)layer * OPTSTAGE_N_WEIGHTS + which] = grad;
   const Shape& s = st->sh;
   int rows = 0, cols = 0;
-  switch (which) {
-    case OPTSTAGE_W_QKV: rows = s.qkv_w; cols = s.h; break;
-    case OPTSTAGE_W_O: rows = s.h; cols = s.nq * s.d; break;
-    case OPTSTAGE_W_GU: rows = s.up_w; cols = s.h; break;
-    case OPTSTAGE_W_D: rows = s.h; cols = s.f; break;
-    default: return OPTSTAGE_OK;
-  }
-  HIP_TRY(launch_transpose(s.dtype, weight_dev, (void*)WT(st, layer, which), rows, cols, st->cs));
+  if (!weight_dims(s, which, &rows, &cols)) return OPTSTAGE_OK;
+  bool sf, sb;
+  slab_modes(s, which, &sf, &sb);
+  if (sb) HIP_TRY(launch_slabs(weight_dev, (void*)WT(st, layer, which), cols, rows, 1, st->cs));
+  else HIP_TRY(launch_transpose(s.dtype, weight_dev, (void*)WT(st, layer, which), rows, cols, st->cs));
+  if (sf) HIP_TRY(launch_slabs(weight_dev, (void*)WF(st, layer, which), rows, cols, 0, st->cs));
   return OPTSTAGE_OK;
 }
 

@@ -93,6 +93,42 @@ def test_gemm_grouped_equals_one_by_one_and_the_oracle():
     assert lib().optstage_op_gemm_grouped(B.GEMM_TN, B.EPI_ACCUM, len(shapes), C.cast(probs, C.c_void_p), 72, stream()) == B.E_ARG
 
 
+def slabs_of(w):
+    """[N, K] -> the slab layout of layout code 2: slab (n // 256, k // 64) holds rows 256 x columns 64, row-major,
+    slabs ordered by (n // 256, k // 64); rows padded to a multiple of 256."""
+    n, k = w.shape
+    n_pad = (n + 255) // 256 * 256
+    wp = np.zeros((n_pad, k), dtype=w.dtype)
+    wp[:n] = w
+    return np.ascontiguousarray(wp.reshape(n_pad // 256, 256, k // 64, 64).transpose(0, 2, 1, 3))
+
+
+@pytest.mark.parametrize("M,N,K,epi", [(2816, 3072, 192, B.EPI_STORE), (2817, 3000, 256, B.EPI_RESID), (4096, 2048, 64, B.EPI_STORE)])
+def test_gemm_with_b_in_slabs(M, N, K, epi):
+    """The layout the stage keeps its weight copies in: bitwise the row-major product, and the oracle's on
+    sampled rows (ragged edges in both directions)."""
+    a = q(RNG.standard_normal((M, K)), BF16)
+    w = q(RNG.standard_normal((N, K)), BF16)
+    r = q(RNG.standard_normal((M, N)), BF16)
+    A, W, WS, R = dev(a, BF16), dev(w, BF16), dev(slabs_of(w), BF16), dev(r, BF16)
+    rp = R.data_ptr() if epi == B.EPI_RESID else 0
+    C0 = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    C1 = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    ok(lib().optstage_op_gemm(BF16, B.GEMM_NT, epi, A.data_ptr(), W.data_ptr(), C0.data_ptr(), rp, M, N, K, K, K, N, stream()))
+    ok(lib().optstage_op_gemm(BF16, B.GEMM_NT_SLAB, epi, A.data_ptr(), WS.data_ptr(), C1.data_ptr(), rp, M, N, K, K, 0, N, stream()))
+    torch.cuda.synchronize()
+    assert torch.equal(C0, C1)
+    rows = RNG.choice(M, size=24, replace=False)
+    ref = a[rows].astype(np.float64) @ w.astype(np.float64).T + (r[rows] if epi == B.EPI_RESID else 0.0)
+    assert rel_err(host(C1)[rows], ref) < TOL[BF16]
+    # too few tiles for the kernel that reads slabs, a contraction that is not whole slabs, fp32: refused
+    f = lib().optstage_op_gemm
+    assert f(BF16, B.GEMM_NT_SLAB, epi, A.data_ptr(), WS.data_ptr(), C1.data_ptr(), rp, 512, 512, K, K, 0, N, stream()) == B.E_ARG
+    assert f(BF16, B.GEMM_NT_SLAB, epi, A.data_ptr(), WS.data_ptr(), C1.data_ptr(), rp, M, N, K - 8, K, 0, N, stream()) == B.E_ARG
+    assert f(FP32, B.GEMM_NT_SLAB, epi, A.data_ptr(), WS.data_ptr(), C1.data_ptr(), rp, M, N, K, K, 0, N, stream()) == B.E_ARG
+    assert f(BF16, B.GEMM_NT_SLAB, B.EPI_ACCUM, A.data_ptr(), WS.data_ptr(), C1.data_ptr(), 0, M, N, K, K, 0, N, stream()) == B.E_ARG
+
+
 def test_gemm_rejects_bad_shapes():
     A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
     f = lib().optstage_op_gemm
