@@ -32,6 +32,12 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
                                  void* C, const void* R, uint32_t M, uint32_t N, uint32_t K, uint32_t lda,
                                  uint32_t ldb, uint32_t ldc, void* stream);
 
+/* Writes a bf16 matrix into the slab layout of layout 2: dst (DEVICE, ceil(N / 256) * 256 * K elements) receives
+ * B(n,k) = src[n * K + k] (transposed = 0) or src[k * N + n] (transposed = 1: the source is [K,N]); rows past N are
+ * zero.  K % 64 must be 0.  The stage does this for its weight copies in optstage_set_weight. */
+optstage_status optstage_op_weight_slabs(const void* src, void* dst, uint32_t N, uint32_t K, uint32_t transposed,
+                                         void* stream);
+
 /* n (1..16) independent bf16 products of the same layout, epilogue and K in ONE launch (the weight-gradient GEMMs
  * of a W op, dW = dY^T X for every linear of every layer, do not depend on one another: Sec. 2.2).  problems is a
  * HOST array; pointers inside are DEVICE.  Each problem must satisfy optstage_op_gemm's alignment rules, K % 64

@@ -85,6 +85,7 @@ _SIGS = {
     "optstage_plan": [C.POINTER(Desc), C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(_u64), C.POINTER(_u64)],
     "optstage_op_gemm": [_u32, _u32, _u32, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _u32, _vp],
     "optstage_op_gemm_grouped": [_u32, _u32, _u32, _vp, _u32, _vp],
+    "optstage_op_weight_slabs": [_vp, _vp, _u32, _u32, _u32, _vp],
     "optstage_op_norm_fwd": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _f32, _vp],
     "optstage_op_norm_bwd": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _vp],
     "optstage_op_act_fwd": [_u32, _u32, _vp, _vp, _u32, _u32, _vp],

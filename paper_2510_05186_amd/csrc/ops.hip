@@ -70,6 +70,13 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
   return wrap(e, "gemm");
 }
 
+optstage_status optstage_op_weight_slabs(const void* src, void* dst, uint32_t N, uint32_t K, uint32_t transposed,
+                                         void* stream) {
+  REQ(src && dst, "weight_slabs: null operand");
+  REQ(N && K && (K % 64) == 0 && N < (1u << 30) && K < (1u << 30) && transposed <= 1, "weight_slabs: bad extent (K must be a multiple of 64)");
+  return wrap(launch_slabs(src, dst, (int)N, (int)K, (int)transposed, (hipStream_t)stream), "weight_slabs");
+}
+
 optstage_status optstage_op_gemm_grouped(uint32_t layout, uint32_t epilogue, uint32_t n,
                                          const optstage_gemm_problem* problems, uint32_t K, void* stream) {
   REQ(problems && n >= 1 && n <= 16 && layout <= 1 && (epilogue == 0 || epilogue == 2), "gemm_grouped: bad argument");

@@ -129,6 +129,20 @@ def test_gemm_with_b_in_slabs(M, N, K, epi):
     assert f(BF16, B.GEMM_NT_SLAB, B.EPI_ACCUM, A.data_ptr(), WS.data_ptr(), C1.data_ptr(), 0, M, N, K, K, 0, N, stream()) == B.E_ARG
 
 
+@pytest.mark.parametrize("N,K", [(512, 128), (300, 64), (1000, 448)])
+def test_weight_slabs_match_the_host_layout(N, K):
+    w = q(RNG.standard_normal((N, K)), BF16)
+    want = torch.from_numpy(slabs_of(w).astype(np.float32)).bfloat16().reshape(-1)
+    n_pad = (N + 255) // 256 * 256
+    for transposed, src in ((0, w), (1, np.ascontiguousarray(w.T))):
+        S = dev(src, BF16)
+        D = torch.full((n_pad * K,), 3.0, dtype=torch.bfloat16, device="cuda")
+        ok(lib().optstage_op_weight_slabs(S.data_ptr(), D.data_ptr(), N, K, transposed, stream()))
+        torch.cuda.synchronize()
+        assert torch.equal(D.cpu(), want), transposed
+    assert lib().optstage_op_weight_slabs(S.data_ptr(), D.data_ptr(), N, K + 8, 0, stream()) == B.E_ARG
+
+
 def test_gemm_rejects_bad_shapes():
     A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
     f = lib().optstage_op_gemm
