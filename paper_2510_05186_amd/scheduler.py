@@ -25,6 +25,7 @@ L are constants and only H is decided.
 """
 from __future__ import annotations
 
+import bisect
 import itertools
 from dataclasses import dataclass, field
 
@@ -265,17 +266,26 @@ def milp_schedule(inst: Instance, time_limit: float = 60.0, cutoff: float | None
 def _list_from_times(start, items, item):
     """Event list of one stage from the solver's values.  Compute ops by start time; O at its start time
     (hence after its forward op); OWAIT just before the first op credited with the memory (M = 1); R at its
-    start time but never after an op charged with it (N = 1), never before its OWAIT."""
+    start time but never after an op charged with it (N = 1), never before its OWAIT.  Eq. 7 looks at memory
+    only where a compute op starts, so the solver leaves the order of an OWAIT and an R that fall between the
+    same two compute ops open; the executor charges by list position, so within such a gap every OWAIT goes
+    before every R (both moved to the start of the op that ends the gap, which changes no op's charge)."""
     layer, kinds = item
     kinds = tuple(kinds)
     rank = {"OWAIT": 0, "R": 1, "F": 2, "B": 2, "W": 2, "O": 3}
     ev = [(t, rank[u[1]], OPS.index(u[1]), u[0], (u[1], u[0])) for u, t in start.items()]
+    op_starts = sorted(round(t, 9) for t in start.values())
+
+    def gap_end(t):
+        k = bisect.bisect_left(op_starts, round(t, 9))
+        return op_starts[k] if k < len(op_starts) else float("inf")
+
     for j, (o_t, r_t, cred, chg) in items.items():
         ev.append((o_t, rank["O"], 0, j, ("O", j, layer, kinds)))
         r_key = min([r_t] + [start[u] for u in chg])
         w_key = min([r_key] + [start[u] for u in cred])
-        ev.append((w_key, rank["OWAIT"], 0, j, ("OWAIT", j, layer, kinds)))
-        ev.append((r_key, rank["R"], 0, j, ("R", j, layer, kinds)))
+        ev.append((gap_end(w_key), rank["OWAIT"], 0, j, ("OWAIT", j, layer, kinds)))
+        ev.append((gap_end(r_key), rank["R"], 0, j, ("R", j, layer, kinds)))
     ev.sort(key=lambda e: (round(e[0], 9), e[1], e[2], e[3]))
     return [e[4] for e in ev]
 
@@ -499,3 +509,79 @@ def expand_items(events, n_layers, kinds):
         else:
             out.append(e)
     return out
+
+
+# ------------------------------------------------------------------------------- online scheduling (Sec. 4.3)
+
+class OnlineSearch:
+    """The solver working beside training: a host thread that starts from AdaOffload's lists and keeps asking
+    the MILP for something strictly better, publishing every improvement; the training loop reads `best()` between
+    iterations and hands the new lists to the stage (which takes a different list every iteration).
+
+    The paper's solver reports incumbents through a callback.  scipy's interface has none, so the same stream of
+    improving schedules is produced by a sequence of solves, each bounded by `slice_seconds` and by C <= (best so
+    far) - min_gain: a solve either returns a better schedule (published), proves there is none (search complete),
+    or runs out of time (the next solve gets a longer slice).  `strict_eq13` and the instance's `own_peak` are
+    passed through, so that what is published fits the executor's accounting.
+
+    judge(solution) -> float may re-time a candidate (e.g. with a simulator fed with measured op times); by default
+    the solver's own makespan is used.  Improvements are compared in the judge's units."""
+
+    def __init__(self, inst: Instance, tolerance: float = 0.0, slice_seconds: float = 5.0, max_seconds: float = 120.0,
+                 min_gain: float = 1e-6, strict_eq13: bool = False, judge=None):
+        import threading
+        self.inst, self.tolerance = inst, tolerance
+        self.slice_seconds, self.max_seconds, self.min_gain = slice_seconds, max_seconds, min_gain
+        self.strict_eq13, self.judge = strict_eq13, judge
+        self._lock = threading.Lock()
+        self._stop = threading.Event()
+        self._best = None                     # (score, Solution)
+        self.history = []                     # (seconds since start, score, status) of every publication
+        self.complete = False                 # True once a solve proved that nothing better exists
+        self._thread = threading.Thread(target=self._run, name="optstage-online-search", daemon=True)
+
+    def start(self):
+        self._thread.start()
+        return self
+
+    def stop(self, wait: bool = True):
+        self._stop.set()
+        if wait and self._thread.is_alive():
+            self._thread.join()
+
+    def join(self, timeout=None):
+        self._thread.join(timeout)
+
+    def best(self):
+        """(score, Solution) of the best schedule published so far, or None before the first."""
+        with self._lock:
+            return self._best
+
+    def _publish(self, sol: Solution, t0: float):
+        import time
+        score = float(self.judge(sol)) if self.judge else float(sol.makespan)
+        with self._lock:
+            if self._best is None or score < self._best[0] - self.min_gain:
+                self._best = (score, sol)
+                self.history.append((time.monotonic() - t0, score, sol.status))
+                return True
+        return False
+
+    def _run(self):
+        import time
+        t0 = time.monotonic()
+        self._publish(adaoffload(self.inst, tolerance=self.tolerance), t0)
+        slice_s = self.slice_seconds
+        while not self._stop.is_set() and time.monotonic() - t0 < self.max_seconds:
+            bound = self.best()[1].makespan - self.min_gain
+            sol = milp_schedule(self.inst, time_limit=slice_s, cutoff=bound, strict_eq13=self.strict_eq13)
+            if sol.lists:
+                self._publish(sol, t0)
+                if "ptimal" in sol.status:            # proven optimal under the bound: nothing better exists
+                    self.complete = True
+                    return
+            elif "nfeasible" in sol.status:            # no schedule beats the incumbent
+                self.complete = True
+                return
+            else:                                      # out of time without an incumbent: look longer
+                slice_s *= 2

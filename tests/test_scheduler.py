@@ -225,3 +225,52 @@ def test_adaoffload_with_a_memory_table_in_which_b_grows(p, m):
         first_b = next(n for n, e in enumerate(lst) if e[0] == "B")
         fills[name] = sum(1 for e in lst[:first_b] if e[0] == "F")
     assert fills["recompute"] >= fills["store_all"]
+
+
+def test_online_search_publishes_improving_schedules_up_to_the_optimum():
+    """Sec. 4.3 on the host: the search starts from AdaOffload's lists and publishes strictly better ones until a
+    solve proves that none is left; the last one is the optimum the brute-force search finds, every published list
+    is valid, and a search that is stopped early still holds its best so far."""
+    m = 3
+    t_op = [{"F": 1, "B": 1, "W": 1}] * 2
+    limit = 2 * DELTA["F"] + TABLE["DY"] + TABLE["DX_MID"] + (DELTA["F"] - GAMMA)
+    inst = SC.Instance(p=2, m=m, t_op=t_op, t_off=[1, 1], delta=[DELTA, DELTA], gamma=[GAMMA, GAMMA],
+                       limit=[limit, None], offload_stages=(0,), offload_mbs=(0, 1), item=ITEM)
+    search = SC.OnlineSearch(inst, tolerance=0.5, slice_seconds=20, max_seconds=120).start()
+    search.join(150)
+    assert search.complete
+    scores = [h[1] for h in search.history]
+    assert search.history[0][2] == "adaoffload"
+    assert all(b < a for a, b in zip(scores, scores[1:]))
+    score, sol = search.best()
+    assert abs(score - brute_optimum(2, m, t_op, 0, 1, limit, (0, 1))) < 1e-5
+    check_solution(inst, sol, 1)
+    # a judge re-times candidates in its own units (here: twice the solver's makespan)
+    judged = SC.OnlineSearch(inst, tolerance=0.5, slice_seconds=20, max_seconds=120, judge=lambda s_: 2 * s_.makespan).start()
+    judged.join(150)
+    assert abs(judged.best()[0] - 2 * score) < 1e-5
+    # stopping: a search on a larger instance is cut off and keeps what it has (at least AdaOffload's lists)
+    big = SC.Instance(p=4, m=6, t_op=[{"F": 1.0, "B": 1.2, "W": 0.8}] * 4, t_comm=0.05, t_off=[0.5] * 4, delta=[DELTA] * 4,
+                      gamma=[GAMMA] * 4, limit=[3 * DELTA["F"] + TABLE["DY"] + TABLE["DX_MID"]] * 4,
+                      offload_stages=(0, 1, 2, 3), item=ITEM)
+    cut = SC.OnlineSearch(big, tolerance=0.5, slice_seconds=1, max_seconds=2).start()
+    cut.join(60)
+    assert not cut._thread.is_alive()
+    assert cut.best() is not None and cut.best()[1].lists and len(cut.history) >= 1
+
+
+def test_list_extraction_orders_transfers_inside_a_gap_for_the_executor():
+    """Eq. 7 is checked where compute ops start, so a solution may start a reload, in solver time, before an
+    offload that ends between the same two compute ops has released its memory.  The executor charges by list
+    position: in the extracted list the OWAIT comes first, the op charges (M, N) stay as solved."""
+    start = {(0, "F"): 0.0, (1, "F"): 1.0, (2, "F"): 2.5, (0, "B"): 5.0, (0, "W"): 6.0, (1, "B"): 7.0, (1, "W"): 8.0,
+             (2, "B"): 9.0, (2, "W"): 10.0}
+    items = {1: (2.0, 3.6, [(2, "F"), (0, "B")], []),              # offloaded before F2 starts, reload asked for at 3.6
+             2: (3.5, 8.0, [(0, "B")], [])}                         # its offload ends at 4.0: after 3.6, before B0
+    ev = SC._list_from_times(start, items, ITEM)
+    pos = {(e[0], e[1]): k for k, e in enumerate(ev)}
+    assert pos[("OWAIT", 2)] < pos[("R", 1)] < pos[("B", 0)]                 # same gap: release first, then reload
+    assert pos[("F", 2)] < pos[("O", 2)] < pos[("OWAIT", 2)]
+    assert pos[("O", 1)] < pos[("OWAIT", 1)] < pos[("F", 2)]                 # credited to F2: released before it
+    assert pos[("B", 1)] < pos[("R", 2)] < pos[("W", 1)]                     # at W1's start time: just before it
+    S.check_order(SC.expand_items(ev, L, ITEM[1]), 3, L)
