@@ -357,16 +357,20 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const bf16_t* _
 //
 // With a single wave per SIMD nothing hides an instruction that waits, so the main loop is laid out by hand
 // (the scheduling barriers pin the order):
-//  * LDS is split [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KB each: the stage (and for TN the
-//    k-step) is an immediate offset of the fragment reads, whose per-lane addresses are computed once; two
-//    k-tiles per loop trip make the stage a compile-time constant, so the loop has no address arithmetic.
+//  * LDS is a ring of five 32 KB slots that the operand tiles take in the order A0 B0 A1 B1 A2 ...; a tile's
+//    operands may lie in any two of them, so the per-lane fragment addresses are rebuilt (one add each) for
+//    the next tile under MFMAs that have nothing else to issue; for TN the k-step is an immediate offset.
 //  * Fragment reads are issued ahead of every pair of MFMAs (k-step s + 1 is fetched under the MFMAs of
-//    k-step s), one tile load ahead of every MFMA of the last k-step; the fragments of the last k-step of a
-//    tile are requested early in the k-step before, so they have landed when the tile barrier is reached.
-//  * The loop is rotated so that the one barrier per tile (next tile landed, this stage free to refill) sits
-//    at the top of the trip.
-//  * Tiles are taken in pairs; a tile index past the end is fetched through a zero-length descriptor, which
-//    zero-fills its stage, so an odd tile count needs no second code path.
+//    k-step s); the fragments of the last k-step of a tile are requested early in the k-step before, so they
+//    have landed when the tile barrier is reached.
+//  * The loop is rotated so that the one barrier per tile (next tile landed, two slots free to refill) sits at
+//    the top of the trip; it waits for all of this wave's loads but the newest eight, which belong to the tile
+//    after the next one.
+//  * One tile load goes out ahead of every fourth MFMA.  Issued back to back (16 loads by each of four waves at
+//    the same point of the loop) they fill the address queue of the texture unit, which blocks the waves that
+//    issue them and the MFMAs behind; the uneven request stream also cost a third more L2 misses.
+//  * A tile index past the end is fetched through a zero-length descriptor, which zero-fills its slot, so the
+//    number of loads in flight is the same on every trip and the waits need no second code path.
 //  * The tile loads are written in assembly: issued through the compiler builtin, every later transposing
 //    read is ordered after them with a full vmcnt(0) wait, which serialises the loop.  The one wait + barrier
 //    per tile orders them instead.
@@ -480,20 +484,20 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // fragment q: 0..3 = A rows (i = q), 4..7 = B rows (j = q - 4).  Byte address of this lane's read within
-  // stage 0: NT one per k-step, TN one (k-step and k-quad are immediates: 8192 and 2048 bytes)
-  int faddr[8][TNL ? 1 : 4];
+  // a slot: NT one per k-step, TN one (k-step and k-quad are immediates: 8192 and 2048 bytes)
+  constexpr int KS = TNL ? 1 : 4;
+  int faddr[8][KS];
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
-    const int base = (q < 4 ? 0 : 2 * OPB);
     const int first = q < 4 ? wm * (BM / WM) + q * 32 : wn * (BN / WN) + (q - 4) * 32;
     if (TNL) {
       const int khalf = lane >> 5, cgrp = (lane >> 4) & 1, e = (lane >> 2) & 3, r = lane & 3;
       const int c16 = (first + cgrp * 16 + r * 4) >> 3;
-      faddr[q][0] = base + (khalf * 8 + e) * 512 + ((c16 ^ (e << 2)) << 4) + (r & 1) * 8;
+      faddr[q][0] = (khalf * 8 + e) * 512 + ((c16 ^ (e << 2)) << 4) + (r & 1) * 8;
     } else {
       const int row = first + (lane & 31), khalf = lane >> 5;
 #pragma unroll
-      for (int ks = 0; ks < (TNL ? 1 : 4); ++ks) faddr[q][ks] = base + row * ROW_BYTES + (((ks * 2 + khalf) ^ swz(row)) << 4);
+      for (int ks = 0; ks < KS; ++ks) faddr[q][ks] = row * ROW_BYTES + (((ks * 2 + khalf) ^ swz(row)) << 4);
     }
   }
   // tile loads: 16 per wave and tile, t even -> A, t odd -> B, each 1 KB of LDS; voff = this lane's byte offset
@@ -536,51 +540,85 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
   };
   const i32x4_t ra = make_desc(A, a_bytes), rb = make_desc(B, b_bytes);
   const unsigned lds0 = (unsigned)(size_t)(lds_void_t*)smem;
-  auto issue_one = [&](i32x4_t da, i32x4_t db, int stage, int kt, int t) {
-    const unsigned dst = lds0 + ((t & 1) ? 2 * OPB : 0) + stage * OPB + (wave * 8 + (t >> 1)) * 1024;
-    const unsigned soff = (t & 1) ? kt * b_tile : kt * a_tile;
+  // load idx (0..7) of this wave for one operand of k-tile `tile` into the ring slot at byte offset `slot_off`
+  auto issue_one = [&](i32x4_t desc, unsigned slot_off, int tile, bool is_b, int idx) __attribute__((always_inline)) {
+    const unsigned dst = lds0 + slot_off + (wave * 8 + idx) * 1024;
+    const unsigned soff = tile * (is_b ? b_tile : a_tile);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(dst), "v"(voff[t]), "s"((t & 1) ? db : da), "s"(soff) : "memory", "m0");
+                 :: "s"(dst), "v"(voff[2 * idx + (is_b ? 1 : 0)]), "s"(desc), "s"(soff) : "memory", "m0");
   };
+  // descriptor of an operand for k-tile `tile`: past the last tile it has length zero (the load then moves nothing
+  // from memory and zero-fills its slot, so the count of loads in flight is the same on every trip)
+  auto desc_for = [&](i32x4_t d, int tile) __attribute__((always_inline)) {
+    d[2] = tile < K / BK ? d[2] : 0;
+    return d;
+  };
+  // LDS is a ring of five 32 KB slots which the operands take in the order A0 B0 A1 B1 A2 ... (operand u in slot
+  // u % 5).  While tile kt is computed its two slots are read, the two that tile kt - 1 has left are refilled with
+  // B of tile kt + 1 and A of tile kt + 2, and A of tile kt + 1 sits in the fifth.  The sync at the top of tile kt
+  // wants both operands of tile kt landed: every load but this wave's last 8 (A of tile kt + 1), which stay in
+  // flight across the barrier, so the memory pipe never runs empty.  The slots of a tile change from trip to
+  // trip: cur[][] = LDS addresses of the fragments of the tile being read, rebuilt for the next tile
+  // under the MFMAs of the last k-step that reads nothing any more.
+  constexpr unsigned RING = 5 * OPB;
+  auto two_on = [](unsigned off) __attribute__((always_inline)) { off += 2 * OPB; return off >= RING ? off - RING : off; };
+  int cur[8][KS];
   i16x4_t fr[2][8][2];
   // half 0 / 1: the two 8-byte halves of fragment q (TN: one transposing read each; NT: one 16-byte read at half 0)
-  auto load_half = [&](int set, int stage, int ks, int q, int half) {
+  auto load_half = [&](int set, int ks, int q, int half) __attribute__((always_inline)) {
     if (TNL) {
-      fr[set][q][half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (lds_i16x4_t*)(smem + stage * OPB + ks * 8192 + half * 2048 + faddr[q][0]));
+      fr[set][q][half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_t*)(unsigned)(cur[q][0] + ks * 8192 + half * 2048));
     } else if (half == 0) {
       typedef short i16x8_t __attribute__((ext_vector_type(8)));
-      const i16x8_t v = *reinterpret_cast<const i16x8_t*>(smem + stage * OPB + faddr[q][TNL ? 0 : ks]);
+      typedef __attribute__((address_space(3))) i16x8_t lds_i16x8_t;
+      const i16x8_t v = *(const lds_i16x8_t*)(unsigned)cur[q][TNL ? 0 : ks];
       fr[set][q][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
       fr[set][q][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
     }
   };
-  auto frag = [&](int set, int q) {
+  auto frag = [&](int set, int q) __attribute__((always_inline)) {
     return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(fr[set][q][0], fr[set][q][1], 0, 1, 2, 3, 4, 5, 6, 7));
   };
   // fragments are read in the order a0 b0 a1 b1 ...; the MFMA order uses the ones read first first
   constexpr int MI[16] = {0, 1, 0, 1, 2, 2, 0, 1, 2, 3, 3, 3, 0, 1, 2, 3};
   constexpr int MJ[16] = {0, 0, 1, 1, 0, 1, 2, 2, 2, 0, 1, 2, 3, 3, 3, 3};
   constexpr int LQ[8] = {0, 4, 1, 5, 2, 6, 3, 7};
-  auto mma_one = [&](int set, int t) {
+  auto mma_one = [&](int set, int t) __attribute__((always_inline)) {
     acc[MI[t]][MJ[t]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(set, 4 + MJ[t]), frag(set, MI[t]), acc[MI[t]][MJ[t]], 0, 0, 0);
   };
-  // k-steps 0..2 of the tile in `stage`: the MFMAs of step ks run over the fragment reads of step ks + 1
-  auto steps_012 = [&](int stage) {
+  // The 16 loads a wave issues per tile are spread evenly over the tile's 64 MFMAs, one ahead of every fourth
+  // (all four waves reach the same point together, and a burst of 64 KB of requests fills the address queue of
+  // the texture unit, which then blocks the issuing waves, MFMAs included): n = 0..15 in issue order, the first
+  // 8 fetch B of tile kt + 1 into the slot at pa, the others A of tile kt + 2 into the slot at pb
+  auto refill_one = [&](i32x4_t db, i32x4_t da, unsigned pa, unsigned pb, int kt, int n) __attribute__((always_inline)) {
+    if (n < 8) issue_one(db, pa, kt + 1, true, n); else issue_one(da, pb, kt + 2, false, n - 8);
+  };
+  // k-steps 0..2 of the tile cur[][] points at: the MFMAs of step ks run over the fragment reads of step ks + 1;
+  // the second half of step 2 points cur[][] at the next tile's slots (byte offsets na, nb)
+  auto steps_012 = [&](unsigned na, unsigned nb, unsigned pa, unsigned pb, int kt, bool refill) __attribute__((always_inline)) {
+    const i32x4_t db = desc_for(rb, kt + 1), da = desc_for(ra, kt + 2);
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
       const int set = ks & 1;
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
         __builtin_amdgcn_sched_barrier(0);
+        if (refill && (q & 1) == 0) refill_one(db, da, pa, pb, kt, 4 + ks * 4 + (q >> 1));
         if (ks < 2) {
-          load_half(set ^ 1, stage, ks + 1, LQ[q], 0);
-          load_half(set ^ 1, stage, ks + 1, LQ[q], 1);
-        } else if (q < 4) {                        // last reads of this stage: all requested in the first half
-          load_half(set ^ 1, stage, ks + 1, LQ[2 * q], 0);
-          load_half(set ^ 1, stage, ks + 1, LQ[2 * q], 1);
-          load_half(set ^ 1, stage, ks + 1, LQ[2 * q + 1], 0);
-          load_half(set ^ 1, stage, ks + 1, LQ[2 * q + 1], 1);
+          load_half(set ^ 1, ks + 1, LQ[q], 0);
+          load_half(set ^ 1, ks + 1, LQ[q], 1);
+        } else if (q < 4) {                        // last reads of these slots: all requested in the first half
+          load_half(set ^ 1, ks + 1, LQ[2 * q], 0);
+          load_half(set ^ 1, ks + 1, LQ[2 * q], 1);
+          load_half(set ^ 1, ks + 1, LQ[2 * q + 1], 0);
+          load_half(set ^ 1, ks + 1, LQ[2 * q + 1], 1);
+        } else {
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int qq = 2 * (q - 4) + h;
+#pragma unroll
+            for (int k2 = 0; k2 < KS; ++k2) cur[qq][k2] = faddr[qq][k2] + (int)(lds0 + (qq < 4 ? na : nb));
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
         mma_one(set, 2 * q);
@@ -589,61 +627,51 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  // k-step 3 of the tile in `stage` (fragment set 1); meanwhile that stage is refilled with tile kt and the
-  // first fragments of the next tile are read from the other stage
-  auto step_3 = [&](int stage, i32x4_t da, i32x4_t db, int kt, bool refill, bool next) {
+  // k-step 3 of the previous tile (fragment set 1, registers only), the first four refill loads of the two slots
+  // that tile has left (byte offsets pa, pb), and the reads of the first fragments of tile kt
+  auto step_3 = [&](unsigned pa, unsigned pb, int kt, bool refill, bool next) __attribute__((always_inline)) {
+    const i32x4_t db = desc_for(rb, kt + 1), da = desc_for(ra, kt + 2);
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       __builtin_amdgcn_sched_barrier(0);
-      if (refill) issue_one(da, db, stage, kt, 2 * q);
-      if (next) load_half(0, stage ^ 1, 0, LQ[q], 0);
+      if (refill && (q & 1) == 0) refill_one(db, da, pa, pb, kt, q >> 1);
+      if (next) load_half(0, 0, LQ[q], 0);
       __builtin_amdgcn_sched_barrier(0);
       mma_one(1, 2 * q);
       __builtin_amdgcn_sched_barrier(0);
-      if (refill) issue_one(da, db, stage, kt, 2 * q + 1);
-      if (next) load_half(0, stage ^ 1, 0, LQ[q], 1);
+      if (next) load_half(0, 0, LQ[q], 1);
       __builtin_amdgcn_sched_barrier(0);
       mma_one(1, 2 * q + 1);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  // the next tile has landed (this wave's part; the barrier covers the others) and every read of the
-  // stage about to be refilled has returned
-#define OPTSTAGE_TILE_SYNC() asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory")
-
-  const int nk = K / BK, npair = (nk + 1) >> 1;
-  {
-    i32x4_t ra1 = ra, rb1 = rb;
-    ra1[2] = nk > 1 ? ra1[2] : 0;                    // word 2 of the descriptor: bytes in range
-    rb1[2] = nk > 1 ? rb1[2] : 0;
+#define OPTSTAGE_TILE_SYNC(n) asm volatile("s_waitcnt vmcnt(" #n ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
+  const int nk = K / BK;
 #pragma unroll
-    for (int t = 0; t < 16; ++t) issue_one(ra, rb, 0, 0, t);
+  for (int u = 0; u < 5; ++u) {
+    const i32x4_t d = desc_for((u & 1) ? rb : ra, u >> 1);
 #pragma unroll
-    for (int t = 0; t < 16; ++t) issue_one(ra1, rb1, 1, 1, t);
+    for (int idx = 0; idx < 8; ++idx) issue_one(d, u * OPB, u >> 1, (u & 1) != 0, idx);
   }
-  OPTSTAGE_TILE_SYNC();
 #pragma unroll
-  for (int q = 0; q < 8; ++q) { load_half(0, 0, 0, LQ[q], 0); load_half(0, 0, 0, LQ[q], 1); }
-  steps_012(0);
-  // at the top of a trip: k-steps 0..2 of tile 2 p (stage 0) are issued, tile 2 p + 1 is in flight to stage 1
-  for (int p = 0; p + 1 < npair; ++p) {
-    i32x4_t ra1 = ra, rb1 = rb;
-    ra1[2] = 2 * p + 3 < nk ? ra1[2] : 0;
-    rb1[2] = 2 * p + 3 < nk ? rb1[2] : 0;
-    OPTSTAGE_TILE_SYNC();
-    step_3(0, ra, rb, 2 * p + 2, true, true);
-    steps_012(1);
-    OPTSTAGE_TILE_SYNC();
-    step_3(1, ra1, rb1, 2 * p + 3, true, true);
-    steps_012(0);
+  for (int q = 0; q < 8; ++q)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) cur[q][ks] = faddr[q][ks] + (int)(lds0 + (q < 4 ? 0 : OPB));
+  OPTSTAGE_TILE_SYNC(24);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) { load_half(0, 0, LQ[q], 0); load_half(0, 0, LQ[q], 1); }
+  unsigned pa = 0, pb = OPB;                         // slots of the tile before tile kt
+  steps_012(two_on(pa), two_on(pb), 0, 0, 0, false);
+  for (int kt = 1; kt < nk; ++kt) {
+    const unsigned oa = two_on(pa), ob = two_on(pb);
+    OPTSTAGE_TILE_SYNC(8);
+    step_3(pa, pb, kt, true, true);
+    steps_012(two_on(oa), two_on(ob), pa, pb, kt, true);
+    pa = oa;
+    pb = ob;
   }
-  OPTSTAGE_TILE_SYNC();
-  step_3(0, ra, rb, 0, false, true);
-  steps_012(1);
-  OPTSTAGE_TILE_SYNC();
-  step_3(1, ra, rb, 0, false, false);
-
-  OPTSTAGE_TILE_SYNC();                              // every wave is done with the operand tiles
+  step_3(0, 0, 0, false, false);
+  OPTSTAGE_TILE_SYNC(0);                             // every wave is done with the operand tiles, nothing in flight
 #undef OPTSTAGE_TILE_SYNC
   if (EPI == EPI_ACCUM)
     epilogue_via_lds<EPI, TM, TN, 4>(acc, smem, wave, lane, Cv, R, M, N, ldc, m0 + wm * (BM / WM), n0 + wn * (BN / WN));
@@ -692,7 +720,7 @@ template <bool TNL, int EPI>
 hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
                          int ldc, hipStream_t s, bool b_slab = false) {
   auto kern = gemm_bf16_direct_kernel<TNL, EPI>;
-  constexpr int smem = 131072;
+  constexpr int smem = 163840;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -720,7 +748,7 @@ bool direct_applies(bool tnl, int M, int N, int K, int lda, int ldb) {
 template <bool TNL, int EPI>
 hipError_t launch_direct_grouped(int n, const GemmProblem* pr, int K, hipStream_t s) {
   auto kern = gemm_bf16_direct_grouped_kernel<TNL, EPI>;
-  constexpr int smem = 131072;
+  constexpr int smem = 163840;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
