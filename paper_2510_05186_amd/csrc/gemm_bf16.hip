@@ -14,6 +14,8 @@
 // each lane then owns 4 consecutive n of one m, which gives 8-byte (bf16) / 16-byte (fp32) row-major
 // global accesses in the epilogue.  Workgroup ids are remapped so that the tiles resident on one XCD
 // (ids congruent mod 8) form a compact patch of the output and share A/B panels in that XCD's L2.
+#include <utility>
+
 #include "common.h"
 
 namespace {
@@ -453,6 +455,27 @@ __device__ __forceinline__ void epilogue_bf16_rows(f32x16_t (&acc)[4][4], char* 
   }
 }
 
+// f(std::integral_constant<int, P0>{}), ..., f(std::integral_constant<int, P1 - 1>{}): a loop whose index is a
+// constant expression inside the body
+template <int P0, class F, int... I>
+__device__ __forceinline__ void for_range_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, P0 + I>{}), ...);
+}
+template <int P0, int P1, class F>
+__device__ __forceinline__ void for_range(F&& f) {
+  for_range_impl<P0>(f, std::make_integer_sequence<int, P1 - P0>{});
+}
+
+// Issue position (0..63 within a trip of the main loop) of the trip's n-th tile load; -1 = none at p
+template <bool TNL>
+__device__ constexpr int load_at(int p) {
+  constexpr int NT_AT[16] = {1, 5, 7, 11, 13, 17, 19, 23, 25, 29, 31, 35, 37, 41, 43, 47};
+  constexpr int TN_AT[16] = {1, 7, 13, 19, 25, 31, 37, 43, 56, 57, 58, 59, 60, 61, 62, 63};
+  for (int n = 0; n < 16; ++n)
+    if ((TNL ? TN_AT[n] : NT_AT[n]) == p) return n;
+  return -1;
+}
+
 // One output tile.  TNL = false: A(m, k) at A[m * lda + k], B(n, k) at B[n * ldb + k].  TNL = true: A[k * lda + m],
 // B[k * ldb + n].  pid = position of the tile in the problem's tile sequence (groups of 8 tile rows, walked
 // column by column).
@@ -540,13 +563,16 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
   };
   const i32x4_t ra = make_desc(A, a_bytes), rb = make_desc(B, b_bytes);
   const unsigned lds0 = (unsigned)(size_t)(lds_void_t*)smem;
-  // load idx (0..7) of this wave for one operand of k-tile `tile` into the ring slot at byte offset `slot_off`
-  auto issue_one = [&](i32x4_t desc, unsigned slot_off, int tile, bool is_b, int idx) __attribute__((always_inline)) {
-    const unsigned dst = lds0 + slot_off + (wave * 8 + idx) * 1024;
+  // load idx (0..7) of this wave for one operand of k-tile `tile` into the ring slot whose address, plus this
+  // wave's 8 KB share, is `base`
+  auto issue_one = [&](i32x4_t desc, unsigned base, int tile, bool is_b, auto idx_c) __attribute__((always_inline)) {
+    constexpr int idx = decltype(idx_c)::value;
     const unsigned soff = tile * (is_b ? b_tile : a_tile);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(dst), "v"(voff[2 * idx + (is_b ? 1 : 0)]), "s"(desc), "s"(soff) : "memory", "m0");
+    const unsigned vo = voff[2 * idx + (is_b ? 1 : 0)];
+    asm volatile("s_add_u32 m0, %0, %4\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(base), "v"(vo), "s"(desc), "s"(soff), "n"(idx * 1024) : "memory", "m0", "scc");
   };
+  const unsigned lds_wave = lds0 + wave * 8192;
   // descriptor of an operand for k-tile `tile`: past the last tile it has length zero (the load then moves nothing
   // from memory and zero-fills its slot, so the count of loads in flight is the same on every trip)
   auto desc_for = [&](i32x4_t d, int tile) __attribute__((always_inline)) {
@@ -586,72 +612,79 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
   auto mma_one = [&](int set, int t) __attribute__((always_inline)) {
     acc[MI[t]][MJ[t]] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(set, 4 + MJ[t]), frag(set, MI[t]), acc[MI[t]][MJ[t]], 0, 0, 0);
   };
-  // The 16 loads a wave issues per tile are spread evenly over the tile's 64 MFMAs, one ahead of every fourth
-  // (all four waves reach the same point together, and a burst of 64 KB of requests fills the address queue of
-  // the texture unit, which then blocks the issuing waves, MFMAs included): n = 0..15 in issue order, the first
-  // 8 fetch B of tile kt + 1 into the slot at pa, the others A of tile kt + 2 into the slot at pb
-  auto refill_one = [&](i32x4_t db, i32x4_t da, unsigned pa, unsigned pb, int kt, int n) __attribute__((always_inline)) {
-    if (n < 8) issue_one(db, pa, kt + 1, true, n); else issue_one(da, pb, kt + 2, false, n - 8);
-  };
-  // k-steps 0..2 of the tile cur[][] points at: the MFMAs of step ks run over the fragment reads of step ks + 1;
-  // the second half of step 2 points cur[][] at the next tile's slots (byte offsets na, nb)
-  auto steps_012 = [&](unsigned na, unsigned nb, unsigned pa, unsigned pb, int kt, bool refill) __attribute__((always_inline)) {
-    const i32x4_t db = desc_for(rb, kt + 1), da = desc_for(ra, kt + 2);
-#pragma unroll
-    for (int ks = 0; ks < 3; ++ks) {
-      const int set = ks & 1;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        __builtin_amdgcn_sched_barrier(0);
-        if (refill && (q & 1) == 0) refill_one(db, da, pa, pb, kt, 4 + ks * 4 + (q >> 1));
-        if (ks < 2) {
-          load_half(set ^ 1, ks + 1, LQ[q], 0);
-          load_half(set ^ 1, ks + 1, LQ[q], 1);
-        } else if (q < 4) {                        // last reads of these slots: all requested in the first half
-          load_half(set ^ 1, ks + 1, LQ[2 * q], 0);
-          load_half(set ^ 1, ks + 1, LQ[2 * q], 1);
-          load_half(set ^ 1, ks + 1, LQ[2 * q + 1], 0);
-          load_half(set ^ 1, ks + 1, LQ[2 * q + 1], 1);
-        } else {
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            const int qq = 2 * (q - 4) + h;
-#pragma unroll
-            for (int k2 = 0; k2 < KS; ++k2) cur[qq][k2] = faddr[qq][k2] + (int)(lds0 + (qq < 4 ? na : nb));
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        mma_one(set, 2 * q);
-        mma_one(set, 2 * q + 1);
+  // One trip of the loop = 64 MFMAs = 64 issue positions p: 0..15 are k-step 3 of the previous tile (fragment set
+  // 1, in registers), 16..63 k-steps 0..2 of tile kt.  An MFMA occupies the matrix pipe for 32 cycles, which is
+  // all the room there is for whatever the wave issues ahead of the next one; a tile load takes most of that by
+  // itself (three scalar instructions and a 64-lane address), so no position carries more than one expensive
+  // thing:
+  //  * fragment reads (k-step 0 of tile kt during positions 0..15, then step s + 1 during step s; the reads of
+  //    step 3 are all out by position 55), NT at even positions, TN one at every position;
+  //  * the 16 tile loads of the trip, n = 0..7 = B of tile kt + 1 into the slot at pa, 8..15 = A of tile kt + 2
+  //    into the slot at pb: NT at odd positions up to 47, TN n < 8 at every sixth position (whose read moves to
+  //    the position before) and the others at 56..63;
+  //  * the fragment addresses of the next tile, rebuilt at positions 56..63 when nothing reads the old ones.
+  // Loads issued back to back (16 by each of four waves at the same point) fill the address queue of the texture
+  // unit, which blocks the waves that issue them and the MFMAs behind, and cost a third more L2 misses.
+  auto reads_at = [&](int p, bool next) __attribute__((always_inline)) {
+    if (p < 16) {
+      if (!next) return;
+      if (TNL) load_half(0, 0, LQ[p >> 1], p & 1);
+      else if ((p & 1) == 0) load_half(0, 0, LQ[p >> 1], 0);
+      return;
+    }
+    const int ks = (p - 16) >> 4, t = (p - 16) & 15, q = t >> 1, set = ks & 1;
+    if (ks < 2) {
+      if (TNL) load_half(set ^ 1, ks + 1, LQ[q], t & 1);
+      else if ((t & 1) == 0) load_half(set ^ 1, ks + 1, LQ[q], 0);
+    } else if (q < 4) {                            // last reads of these slots: all requested in the first half
+      if (TNL) {
+        load_half(set ^ 1, ks + 1, LQ[t], 0);
+        load_half(set ^ 1, ks + 1, LQ[t], 1);
+      } else if ((t & 1) == 0) {
+        load_half(set ^ 1, ks + 1, LQ[t], 0);
+        load_half(set ^ 1, ks + 1, LQ[t + 1], 0);
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
   };
-  // k-step 3 of the previous tile (fragment set 1, registers only), the first four refill loads of the two slots
-  // that tile has left (byte offsets pa, pb), and the reads of the first fragments of tile kt
-  auto step_3 = [&](unsigned pa, unsigned pb, int kt, bool refill, bool next) __attribute__((always_inline)) {
-    const i32x4_t db = desc_for(rb, kt + 1), da = desc_for(ra, kt + 2);
+  auto position = [&](auto p_c, unsigned na, unsigned nb, i32x4_t db, i32x4_t da, unsigned base_b, unsigned base_a, int kt,
+                      bool refill, bool next) __attribute__((always_inline)) {
+    constexpr int p = decltype(p_c)::value;
+    constexpr int n = load_at<TNL>(p), n1 = p < 63 ? load_at<TNL>(p + 1) : -1;
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (n >= 0) {
+      if (refill) {
+        if constexpr (n < 8) issue_one(db, base_b, kt + 1, true, std::integral_constant<int, n>{});
+        else issue_one(da, base_a, kt + 2, false, std::integral_constant<int, n - 8>{});
+      }
+    }
+    if (!(TNL && n >= 0)) reads_at(p, next);
+    if (TNL && n1 >= 0) reads_at(p + 1, next);
+    if (p >= 56) {
+      constexpr int PER = 8 * KS / 8;              // addresses per position
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      __builtin_amdgcn_sched_barrier(0);
-      if (refill && (q & 1) == 0) refill_one(db, da, pa, pb, kt, q >> 1);
-      if (next) load_half(0, 0, LQ[q], 0);
-      __builtin_amdgcn_sched_barrier(0);
-      mma_one(1, 2 * q);
-      __builtin_amdgcn_sched_barrier(0);
-      if (next) load_half(0, 0, LQ[q], 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mma_one(1, 2 * q + 1);
+      for (int e = (p - 56) * PER; e < (p - 55) * PER; ++e) cur[e / KS][e % KS] = faddr[e / KS][e % KS] + (int)(lds0 + (e / KS < 4 ? na : nb));
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (p < 16) mma_one(1, p); else mma_one(((p - 16) >> 4) & 1, (p - 16) & 15);
   };
+  // positions [p0, p1) of the trip of tile kt; pa, pb = byte offsets of the slots the previous tile has left
+  auto trip = [&](auto p0, auto p1, unsigned pa, unsigned pb, unsigned na, unsigned nb, int kt, bool refill, bool next)
+      __attribute__((always_inline)) {
+    const i32x4_t db = desc_for(rb, kt + 1), da = desc_for(ra, kt + 2);
+    const unsigned base_b = lds_wave + pa, base_a = lds_wave + pb;
+    for_range<decltype(p0)::value, decltype(p1)::value>(
+        [&](auto p) __attribute__((always_inline)) { position(p, na, nb, db, da, base_b, base_a, kt, refill, next); });
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  constexpr std::integral_constant<int, 0> P0{};
+  constexpr std::integral_constant<int, 16> P16{};
+  constexpr std::integral_constant<int, 64> P64{};
 #define OPTSTAGE_TILE_SYNC(n) asm volatile("s_waitcnt vmcnt(" #n ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
   const int nk = K / BK;
 #pragma unroll
   for (int u = 0; u < 5; ++u) {
     const i32x4_t d = desc_for((u & 1) ? rb : ra, u >> 1);
-#pragma unroll
-    for (int idx = 0; idx < 8; ++idx) issue_one(d, u * OPB, u >> 1, (u & 1) != 0, idx);
+    for_range<0, 8>([&](auto idx) __attribute__((always_inline)) { issue_one(d, lds_wave + u * OPB, u >> 1, (u & 1) != 0, idx); });
   }
 #pragma unroll
   for (int q = 0; q < 8; ++q)
@@ -661,16 +694,15 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
 #pragma unroll
   for (int q = 0; q < 8; ++q) { load_half(0, 0, LQ[q], 0); load_half(0, 0, LQ[q], 1); }
   unsigned pa = 0, pb = OPB;                         // slots of the tile before tile kt
-  steps_012(two_on(pa), two_on(pb), 0, 0, 0, false);
+  trip(P16, P64, 0, 0, two_on(pa), two_on(pb), 0, false, true);
   for (int kt = 1; kt < nk; ++kt) {
     const unsigned oa = two_on(pa), ob = two_on(pb);
     OPTSTAGE_TILE_SYNC(8);
-    step_3(pa, pb, kt, true, true);
-    steps_012(two_on(oa), two_on(ob), pa, pb, kt, true);
+    trip(P0, P64, pa, pb, two_on(oa), two_on(ob), kt, true, true);
     pa = oa;
     pb = ob;
   }
-  step_3(0, 0, 0, false, false);
+  trip(P0, P16, 0, 0, 0, 0, 0, false, false);
   OPTSTAGE_TILE_SYNC(0);                             // every wave is done with the operand tiles, nothing in flight
 #undef OPTSTAGE_TILE_SYNC
   if (EPI == EPI_ACCUM)

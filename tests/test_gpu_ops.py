@@ -24,6 +24,10 @@ def lib():
     (BF16, 2824, 3080, 320),      # same, K a multiple of 64: direct global->LDS tile loads, ragged M and N
     (BF16, 4096, 2048, 64),       # direct path, a single k-tile
     (BF16, 3000, 4096, 128),      # direct path, two k-tiles
+    (BF16, 2824, 3080, 192),      # direct path: 3, 6, 7 and 11 k-tiles walk the ring of five LDS slots through every
+    (BF16, 2824, 3080, 384),      # alignment of a tile's two slots, with and without a wrap inside the tile
+    (BF16, 2824, 3080, 448),
+    (BF16, 2824, 3080, 704),
     (BF16, 256, 256, 64),
     (BF16, 8, 8, 8),
     (FP32, 130, 77, 50),
@@ -46,6 +50,11 @@ def test_gemm_nt_store_and_residual(dtype, M, N, K):
 @pytest.mark.parametrize("dtype,M,N,K", [
     (BF16, 520, 776, 333),        # K (tokens) need not be a multiple of anything
     (BF16, 2824, 3080, 200),
+    (BF16, 2824, 3080, 64),       # direct path (whole 64-token k-tiles, 156 tiles): 1, 2, 5, 7 and 11 k-tiles
+    (BF16, 2824, 3080, 128),
+    (BF16, 2824, 3080, 320),
+    (BF16, 2824, 3080, 448),
+    (BF16, 2824, 3080, 704),
     (BF16, 8, 16, 1),
     (FP32, 130, 76, 50),
 ])
