@@ -669,3 +669,24 @@ def test_repair_to_fit_with_the_oracle_as_planner():
     assert [e for e in fixed if e[0] in "FBW"] == comp                # compute order untouched
     # an impossible budget is reported, not looped on
     assert G.repair_to_fit(opt, planner(S.op_delta("F", L, TABLE) - 1)) is None
+
+
+def test_gpt_workload_has_the_shapes_the_paper_prints():
+    """Appendix "Configuration": the GPT-family workload (cfg 6) is the 1.5B / 3.6B column of the model table at the
+    paper's sequence length, one stage of a p = 16 pipeline holding its equal share of the layers."""
+    import os
+    from stage_inputs import configs as CFG
+    table = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "model_configuration.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, small, large = line.split()
+                assert small == large                      # the two usable columns print the same shapes
+                table[name] = int(small)
+    c = CFG.CFG6
+    assert c.hidden == table["hidden-size"] and c.ffn == table["ffn-hidden-size"]
+    assert c.n_q_heads == table["num-attention-heads"] and c.n_kv_heads == table["num-query-groups"]
+    assert c.n_q_heads * c.head_dim == c.hidden
+    assert c.seq == table["sequence-length"]
+    assert c.n_layers * c.n_stages == table["num-layers"] and c.n_stages == 16
+    assert c.family == CFG.GPT
