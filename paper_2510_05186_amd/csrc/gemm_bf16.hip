@@ -466,15 +466,9 @@ __device__ __forceinline__ void for_range(F&& f) {
   for_range_impl<P0>(f, std::make_integer_sequence<int, P1 - P0>{});
 }
 
-// Issue position (0..63 within a trip of the main loop) of the trip's n-th tile load; -1 = none at p
-template <bool TNL>
-__device__ constexpr int load_at(int p) {
-  constexpr int NT_AT[16] = {1, 5, 7, 11, 13, 17, 19, 23, 25, 29, 31, 35, 37, 41, 43, 47};
-  constexpr int TN_AT[16] = {1, 7, 13, 19, 25, 31, 37, 43, 56, 57, 58, 59, 60, 61, 62, 63};
-  for (int n = 0; n < 16; ++n)
-    if ((TNL ? TN_AT[n] : NT_AT[n]) == p) return n;
-  return -1;
-}
+// Issue position (0..63 within a trip of the main loop) of the trip's n-th tile load: one ahead of every fourth
+// MFMA; -1 = none at p
+__device__ constexpr int load_at(int p) { return (p & 3) == 1 ? p >> 2 : -1; }
 
 // One output tile.  TNL = false: A(m, k) at A[m * lda + k], B(n, k) at B[n * ldb + k].  TNL = true: A[k * lda + m],
 // B[k * ldb + n].  pid = position of the tile in the problem's tile sequence (groups of 8 tile rows, walked
@@ -620,8 +614,7 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
   //  * fragment reads (k-step 0 of tile kt during positions 0..15, then step s + 1 during step s; the reads of
   //    step 3 are all out by position 55), NT at even positions, TN one at every position;
   //  * the 16 tile loads of the trip, n = 0..7 = B of tile kt + 1 into the slot at pa, 8..15 = A of tile kt + 2
-  //    into the slot at pb: NT at odd positions up to 47, TN n < 8 at every sixth position (whose read moves to
-  //    the position before) and the others at 56..63;
+  //    into the slot at pb, at positions 1, 5, ..., 61 (for TN the read of such a position moves to the one before);
   //  * the fragment addresses of the next tile, rebuilt at positions 56..63 when nothing reads the old ones.
   // Loads issued back to back (16 by each of four waves at the same point) fill the address queue of the texture
   // unit, which blocks the waves that issue them and the MFMAs behind, and cost a third more L2 misses.
@@ -649,7 +642,7 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
   auto position = [&](auto p_c, unsigned na, unsigned nb, i32x4_t db, i32x4_t da, unsigned base_b, unsigned base_a, int kt,
                       bool refill, bool next) __attribute__((always_inline)) {
     constexpr int p = decltype(p_c)::value;
-    constexpr int n = load_at<TNL>(p), n1 = p < 63 ? load_at<TNL>(p + 1) : -1;
+    constexpr int n = load_at(p), n1 = p < 63 ? load_at(p + 1) : -1;
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (n >= 0) {
       if (refill) {
