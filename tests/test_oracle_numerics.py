@@ -183,6 +183,13 @@ def test_micro_batch_of_several_sequences_is_the_sequences_side_by_side(family):
             np.testing.assert_allclose(dW[l][name], sum(p[2][l][name] for p in parts), rtol=1e-11, atol=1e-12)
         for name in dn[l]:
             np.testing.assert_allclose(dn[l][name], sum(p[3][l][name] for p in parts), rtol=1e-11, atol=1e-12)
+    # the saved softmax statistics are laid out [sequence, head, position]
+    saved = O.stage_forward(sh, ws, x)[1]
+    for i in range(b):
+        one = O.stage_forward(sh, ws, x[i * sh.seq:(i + 1) * sh.seq])[1]
+        for l in range(sh.n_layers):
+            assert saved[l]["lse"].shape == (b, sh.n_q_heads, sh.seq)
+            np.testing.assert_allclose(saved[l]["lse"][i], one[l]["lse"][0], rtol=1e-12)
     # coupling test: changing the last sequence leaves the first one's output alone, changing the first token of a
     # sequence changes the rest of that sequence
     x2 = x.copy()
@@ -327,3 +334,26 @@ def test_flop_formula_matches_workload_table():
     assert abs(fl["F"] / 4 / 1e12 - 1.795) < 1e-3
     assert abs(fl["B"] / 4 / 1e12 - 2.002) < 1e-3
     assert abs(fl["W"] / 4 / 1e12 - 1.658) < 1e-3
+
+
+def test_attention_with_large_scores_stays_finite_and_equals_library_softmax():
+    """Scores of magnitude several hundred (exp overflows in fp64 beyond 709): the running-maximum shift keeps the
+    result finite and equal to scipy's softmax of the same masked scores; lse equals scipy's logsumexp."""
+    from scipy.special import logsumexp, softmax
+    rng = np.random.default_rng(11)
+    s, d = 12, 8
+    q = 40.0 * rng.standard_normal((s, 1, d))
+    k = 40.0 * rng.standard_normal((s, 1, d))
+    v = rng.standard_normal((s, 1, d))
+    o, lse = O.attention_fwd(q, k, v)
+    sc = (q[:, 0, :] @ k[:, 0, :].T) / np.sqrt(d)
+    assert np.abs(sc).max() > 800
+    sc = np.where(np.tril(np.ones((s, s), dtype=bool)), sc, -np.inf)
+    assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+    np.testing.assert_allclose(o[:, 0, :], softmax(sc, axis=1) @ v[:, 0, :], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(lse[0], logsumexp(sc, axis=1), rtol=1e-12)
+    np.testing.assert_allclose(O.attention_probs(q, k, 0, 0), softmax(sc, axis=1), rtol=1e-12, atol=1e-300)
+    do = rng.standard_normal((s, 1, d))
+    dq, dk, dv = O.attention_bwd(q, k, v, o, do)
+    assert np.all(np.isfinite(dq)) and np.all(np.isfinite(dk)) and np.all(np.isfinite(dv))
+    np.testing.assert_allclose(dv[:, 0, :], softmax(sc, axis=1).T @ do[:, 0, :], rtol=1e-10, atol=1e-12)

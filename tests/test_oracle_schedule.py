@@ -690,3 +690,69 @@ def test_gpt_workload_has_the_shapes_the_paper_prints():
     assert c.seq == table["sequence-length"]
     assert c.n_layers * c.n_stages == table["num-layers"] and c.n_stages == 16
     assert c.family == CFG.GPT
+
+
+def test_backward_memory_steps_by_hand_and_chunk_offset():
+    """The order in which a B op of two layers takes and frees buffers, written out from the layer's data flow: the
+    incoming dY, then per layer (last first) the gradient at the mid residual, the mid residual and the softmax
+    statistics freed once attention is differentiated, the next dY made before this layer's input is freed.  A
+    model chunk that starts at layer 3 tags the same steps with layers 3 and 4."""
+    want = [(+1, 1, "DY"),
+            (+1, 1, "DX_MID"), (-1, 1, "X_MID"), (-1, 1, "LSE"), (+1, 0, "DY"), (-1, 1, "X_IN"), (-1, 1, "STATS"),
+            (+1, 0, "DX_MID"), (-1, 0, "X_MID"), (-1, 0, "LSE"), (-1, 0, "X_IN"), (-1, 0, "STATS")]
+    assert S.op_memory_steps("B", 2) == want
+    assert S.op_memory_steps("B", 2, first_layer=3) == [(s, l + 3, k) for s, l, k in want]
+    assert [l for _, l, _ in S.op_memory_steps("F", 2, first_layer=3)] == [3] * len(S.F_KINDS) + [4] * len(S.F_KINDS)
+
+
+def test_index_bounds_are_exclusive():
+    """Micro-batch m and layer L do not exist (indices run from 0)."""
+    ok = [("F", 0), ("O", 0, L - 1, ("QKV",)), ("OWAIT", 0, L - 1, ("QKV",)), ("R", 0, L - 1, ("QKV",)), ("B", 0), ("W", 0)]
+    S.check_order(ok, 1, L)
+    with pytest.raises(S.ScheduleError):
+        S.check_order(G.one_f_one_b(1, 2, 0), 1, L)         # a valid list of two micro-batches, checked for one
+    with pytest.raises(S.ScheduleError):
+        S.check_order([("F", 0), ("O", 0, L, ("QKV",)), ("OWAIT", 0, L, ("QKV",)), ("R", 0, L, ("QKV",)), ("B", 0), ("W", 0)], 1, L)
+
+
+def test_eq7_usage_with_an_offloaded_item_by_hand():
+    """Eq. 7 as printed: an op is charged its own Delta, the Delta of every op before it, minus Gamma of every
+    offload completed before it, plus Gamma of every reload started before it."""
+    d = {c: S.op_delta(c, L, TABLE) for c in "FBW"}
+    item = ("QKV", "X_MID")
+    g = TABLE["QKV"] + TABLE["X_MID"]
+    ev = [("F", 0), ("O", 0, 1, item), ("OWAIT", 0, 1, item), ("F", 1), ("R", 0, 1, item), ("B", 0), ("W", 0), ("B", 1), ("W", 1)]
+    use = dict(S.eq7_usage(ev, L, TABLE))
+    assert use[0] == d["F"]
+    assert use[3] == 2 * d["F"] - g                      # F1: the offload of micro-batch 0 has completed
+    assert use[5] == 2 * d["F"] - g + g + d["B"]         # B0: and its reload has started
+    assert use[6] == 2 * d["F"] + d["B"] + d["W"]
+    assert use[8] == 2 * (d["F"] + d["B"] + d["W"]) == 0
+
+
+def test_makespan_per_stage_is_the_longest_span_of_a_stage():
+    """Eq. 16 against Eq. 17 on 1F1B with unit times: stage 0 runs from the first F to the last W, so its span is the
+    whole makespan; the last stage starts p - 1 steps late and ends earlier, and must not set the figure."""
+    p, m = 3, 4
+    lists = [G.one_f_one_b(p, m, i) for i in range(p)]
+    t = S.simulate(lists, [{"F": 1.0, "B": 1.0, "W": 1.0}] * p)
+    spans = [max(e for e in t.end[i] if e is not None) - min(s for s in t.start[i] if s is not None) for i in range(p)]
+    assert t.makespan_per_stage == max(spans) == spans[0] == t.makespan_global
+    assert spans[p - 1] < spans[0]
+
+
+def test_sizes_round_up_to_the_allocation_grain():
+    """Buffer sizes are whole multiples of the allocator's grain, the smallest that holds the bytes."""
+    a = S.ALIGN
+    assert [S._round_up(n) for n in (1, a - 1, a, a + 1, 2 * a, 2 * a + 1)] == [a, a, a, 2 * a, 2 * a, 3 * a]
+
+
+def test_v_shaped_placement_with_four_chunks():
+    """Four chunks per stage in the V-shaped placement make a W: even chunks run down the stages, odd ones back
+    up, so on p = 3 stages the 12 pieces sit on stages 0 1 2 2 1 0 0 1 2 2 1 0."""
+    p, v = 3, 4
+    where = {S.virtual_stage(i, c, p, "v"): i for i in range(p) for c in range(v)}
+    assert [where[n] for n in range(p * v)] == [0, 1, 2, 2, 1, 0, 0, 1, 2, 2, 1, 0]
+    assert [S._holder(n, p, "v") for n in range(p * v)] == [(where[n], n // p) for n in range(p * v)]
+    where = {S.virtual_stage(i, c, p, "interleaved"): i for i in range(p) for c in range(v)}
+    assert [where[n] for n in range(p * v)] == [0, 1, 2] * v
