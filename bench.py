@@ -9,6 +9,7 @@ split B/W schedule, no offload).  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -242,8 +243,14 @@ def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event, duplex=False,
     t_op = [{"F": t_op_ms[0], "B": t_op_ms[1], "W": t_op_ms[2]}] * p
     tm = S.simulate(events_all_stages, t_op, t_comm=0.0, t_copy=lambda i, ev: copy_ms_per_event, duplex=duplex,
                     n_chunks=n_chunks, layers_per_chunk=cfg.n_layers // n_chunks)
+    # second run with the neighbour exchange priced: one [tokens, hidden] tensor over a 153 GB/s point-to-point link
+    t_comm_ms = cfg.seq * cfg.micro_batch * cfg.hidden * cfg.elem_size / 153e9 * 1e3
+    tc = S.simulate(events_all_stages, t_op, t_comm=t_comm_ms, t_copy=lambda i, ev: copy_ms_per_event, duplex=duplex,
+                    n_chunks=n_chunks, layers_per_chunk=cfg.n_layers // n_chunks)
     model = {"stage_bubble_frac": tm.bubble[cfg.stage_index], "makespan_ms": tm.makespan_global,
-             "assumption": "p identical stages with this stage's measured mean T_F/T_B/T_W, T_comm = 0"}
+             "assumption": "p identical stages with this stage's measured mean T_F/T_B/T_W, T_comm = 0",
+             "with_t_comm": {"t_comm_ms": t_comm_ms, "stage_bubble_frac": tc.bubble[cfg.stage_index],
+                             "makespan_ms": tc.makespan_global}}
     return base, model
 
 
@@ -329,7 +336,8 @@ def main():
                    "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim, "ffn": cfg.ffn, "seq": cfg.seq,
                    "micro_batch": cfg.micro_batch, "stage": cfg.stage_index, "p": cfg.n_stages,
                    "m": cfg.n_microbatches, "schedule": cfg.schedule, "schedule_knobs": knobs,
-                   "events": len(events), "memory_table": "recompute n1, n2, a in B" if RECOMPUTE else "store all"},
+                   "events": len(events), "events_sha256": hashlib.sha256(repr(list(map(tuple, events))).encode()).hexdigest()[:16],
+                   "memory_table": "recompute n1, n2, a in B" if RECOMPUTE else "store all"},
         "frac_of_bf16_peak": value / peak_tf,
         "stage_busy_frac": busy_ms / ms_per_step,
         "stage_idle_frac": 1.0 - busy_ms / ms_per_step,
