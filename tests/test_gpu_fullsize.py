@@ -52,6 +52,36 @@ def test_gemm_nt_full_size_sampled(name, M, N, K, epi):
     assert torch.isfinite(C.float()).all()
 
 
+@pytest.mark.parametrize("name,layout,M,N,K", [
+    ("nt_a_3gib", B.GEMM_NT, 98304, 512, 16384),      # byte offsets past 2^31 on the direct path (32-bit buffer offsets)
+    ("nt_a_5gib", B.GEMM_NT, 163840, 512, 16384),     # operand beyond the direct path's 4 GiB reach: register-staged kernel
+    ("tn_a_3gib", B.GEMM_TN, 393216, 256, 4096),      # dY [K, M] of 3 GiB, rows 768 KiB apart
+    ("tn_a_5gib", B.GEMM_TN, 655360, 256, 4096),
+])
+def test_gemm_operands_of_several_gib_sampled(name, layout, M, N, K):
+    """Largest operands the kernels address: sampled output rows (first, last, tile edges, random) against fp64
+    products of the same rows; for TN with a non-zero accumulator to start from."""
+    rng = np.random.default_rng(17)
+    ms = np.unique(np.concatenate([[0, 255, 256, M - 257, M - 256, M - 1], rng.integers(0, M, 26)]))
+    mt = torch.as_tensor(ms, device="cuda")
+    if layout == B.GEMM_NT:
+        A, W = dev_randn((M, K), 21), dev_randn((N, K), 22, 0.02)
+        C = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        ok(B.lib().optstage_op_gemm(BF16, layout, B.EPI_STORE, A.data_ptr(), W.data_ptr(), C.data_ptr(), 0, M, N, K, K, K, N, stream()))
+        torch.cuda.synchronize()
+        ref = host(A[mt]) @ host(W).T
+        assert rel_err(host(C[mt]), ref) < TOL[BF16]
+        assert torch.isfinite(C.float()).all()
+    else:
+        DY, X = dev_randn((K, M), 23, 1e-3), dev_randn((K, N), 24)
+        C = torch.full((M, N), 0.25, dtype=torch.float32, device="cuda")
+        ok(B.lib().optstage_op_gemm(BF16, layout, B.EPI_ACCUM, DY.data_ptr(), X.data_ptr(), C.data_ptr(), 0, M, N, K, M, N, N, stream()))
+        torch.cuda.synchronize()
+        ref = 0.25 + host(DY[:, mt]).T @ host(X)
+        assert rel_err(host(C[mt]), ref) < 1e-4
+        assert torch.isfinite(C).all()
+
+
 @pytest.mark.parametrize("name,M,N,K", [("dW_gu", 22016, 4096, 4096), ("dW_d", 4096, 11008, 4096), ("cfg5_dW_qkv", 15360, 5120, 16384)])
 def test_gemm_tn_full_size_sampled(name, M, N, K):
     DY, X = dev_randn((K, M), 11, 1e-3), dev_randn((K, N), 12)
