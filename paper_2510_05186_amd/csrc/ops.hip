@@ -99,7 +99,7 @@ optstage_status optstage_op_norm_fwd(uint32_t dtype, uint32_t family, const void
                                      const void* beta, void* out, float* stats, uint32_t rows, uint32_t hidden,
                                      float eps, void* stream) {
   REQ(x && gamma && out && stats && (family == OPTSTAGE_LLAMA || beta), "norm_fwd: null operand");
-  REQ(dtype <= 1 && family <= 1 && rows && rows < (1u << 30), "norm_fwd: bad argument");
+  REQ(dtype <= 1 && family <= 1 && rows && hidden && rows < (1u << 30), "norm_fwd: bad argument");
   return wrap(launch_norm_fwd(dtype, family, x, gamma, beta, out, stats, rows, hidden, eps, (hipStream_t)stream), "norm_fwd");
 }
 
@@ -108,19 +108,19 @@ optstage_status optstage_op_norm_bwd(uint32_t dtype, uint32_t family, const void
                                      float* partial, float* dgamma, float* dbeta, uint32_t rows, uint32_t hidden,
                                      void* stream) {
   REQ(dn && x && stats && gamma && dx && partial && dgamma && (family == OPTSTAGE_LLAMA || dbeta), "norm_bwd: null operand");
-  REQ(dtype <= 1 && family <= 1 && rows && rows < (1u << 30), "norm_bwd: bad argument");
+  REQ(dtype <= 1 && family <= 1 && rows && hidden && rows < (1u << 30), "norm_bwd: bad argument");
   return wrap(launch_norm_bwd(dtype, family, dn, x, stats, gamma, dres, dx, partial, dgamma, dbeta, rows, hidden, (hipStream_t)stream), "norm_bwd");
 }
 
 optstage_status optstage_op_act_fwd(uint32_t dtype, uint32_t family, const void* gu, void* a, uint32_t rows,
                                     uint32_t ffn, void* stream) {
-  REQ(gu && a && dtype <= 1 && family <= 1 && rows < (1u << 30) && ffn < (1u << 30), "act_fwd: bad argument");
+  REQ(gu && a && dtype <= 1 && family <= 1 && rows && ffn && rows < (1u << 30) && ffn < (1u << 30), "act_fwd: bad argument");
   return wrap(launch_act_fwd(dtype, family, gu, a, rows, ffn, (hipStream_t)stream), "act_fwd");
 }
 
 optstage_status optstage_op_act_bwd(uint32_t dtype, uint32_t family, const void* da, const void* gu, void* dgu,
                                     uint32_t rows, uint32_t ffn, void* stream) {
-  REQ(da && gu && dgu && dtype <= 1 && family <= 1 && rows < (1u << 30) && ffn < (1u << 30), "act_bwd: bad argument");
+  REQ(da && gu && dgu && dtype <= 1 && family <= 1 && rows && ffn && rows < (1u << 30) && ffn < (1u << 30), "act_bwd: bad argument");
   return wrap(launch_act_bwd(dtype, family, da, gu, dgu, rows, ffn, (hipStream_t)stream), "act_bwd");
 }
 

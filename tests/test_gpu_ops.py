@@ -325,3 +325,25 @@ def test_checksum_matches_host_arithmetic():
         s = int(np.sum(a, dtype=np.uint64)) if n else 0
         x = int(np.bitwise_xor.reduce(a)) if n else 0
         assert int(got[0]) == s and int(got[1]) == x
+
+
+def test_empty_inputs_are_refused_not_launched():
+    """A zero extent anywhere is an argument error of the call (nothing is launched, nothing is written)."""
+    L_ = lib()
+    a = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    f = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    p, q = a.data_ptr(), f.data_ptr()
+    for M, N, K in ((0, 64, 64), (64, 0, 64), (64, 64, 0)):
+        assert L_.optstage_op_gemm(BF16, B.GEMM_NT, B.EPI_STORE, p, p, p, 0, M, N, K, 64, 64, 64, stream()) == B.E_ARG
+        assert L_.optstage_op_gemm(BF16, B.GEMM_TN, B.EPI_ACCUM, p, p, q, 0, M, N, K, 64, 64, 64, stream()) == B.E_ARG
+    assert L_.optstage_op_norm_fwd(BF16, O.LLAMA, p, p, 0, p, q, 0, 64, 1e-5, stream()) == B.E_ARG
+    assert L_.optstage_op_norm_fwd(BF16, O.LLAMA, p, p, 0, p, q, 8, 0, 1e-5, stream()) == B.E_ARG
+    assert L_.optstage_op_norm_bwd(BF16, O.LLAMA, p, p, q, p, 0, p, q, q, 0, 0, 64, stream()) == B.E_ARG
+    assert L_.optstage_op_act_fwd(BF16, O.LLAMA, p, p, 0, 64, stream()) == B.E_ARG
+    assert L_.optstage_op_act_bwd(BF16, O.LLAMA, p, p, p, 8, 0, stream()) == B.E_ARG
+    assert L_.optstage_op_rope(BF16, p, p, q, 0, 8, 2, 2, 128, 0, stream()) == B.E_ARG
+    assert L_.optstage_op_attn_fwd(BF16, p, p, q, 0, 1, 2, 2, 128, stream()) == B.E_ARG
+    assert L_.optstage_op_attn_bwd(BF16, p, p, p, q, q, q, 0, 1, 2, 2, 128, stream()) == B.E_ARG
+    assert L_.optstage_op_weight_slabs(p, q, 0, 64, 0, stream()) == B.E_ARG
+    torch.cuda.synchronize()
+    assert float(a.float().abs().sum()) == 0.0 and float(f.abs().sum()) == 0.0
