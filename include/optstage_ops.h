@@ -7,7 +7,8 @@
  * All tensor pointers are DEVICE memory, caller-owned, 16-byte aligned, row-major with tokens as rows.
  * dtype is optstage_dtype (storage type; arithmetic is fp32 / bf16 MFMA with fp32 accumulation).
  * stream is a hipStream_t.  Calls only enqueue; errors are reported as optstage_status with a message
- * in optstage_last_error().  Shapes the kernels cannot handle are rejected on the host (OPTSTAGE_E_ARG).
+ * in optstage_last_error().  Shapes the kernels cannot handle are rejected on the host (OPTSTAGE_E_ARG), and so
+ * is a null pointer or an extent of zero: a refused call launches nothing and writes nothing.
  */
 #ifndef OPTSTAGE_OPS_H
 #define OPTSTAGE_OPS_H
