@@ -971,12 +971,8 @@ bool attn_mfma_applies(int dtype, int d, int seq, int n_q, int n_kv) {
 }
 
 hipError_t launch_attn_fwd_mfma(const void* qkv, void* o, float* lse, int seq, int batch, int n_q, int n_kv, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, FWD_SMEM);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce lds_attr;
+  if (hipError_t e = lds_attr.ensure(reinterpret_cast<const void*>(attn_fwd_mfma), FWD_SMEM); e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_fwd_mfma, dim3(n_q, batch, (seq + 255) / 256), dim3(256), FWD_SMEM, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, n_q, n_kv);
   return hipGetLastError();
 }
@@ -984,21 +980,12 @@ hipError_t launch_attn_fwd_mfma(const void* qkv, void* o, float* lse, int seq, i
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv, float* ws,
                                 int seq, int batch, int n_q, int n_kv, hipStream_t s) {
   hipError_t e;
-  static bool dq_attr_set = false;
-  if (!dq_attr_set) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, DQ_SMEM);
-    if (e != hipSuccess) return e;
-    dq_attr_set = true;
-  }
+  static LdsAttrOnce dq_attr, dkv_attr;
+  if ((e = dq_attr.ensure(reinterpret_cast<const void*>(attn_bwd_dq_mfma), DQ_SMEM)) != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 255) / 256), dim3(256), DQ_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  static bool attr_set = false;
-  if (!attr_set) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma), hipFuncAttributeMaxDynamicSharedMemorySize, DKV_SMEM);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if ((e = dkv_attr.ensure(reinterpret_cast<const void*>(attn_bwd_dkv_mfma), DKV_SMEM)) != hipSuccess) return e;
   const int split = attn_dkv_split(seq, batch, n_q, n_kv);
   float* partial = ws + (size_t)batch * n_q * seq;            // behind the D array
   hipLaunchKernelGGL(attn_bwd_dkv_mfma, dim3(n_kv * split, batch, (seq + 255) / 256), dim3(256), DKV_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, partial, split, seq, n_q, n_kv);

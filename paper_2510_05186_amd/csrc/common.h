@@ -2,6 +2,23 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
+
+// Raises a kernel's dynamic LDS limit, once per device (the attribute belongs to the function on one device; a
+// process that drives several GPUs needs it on each).  One slot of flags per kernel at the call site.
+struct LdsAttrOnce {
+  std::atomic<unsigned long long> done{0};        // bit d: set on device d (devices past 63 set it on every launch)
+  hipError_t ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = dev < 64 ? 1ull << dev : 0ull;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+  }
+};
 
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));

@@ -746,12 +746,8 @@ hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, i
                          int ldc, hipStream_t s, bool b_slab = false) {
   auto kern = gemm_bf16_direct_kernel<TNL, EPI>;
   constexpr int smem = 163840;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce lds_attr;
+  if (hipError_t e = lds_attr.ensure(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
   // byte extent of each operand: whatever lies past it reads as zero
   const unsigned a_bytes = (unsigned)(TNL ? ((size_t)(K - 1) * lda + M) * 2 : ((size_t)(M - 1) * lda + K) * 2);
@@ -774,12 +770,8 @@ template <bool TNL, int EPI>
 hipError_t launch_direct_grouped(int n, const GemmProblem* pr, int K, hipStream_t s) {
   auto kern = gemm_bf16_direct_grouped_kernel<TNL, EPI>;
   constexpr int smem = 163840;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce lds_attr;
+  if (hipError_t e = lds_attr.ensure(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   GroupedArgs g;
   g.n = n;
   g.K = K;
@@ -805,12 +797,8 @@ hipError_t launch_cfg(const void* A, const void* B, void* C, const void* R, int 
                       int ldc, hipStream_t s) {
   auto kern = gemm_bf16_kernel<BM, BN, WM, WN, A_RC, B_RC, EPI>;
   constexpr int smem = 2 * (BM + BN) * ROW_BYTES;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce lds_attr;
+  if (hipError_t e = lds_attr.ensure(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WM * WN), smem, s, (const bf16_t*)A, (const bf16_t*)B, C,
                      (const bf16_t*)R, M, N, K, lda, ldb, ldc, tiles_m, tiles_n);
