@@ -537,7 +537,9 @@ class OnlineSearch:
         self._stop = threading.Event()
         self._best = None                     # (score, Solution)
         self.history = []                     # (seconds since start, score, status) of every publication
-        self.complete = False                 # True once a solve proved that nothing better exists
+        self.complete = False                 # True once a solve proved that nothing better exists (with best()
+                                              # still None: that no schedule exists under the limits)
+        self.error = None                     # exception that ended the search thread, if any
         self._thread = threading.Thread(target=self._run, name="optstage-online-search", daemon=True)
 
     def start(self):
@@ -568,12 +570,22 @@ class OnlineSearch:
         return False
 
     def _run(self):
+        try:
+            self._search()
+        except Exception as e:                         # the thread must not die silently: the loop reads `error`
+            self.error = e
+
+    def _search(self):
         import time
         t0 = time.monotonic()
-        self._publish(adaoffload(self.inst, tolerance=self.tolerance), t0)
+        try:
+            self._publish(adaoffload(self.inst, tolerance=self.tolerance), t0)
+        except RuntimeError:                           # the heuristic found no list (limit too tight for it):
+            pass                                       # the solver starts without a bound
         slice_s = self.slice_seconds
         while not self._stop.is_set() and time.monotonic() - t0 < self.max_seconds:
-            bound = self.best()[1].makespan - self.min_gain
+            have = self.best()
+            bound = have[1].makespan - self.min_gain if have else None
             sol = milp_schedule(self.inst, time_limit=slice_s, cutoff=bound, strict_eq13=self.strict_eq13)
             if sol.lists:
                 self._publish(sol, t0)

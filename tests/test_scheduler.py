@@ -274,3 +274,21 @@ def test_list_extraction_orders_transfers_inside_a_gap_for_the_executor():
     assert pos[("O", 1)] < pos[("OWAIT", 1)] < pos[("F", 2)]                 # credited to F2: released before it
     assert pos[("B", 1)] < pos[("R", 2)] < pos[("W", 1)]                     # at W1's start time: just before it
     S.check_order(SC.expand_items(ev, L, ITEM[1]), 3, L)
+
+
+def test_online_search_on_an_instance_without_any_schedule():
+    """A limit below one forward activation, offload or not: the heuristic gives up, the solver proves that nothing
+    exists, the search ends complete with nothing published and no error."""
+    inst = SC.Instance(p=2, m=2, t_op=[{"F": 1, "B": 1, "W": 1}] * 2, t_off=[0.5, 0.5], delta=[DELTA, DELTA],
+                       gamma=[GAMMA, GAMMA], limit=[DELTA["F"] // 2] * 2, offload_stages=(0, 1), item=ITEM)
+    with pytest.raises(RuntimeError):
+        SC.adaoffload(inst)
+    assert SC.milp_schedule(inst, time_limit=20).lists == []
+    s = SC.OnlineSearch(inst, slice_seconds=5, max_seconds=20).start()
+    s.join(60)
+    assert s.complete and s.best() is None and s.error is None and s.history == []
+    # degenerate sizes: one stage, one micro-batch
+    for p, m, want in ((1, 1, 3.0), (1, 3, 9.0), (3, 1, 7.0)):
+        one = SC.Instance(p=p, m=m, t_op=[{"F": 1, "B": 1, "W": 1}] * p, t_off=[0.5] * p, delta=[DELTA] * p, gamma=[GAMMA] * p,
+                          limit=[None] * p, item=ITEM)
+        assert abs(SC.adaoffload(one).makespan - want) < 1e-6 and abs(SC.milp_schedule(one, time_limit=20).makespan - want) < 1e-4
