@@ -380,32 +380,47 @@ __global__ void rope_table_kernel(float2* __restrict__ table, int seq, int half,
 
 // rotates the q and k heads of packed qkv rows, pairing element k with k + d/2; sign = -1 applies the
 // transposed rotation (gradients).  When dst != src the v part is copied as well.
-template <typename T>
+template <typename T, int HG>
 __global__ void rope_kernel(const T* src, T* dst, const float2* __restrict__ table, int rows, int seq, int n_rot,
                             int n_v, int d, float sign, int do_rotate) {
   typedef Vec16<T> V;
   const int half = d / 2, vph = half / V::N;        // vectors per half head
   const int ld = (n_rot + n_v) * d;
-  const size_t rot_items = (size_t)rows * n_rot * vph;
+  const int groups = n_rot / HG;                    // HG heads share the cos / sin values a thread has fetched
+  const size_t rot_items = (size_t)rows * groups * vph;
   const size_t cp_items = (src != dst) ? (size_t)rows * n_v * (d / V::N) : 0;
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < rot_items + cp_items; i += (size_t)gridDim.x * blockDim.x) {
     if (i < rot_items) {
       int c = i % vph;
       size_t t = i / vph;
-      int head = t % n_rot, row = t / n_rot;
+      int grp = t % groups, row = t / groups;
       int pos = row % seq;
-      size_t off = (size_t)row * ld + head * d + c * V::N;
-      V lo = *reinterpret_cast<const V*>(src + off), hi = *reinterpret_cast<const V*>(src + off + half), olo, ohi;
+      float cs[V::N], sn[V::N];
 #pragma unroll
       for (int e = 0; e < V::N; ++e) {
-        float cs = 1.f, sn = 0.f;
-        if (do_rotate) { float2 cssn = table[(size_t)pos * half + c * V::N + e]; cs = cssn.x; sn = sign * cssn.y; }
-        float a = lo.get(e), b = hi.get(e);
-        olo.set(e, a * cs - b * sn);
-        ohi.set(e, b * cs + a * sn);
+        cs[e] = 1.f; sn[e] = 0.f;
+        if (do_rotate) { float2 cssn = table[(size_t)pos * half + c * V::N + e]; cs[e] = cssn.x; sn[e] = sign * cssn.y; }
       }
-      *reinterpret_cast<V*>(dst + off) = olo;
-      *reinterpret_cast<V*>(dst + off + half) = ohi;
+      V lo[HG], hi[HG];
+#pragma unroll
+      for (int g = 0; g < HG; ++g) {
+        const size_t off = (size_t)row * ld + (size_t)(grp * HG + g) * d + c * V::N;
+        lo[g] = *reinterpret_cast<const V*>(src + off);
+        hi[g] = *reinterpret_cast<const V*>(src + off + half);
+      }
+#pragma unroll
+      for (int g = 0; g < HG; ++g) {
+        const size_t off = (size_t)row * ld + (size_t)(grp * HG + g) * d + c * V::N;
+        V olo, ohi;
+#pragma unroll
+        for (int e = 0; e < V::N; ++e) {
+          float a = lo[g].get(e), b = hi[g].get(e);
+          olo.set(e, a * cs[e] - b * sn[e]);
+          ohi.set(e, b * cs[e] + a * sn[e]);
+        }
+        *reinterpret_cast<V*>(dst + off) = olo;
+        *reinterpret_cast<V*>(dst + off + half) = ohi;
+      }
     } else {
       size_t k = i - rot_items;
       int per_row = n_v * (d / V::N);
@@ -579,11 +594,15 @@ hipError_t launch_rope(int dtype, const void* src, void* dst, const float* table
   const int vn = dtype == DT_BF16 ? 8 : 4;
   if ((d / 2) % vn) return hipErrorInvalidValue;
   const int n_rot = n_q + n_kv;
-  size_t items = (size_t)rows * n_rot * (d / 2 / vn) + (src != dst ? (size_t)rows * n_kv * (d / vn) : 0);
+  const int hg = n_rot % 8 == 0 ? 8 : n_rot % 4 == 0 ? 4 : 1;            // heads per thread
+  size_t items = (size_t)rows * (n_rot / hg) * (d / 2 / vn) + (src != dst ? (size_t)rows * n_kv * (d / vn) : 0);
   int g = grid_for(items, 256);
   float sign = backward ? -1.f : 1.f;
-  if (dtype == DT_BF16) hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(g), dim3(256), 0, s, (const bf16_t*)src, (bf16_t*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate);
-  else hipLaunchKernelGGL(rope_kernel<float>, dim3(g), dim3(256), 0, s, (const float*)src, (float*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate);
+#define OPTSTAGE_ROPE(T, HG) \
+  hipLaunchKernelGGL((rope_kernel<T, HG>), dim3(g), dim3(256), 0, s, (const T*)src, (T*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate)
+  if (dtype == DT_BF16) { if (hg == 8) OPTSTAGE_ROPE(bf16_t, 8); else if (hg == 4) OPTSTAGE_ROPE(bf16_t, 4); else OPTSTAGE_ROPE(bf16_t, 1); }
+  else { if (hg == 8) OPTSTAGE_ROPE(float, 8); else if (hg == 4) OPTSTAGE_ROPE(float, 4); else OPTSTAGE_ROPE(float, 1); }
+#undef OPTSTAGE_ROPE
   return hipGetLastError();
 }
 

@@ -223,7 +223,8 @@ def test_activation_fwd_bwd(dtype, family, rows, f):
 
 
 # ------------------------------------------------------------------ rotary
-@pytest.mark.parametrize("dtype,seq,batch,nq,nkv,d", [(BF16, 300, 1, 4, 2, 128), (FP32, 70, 2, 3, 3, 64), (BF16, 4096, 1, 2, 1, 128)])
+@pytest.mark.parametrize("dtype,seq,batch,nq,nkv,d", [(BF16, 300, 1, 4, 2, 128), (FP32, 70, 2, 3, 3, 64), (BF16, 4096, 1, 2, 1, 128),
+                                                       (BF16, 333, 2, 6, 2, 128), (FP32, 70, 1, 2, 2, 64)])   # q + k heads a multiple of 4
 def test_rotary(dtype, seq, batch, nq, nkv, d):
     base = 10000.0
     rows = seq * batch
