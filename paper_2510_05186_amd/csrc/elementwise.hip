@@ -93,9 +93,10 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, 
 #pragma unroll
     for (int e = 0; e < V::N; ++e) { pg[c][e] = 0.f; pb[c][e] = 0.f; }
   }
-  // two register sets: the loads of the next row are in flight while the current one is reduced and written
-  V xv[2][MAXC], dv[2][MAXC], rv[2][MAXC];
-  float mean_[2], r_[2];
+  // three register sets: the loads of the next two rows are in flight while the current one is reduced and
+  // written (with one workgroup per compute unit the bytes in flight, not the arithmetic, set the pace)
+  V xv[3][MAXC], dv[3][MAXC], rv[3][MAXC];
+  float mean_[3], r_[3];
   auto load_row = [&](int buf, int row) {
     if (LN) { mean_[buf] = stats[2 * row]; r_[buf] = stats[2 * row + 1]; } else { mean_[buf] = 0.f; r_[buf] = stats[row]; }
 #pragma unroll
@@ -158,13 +159,18 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const T* __restrict__ dn, 
   const int gd = gridDim.x;
   int row = blockIdx.x;
   if (row < rows) load_row(0, row);
-  for (; row < rows; row += 2 * gd) {
-    const int r1 = row + gd, r2 = row + 2 * gd;
-    if (r1 < rows) load_row(1, r1);
+  if (row + gd < rows) load_row(1, row + gd);
+  for (; row < rows; row += 3 * gd) {
+    const int r1 = row + gd, r2 = row + 2 * gd, r3 = row + 3 * gd, r4 = row + 4 * gd;
+    if (r2 < rows) load_row(2, r2);
     process(0, row);
     if (r1 < rows) {
-      if (r2 < rows) load_row(0, r2);
+      if (r3 < rows) load_row(0, r3);
       process(1, r1);
+    }
+    if (r2 < rows) {
+      if (r4 < rows) load_row(1, r4);
+      process(2, r2);
     }
   }
   float* pgo = partial + (size_t)blockIdx.x * h;
