@@ -108,7 +108,7 @@ template <int R_T, int NTH, bool RC> struct StageSel { typedef StageKC<R_T, NTH>
 template <int R_T, int NTH> struct StageSel<R_T, NTH, true> { typedef StageRC<R_T, NTH> type; };
 
 // Epilogue through LDS for 256 x 256 workgroup tiles: each wave transposes its accumulator tile (32 TM rows
-// x 128 columns), 32 or 64 rows at a time, through a private slice of the first 128 KB of
+// x 128 columns), 32 * 128 KB / (NWAVES * 16 KB) rows at a time, through a private slice of the 128 KB of
 // LDS (16-byte chunks XOR-swizzled by the row, conflict free both ways), so that global memory sees whole
 // 512-byte row segments instead of 16-byte pieces of 32 different rows.  The caller has made sure that no
 // wave still reads operand tiles.
@@ -116,39 +116,36 @@ template <int EPI, int TM, int TN, int NWAVES>
 __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* smem, int wave, int lane, void* Cv,
                                                  const bf16_t* R, int M, int N, int ldc, int mw, int nw) {
   static_assert(TN == 4, "a wave tile is 128 columns wide");
-  // accumulate / residual: the old values of a pass are requested one pass ahead, so that their latency runs under
-  // the transposition and the stores of the pass before (only where the register budget allows it: the 4-wave
-  // kernels, which then take one MFMA tile row per pass and keep two passes' old values in registers)
-  constexpr bool PRE = NWAVES == 4 && EPI != EPI_STORE;
-  constexpr int SLICE = 131072 / NWAVES, IPP = PRE ? 1 : SLICE / 16384;     // MFMA tile rows (32 matrix rows) per pass
+  constexpr int SLICE = 131072 / NWAVES, IPP = SLICE / 16384;     // MFMA tile rows (32 matrix rows) per pass
   static_assert(IPP >= 1 && TM % IPP == 0, "wave tile must split into whole passes");
   constexpr int NIT = 16 * IPP;                                   // row pairs per pass
-  constexpr int NPASS = TM / IPP;
   char* const wl = smem + wave * SLICE;
   const int khalf = lane >> 5;
   const int c = lane & 31;
   const int n = nw + c * 4;
-  f32x4_t cold[EPI == EPI_ACCUM && PRE ? 2 : 1][EPI == EPI_ACCUM && PRE ? NIT : 1];
-  bf16x4_t rold[EPI == EPI_RESID && PRE ? 2 : 1][EPI == EPI_RESID && PRE ? NIT : 1];
-  auto request = [&](int pass) __attribute__((always_inline)) {
 #pragma unroll
-    for (int p2 = 0; p2 < NIT; ++p2) {
-      const int m = mw + pass * IPP * 32 + 2 * p2 + khalf;
-      const bool ok = m < M && n < N;
-      const size_t off = (size_t)m * ldc + n;
-      if (EPI == EPI_ACCUM) {
-        f32x4_t z = {0.f, 0.f, 0.f, 0.f};
-        cold[PRE ? pass & 1 : 0][PRE ? p2 : 0] = ok ? *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off) : z;
-      } else {
-        bf16x4_t z = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
-        rold[PRE ? pass & 1 : 0][PRE ? p2 : 0] = ok ? *reinterpret_cast<const bf16x4_t*>(R + off) : z;
+  for (int pass = 0; pass < TM / IPP; ++pass) {
+    // accumulate / residual: request this pass's rows of the old values first, so that their latency runs
+    // under the LDS transposition
+    // (only where the register budget allows it: 4-wave kernels)
+    constexpr bool PRE = NWAVES == 4;
+    f32x4_t cold[EPI == EPI_ACCUM && PRE ? NIT : 1];
+    bf16x4_t rold[EPI == EPI_RESID && PRE ? NIT : 1];
+    if (EPI != EPI_STORE && PRE) {
+#pragma unroll
+      for (int p2 = 0; p2 < NIT; ++p2) {
+        const int m = mw + pass * IPP * 32 + 2 * p2 + khalf;
+        const bool ok = m < M && n < N;
+        const size_t off = (size_t)m * ldc + n;
+        if (EPI == EPI_ACCUM) {
+          f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+          cold[p2] = ok ? *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off) : z;
+        } else {
+          bf16x4_t z = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+          rold[p2] = ok ? *reinterpret_cast<const bf16x4_t*>(R + off) : z;
+        }
       }
     }
-  };
-  if (PRE) request(0);
-#pragma unroll
-  for (int pass = 0; pass < NPASS; ++pass) {
-    if (PRE && pass + 1 < NPASS) request(pass + 1);
 #pragma unroll
     for (int i2 = 0; i2 < IPP; ++i2) {
       const int row = i2 * 32 + (lane & 31);
@@ -171,12 +168,12 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* 
       if (m < M && n < N) {
         const size_t off = (size_t)m * ldc + n;
         if (EPI == EPI_ACCUM) {
-          const f32x4_t o = PRE ? cold[PRE ? pass & 1 : 0][PRE ? p2 : 0] : *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off);
+          const f32x4_t o = PRE ? cold[PRE ? p2 : 0] : *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off);
           v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
           *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off) = v;
         } else {
           if (EPI == EPI_RESID) {
-            const bf16x4_t r = PRE ? rold[PRE ? pass & 1 : 0][PRE ? p2 : 0] : *reinterpret_cast<const bf16x4_t*>(R + off);
+            const bf16x4_t r = PRE ? rold[PRE ? p2 : 0] : *reinterpret_cast<const bf16x4_t*>(R + off);
             v[0] += (float)r[0]; v[1] += (float)r[1]; v[2] += (float)r[2]; v[3] += (float)r[3];
           }
           bf16x4_t o;
