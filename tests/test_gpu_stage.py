@@ -309,6 +309,54 @@ def test_training_loop_takes_the_online_search_lists_as_they_improve():
     ref.close()
 
 
+def test_chunks_recompute_and_offload_together():
+    """Two model chunks, the recompute memory table and offload under one budget in one run: the accounting is the
+    oracle's for that combination (byte for byte, per event), and every output and gradient is bitwise what the
+    plain stage (one chunk of all layers, store-all, no offload) produces for the same micro-batches."""
+    v, m = 2, 4
+    cfg = replace(SMALL2, name="cfg2_small_chunks_recompute", n_layers=4, n_microbatches=m, n_stages=2, stage_index=0)
+    Lc = cfg.n_layers // v
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    base = G.interleaved_one_f_one_b(cfg.n_stages, m, cfg.stage_index, v)
+    events = G.add_offload(base, cfg.n_layers, ("X_IN", "QKV", "X_MID"), min_gap=3, lead=1)
+    assert any(e[0] == "O" for e in events)
+    S.check_order(events, m, cfg.n_layers, recompute=True, n_chunks=v)
+    peak, trace = S.account_memory(events, cfg.n_layers, t, recompute=True, n_chunks=v)
+    assert peak < S.account_memory(events, cfg.n_layers, t, n_chunks=v)[0]          # smaller than with store-all
+    with pytest.raises(S.ScheduleError):                                              # N1 is not kept: cannot be offloaded
+        S.check_order([("F", 0, 0), ("O", 0, 0, ("N1",))], m, cfg.n_layers, recompute=True, n_chunks=v)
+    io = {(c, j): (T.stage_input(cfg, c * m + j), T.output_grad(cfg, c * m + j)) for c in range(v) for j in range(m)}
+    pool = sum(t[k] for k in ("X_IN", "QKV", "X_MID")) * cfg.n_layers * m
+    st = Stage(cfg, budget=peak, host_pool_bytes=pool, arena_bytes=2 * peak, recompute=True, n_chunks=v)
+    st.set_weights(ws)
+    for (c, j), (x, dy) in io.items():
+        st.bind(j, x, dy, chunk=c)
+    code, bad, ppeak, live = B.plan(cfg, events, budget=peak, recompute=1, n_chunks=v)
+    assert code == B.OK and ppeak == peak and list(live[:len(events)]) == trace
+    st.run(events)
+    st.synchronize()
+    sst = st.stats()
+    assert sst.peak_bytes == peak and sst.live_bytes == 0 and sst.bytes_offloaded == sst.bytes_reloaded > 0
+    # chunk c of the chunked stage = layers c Lc .. of the model; the plain stage run chunk by chunk, store-all
+    for c in range(v):
+        sub = replace(cfg, name=f"plain_chunk{c}", n_layers=Lc)
+        one = Stage(sub)
+        one.set_weights(ws[c * Lc:(c + 1) * Lc])
+        for j in range(m):
+            one.bind(j, *io[(c, j)])
+        one.run([e for j in range(m) for e in (("F", j), ("B", j), ("W", j))])
+        one.synchronize()
+        key = lambda j: j if c == 0 else (c, j)
+        for j in range(m):
+            assert torch.equal(st.y[key(j)], one.y[j]) and torch.equal(st.dx[key(j)], one.dx[j]), (c, j)
+        for l in range(Lc):
+            for name in one.grads[l]:
+                assert torch.equal(st.grads[c * Lc + l][name], one.grads[l][name]), (c, l, name)
+        one.close()
+    st.close()
+
+
 def test_duplex_reload_stream_changes_no_bit():
     """Reloads on a stream of their own (full-duplex host link) instead of the single transfer channel of the
     paper's model (Eq. 8-11): same bytes, same accounting, bitwise the same results."""
