@@ -268,3 +268,26 @@ def repair_to_fit(events: list, fits, max_rounds: int = 2000) -> list | None:
         if not moved:
             return None
     return None
+
+
+def random_valid_list(rng, m, n_layers, kinds, p_offload=0.6):
+    """A random member of the schedule grammar: compute ops in a random order that keeps F j before B j before W j
+    and every op type in increasing micro-batch order; a random subset of (micro-batch, layer, kind set) items
+    offloaded, each with O somewhere after its F, OWAIT after the O, R after the OWAIT, all before its B."""
+    nxt = {"F": 0, "B": 0, "W": 0}
+    comp = []
+    while len(comp) < 3 * m:
+        can = [c for c in "FBW" if nxt[c] < m and (c == "F" or nxt[c] < nxt["FB"[("BW".index(c))]])]
+        c = can[int(rng.integers(len(can)))]
+        comp.append((c, nxt[c]))
+        nxt[c] += 1
+    ev = list(comp)
+    for j in range(m):
+        for l in range(n_layers):
+            if rng.random() < p_offload:
+                ks = tuple(k for k in kinds if rng.random() < 0.7) or (kinds[0],)
+                f, b = ev.index(("F", j)), ev.index(("B", j))
+                pos = sorted(int(x) for x in rng.integers(f + 1, b + 1, 3))       # insertion points, in list order
+                for off, name in zip(pos, ("O", "OWAIT", "R")):
+                    ev.insert(off + ("O", "OWAIT", "R").index(name), (name, j, l, ks))
+    return ev

@@ -1,6 +1,7 @@
 """CPU-only checks of the boundary: the library loads, exports every symbol the headers declare, and its
 pure-host planner (ordering rules + list-order memory accounting) agrees bit for bit with the oracle."""
 import ctypes
+from dataclasses import replace
 import os
 import random
 import re
@@ -199,3 +200,23 @@ def test_plan_random_valid_interleavings():
         peak, trace = S.account_memory(ev, L, t)
         st, _, lib_peak, live = B.plan(cfg, ev)
         assert st == B.OK and lib_peak == peak and live == trace
+
+
+@pytest.mark.parametrize("recompute", [False, True])
+def test_planner_equals_oracle_accounting_on_random_valid_lists(recompute):
+    """Property over the schedule grammar, host only: for random valid lists (compute order, offloaded items and
+    transfer positions all drawn) the library's planner reports the oracle's live bytes after every event and the
+    oracle's peak, accepts a budget equal to that peak and refuses one allocation granule less."""
+    import numpy as np
+    from stage_inputs import schedules as G
+    cfg = replace(CFG.shrunken(CFG.CFG2, hidden=256, n_q=2, n_kv=2, ffn=512, seq=256, n_layers=3, n_microbatches=5), name="plan_random")
+    t = S.memory_table(cfg.family, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.ffn, cfg.seq * cfg.micro_batch, cfg.elem_size)
+    kinds = ("X_IN", "QKV", "X_MID", "O", "GU", "LSE") if recompute else ("X_IN", "N1", "QKV", "X_MID", "O", "GU", "A", "STATS")
+    for seed in range(40):
+        rng = np.random.default_rng(seed)
+        ev = G.random_valid_list(rng, cfg.n_microbatches, cfg.n_layers, kinds, p_offload=0.5)
+        S.check_order(ev, cfg.n_microbatches, cfg.n_layers, recompute=recompute)
+        peak, trace = S.account_memory(ev, cfg.n_layers, t, recompute=recompute)
+        code, bad, ppeak, live = B.plan(cfg, ev, budget=peak, recompute=int(recompute))
+        assert code == B.OK and ppeak == peak and list(live[:len(ev)]) == trace, (seed, code, bad)
+        assert B.plan(cfg, ev, budget=peak - S.ALIGN, recompute=int(recompute))[0] == B.E_BUDGET, seed
