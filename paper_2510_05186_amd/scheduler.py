@@ -511,6 +511,315 @@ def expand_items(events, n_layers, kinds):
     return out
 
 
+# ------------------------------------------------------------------- timing of given lists (Eq. 3-6, 8-14)
+
+@dataclass
+class Timeline:
+    start: list                  # per stage, aligned with the list (None for OWAIT)
+    end: list
+    makespan: float              # Eq. 17: last end - first start over all stages' compute ops
+    busy: list                   # per stage: summed compute time
+    bubble: list                 # per stage: 1 - busy / makespan
+    stall: list                  # per stage: time compute ops spent waiting for an offload (Eq. 12) or a reload
+
+
+def pipeline_timeline(lists, t_op, t_comm=0.0, t_copy=None, duplex=False) -> Timeline:
+    """Earliest start times of every event of p per-stage lists (one model chunk per stage), as the executor and
+    the paper's constraints order them: compute ops of a stage one after the other in list order (Eq. 5), F of
+    stage i after F of stage i - 1 plus T_comm (Eq. 3), B after B of stage i + 1 plus T_comm (Eq. 4), transfers of
+    a stage one at a time in list order (Eq. 8-11; per direction when `duplex`), an offload after its F, a compute
+    op listed after OWAIT(x) after offload x ended (Eq. 12), a reload after the compute ops listed before it
+    (Eq. 14) and after its item's offload, B j after every reload of micro-batch j.
+    t_op[i] = {"F", "B", "W"} durations; t_copy(i, event) = duration of that O or R event.
+    Built as a longest-path pass over the precedence graph (a cycle = lists that deadlock each other)."""
+    p = len(lists)
+    t_copy = t_copy or (lambda i, ev: 0.0)
+    node = {}                                   # (stage, index) -> id
+    dur, preds = [], []
+
+    def add(i, n, d):
+        node[(i, n)] = len(dur)
+        dur.append(d)
+        preds.append([])
+        return len(dur) - 1
+
+    where_f = [dict() for _ in range(p)]        # j -> node of F j on stage i
+    where_b = [dict() for _ in range(p)]
+    for i, ev in enumerate(lists):
+        for n, e in enumerate(ev):
+            if e[0] in OPS:
+                v = add(i, n, t_op[i][e[0]])
+                if e[0] == "F":
+                    where_f[i][e[1]] = v
+                elif e[0] == "B":
+                    where_b[i][e[1]] = v
+            elif e[0] in ("O", "R"):
+                add(i, n, t_copy(i, e))
+    lag = {}                                    # (pred, succ) -> extra delay on that edge
+    for i, ev in enumerate(lists):
+        last_compute = None
+        last_copy = [None, None]                # last transfer per channel (offload, reload)
+        gate = []                               # offloads whose OWAIT has been passed
+        off_node, rel_nodes = {}, {}
+        for n, e in enumerate(ev):
+            if e[0] in OPS:
+                v = node[(i, n)]
+                if last_compute is not None:
+                    preds[v].append(last_compute)
+                preds[v].extend(gate)
+                j = e[1]
+                if e[0] == "F" and i > 0:
+                    u = where_f[i - 1].get(j)
+                    if u is None:
+                        raise ValueError(f"stage {i - 1} never runs F {j}")
+                    preds[v].append(u)
+                    lag[(u, v)] = t_comm
+                if e[0] == "B":
+                    if i < p - 1:
+                        u = where_b[i + 1].get(j)
+                        if u is None:
+                            raise ValueError(f"stage {i + 1} never runs B {j}")
+                        preds[v].append(u)
+                        lag[(u, v)] = t_comm
+                    preds[v].extend(rel_nodes.get(j, []))
+                last_compute = v
+            elif e[0] == "O":
+                v = node[(i, n)]
+                preds[v].append(where_f[i][e[1]])
+                if last_copy[0] is not None:
+                    preds[v].append(last_copy[0])
+                last_copy[0] = v
+                for k in e[3]:
+                    off_node[(e[1], e[2], k)] = v
+            elif e[0] == "OWAIT":
+                gate = gate + [off_node[(e[1], e[2], k)] for k in e[3]]
+            elif e[0] == "R":
+                v = node[(i, n)]
+                ch = 1 if duplex else 0
+                if last_copy[ch] is not None:
+                    preds[v].append(last_copy[ch])
+                if last_compute is not None:
+                    preds[v].append(last_compute)
+                preds[v].extend(off_node[(e[1], e[2], k)] for k in e[3])
+                last_copy[ch] = v
+                rel_nodes.setdefault(e[1], []).append(v)
+    n_nodes = len(dur)
+    succs = [[] for _ in range(n_nodes)]
+    indeg = [0] * n_nodes
+    for v in range(n_nodes):
+        preds[v] = list(dict.fromkeys(preds[v]))
+        indeg[v] = len(preds[v])
+        for u in preds[v]:
+            succs[u].append(v)
+    t_start = [0.0] * n_nodes
+    ready = [v for v in range(n_nodes) if indeg[v] == 0]
+    seen = 0
+    while ready:
+        u = ready.pop()
+        seen += 1
+        end_u = t_start[u] + dur[u]
+        for v in succs[u]:
+            t = end_u + lag.get((u, v), 0.0)
+            if t > t_start[v]:
+                t_start[v] = t
+            indeg[v] -= 1
+            if indeg[v] == 0:
+                ready.append(v)
+    if seen != n_nodes:
+        raise ValueError("the lists deadlock each other")
+    start = [[None] * len(ev) for ev in lists]
+    end = [[None] * len(ev) for ev in lists]
+    first, last = float("inf"), 0.0
+    busy, stall = [0.0] * p, [0.0] * p
+    is_compute = [False] * n_nodes
+    for i, ev in enumerate(lists):
+        for n, e in enumerate(ev):
+            if e[0] in OPS:
+                is_compute[node[(i, n)]] = True
+    for i, ev in enumerate(lists):
+        for n, e in enumerate(ev):
+            if e[0] == "OWAIT":
+                continue
+            v = node[(i, n)]
+            start[i][n], end[i][n] = t_start[v], t_start[v] + dur[v]
+            if e[0] in OPS:
+                first, last = min(first, start[i][n]), max(last, end[i][n])
+                busy[i] += dur[v]
+                # waiting that only a transfer explains: the op could have started once its compute predecessors
+                # (the op before it on this stage, the neighbour's op) were done
+                free = max([t_start[u] + dur[u] + lag.get((u, v), 0.0) for u in preds[v] if is_compute[u]] + [0.0])
+                stall[i] += max(0.0, t_start[v] - free)
+    makespan = last - first if last > first else 0.0
+    return Timeline(start=start, end=end, makespan=makespan, busy=busy,
+                    bubble=[1.0 - b / makespan if makespan > 0 else 0.0 for b in busy], stall=stall)
+
+
+# --------------------------------------------------- lists under a byte budget with per-item offload (Sec. 3, Eq. 7)
+
+def fit_offloads(comp, n_layers, kinds, kind_bytes, fits, lead=1):
+    """Adds to a compute order the fewest offloads that make it fit: the decision variable of Sec. 3 is per
+    item, and Eq. 7 only asks that the bytes in use stay within the limit.
+
+    `fits(events) -> (ok, index of the first failing event)` is the consumer's planner (ordering rules and
+    list-order accounting against the budget); no accounting happens here.  While the list fails at an
+    allocating event, one more item (micro-batch, layer, kind) that is on the device at that point and not
+    needed there is offloaded: the micro-batch whose B is furthest away first, within it the layer B reaches
+    last, the smallest kind first.  Its O follows its F directly (the copy has the longest time to run under
+    compute), its OWAIT sits right before the event that needed the bytes (the credit as late as possible), its R
+    `lead` compute ops ahead of its B.  A reload that itself does not fit where it is listed first makes other
+    items leave, then moves down to right before its B.  Returns None when nothing more can leave."""
+    comp = [e for e in comp if e[0] in OPS]
+    pos_f = {e[1]: n for n, e in enumerate(comp) if e[0] == "F"}
+    pos_b = {e[1]: n for n, e in enumerate(comp) if e[0] == "B"}
+    kinds = sorted(kinds, key=lambda k: (kind_bytes[k], k))
+    chosen = {}                                  # (j, layer, kind) -> [owait slot, reload slot]
+
+    def assemble():
+        slots = {}
+        for (j, l, k), (w, r) in chosen.items():
+            slots.setdefault(("O", pos_f[j] + 1, j, l), []).append(k)
+            slots.setdefault(("OWAIT", w, j, l), []).append(k)
+            slots.setdefault(("R", r, j, l), []).append(k)
+        before = {}
+        for (op, at, j, l), ks in slots.items():
+            before.setdefault(at, []).append((op, j, l, tuple(ks)))
+        out, owner = [], []                      # owner[n] = compute slot of event n
+        for n in range(len(comp) + 1):
+            # at one slot: credits of earlier offloads, then the offloads that start here, then the credits of
+            # those (an offload nothing overlaps), then reloads (the layer B reaches first is reloaded first)
+            def rank(e):
+                if e[0] == "O":
+                    return 1
+                if e[0] == "R":
+                    return 3
+                return 2 if pos_f[e[1]] + 1 == n else 0
+            for e in sorted(before.get(n, []), key=lambda e: (rank(e), e[1], -e[2] if e[0] == "R" else e[2])):
+                out.append(e)
+                owner.append(n)
+            if n < len(comp):
+                out.append(comp[n])
+                owner.append(n)
+        return out, owner
+
+    for _ in range(3 * len(pos_f) * n_layers * max(1, len(kinds)) + 8):
+        ev, owner = assemble()
+        ok, bad = fits(ev)
+        if ok:
+            return ev
+        if bad >= len(ev):
+            return None
+        n = owner[bad]
+        failing = ev[bad]
+        cands = [(j, l, k) for j in pos_f for l in range(n_layers) for k in kinds
+                 if (j, l, k) not in chosen and pos_f[j] < n and max(n, pos_b[j] - lead) > n
+                 and not (failing[0] in OPS and failing[1] == j)]
+        if failing[0] == "R":
+            cands = [c for c in cands if c[0] != failing[1]]
+        if cands:
+            j, l, k = min(cands, key=lambda c: (-pos_b[c[0]], c[1], kind_bytes[c[2]], c[2]))
+            chosen[(j, l, k)] = [n, max(n, pos_b[j] - lead)]
+            continue
+        if failing[0] == "R":
+            moved = False
+            for k in failing[3]:
+                key = (failing[1], failing[2], k)
+                if chosen[key][1] < pos_b[failing[1]]:
+                    chosen[key][1] = pos_b[failing[1]]
+                    moved = True
+            if moved:
+                continue
+        return None
+    return None
+
+
+def budgeted_lists(p, m, n_layers, kinds, kind_bytes, fits, base_lists, t_op, t_copy_of_bytes, duplex=False,
+                   t_comm=0.0, max_extra=None, lead=1):
+    """Per-stage lists for a pipeline in which every device has the same byte budget, chosen by modelled makespan.
+
+    base_lists(cap_of_stage) -> p compute orders (split B/W) in which stage i holds at most cap_of_stage(i)
+    micro-batches between F and W; `fits` as in fit_offloads (all stages have the same shape).  For every fill
+    level e = 0 .. max_extra the caps are p - i + e (a denser fill than p - i in flight shortens the bubble and
+    costs memory); a stage whose list cannot be made to fit even with offloads gets its cap lowered until it can.
+    Every candidate is timed with pipeline_timeline from the given op and transfer times; the fastest is returned
+    as (lists, info)."""
+    max_extra = p - 1 if max_extra is None else max_extra
+    best = None
+    tried = []
+    seen = set()
+    for extra in range(max_extra + 1):
+        caps = [min(m, p - i + extra) for i in range(p)]
+        lists = None
+        while True:
+            comp = base_lists(lambda i, c=tuple(caps): c[i])
+            out, lowered = [], False
+            for i in range(p):
+                ev = comp[i]
+                if not fits(ev)[0]:
+                    ev = fit_offloads(comp[i], n_layers, kinds, kind_bytes, fits, lead=lead)
+                if ev is None:
+                    if caps[i] == 1:
+                        raise RuntimeError("one micro-batch does not fit the budget")
+                    caps[i] -= 1
+                    lowered = True
+                    break
+                out.append(ev)
+            if not lowered:
+                lists = out
+                break
+        key = tuple(caps)
+        if key in seen:
+            continue
+        seen.add(key)
+        size = lambda e: sum(kind_bytes[k] for k in e[3])
+        tl = pipeline_timeline(lists, t_op, t_comm=t_comm, t_copy=lambda i, e: t_copy_of_bytes(size(e)), duplex=duplex)
+        info = {"extra_fill": extra, "caps": list(caps), "makespan_model": tl.makespan, "bubble_model": list(tl.bubble),
+                "stall_model": list(tl.stall),
+                "offloaded_bytes": [sum(size(e) for e in ev if e[0] == "O") for ev in lists]}
+        tried.append({k: info[k] for k in ("extra_fill", "caps", "makespan_model")})
+        if best is None or tl.makespan < best[1]["makespan_model"] * (1 - 1e-9):
+            best = (lists, info)
+    best[1]["candidates"] = tried
+    return best
+
+
+def nominal_op_times(cfg, tflops=1100.0):
+    """T_F, T_B, T_W in ms of one micro-batch on one stage from the algorithmic flop counts (2 tokens N K per GEMM in
+    each of F, B, W; causal attention 2 s^2 n_q d forward, 5 s^2 n_q d backward) at a nominal rate: the stand-in for
+    measured op times where none exist yet."""
+    s, h, f = cfg.seq * cfg.micro_batch, cfg.hidden, cfg.ffn
+    gemm = 2 * s * (cfg.qkv_width * h + h * cfg.n_q_heads * cfg.head_dim + cfg.up_width * h + h * f)
+    att = cfg.micro_batch * cfg.seq * cfg.seq * cfg.n_q_heads * cfg.head_dim
+    ms = lambda fl: cfg.n_layers * fl / (tflops * 1e9)
+    return {"F": ms(gemm + 2 * att), "B": ms(gemm + 5 * att), "W": ms(gemm)}
+
+
+def workload_lists(cfg, budget, t_op=None, link_gbps=55.0, copy_latency_ms=0.02, duplex=False, m=None, max_extra=None,
+                   recompute=0):
+    """The lists of all p stages for a benchmark workload with a split B/W schedule under `budget` bytes of
+    activations per device (0 = no budget: the plain split B/W lists with p - i micro-batches in flight), every stage
+    shaped like cfg.  The library's planner decides what fits; offloads are chosen item by item (fit_offloads), the
+    fill level by modelled makespan (budgeted_lists) from t_op (default: nominal_op_times) and the host-link rate.
+    m overrides the micro-batch count (tests run fewer).  -> (lists, info)"""
+    from stage_inputs import schedules as G
+    from . import binding as B
+    p = cfg.n_stages
+    m = cfg.n_microbatches if m is None else m
+    if not budget:
+        return G.split_bw_greedy(p, m), {"extra_fill": 0, "caps": [min(m, p - i) for i in range(p)], "offloaded_bytes": [0] * p}
+    import dataclasses
+    c = dataclasses.replace(cfg, n_microbatches=m)
+    kb = B.query_sizes(c, recompute=recompute)[2]
+    t_op = t_op or nominal_op_times(cfg)
+
+    def fits(ev):
+        st, bad, _, _ = B.plan(c, ev, budget=budget, recompute=recompute)
+        return st == B.OK, bad
+
+    return budgeted_lists(p, m, cfg.n_layers, tuple(cfg.offload_kinds), kb, fits,
+                          lambda cap: G.split_bw_greedy(p, m, cap_of_stage=cap), [dict(t_op)] * p,
+                          lambda nbytes: nbytes / (link_gbps * 1e6) + copy_latency_ms, duplex=duplex, max_extra=max_extra)
+
+
 # ------------------------------------------------------------------------------- online scheduling (Sec. 4.3)
 
 class OnlineSearch:
@@ -578,22 +887,33 @@ class OnlineSearch:
     def _search(self):
         import time
         t0 = time.monotonic()
+        inst = self.inst
+        bound, bound_proven = None, False             # C <= bound for the next solve; proven = it is a solver's own makespan
         try:
-            self._publish(adaoffload(self.inst, tolerance=self.tolerance), t0)
+            sol = adaoffload(inst, tolerance=self.tolerance)
+            # the construction's own makespan ignores the reloads' share of the channel: time its lists under the
+            # model the solver uses before publishing them or bounding a solve by them
+            sol.makespan = pipeline_timeline(sol.lists, inst.t_op, inst.t_comm, lambda i, e: inst.t_off[i]).makespan
+            self._publish(sol, t0)
+            bound = sol.makespan - self.min_gain
         except RuntimeError:                           # the heuristic found no list (limit too tight for it):
             pass                                       # the solver starts without a bound
         slice_s = self.slice_seconds
         while not self._stop.is_set() and time.monotonic() - t0 < self.max_seconds:
-            have = self.best()
-            bound = have[1].makespan - self.min_gain if have else None
-            sol = milp_schedule(self.inst, time_limit=slice_s, cutoff=bound, strict_eq13=self.strict_eq13)
+            sol = milp_schedule(inst, time_limit=slice_s, cutoff=bound, strict_eq13=self.strict_eq13)
             if sol.lists:
                 self._publish(sol, t0)
+                # the next solve must beat this one in the solver's own units, whatever the judge made of it:
+                # otherwise a candidate the judge rejects would come back from every solve
+                bound, bound_proven = sol.makespan - self.min_gain, True
                 if "ptimal" in sol.status:            # proven optimal under the bound: nothing better exists
                     self.complete = True
                     return
-            elif "nfeasible" in sol.status:            # no schedule beats the incumbent
-                self.complete = True
+            elif "nfeasible" in sol.status:
+                if bound is not None and not bound_proven:
+                    bound = None                       # a heuristic list's timing is no proof: ask again without it
+                    continue
+                self.complete = True                   # no schedule beats the incumbent (or none exists at all)
                 return
             else:                                      # out of time without an incumbent: look longer
                 slice_s *= 2

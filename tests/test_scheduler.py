@@ -292,3 +292,129 @@ def test_online_search_on_an_instance_without_any_schedule():
         one = SC.Instance(p=p, m=m, t_op=[{"F": 1, "B": 1, "W": 1}] * p, t_off=[0.5] * p, delta=[DELTA] * p, gamma=[GAMMA] * p,
                           limit=[None] * p, item=ITEM)
         assert abs(SC.adaoffload(one).makespan - want) < 1e-6 and abs(SC.milp_schedule(one, time_limit=20).makespan - want) < 1e-4
+
+
+# ------------------------------------------------------------- timing of given lists, lists under a byte budget
+
+def _small_cfg():
+    from stage_inputs import configs as CFG
+    return CFG.shrunken(CFG.CFG3, hidden=512, n_q=4, n_kv=4, ffn=1376, seq=512, n_layers=3, n_microbatches=8, name="cfg3_small")
+
+
+def _table(cfg):
+    return S.memory_table(cfg.family, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.ffn,
+                          cfg.seq * cfg.micro_batch, cfg.elem_size)
+
+
+@pytest.mark.parametrize("duplex", [False, True])
+def test_pipeline_timeline_equals_the_oracle_simulator_on_random_lists(duplex):
+    """The library-side timing of given lists (used to choose between candidate schedules) against the oracle's
+    simulator: every start and end time, the makespan and the per-stage bubble, on random members of the schedule
+    grammar with random op and transfer times."""
+    import numpy as np
+    rng = np.random.default_rng(11)
+    kinds = ("X_IN", "QKV", "X_MID")
+    deadlocks = compared = 0
+    for trial in range(60):
+        p, m, nl = int(rng.integers(1, 5)), int(rng.integers(1, 6)), int(rng.integers(1, 3))
+        lists = [G.random_valid_list(rng, m, nl, kinds, p_offload=0.5) for _ in range(p)]
+        t_op = [{c: float(rng.uniform(0.5, 3.0)) for c in "FBW"} for _ in range(p)]
+        t_comm = float(rng.uniform(0, 0.5))
+        cost = {k: float(rng.uniform(0.1, 2.0)) for k in kinds}
+        t_copy = lambda i, e: sum(cost[k] for k in e[3]) * (1 + 0.1 * i)
+        try:
+            ref = S.simulate(lists, t_op, t_comm, t_copy, duplex=duplex)
+        except S.ScheduleError:                         # random orders of several stages may wait for each other
+            with pytest.raises(ValueError):
+                SC.pipeline_timeline(lists, t_op, t_comm, t_copy, duplex=duplex)
+            deadlocks += 1
+            continue
+        got = SC.pipeline_timeline(lists, t_op, t_comm, t_copy, duplex=duplex)
+        compared += 1
+        assert got.makespan == pytest.approx(ref.makespan_global, rel=1e-12)
+        for i in range(p):
+            assert got.bubble[i] == pytest.approx(ref.bubble[i], abs=1e-12)
+            for n, e in enumerate(lists[i]):
+                if e[0] == "OWAIT":
+                    continue
+                assert got.start[i][n] == pytest.approx(ref.start[i][n], abs=1e-9), (trial, i, n, e)
+                assert got.end[i][n] == pytest.approx(ref.end[i][n], abs=1e-9)
+    assert compared >= 15 and deadlocks >= 1
+
+
+def test_pipeline_timeline_stall_is_the_time_lost_to_transfers():
+    # one stage, F0 F1 B0 ...; micro-batch 1's item leaves and comes back: B1 waits for the reload, nothing else does
+    ev = [("F", 0), ("F", 1), ("O", 1, 0, ("X_IN",)), ("OWAIT", 1, 0, ("X_IN",)), ("B", 0), ("W", 0),
+          ("R", 1, 0, ("X_IN",)), ("B", 1), ("W", 1)]
+    t_op = [{"F": 1.0, "B": 2.0, "W": 1.0}]
+    tl = SC.pipeline_timeline([ev], t_op, 0.0, lambda i, e: 0.5)
+    # O runs 2.0-2.5 while B0 would start at 2.0: B0 is listed after the OWAIT, so it waits 0.5; R starts at the end
+    # of W0 (5.5) and ends at 6.0: B1 waits another 0.5
+    assert tl.stall[0] == pytest.approx(1.0) and tl.makespan == pytest.approx(9.0)
+    free = SC.pipeline_timeline([[e for e in ev if e[0] in "FBW"]], t_op)
+    assert free.stall[0] == 0.0 and free.makespan == pytest.approx(8.0)
+
+
+def test_fit_offloads_takes_the_fewest_items_the_budget_needs():
+    from paper_2510_05186_amd import binding as B
+    cfg = _small_cfg()
+    t = _table(cfg)
+    kb = B.query_sizes(cfg)[2]
+    kinds = ("X_IN", "QKV", "X_MID")
+    comp = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches)[cfg.stage_index]
+    peak0, _ = S.account_memory(comp, cfg.n_layers, t)
+    fits_at = lambda budget: (lambda ev: (lambda r: (r[0] == B.OK, r[1]))(B.plan(cfg, ev, budget=budget)))
+    assert SC.fit_offloads(comp, cfg.n_layers, kinds, kb, fits_at(peak0)) == comp            # fits: nothing leaves
+    moved_prev = 0
+    for frac in (0.95, 0.9, 0.85):
+        budget = int(frac * peak0)
+        ev = SC.fit_offloads(comp, cfg.n_layers, kinds, kb, fits_at(budget))
+        assert ev is not None and [e for e in ev if e[0] in "FBW"] == comp
+        S.check_order(ev, cfg.n_microbatches, cfg.n_layers)
+        peak, trace = S.account_memory(ev, cfg.n_layers, t, limit=budget)
+        assert peak <= budget and trace[-1] == 0
+        moved = sum(t[k] for e in ev if e[0] == "O" for k in e[3])
+        everything = G.add_offload(comp, cfg.n_layers, kinds, min_gap=1, lead=1)
+        assert 0 < moved < sum(t[k] for e in everything if e[0] == "O" for k in e[3])
+        assert moved >= moved_prev                      # a tighter budget never moves fewer bytes
+        moved_prev = moved
+        # none of the chosen items is superfluous where it was chosen: without the last one the list overruns
+        last = [e for e in ev if e[0] == "O"][-1]
+        drop = (last[1], last[2], last[3][-1])
+        thinner = []
+        for e in ev:
+            if e[0] in ("O", "OWAIT", "R") and (e[1], e[2]) == drop[:2]:
+                ks = tuple(k for k in e[3] if k != drop[2])
+                if ks:
+                    thinner.append((e[0], e[1], e[2], ks))
+            else:
+                thinner.append(e)
+        with pytest.raises(S.ScheduleError):
+            S.account_memory(thinner, cfg.n_layers, t, limit=budget)
+    # a budget below what one micro-batch needs during its B cannot be met
+    assert SC.fit_offloads(comp, cfg.n_layers, kinds, kb, fits_at(int(0.9 * sum(t[k] for k in S.F_KINDS) * cfg.n_layers))) is None
+
+
+def test_workload_lists_fill_the_budget_and_are_chosen_by_modelled_makespan():
+    from paper_2510_05186_amd import binding as B
+    cfg = _small_cfg()
+    t = _table(cfg)
+    p, m = cfg.n_stages, cfg.n_microbatches
+    base = G.split_bw_greedy(p, m)
+    peak0 = max(S.account_memory(ev, cfg.n_layers, t)[0] for ev in base)
+    t_op = SC.nominal_op_times(cfg)
+    size = lambda e: sum(t[k] for k in e[3])
+    for frac in (0.5, 1.3):
+        budget = int(frac * peak0)
+        lists, info = SC.workload_lists(cfg, budget, t_op=t_op, link_gbps=55.0)
+        assert len(lists) == p
+        for ev in lists:
+            S.check_order(ev, m, cfg.n_layers)
+            assert S.account_memory(ev, cfg.n_layers, t, limit=budget)[0] <= budget
+        ref = S.simulate(lists, [t_op] * p, 0.0, lambda i, e: size(e) / 55e6 + 0.02)
+        assert info["makespan_model"] == pytest.approx(ref.makespan_global, rel=1e-12)
+        assert info["makespan_model"] <= min(c["makespan_model"] for c in info["candidates"]) * (1 + 1e-12)
+        assert info["offloaded_bytes"] == [sum(size(e) for e in ev if e[0] == "O") for ev in lists]
+    # with room to spare the fill is denser than p - i in flight, and it pays in the model
+    assert info["extra_fill"] > 0 and info["makespan_model"] < info["candidates"][0]["makespan_model"]
+    assert SC.workload_lists(cfg, 0)[0] == base
