@@ -24,6 +24,22 @@ Everything is numpy float64, whole-matrix, no tiling, no fusion.  The only
 concession to size is `attn_chunk`: the s x s score matrix may be evaluated
 in blocks of query rows (each block still uses the plain definition).
 
+Storage precision (`store`).  The bf16 workloads name a storage type: the
+tensors that pass from one op of the layer graph to the next (each z and
+sigma(z) of Sec. 2.2 and each gradient of them, which is also what the
+activation-memory parameters Delta and Gamma of Eq. 7 count at two bytes per
+element) are bf16 values, while the arithmetic inside an op is not limited
+by it.  With store=None (default) the oracle keeps every tensor in float64:
+the exact function.  With store=round_bf16 the output of every op (norm,
+linear map, rotary, attention, residual add, activation, and the backward
+counterpart of each) is rounded to the nearest bf16 value (ties to even)
+before the next op reads it, and everything inside an op stays float64: the
+exact function OF THE STORED VALUES, which is what an executor with that
+storage type can be held to far more tightly than to the float64 chain (a
+gradient four layers deep moves by about 1.5 % RMS under storage rounding
+alone).  Norm statistics and the attention log-sum-exp stay unrounded (the
+memory table holds them as fp32).
+
 Layouts: activations are [tokens, features] row-major; linear weights are
 [out_features, in_features].  The packed qkv row is [q heads | k heads |
 v heads], each head `d` wide.  The packed gate/up row is [gate f | up f].
@@ -47,6 +63,18 @@ except Exception:  # pragma: no cover
 
 GPT = 0
 LLAMA = 1
+
+
+def round_bf16(a):
+    """Nearest bf16 value (8 significant bits, ties to even) of every element, returned as float64.
+    Written on the value, not on bit patterns: a = m 2^e with 0.5 <= |m| < 1, and m is rounded to a
+    multiple of 2^-8.  The workloads' values are far from bf16's exponent limits; none are handled."""
+    m, e = np.frexp(np.asarray(a, dtype=np.float64))
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+def _keep(x):
+    return x
 
 
 @dataclass(frozen=True)
@@ -178,6 +206,10 @@ def attention_probs(q, k, a, g):
 
 
 def attention_bwd(q, k, v, o, do, attn_chunk=None):
+    """Softmax-attention backward by the definition dS = P o (dP - D), D_t = sum_t' P_tt' dP_tt'.
+    o=None: D from that definition.  o given: D_t = <dO_t, o_t>, the same number when o is the exact forward
+    output (sum_t' P_tt' dP_tt' = <dO_t, sum_t' P_tt' V_t'>); tests that feed a kernel's own stored, rounded
+    output use this form to check the kernel against the inputs it really had."""
     s, n_q, d = q.shape
     n_kv = k.shape[1]
     scale = 1.0 / math.sqrt(d)
@@ -200,7 +232,10 @@ def attention_bwd(q, k, v, o, do, attn_chunk=None):
             dO = do[t0:t1, a, :]
             dv[:t1, g, :] += P.T @ dO
             dP = dO @ V[:t1].T
-            D = np.sum(dO * o[t0:t1, a, :], axis=1, keepdims=True)
+            if o is None:
+                D = np.sum(P * dP, axis=1, keepdims=True)
+            else:
+                D = np.sum(dO * o[t0:t1, a, :], axis=1, keepdims=True)
             dS = P * (dP - D)
             dq[t0:t1, a, :] = (dS @ K[:t1]) * scale
             dk[:t1, g, :] += (dS.T @ q[t0:t1, a, :]) * scale
@@ -265,9 +300,11 @@ def _sequences(sh: StageShape, rows: int):
     return [slice(b * sh.seq, (b + 1) * sh.seq) for b in range(rows // sh.seq)]
 
 
-def layer_forward(sh: StageShape, w: dict, x, attn_chunk=None):
+def layer_forward(sh: StageShape, w: dict, x, attn_chunk=None, store=None):
     """Returns (y, saved).  saved holds every tensor the store-all inventory keeps:
-    x_in, n1, qkv (after rotary), o, lse, x_mid, n2, gu, a and the norm statistics."""
+    x_in, n1, qkv (after rotary), o, lse, x_mid, n2, gu, a and the norm statistics.
+    store: rounding applied to every op's output (see the module header); None keeps float64."""
+    st = store or _keep
     sv = {"x_in": x}
     if sh.family == LLAMA:
         n1, r1 = rmsnorm_fwd(x, w["g1"], sh.norm_eps)
@@ -275,64 +312,70 @@ def layer_forward(sh: StageShape, w: dict, x, attn_chunk=None):
     else:
         n1, mu1, r1 = layernorm_fwd(x, w["g1"], w["b1"], sh.norm_eps)
         sv["mu1"], sv["r1"] = mu1, r1
-    qkv = linear_fwd(n1, w["wqkv"])
+    n1 = st(n1)
+    qkv = st(linear_fwd(n1, w["wqkv"]))
     q, k, v = _split_qkv(sh, qkv)
     seqs = _sequences(sh, x.shape[0])
     if sh.family == LLAMA:
         q = np.concatenate([rope_apply(q[sl], sh.rope_base) for sl in seqs], axis=0)
         k = np.concatenate([rope_apply(k[sl], sh.rope_base) for sl in seqs], axis=0)
-        qkv = _merge_qkv(q, k, v)
+        qkv = st(_merge_qkv(q, k, v))
+        q, k, v = _split_qkv(sh, qkv)
     per_seq = [attention_fwd(q[sl], k[sl], v[sl], attn_chunk) for sl in seqs]
     o = np.concatenate([o_b for o_b, _ in per_seq], axis=0)
     lse = np.stack([l_b for _, l_b in per_seq], axis=0)          # [sequence, head, position]
-    o = o.reshape(x.shape[0], -1)
-    x_mid = x + linear_fwd(o, w["wo"])
+    o = st(o.reshape(x.shape[0], -1))
+    x_mid = st(x + linear_fwd(o, w["wo"]))
     if sh.family == LLAMA:
         n2, r2 = rmsnorm_fwd(x_mid, w["g2"], sh.norm_eps)
         sv["r2"] = r2
     else:
         n2, mu2, r2 = layernorm_fwd(x_mid, w["g2"], w["b2"], sh.norm_eps)
         sv["mu2"], sv["r2"] = mu2, r2
-    gu = linear_fwd(n2, w["wgu"])
-    a = swiglu_fwd(gu) if sh.family == LLAMA else gelu_fwd(gu)
-    y = x_mid + linear_fwd(a, w["wd"])
+    n2 = st(n2)
+    gu = st(linear_fwd(n2, w["wgu"]))
+    a = st(swiglu_fwd(gu) if sh.family == LLAMA else gelu_fwd(gu))
+    y = st(x_mid + linear_fwd(a, w["wd"]))
     sv.update(n1=n1, qkv=qkv, o=o, lse=lse, x_mid=x_mid, n2=n2, gu=gu, a=a)
     return y, sv
 
 
-def layer_backward_input(sh: StageShape, w: dict, sv: dict, dy, attn_chunk=None):
+def layer_backward_input(sh: StageShape, w: dict, sv: dict, dy, attn_chunk=None, store=None):
     """B for one layer.  Returns (dx_in, stash, dnorm) where stash holds, for each
     of the four linears, the pair (grad of its output, its input) that W needs,
     and dnorm the norm-parameter gradients (they are produced in B because B
     releases x_in / x_mid and the statistics they depend on)."""
+    st = store or _keep
     s = dy.shape[0]
-    da = linear_bwd_input(dy, w["wd"])
-    dgu = swiglu_bwd(da, sv["gu"]) if sh.family == LLAMA else gelu_bwd(da, sv["gu"])
-    dn2 = linear_bwd_input(dgu, w["wgu"])
+    da = st(linear_bwd_input(dy, w["wd"]))
+    dgu = st(swiglu_bwd(da, sv["gu"]) if sh.family == LLAMA else gelu_bwd(da, sv["gu"]))
+    dn2 = st(linear_bwd_input(dgu, w["wgu"]))
     dnorm = {}
     if sh.family == LLAMA:
         dxm, dnorm["g2"] = rmsnorm_bwd(dn2, sv["x_mid"], sv["r2"], w["g2"])
     else:
         dxm, dnorm["g2"], dnorm["b2"] = layernorm_bwd(dn2, sv["x_mid"], sv["mu2"], sv["r2"], w["g2"])
-    dx_mid = dy + dxm
-    do = linear_bwd_input(dx_mid, w["wo"])
+    dx_mid = st(dy + dxm)
+    do = st(linear_bwd_input(dx_mid, w["wo"]))
     q, k, v = _split_qkv(sh, sv["qkv"])
     nq, d = sh.n_q_heads, sh.head_dim
     o3, do3 = sv["o"].reshape(s, nq, d), do.reshape(s, nq, d)
     parts = []
     for sl in _sequences(sh, s):
-        dq, dk, dv = attention_bwd(q[sl], k[sl], v[sl], o3[sl], do3[sl], attn_chunk)
+        # with a storage type the stored o is no longer the exact output: D then comes from its definition
+        dq, dk, dv = attention_bwd(q[sl], k[sl], v[sl], o3[sl] if store is None else None, do3[sl], attn_chunk)
+        dq, dk, dv = st(dq), st(dk), st(dv)                       # what the attention op hands on
         if sh.family == LLAMA:
-            dq = rope_apply(dq, sh.rope_base, sign=-1.0)
-            dk = rope_apply(dk, sh.rope_base, sign=-1.0)
+            dq = st(rope_apply(dq, sh.rope_base, sign=-1.0))
+            dk = st(rope_apply(dk, sh.rope_base, sign=-1.0))
         parts.append(_merge_qkv(dq, dk, dv))
     dqkv = np.concatenate(parts, axis=0)
-    dn1 = linear_bwd_input(dqkv, w["wqkv"])
+    dn1 = st(linear_bwd_input(dqkv, w["wqkv"]))
     if sh.family == LLAMA:
         dxi, dnorm["g1"] = rmsnorm_bwd(dn1, sv["x_in"], sv["r1"], w["g1"])
     else:
         dxi, dnorm["g1"], dnorm["b1"] = layernorm_bwd(dn1, sv["x_in"], sv["mu1"], sv["r1"], w["g1"])
-    dx_in = dx_mid + dxi
+    dx_in = st(dx_mid + dxi)
     stash = {"wd": (dy, sv["a"]), "wgu": (dgu, sv["n2"]), "wo": (dx_mid, sv["o"]), "wqkv": (dqkv, sv["n1"])}
     return dx_in, stash, dnorm
 
@@ -345,19 +388,19 @@ def layer_backward_weight(stash: dict):
 # --------------------------------------------------------------------------
 # the stage: L layers in sequence
 # --------------------------------------------------------------------------
-def stage_forward(sh: StageShape, weights: list, x, attn_chunk=None):
+def stage_forward(sh: StageShape, weights: list, x, attn_chunk=None, store=None):
     saved = []
     for l in range(sh.n_layers):
-        x, sv = layer_forward(sh, weights[l], x, attn_chunk)
+        x, sv = layer_forward(sh, weights[l], x, attn_chunk, store)
         saved.append(sv)
     return x, saved
 
 
-def stage_backward_input(sh: StageShape, weights: list, saved: list, dy, attn_chunk=None):
+def stage_backward_input(sh: StageShape, weights: list, saved: list, dy, attn_chunk=None, store=None):
     stashes = [None] * sh.n_layers
     dnorms = [None] * sh.n_layers
     for l in reversed(range(sh.n_layers)):
-        dy, stashes[l], dnorms[l] = layer_backward_input(sh, weights[l], saved[l], dy, attn_chunk)
+        dy, stashes[l], dnorms[l] = layer_backward_input(sh, weights[l], saved[l], dy, attn_chunk, store)
     return dy, stashes, dnorms
 
 
@@ -365,11 +408,12 @@ def stage_backward_weight(stashes: list):
     return [layer_backward_weight(st) for st in stashes]
 
 
-def stage_fbw(sh: StageShape, weights: list, x, dy, attn_chunk=None):
+def stage_fbw(sh: StageShape, weights: list, x, dy, attn_chunk=None, store=None):
     """F, then B, then W of one micro-batch.  Returns y, dx, dW (per layer dict),
-    dnorm (per layer dict)."""
-    y, saved = stage_forward(sh, weights, x, attn_chunk)
-    dx, stashes, dnorms = stage_backward_input(sh, weights, saved, dy, attn_chunk)
+    dnorm (per layer dict).  Parameter gradients are sums held in fp32 by the workloads
+    and are never rounded to the storage type."""
+    y, saved = stage_forward(sh, weights, x, attn_chunk, store)
+    dx, stashes, dnorms = stage_backward_input(sh, weights, saved, dy, attn_chunk, store)
     return y, dx, stage_backward_weight(stashes), dnorms
 
 
