@@ -57,6 +57,17 @@ optstage_status optstage_op_norm_bwd(uint32_t dtype, uint32_t family, const void
                                      const float* stats, const void* gamma, const void* dres, void* dx,
                                      float* partial, float* dgamma, float* dbeta, uint32_t rows, uint32_t hidden,
                                      void* stream);
+/* optstage_op_norm_bwd for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without `partial`, same kernels,
+ * bit-identical results.  The partials live in a 16 MiB array that is part of the library's device image (one copy
+ * per GPU, held until the process ends); the call allocates nothing and frees nothing.  hidden may be at most 8192,
+ * else OPTSTAGE_E_ARG and nothing runs.  All calls on one GPU share that array: two calls that overlap in time on
+ * one GPU (different streams, or different host threads) race; calls on one stream are safe.  The first call on a
+ * device resolves the array's address there (a HIP runtime call that may load the code object). */
+optstage_status optstage_op_norm_bwd_static(uint32_t dtype, uint32_t family, const void* dn, const void* x,
+                                            const float* stats, const void* gamma, const void* dres, void* dx,
+                                            float* dgamma, float* dbeta, uint32_t rows, uint32_t hidden,
+                                            void* stream);
 /* LLAMA: a[rows, f] = silu(gu[:, :f]) * gu[:, f:], gu is [rows, 2f].  GPT: a = gelu(gu), gu is [rows, f]. */
 optstage_status optstage_op_act_fwd(uint32_t dtype, uint32_t family, const void* gu, void* a, uint32_t rows,
                                     uint32_t ffn, void* stream);

@@ -88,6 +88,7 @@ _SIGS = {
     "optstage_op_weight_slabs": [_vp, _vp, _u32, _u32, _u32, _vp],
     "optstage_op_norm_fwd": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _f32, _vp],
     "optstage_op_norm_bwd": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _vp],
+    "optstage_op_norm_bwd_static": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _vp],
     "optstage_op_act_fwd": [_u32, _u32, _vp, _vp, _u32, _u32, _vp],
     "optstage_op_act_bwd": [_u32, _u32, _vp, _vp, _vp, _u32, _u32, _vp],
     "optstage_op_rope_table": [_vp, _u32, _u32, _f32, _vp],

@@ -1,5 +1,7 @@
 // Single-kernel C-ABI entry points (include/optstage_ops.h) and the attention dispatch between the
 // MFMA kernels and the general path.
+#include <mutex>
+
 #include "../../include/optstage_ops.h"
 #include "common.h"
 
@@ -110,6 +112,61 @@ optstage_status optstage_op_norm_bwd(uint32_t dtype, uint32_t family, const void
   REQ(dn && x && stats && gamma && dx && partial && dgamma && (family == OPTSTAGE_LLAMA || dbeta), "norm_bwd: null operand");
   REQ(dtype <= 1 && family <= 1 && rows && hidden && rows < (1u << 30), "norm_bwd: bad argument");
   return wrap(launch_norm_bwd(dtype, family, dn, x, stats, gamma, dres, dx, partial, dgamma, dbeta, rows, hidden, (hipStream_t)stream), "norm_bwd");
+}
+
+}  // extern "C"
+
+// Scratch of the entry point that allocates nothing: the per-workgroup gain / bias partials of the norm backward
+// kernels, 2 x 256 workgroups x hidden fp32.  One copy per GPU, held until the process ends; host code reaches
+// it only through the per-device address resolved below (the symbol's name is not a device address on the host).
+namespace {
+constexpr uint32_t STATIC_MAX_HIDDEN = 8192;
+constexpr int STATIC_PARTIAL_ROWS = 256;
+constexpr int STATIC_MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) float scratch[2 * STATIC_PARTIAL_ROWS * STATIC_MAX_HIDDEN];
+namespace {
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+
+// address of the current device's copy of `scratch`, resolved once per device
+optstage_status static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return wrap(e, "norm_bwd_static: hipGetDevice");
+  REQ(dev >= 0 && dev < STATIC_MAX_DEVICES, "norm_bwd_static: device index beyond the per-device table");
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return wrap(e, "norm_bwd_static: hipGetSymbolAddress");
+    REQ(p, "norm_bwd_static: the scratch symbol resolved to a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return OPTSTAGE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+optstage_status optstage_op_norm_bwd_static(uint32_t dtype, uint32_t family, const void* dn, const void* x,
+                                            const float* stats, const void* gamma, const void* dres, void* dx,
+                                            float* dgamma, float* dbeta, uint32_t rows, uint32_t hidden,
+                                            void* stream) {
+  REQ(dn && x && stats && gamma && dx && dgamma && (family == OPTSTAGE_LLAMA || dbeta), "norm_bwd_static: null operand");
+  REQ(dtype <= 1 && family <= 1 && rows && hidden && rows < (1u << 30), "norm_bwd_static: bad argument");
+  if (hidden > STATIC_MAX_HIDDEN) {
+    char msg[160];
+    snprintf(msg, sizeof msg, "norm_bwd_static: hidden %u exceeds the static scratch's maximum of %u", hidden, STATIC_MAX_HIDDEN);
+    return (optstage_status)optstage_fail_(OPTSTAGE_E_ARG, msg);
+  }
+  REQ(norm_bwd_partial_rows((int)rows) <= STATIC_PARTIAL_ROWS, "norm_bwd_static: more partial rows than the static scratch holds");
+  float* partial = nullptr;
+  optstage_status st = static_scratch(&partial);
+  if (st != OPTSTAGE_OK) return st;
+  // every partial row the reduction reads is written in full by the first kernel: nothing needs clearing
+  return wrap(launch_norm_bwd(dtype, family, dn, x, stats, gamma, dres, dx, partial, dgamma, dbeta, rows, hidden, (hipStream_t)stream), "norm_bwd_static");
 }
 
 optstage_status optstage_op_act_fwd(uint32_t dtype, uint32_t family, const void* gu, void* a, uint32_t rows,
