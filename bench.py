@@ -56,34 +56,6 @@ def measured_traffic(cfg):
     return int(m.group(1)) if m else None
 
 
-def device_weights(cfg, torch):
-    """Seeded synthetic parameters generated on the device: linear weights N(0, 0.02), gains 1 + N(0, 0.02)."""
-    from stage_inputs import tensors as T
-    g = torch.Generator(device="cuda")
-    dt = torch.bfloat16 if cfg.dtype == 1 else torch.float32
-    out = []
-    for l in range(cfg.n_layers):
-        w = {}
-        for i, (name, shape) in enumerate(T.weight_shapes(cfg).items()):
-            g.manual_seed(cfg.seed * 1000003 + l * 101 + i)
-            t = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * 0.02
-            if name in ("g1", "g2"):
-                t = t + 1.0
-            w[name] = t.to(dt).contiguous()
-        out.append(w)
-    return out
-
-
-def device_io(cfg, mb, torch):
-    g = torch.Generator(device="cuda")
-    dt = torch.bfloat16 if cfg.dtype == 1 else torch.float32
-    g.manual_seed(cfg.seed * 1000003 + 50000 + mb)
-    x = torch.randn((cfg.seq * cfg.micro_batch, cfg.hidden), generator=g, device="cuda", dtype=torch.float32).to(dt)
-    g.manual_seed(cfg.seed * 1000003 + 90000 + mb)
-    dy = (torch.randn((cfg.seq * cfg.micro_batch, cfg.hidden), generator=g, device="cuda", dtype=torch.float32) * 1e-3).to(dt)
-    return x.contiguous(), dy.contiguous()
-
-
 CHUNKS = 1      # --chunks: model chunks on the stage (interleaved 1F1B instead of the configuration's schedule)
 RECOMPUTE = 0   # --recompute: the memory-table variant in which F keeps no norm outputs and no MLP activation output
 
@@ -159,6 +131,7 @@ def build_schedule(cfg, budget=0, generator="greedy"):
 
 def make_stage(cfg, events, budget, torch, duplex=False):
     from paper_2510_05186_amd import binding as B
+    from stage_inputs import tensors as T
     from paper_2510_05186_amd.stage import Stage
     _, _, peak, _ = B.plan(cfg, events, budget=0, recompute=RECOMPUTE, n_chunks=CHUNKS)
     n_off = sum(1 for e in events if e[0] == "O")
@@ -169,10 +142,10 @@ def make_stage(cfg, events, budget, torch, duplex=False):
         pool = per_mb * cfg.n_microbatches
     st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=pool, duplex=duplex,
                recompute=bool(RECOMPUTE), n_chunks=CHUNKS)
-    st.set_weights_device(device_weights(cfg, torch))
+    st.set_weights_device(T.device_weights(cfg))
     for c in range(CHUNKS):
         for j in range(cfg.n_microbatches):
-            x, dy = device_io(cfg, c * cfg.n_microbatches + j, torch)
+            x, dy = T.device_io(cfg, c * cfg.n_microbatches + j)
             st.bind(j, x, dy, chunk=c)
     return st, peak
 

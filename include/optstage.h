@@ -23,7 +23,11 @@
  *  - The library orders its own streams against each other and nothing else: work the caller has
  *    queued on OTHER streams that produces a buffer the library will read (a weight, x[j], dy[j]) must
  *    have completed, or been made a dependency of the library's streams, before the call that reads it.
- *  - A failing call changes no accounting state (validate, then commit).
+ *  - A call that fails on its arguments, on the ordering rules or on the budget changes no accounting state and
+ *    enqueues nothing (the whole list is validated on a copy of the state before anything is committed).  The one
+ *    exception: if a HIP runtime call fails while a validated list is being enqueued (OPTSTAGE_E_HIP), the
+ *    accounting is ahead of what reached the streams; the handle then refuses every further event with
+ *    OPTSTAGE_E_STATE until optstage_synchronize() and optstage_reset() have been called.
  *  - A handle is not thread-safe; use one host thread per handle.
  */
 #ifndef OPTSTAGE_H
@@ -133,7 +137,26 @@ typedef struct {
   uint64_t kernel_launches[OPTSTAGE_N_KERNEL_CLASSES];
   double kernel_ms[OPTSTAGE_N_KERNEL_CLASSES];
   double kernel_work[OPTSTAGE_N_KERNEL_CLASSES];
+  /* list-order accounting over the executed events since the last reset: the lowest live byte count after any
+   * event while a micro-batch was in flight (F done, W not done), and the mean of the live bytes after every event */
+  uint64_t min_live_bytes;
+  double avg_live_bytes;
+  /* time the compute stream spent waiting for transfers (valid after synchronize): [0] at OWAIT events, for an
+   * offload to end before the bytes it frees are reused (Eq. 12); [1] ahead of B ops, for the reloads of their
+   * micro-batch to end */
+  double stall_ms[2];
+  uint64_t n_trace;                             /* entries optstage_get_trace() holds */
 } optstage_stats;
+
+/* One executed event: what was enqueued, the live activation bytes after it (list-order accounting), and, once
+ * optstage_synchronize() has returned, its device times in ms since the first event after the last reset: F, B, W
+ * on the compute stream, O and R on their transfer stream; -1 for OWAIT, which takes no time of its own.
+ * stall_ms: how long the compute stream waited at this event (OWAIT: for the offload; B: for the reloads). */
+typedef struct {
+  uint32_t op, microbatch, layer, kind_mask;    /* as in optstage_event */
+  uint64_t live_bytes;
+  double start_ms, end_ms, stall_ms;
+} optstage_trace_entry;
 
 /* The memory table (the parameters Delta and Gamma of Eq. 7): bytes of each activation kind for one
  * layer of one micro-batch (each rounded up to 256), written to bytes_per_kind[OPTSTAGE_N_KINDS] (HOST);
@@ -147,7 +170,8 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out);
 void optstage_destroy(optstage_t* st);
 
 /* Registers layer `layer`'s parameter `which` (DEVICE, stage dtype) and its gradient accumulator
- * (DEVICE, fp32, same shape, caller-zeroed; B and W add into it).  For the four linear weights the
+ * (DEVICE, fp32, same shape; B and W add into it, so the caller zeroes it, unless
+ * optstage_set_grad_overwrite is on).  For the four linear weights the
  * library also keeps a transposed copy in the workspace (enqueued on compute_stream) so that B's
  * dX = dY W runs with both operands contiguous along the contraction; call again after the weight
  * changes. */
@@ -187,15 +211,27 @@ optstage_status optstage_synchronize(optstage_t* st);
  * cleared).  Requires that nothing is in flight (call after optstage_synchronize). */
 optstage_status optstage_reset(optstage_t* st);
 optstage_status optstage_get_stats(optstage_t* st, optstage_stats* out /* HOST */);
+/* The executed trace since the last reset, in enqueue order: copies min(capacity, total) entries to out (HOST,
+ * may be null when capacity is 0) and writes the total to *n_total (may be null). */
+optstage_status optstage_get_trace(optstage_t* st, optstage_trace_entry* out /* HOST */, size_t capacity,
+                                   size_t* n_total);
+/* on != 0: the first B and the first W of every model chunk after a reset (micro-batch 0: the fixed micro-batch
+ * order makes it the first) STORE their parameter gradients (dW = dY^T X of Sec. 2.2, norm gains and biases)
+ * instead of adding them to what the accumulators hold, so nobody has to clear the accumulators between
+ * iterations and the first W op reads none of them; later ops add as usual.  The stored values are bit for bit
+ * what adding to zeroed accumulators gives.  Off by default (gradients accumulate across iterations). */
+optstage_status optstage_set_grad_overwrite(optstage_t* st, uint32_t on);
 /* on != 0: bracket every kernel launch of the op graphs with timing events on the compute stream (the
  * measurement mode the benchmark uses for per-kernel roofline figures); off by default. */
 optstage_status optstage_set_kernel_timing(optstage_t* st, uint32_t on);
 
-/* Test support: 64-bit checksum (sum of 64-bit words and xor of 64-bit words, combined) of a live or
- * offloaded activation buffer.  where: 0 = the device copy, 1 = the pinned host copy.  Blocks. */
+/* Test support: two 64-bit checksums of a live or offloaded activation buffer, written to out (HOST, TWO words):
+ * out[0] = sum of the buffer's 64-bit words mod 2^64, out[1] = their xor.  where: 0 = the device copy, 1 = the
+ * pinned host copy.  Blocks (drains all of the handle's streams first). */
 optstage_status optstage_debug_checksum(optstage_t* st, uint32_t mb, uint32_t layer, uint32_t kind,
-                                        uint32_t where, uint64_t* out /* HOST */);
-/* Test support: copies a live activation buffer to dst (HOST, at least the kind's byte size).  Blocks. */
+                                        uint32_t where, uint64_t out[2] /* HOST */);
+/* Test support: copies a live activation buffer to dst (HOST, at least the kind's byte size).  Blocks (waits for
+ * the transfer streams first, so a reload into the buffer has landed). */
 optstage_status optstage_debug_read(optstage_t* st, uint32_t mb, uint32_t layer, uint32_t kind,
                                     void* dst_host, uint64_t dst_bytes);
 

@@ -27,7 +27,8 @@ extern "C" {
  *          workgroup loads per step of the contraction are consecutive in memory (how the stage keeps its weight
  *          copies); B spans ceil(N / 256) * (K / 64) slabs, rows past N are never used; ldb is ignored.  Needs
  *          K % 64 == 0 and at least 128 output tiles of 256 x 256, else OPTSTAGE_E_ARG.
- * epilogue 0: C (stage dtype) = product; 1: C = product + R (R like C); 2: C (fp32) += product.
+ * epilogue 0: C (stage dtype) = product; 1: C = product + R (R like C); 2: C (fp32) += product;
+ *          3: C (fp32) = product (layout 1 only for bf16: the first weight-gradient product of an iteration).
  * bf16 needs lda, ldb multiples of 8, N and ldc multiples of 4, K (NT) or M and N (TN) multiples of 8. */
 optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilogue, const void* A, const void* B,
                                  void* C, const void* R, uint32_t M, uint32_t N, uint32_t K, uint32_t lda,

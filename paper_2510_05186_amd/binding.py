@@ -50,7 +50,14 @@ class Stats(C.Structure):
     _fields_ = [("live_bytes", C.c_uint64), ("peak_bytes", C.c_uint64), ("bytes_offloaded", C.c_uint64),
                 ("bytes_reloaded", C.c_uint64), ("n_ops", C.c_uint64 * 6), ("ms_ops", C.c_double * 6),
                 ("arena_high_water", C.c_uint64), ("kernel_launches", C.c_uint64 * 10),
-                ("kernel_ms", C.c_double * 10), ("kernel_work", C.c_double * 10)]
+                ("kernel_ms", C.c_double * 10), ("kernel_work", C.c_double * 10),
+                ("min_live_bytes", C.c_uint64), ("avg_live_bytes", C.c_double), ("stall_ms", C.c_double * 2),
+                ("n_trace", C.c_uint64)]
+
+
+class TraceEntry(C.Structure):
+    _fields_ = [("op", C.c_uint32), ("microbatch", C.c_uint32), ("layer", C.c_uint32), ("kind_mask", C.c_uint32),
+                ("live_bytes", C.c_uint64), ("start_ms", C.c_double), ("end_ms", C.c_double), ("stall_ms", C.c_double)]
 
 
 class OptstageError(RuntimeError):
@@ -80,6 +87,8 @@ _SIGS = {
     "optstage_reset": [_vp],
     "optstage_get_stats": [_vp, C.POINTER(Stats)],
     "optstage_set_kernel_timing": [_vp, _u32],
+    "optstage_get_trace": [_vp, C.POINTER(TraceEntry), C.c_size_t, C.POINTER(C.c_size_t)],
+    "optstage_set_grad_overwrite": [_vp, _u32],
     "optstage_debug_checksum": [_vp, _u32, _u32, _u32, _u32, C.POINTER(_u64)],
     "optstage_debug_read": [_vp, _u32, _u32, _u32, _vp, _u64],
     "optstage_plan": [C.POINTER(Desc), C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(_u64), C.POINTER(_u64)],

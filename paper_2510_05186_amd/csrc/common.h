@@ -35,8 +35,8 @@ enum { FAM_GPT = 0, FAM_LLAMA = 1 };
 // GEMM_NT_SLAB: C = A B^T with B stored in slabs of 256 rows x 64 columns, slab (n / 256, k / 64) at element offset
 // ((n / 256) * (K / 64) + k / 64) * 16384, row-major inside, rows padded to a multiple of 256
 enum { GEMM_NT = 0, GEMM_TN = 1, GEMM_NT_SLAB = 2 };
-// epilogues: store C (stage dtype); store C + R (R like C); C (fp32) += product
-enum { EPI_STORE = 0, EPI_RESID = 1, EPI_ACCUM = 2 };
+// epilogues: store C (stage dtype); store C + R (R like C); C (fp32) += product; C (fp32) = product
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_ACCUM = 2, EPI_STOREF = 3 };
 
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
@@ -84,7 +84,7 @@ hipError_t launch_norm_fwd(int dtype, int family, const void* x, const void* gam
                            float* stats, int rows, int h, float eps, hipStream_t s);
 hipError_t launch_norm_bwd(int dtype, int family, const void* dn, const void* x, const float* stats,
                            const void* gamma, const void* dres, void* dx, float* partial, float* dgamma,
-                           float* dbeta, int rows, int h, hipStream_t s);
+                           float* dbeta, int rows, int h, hipStream_t s, int overwrite = 0);
 int norm_bwd_partial_rows(int rows);
 hipError_t launch_act_fwd(int dtype, int family, const void* gu, void* a, int rows, int f, hipStream_t s);
 hipError_t launch_act_bwd(int dtype, int family, const void* da, const void* gu, void* dgu, int rows, int f,

@@ -289,10 +289,10 @@ __global__ __launch_bounds__(NT) void norm_bwd_wave_kernel(const T* __restrict__
   }
 }
 
-// sums the per-workgroup partials column-wise and adds them into the caller's fp32 accumulators:
-// workgroup = 32 columns x 8 row groups, fixed summation order (deterministic)
+// sums the per-workgroup partials column-wise and adds them into the caller's fp32 accumulators (overwrite: stores
+// them instead): workgroup = 32 columns x 8 row groups, fixed summation order (deterministic)
 __global__ __launch_bounds__(256) void norm_bwd_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dgamma,
-                                                              float* __restrict__ dbeta, int nb, int h) {
+                                                              float* __restrict__ dbeta, int nb, int h, int overwrite) {
   __shared__ float red[8][33];
   const int cx = threadIdx.x & 31, rg = threadIdx.x >> 5;
   const int col = blockIdx.x * 32 + cx;
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(256) void norm_bwd_reduce_kernel(const float* __res
 #pragma unroll
     for (int r = 0; r < 8; ++r) t += red[r][cx];
     float* dst = blockIdx.y == 0 ? dgamma : dbeta;
-    dst[col] += t;
+    dst[col] = overwrite ? t : dst[col] + t;
   }
 }
 
@@ -527,7 +527,7 @@ int norm_bwd_partial_rows(int rows) { return rows < 256 ? rows : 256; }
 
 hipError_t launch_norm_bwd(int dtype, int family, const void* dn, const void* x, const float* stats,
                            const void* gamma, const void* dres, void* dx, float* partial, float* dgamma,
-                           float* dbeta, int rows, int h, hipStream_t s) {
+                           float* dbeta, int rows, int h, hipStream_t s, int overwrite) {
   if (rows <= 0) return hipErrorInvalidValue;
   const bool ln = family == FAM_GPT;
   const int nb = norm_bwd_partial_rows(rows);
@@ -548,7 +548,7 @@ hipError_t launch_norm_bwd(int dtype, int family, const void* dn, const void* x,
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(norm_bwd_reduce_kernel, dim3((h + 31) / 32, ln ? 2 : 1), dim3(256), 0, s, partial, dgamma, dbeta, nb, h);
+  hipLaunchKernelGGL(norm_bwd_reduce_kernel, dim3((h + 31) / 32, ln ? 2 : 1), dim3(256), 0, s, partial, dgamma, dbeta, nb, h, overwrite);
   return hipGetLastError();
 }
 

@@ -4,10 +4,11 @@
 // activations dX = dY W (NT against the transposed weight copy), backward for weights dW += dY^T X (TN).
 //
 // Design (CDNA4): one workgroup of 4 or 8 waves owns a BM x BN output tile (256 x 256 for large problems);
-// the K loop advances 64 elements at a time through double-buffered LDS tiles with one barrier per step.
+// the K loop advances 64 elements at a time through LDS tiles (two buffers in the register-staged kernel, a ring
+// of five operand slots in the direct kernels) with one barrier per step.
 // Large problems with K % 64 == 0 load their tiles straight from global memory into LDS (no registers, no
-// ds_write; see the direct kernels below); everything else stages tiles global -> registers -> LDS.  LDS tiles are always [row][64 k] with the 16-byte chunk index XOR-swizzled by the row so that
-// both the 16-byte operand reads of v_mfma_f32_32x32x16_bf16 and the tile writes are bank-conflict
+// ds_write; see the direct kernels below); everything else stages tiles global -> registers -> LDS.  LDS tiles
+// are always [row][64 k] with the 16-byte chunk index XOR-swizzled by the row so that both the 16-byte operand reads of v_mfma_f32_32x32x16_bf16 and the tile writes are bank-conflict
 // free.  Operands that are contiguous along their output index (TN) are transposed in registers on the
 // way into LDS (each thread gathers a KV x 8 patch and writes 8 k-contiguous pieces), so the MFMA read
 // path is identical for every layout.  The MFMA is issued with the B fragment as its first operand:
@@ -131,7 +132,7 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* 
     constexpr bool PRE = NWAVES == 4;
     f32x4_t cold[EPI == EPI_ACCUM && PRE ? NIT : 1];
     bf16x4_t rold[EPI == EPI_RESID && PRE ? NIT : 1];
-    if (EPI != EPI_STORE && PRE) {
+    if ((EPI == EPI_ACCUM || EPI == EPI_RESID) && PRE) {
 #pragma unroll
       for (int p2 = 0; p2 < NIT; ++p2) {
         const int m = mw + pass * IPP * 32 + 2 * p2 + khalf;
@@ -167,7 +168,9 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* 
       f32x4_t v = *reinterpret_cast<const f32x4_t*>(wl + row * 512 + ((c ^ (row & 31)) << 4));
       if (m < M && n < N) {
         const size_t off = (size_t)m * ldc + n;
-        if (EPI == EPI_ACCUM) {
+        if (EPI == EPI_STOREF) {
+          *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off) = v;
+        } else if (EPI == EPI_ACCUM) {
           const f32x4_t o = PRE ? cold[PRE ? p2 : 0] : *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off);
           v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
           *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off) = v;
@@ -322,7 +325,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const bf16_t* _
         if (n >= N) continue;
         const size_t off = (size_t)m * ldc + n;
         float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1], v2 = acc[i][j][g * 4 + 2], v3 = acc[i][j][g * 4 + 3];
-        if (EPI == EPI_ACCUM) {
+        if (EPI == EPI_STOREF) {
+          f32x4_t c = {v0, v1, v2, v3};
+          *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off) = c;
+        } else if (EPI == EPI_ACCUM) {
           float* C = reinterpret_cast<float*>(Cv);
           f32x4_t c = *reinterpret_cast<const f32x4_t*>(C + off);
           c[0] += v0; c[1] += v1; c[2] += v2; c[3] += v3;
@@ -698,7 +704,7 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
   trip(P0, P16, 0, 0, 0, 0, 0, false, false);
   OPTSTAGE_TILE_SYNC(0);                             // every wave is done with the operand tiles, nothing in flight
 #undef OPTSTAGE_TILE_SYNC
-  if (EPI == EPI_ACCUM)
+  if (EPI == EPI_ACCUM || EPI == EPI_STOREF)
     epilogue_via_lds<EPI, TM, TN, 4>(acc, smem, wave, lane, Cv, R, M, N, ldc, m0 + wm * (BM / WM), n0 + wn * (BN / WN));
   else
     epilogue_bf16_rows<EPI>(acc, smem, wave, lane, reinterpret_cast<bf16_t*>(Cv), R, M, N, ldc, m0 + wm * (BM / WM),
@@ -851,6 +857,7 @@ hipError_t launch_gemm_bf16(int layout, int epi, const void* A, const void* B, v
     if ((M & 7) || (N & 7)) return hipErrorInvalidValue;
     if (epi == EPI_STORE) return launch_layout<true, EPI_STORE>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
     if (epi == EPI_ACCUM) return launch_layout<true, EPI_ACCUM>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
+    if (epi == EPI_STOREF) return launch_layout<true, EPI_STOREF>(A, B, C, R, M, N, K, lda, ldb, ldc, s);
   }
   return hipErrorInvalidValue;
 }
@@ -875,6 +882,7 @@ hipError_t launch_gemm_bf16_grouped(int layout, int epi, int n, const GemmProble
   if (!gemm_bf16_grouped_applies(layout, n, pr, K)) return hipErrorInvalidValue;
   if (layout == GEMM_TN && epi == EPI_ACCUM) return launch_direct_grouped<true, EPI_ACCUM>(n, pr, K, s);
   if (layout == GEMM_TN && epi == EPI_STORE) return launch_direct_grouped<true, EPI_STORE>(n, pr, K, s);
+  if (layout == GEMM_TN && epi == EPI_STOREF) return launch_direct_grouped<true, EPI_STOREF>(n, pr, K, s);
   if (layout == GEMM_NT && epi == EPI_STORE) return launch_direct_grouped<false, EPI_STORE>(n, pr, K, s);
   if (layout == GEMM_NT && epi == EPI_ACCUM) return launch_direct_grouped<false, EPI_ACCUM>(n, pr, K, s);
   return hipErrorInvalidValue;

@@ -60,7 +60,8 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
                                  uint32_t ldb, uint32_t ldc, void* stream) {
   REQ(A && B && C && (epilogue != 1 || R), "gemm: null operand");
   REQ(aligned16(A) && aligned16(B) && aligned16(C) && aligned16(R), "gemm: operands must be 16-byte aligned");
-  REQ(dtype <= 1 && layout <= 2 && epilogue <= 2, "gemm: bad dtype / layout / epilogue");
+  REQ(dtype <= 1 && layout <= 2 && epilogue <= 3, "gemm: bad dtype / layout / epilogue");
+  REQ(epilogue != 3 || layout == 1 || dtype == OPTSTAGE_FP32, "gemm: the fp32 store epilogue serves layout 1");
   REQ(M && N && K && M < (1u << 30) && N < (1u << 30) && K < (1u << 30), "gemm: bad extent");
   if (layout == 0) { REQ(lda >= K && ldb >= K, "gemm: leading dimension smaller than K"); }
   else if (layout == 1) { REQ(lda >= M && ldb >= N, "gemm: leading dimension smaller than the row length"); }
@@ -81,7 +82,7 @@ optstage_status optstage_op_weight_slabs(const void* src, void* dst, uint32_t N,
 
 optstage_status optstage_op_gemm_grouped(uint32_t layout, uint32_t epilogue, uint32_t n,
                                          const optstage_gemm_problem* problems, uint32_t K, void* stream) {
-  REQ(problems && n >= 1 && n <= 16 && layout <= 1 && (epilogue == 0 || epilogue == 2), "gemm_grouped: bad argument");
+  REQ(problems && n >= 1 && n <= 16 && layout <= 1 && (epilogue == 0 || epilogue == 2 || (epilogue == 3 && layout == 1)), "gemm_grouped: bad argument");
   GemmProblem pr[16];
   for (uint32_t i = 0; i < n; ++i) {
     const optstage_gemm_problem& q = problems[i];

@@ -188,7 +188,10 @@ struct OpBufs {   // device offsets an op touches, captured before its releases;
   std::vector<uint64_t> dev, host;   // [layer][kind]
 };
 
-struct TimedSpan { int op; hipEvent_t a, b; };   // op >= 0: schedule op; op < 0: kernel class -(op + 1)
+// op >= 0: schedule op; op < 0: kernel class -(op + 1); op == SPAN_STALL: the compute stream waiting for transfers.
+// trace >= 0: the entry of the executed trace that receives the span's times
+constexpr int SPAN_STALL = 100;
+struct TimedSpan { int op; hipEvent_t a, b; int trace; };
 
 }  // namespace
 
@@ -210,6 +213,14 @@ struct optstage {
   std::vector<TimedSpan> spans;
   optstage_stats stats;
   bool ktiming = false;
+  bool failed = false;           // a HIP call failed while a list was being enqueued: unusable until optstage_reset
+  bool overwrite = false;        // the first B / W of an iteration store the gradients instead of adding to them
+  hipEvent_t origin = nullptr;   // recorded on the compute stream when the first event after a reset is enqueued
+  bool origin_set = false;
+  std::vector<optstage_trace_entry> trace;   // executed events since the last reset
+  std::vector<uint8_t> reloaded;             // [chunk][mb]: a reload of this micro-batch was enqueued this iteration
+  uint64_t in_flight = 0, min_live = UINT64_MAX;
+  double sum_live = 0.0;
   char* arena() const { return (char*)desc.arena; }
   char* wsp() const { return (char*)desc.workspace; }
 };
@@ -383,8 +394,9 @@ hipEvent_t timing_event(optstage* st) {
   return st->tpool[st->tnext++];
 }
 
-optstage_status span_begin(optstage* st, int op, hipStream_t s, TimedSpan* sp) {
+optstage_status span_begin(optstage* st, int op, hipStream_t s, TimedSpan* sp, int trace = -1) {
   sp->op = op;
+  sp->trace = trace;
   sp->a = timing_event(st);
   sp->b = timing_event(st);
   if (!sp->a || !sp->b) return fail(OPTSTAGE_E_HIP, "hipEventCreate failed");
@@ -456,9 +468,9 @@ optstage_status k_norm_fwd(optstage* st, const void* x, const void* g, const voi
   KT(OPTSTAGE_KC_NORM_FWD, 2.0 * s.e * s.tokens * s.h, launch_norm_fwd(s.dtype, s.family, x, g, b, out, stats, s.tokens, s.h, st->desc.norm_eps, st->cs));
   return OPTSTAGE_OK;
 }
-optstage_status k_norm_bwd(optstage* st, const void* dn, const void* x, const float* stats, const void* g, const void* dres, void* dx, float* dg, float* db) {
+optstage_status k_norm_bwd(optstage* st, const void* dn, const void* x, const float* stats, const void* g, const void* dres, void* dx, float* dg, float* db, bool store) {
   const Shape& s = st->sh;
-  KT(OPTSTAGE_KC_NORM_BWD, 4.0 * s.e * s.tokens * s.h, launch_norm_bwd(s.dtype, s.family, dn, x, stats, g, dres, dx, (float*)(st->wsp() + st->ws.partial), dg, db, s.tokens, s.h, st->cs));
+  KT(OPTSTAGE_KC_NORM_BWD, 4.0 * s.e * s.tokens * s.h, launch_norm_bwd(s.dtype, s.family, dn, x, stats, g, dres, dx, (float*)(st->wsp() + st->ws.partial), dg, db, s.tokens, s.h, st->cs, store ? 1 : 0));
   return OPTSTAGE_OK;
 }
 optstage_status k_act_fwd(optstage* st, const void* gu, void* a) {
@@ -546,6 +558,9 @@ optstage_status exec_backward_input(optstage* st, int j, int c, const OpBufs& ob
   const bool rc = st->lg.recompute;
   const int l0 = c * s.Lc, l1 = l0 + s.Lc;
   const size_t io = (size_t)c * st->desc.n_microbatches + j;
+  // B ops of a chunk run in micro-batch order, so micro-batch 0 is the iteration's first: in overwrite mode it
+  // stores the norm parameters' gradients instead of adding to what the accumulators held
+  const bool store = st->overwrite && j == 0;
   HIP_TRY(hipMemcpyAsync(P(l1 - 1, OPTSTAGE_K_DY), st->dy_out[io], st->raw[OPTSTAGE_K_DY], hipMemcpyDeviceToDevice, cs));
   for (int l = l1 - 1; l >= l0; --l) {
     void* dy = P(l, OPTSTAGE_K_DY);
@@ -560,7 +575,7 @@ optstage_status exec_backward_input(optstage* st, int j, int c, const OpBufs& ob
     TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_GU), wgu, dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h));
     if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T));
     // dx_mid = dy + norm2'(dn2)
-    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2)));
+    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2), store));
     // do = dx_mid W_o ; attention backward ; rotary backward into the qkv buffer
     const void* wo = bwd_operand(st, l, OPTSTAGE_W_O, &lay);
     TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_DX_MID), wo, dout, nullptr, T, s.nq * s.d, s.h, s.h, s.h, s.nq * s.d));
@@ -574,7 +589,7 @@ optstage_status exec_backward_input(optstage* st, int j, int c, const OpBufs& ob
     TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_QKV), wq, dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h));
     if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_IN), W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats));
     void* dx = l > l0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[io];
-    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1)));
+    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1), store));
   }
   return OPTSTAGE_OK;
 }
@@ -594,20 +609,32 @@ optstage_status exec_backward_weight(optstage* st, int j, int c, const OpBufs& o
     pr.push_back({P(l, OPTSTAGE_K_DX_MID), P(l, OPTSTAGE_K_O), GW(st, l, OPTSTAGE_W_O), nullptr, s.h, s.nq * s.d, s.h, s.nq * s.d, s.nq * s.d});
     pr.push_back({P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_N1), GW(st, l, OPTSTAGE_W_QKV), nullptr, s.qkv_w, s.h, s.qkv_w, s.h, s.h});
   }
+  // W ops of a chunk run in micro-batch order: in overwrite mode micro-batch 0 stores its products (no read of the
+  // accumulators, and nobody has to clear them between iterations), the others add
+  const int epi = st->overwrite && j == 0 ? EPI_STOREF : EPI_ACCUM;
   for (size_t i0 = 0; i0 < pr.size(); i0 += 16) {
     const int n = (int)std::min<size_t>(16, pr.size() - i0);
     const bool grouped = s.dtype == OPTSTAGE_BF16 && gemm_bf16_grouped_applies(GEMM_TN, n, &pr[i0], T);
-    if (grouped) TRY(k_gemm_grouped(st, GEMM_TN, EPI_ACCUM, n, &pr[i0], T));
+    if (grouped) TRY(k_gemm_grouped(st, GEMM_TN, epi, n, &pr[i0], T));
     if (!grouped)
       for (int i = 0; i < n; ++i) {
         const GemmProblem& q = pr[i0 + i];
-        TRY(k_gemm(st, GEMM_TN, EPI_ACCUM, q.A, q.B, q.C, nullptr, q.M, q.N, T, q.lda, q.ldb, q.ldc));
+        TRY(k_gemm(st, GEMM_TN, epi, q.A, q.B, q.C, nullptr, q.M, q.N, T, q.lda, q.ldb, q.ldc));
       }
   }
   return OPTSTAGE_OK;
 }
 
-optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs& ob) {
+// enqueues the compute-stream wait for `n` events bracketed by a stall span
+optstage_status timed_wait(optstage* st, const hipEvent_t* evs, int n, int trace) {
+  TimedSpan sp;
+  optstage_status rc = span_begin(st, SPAN_STALL, st->cs, &sp, trace);
+  if (rc != OPTSTAGE_OK) return rc;
+  for (int i = 0; i < n; ++i) HIP_TRY(hipStreamWaitEvent(st->cs, evs[i], 0));
+  return span_end(st, st->cs, sp);
+}
+
+optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs& ob, int ti) {
   const int j = ev.microbatch, L = st->sh.L, m = st->desc.n_microbatches;
   // F / B / W carry their chunk in the layer field; a transfer belongs to the chunk that holds its layer
   const int c = ev.op <= OPTSTAGE_W ? (int)ev.layer : (int)ev.layer / st->sh.Lc;
@@ -616,20 +643,23 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
   optstage_status rc;
   switch (ev.op) {
     case OPTSTAGE_F:
-      if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
+      if ((rc = span_begin(st, ev.op, st->cs, &sp, ti)) != OPTSTAGE_OK) return rc;
       if ((rc = exec_forward(st, j, c, ob)) != OPTSTAGE_OK) return rc;
       if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
       HIP_TRY(hipEventRecord(ev_f, st->cs));
       break;
     case OPTSTAGE_B:
-      // every reload of this micro-batch must have completed (the reload ends before its consumer starts)
-      for (int l = c * st->sh.Lc; l < (c + 1) * st->sh.Lc; ++l) HIP_TRY(hipStreamWaitEvent(st->cs, st->ev_r[(size_t)j * L + l], 0));
-      if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
+      // every reload of this micro-batch must have completed (the reload ends before its consumer starts); an
+      // event that was not recorded in this iteration holds an older, completed record
+      if (st->reloaded[(size_t)c * m + j]) {
+        if ((rc = timed_wait(st, &st->ev_r[(size_t)j * L + c * st->sh.Lc], st->sh.Lc, ti)) != OPTSTAGE_OK) return rc;
+      }
+      if ((rc = span_begin(st, ev.op, st->cs, &sp, ti)) != OPTSTAGE_OK) return rc;
       if ((rc = exec_backward_input(st, j, c, ob)) != OPTSTAGE_OK) return rc;
       if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
       break;
     case OPTSTAGE_W:
-      if ((rc = span_begin(st, ev.op, st->cs, &sp)) != OPTSTAGE_OK) return rc;
+      if ((rc = span_begin(st, ev.op, st->cs, &sp, ti)) != OPTSTAGE_OK) return rc;
       if ((rc = exec_backward_weight(st, j, c, ob)) != OPTSTAGE_OK) return rc;
       if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
       break;
@@ -639,7 +669,7 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
       // a pinned slot released by a reload listed earlier may be handed to this offload: with a reload stream
       // of its own that reload must have drained first (on a shared channel stream order already says so)
       if (st->rs != st->xs && st->last_r) HIP_TRY(hipStreamWaitEvent(st->xs, st->last_r, 0));
-      if ((rc = span_begin(st, ev.op, st->xs, &sp)) != OPTSTAGE_OK) return rc;
+      if ((rc = span_begin(st, ev.op, st->xs, &sp, ti)) != OPTSTAGE_OK) return rc;
       for (int k = 0; k < NFK; ++k)
         if (ev.kind_mask & (1u << k)) {
           size_t i = (size_t)ev.layer * NK + k;
@@ -652,7 +682,7 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
     }
     case OPTSTAGE_OWAIT:
       // compute ops listed from here on may reuse the freed bytes: they start after the offload ended
-      HIP_TRY(hipStreamWaitEvent(st->cs, st->ev_o[(size_t)j * L + ev.layer], 0));
+      if ((rc = timed_wait(st, &st->ev_o[(size_t)j * L + ev.layer], 1, ti)) != OPTSTAGE_OK) return rc;
       break;
     case OPTSTAGE_R: {
       // the reload starts after the compute ops listed before it have ended
@@ -661,7 +691,7 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
       HIP_TRY(hipStreamWaitEvent(st->rs, pos, 0));
       // ... and after the offload that filled the host slot (implied by stream order on a shared channel)
       if (st->rs != st->xs) HIP_TRY(hipStreamWaitEvent(st->rs, st->ev_o[(size_t)j * L + ev.layer], 0));
-      if ((rc = span_begin(st, ev.op, st->rs, &sp)) != OPTSTAGE_OK) return rc;
+      if ((rc = span_begin(st, ev.op, st->rs, &sp, ti)) != OPTSTAGE_OK) return rc;
       for (int k = 0; k < NFK; ++k)
         if (ev.kind_mask & (1u << k)) {
           size_t i = (size_t)ev.layer * NK + k;
@@ -671,6 +701,7 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
       if ((rc = span_end(st, st->rs, sp)) != OPTSTAGE_OK) return rc;
       HIP_TRY(hipEventRecord(st->ev_r[(size_t)j * L + ev.layer], st->rs));
       st->last_r = st->ev_r[(size_t)j * L + ev.layer];
+      st->reloaded[(size_t)c * m + j] = 1;
       break;
     }
   }
@@ -700,6 +731,7 @@ optstage_status precheck(optstage* st, const optstage_event* events, size_t n) {
 
 optstage_status run_list(optstage* st, const optstage_event* events, size_t n) {
   if (!st || (!events && n)) return fail(OPTSTAGE_E_ARG, "null argument");
+  if (st->failed) return fail(OPTSTAGE_E_STATE, "an earlier call failed while enqueueing: call optstage_synchronize and optstage_reset");
   optstage_status rc = precheck(st, events, n);
   if (rc != OPTSTAGE_OK) return rc;
   {
@@ -711,10 +743,29 @@ optstage_status run_list(optstage* st, const optstage_event* events, size_t n) {
         return fail(rc, "event %zu: %s", i, tmp);
       }
   }
+  if (n && !st->origin_set) {
+    HIP_TRY(hipEventRecord(st->origin, st->cs));
+    st->origin_set = true;
+  }
   OpBufs ob;
   for (size_t i = 0; i < n; ++i) {
     if ((rc = apply_event(st->lg, events[i], &ob)) != OPTSTAGE_OK) return rc;   // cannot fail: same steps as the trial
-    if ((rc = exec_event(st, events[i], ob)) != OPTSTAGE_OK) return rc;
+    if (events[i].op == OPTSTAGE_F) st->in_flight++;
+    if (events[i].op == OPTSTAGE_W) st->in_flight--;
+    st->sum_live += (double)st->lg.live;
+    if (st->in_flight && st->lg.live < st->min_live) st->min_live = st->lg.live;
+    optstage_trace_entry te;
+    memset(&te, 0, sizeof te);
+    te.op = events[i].op; te.microbatch = events[i].microbatch; te.layer = events[i].layer; te.kind_mask = events[i].kind_mask;
+    te.live_bytes = st->lg.live;
+    te.start_ms = te.end_ms = -1.0;
+    st->trace.push_back(te);
+    if ((rc = exec_event(st, events[i], ob, (int)st->trace.size() - 1)) != OPTSTAGE_OK) {
+      // the accounting is ahead of what was enqueued and an op graph may be half launched: nothing more runs on
+      // this handle until optstage_reset
+      st->failed = true;
+      return rc;
+    }
   }
   return OPTSTAGE_OK;
 }
@@ -803,6 +854,12 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
       if (hipEventCreateWithFlags(&v[i], hipEventDisableTiming) != hipSuccess) return false;
     return true;
   };
+  st->reloaded.assign(nio, 0);
+  if (hipEventCreate(&st->origin) != hipSuccess) {
+    st->origin = nullptr;
+    optstage_destroy(st);
+    return fail(OPTSTAGE_E_HIP, "hipEventCreate failed");
+  }
   if (!mk(st->ev_f, nio) || !mk(st->ev_o, m * L) || !mk(st->ev_r, m * L) || !mk(st->ev_pos, m * L)) {
     optstage_destroy(st);
     return fail(OPTSTAGE_E_HIP, "hipEventCreateWithFlags failed");
@@ -820,6 +877,7 @@ void optstage_destroy(optstage_t* st) {
   if (!st) return;
   for (auto* v : {&st->ev_f, &st->ev_o, &st->ev_r, &st->ev_pos, &st->tpool})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
+  if (st->origin) (void)hipEventDestroy(st->origin);
   delete st;
 }
 
@@ -928,7 +986,21 @@ optstage_status optstage_synchronize(optstage_t* st) {
   for (const TimedSpan& sp : st->spans) {
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
-    if (sp.op >= 0) st->stats.ms_ops[sp.op] += ms; else st->stats.kernel_ms[-sp.op - 1] += ms;
+    if (sp.op == SPAN_STALL) {
+      const bool reload = sp.trace >= 0 && st->trace[sp.trace].op == OPTSTAGE_B;
+      st->stats.stall_ms[reload ? 1 : 0] += ms;
+      if (sp.trace >= 0) st->trace[sp.trace].stall_ms += ms;
+    } else if (sp.op >= 0) {
+      st->stats.ms_ops[sp.op] += ms;
+      if (sp.trace >= 0 && st->origin_set) {
+        float t0 = 0.f;
+        HIP_TRY(hipEventElapsedTime(&t0, st->origin, sp.a));
+        st->trace[sp.trace].start_ms = t0;
+        st->trace[sp.trace].end_ms = t0 + ms;
+      }
+    } else {
+      st->stats.kernel_ms[-sp.op - 1] += ms;
+    }
   }
   st->spans.clear();
   st->tnext = 0;
@@ -941,6 +1013,13 @@ optstage_status optstage_reset(optstage_t* st) {
   reset_logical(st);
   memset(&st->stats, 0, sizeof st->stats);
   st->last_r = nullptr;
+  st->failed = false;
+  st->origin_set = false;
+  st->trace.clear();
+  std::fill(st->reloaded.begin(), st->reloaded.end(), 0);
+  st->in_flight = 0;
+  st->min_live = UINT64_MAX;
+  st->sum_live = 0.0;
   return OPTSTAGE_OK;
 }
 
@@ -956,6 +1035,23 @@ optstage_status optstage_get_stats(optstage_t* st, optstage_stats* out) {
   out->live_bytes = st->lg.live;
   out->peak_bytes = st->lg.peak;
   out->arena_high_water = st->lg.arena.high_water();
+  out->n_trace = st->trace.size();
+  out->min_live_bytes = st->min_live == UINT64_MAX ? 0 : st->min_live;
+  out->avg_live_bytes = st->trace.empty() ? 0.0 : st->sum_live / (double)st->trace.size();
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_get_trace(optstage_t* st, optstage_trace_entry* out, size_t capacity, size_t* n_total) {
+  if (!st || (!out && capacity)) return fail(OPTSTAGE_E_ARG, "null argument");
+  if (n_total) *n_total = st->trace.size();
+  const size_t n = std::min(capacity, st->trace.size());
+  if (n) memcpy(out, st->trace.data(), n * sizeof(optstage_trace_entry));
+  return OPTSTAGE_OK;
+}
+
+optstage_status optstage_set_grad_overwrite(optstage_t* st, uint32_t on) {
+  if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
+  st->overwrite = on != 0;
   return OPTSTAGE_OK;
 }
 
@@ -989,6 +1085,7 @@ optstage_status optstage_debug_read(optstage_t* st, uint32_t mb, uint32_t layer,
   const BufRec& b = st->lg.buf(mb, layer, kind);
   if (b.state != B_DEV && b.state != B_OFFLOADING && b.state != B_RELOADED) return fail(OPTSTAGE_E_STATE, "buffer has no device copy");
   HIP_TRY(hipStreamSynchronize(st->xs));
+  if (st->rs != st->xs) HIP_TRY(hipStreamSynchronize(st->rs));      // a reload into this buffer may be in flight there
   HIP_TRY(hipMemcpyAsync(dst, st->arena() + b.dev_off, st->raw[kind], hipMemcpyDeviceToHost, st->cs));
   HIP_TRY(hipStreamSynchronize(st->cs));
   return OPTSTAGE_OK;

@@ -33,10 +33,12 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 
 class Stage:
     def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0,
-                 duplex: bool = False, recompute: bool = False, n_chunks: int = 1):
+                 duplex: bool = False, recompute: bool = False, n_chunks: int = 1, grad_overwrite: bool = False):
         """duplex: reloads get a stream of their own instead of sharing the offloads' (single channel).
         recompute: F keeps no norm outputs and no MLP activation output; B rebuilds them for W.
-        n_chunks: model chunks on this stage (cfg.n_layers counts all of them)."""
+        n_chunks: model chunks on this stage (cfg.n_layers counts all of them).
+        grad_overwrite: the first B / W of an iteration store the parameter gradients instead of adding to them, so
+        the accumulators need no clearing between iterations."""
         if not torch.cuda.is_available():
             raise RuntimeError("optstage needs a GPU: there is no CPU path")
         self.cfg = cfg
@@ -63,6 +65,8 @@ class Stage:
         h = C.c_void_p()
         B.check(self.lib.optstage_create(C.byref(self.desc), C.byref(h)))
         self.h = h
+        if grad_overwrite:
+            B.check(self.lib.optstage_set_grad_overwrite(self.h, 1))
         self.weights, self.grads = [], []
         self.x, self.dy, self.y, self.dx = {}, {}, {}, {}
 
@@ -165,6 +169,17 @@ class Stage:
         s = B.Stats()
         B.check(self.lib.optstage_get_stats(self.h, C.byref(s)))
         return s
+
+    def trace(self) -> list:
+        """Executed events since the last reset: (op name, micro-batch, layer or chunk, kind_mask, live bytes after the
+        event, start ms, end ms, stall ms); times are valid after synchronize()."""
+        n = C.c_size_t(0)
+        B.check(self.lib.optstage_get_trace(self.h, None, 0, C.byref(n)))
+        arr = (B.TraceEntry * max(1, n.value))()
+        B.check(self.lib.optstage_get_trace(self.h, arr, n.value, None))
+        names = {v: k for k, v in B.OP_CODE.items()}
+        return [(names[e.op], e.microbatch, e.layer, e.kind_mask, e.live_bytes, e.start_ms, e.end_ms, e.stall_ms)
+                for e in arr[:n.value]]
 
     def checksum(self, mb, layer, kind, where=0):
         out = (C.c_uint64 * 2)()

@@ -77,3 +77,38 @@ def output_grad(cfg: StageConfig, mb: int) -> np.ndarray:
     r = _rng(cfg.seed, _TAG_DY, mb)
     g = r.standard_normal((cfg.seq * cfg.micro_batch, cfg.hidden), dtype=np.float32) * np.float32(1e-3)
     return quantize(g, cfg.dtype)
+
+
+# ---- the same distributions drawn on the device (host generation of several GiB of weights is slow): seeded
+# torch generators, so a tensor can be rebuilt alone; checks against the oracle read these tensors back
+
+def device_weights(cfg: StageConfig) -> list:
+    """Per layer dict name -> device tensor in the workload dtype: linear weights N(0, 0.02), gains 1 + N(0, 0.02),
+    biases N(0, 0.02)."""
+    import torch
+    g = torch.Generator(device="cuda")
+    dt = torch.bfloat16 if cfg.dtype == BF16 else torch.float32
+    out = []
+    for l in range(cfg.n_layers):
+        w = {}
+        for i, (name, shape) in enumerate(weight_shapes(cfg).items()):
+            g.manual_seed(cfg.seed * 1000003 + l * 101 + i)
+            t = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * 0.02
+            if name in ("g1", "g2"):
+                t = t + 1.0
+            w[name] = t.to(dt).contiguous()
+        out.append(w)
+    return out
+
+
+def device_io(cfg: StageConfig, mb: int):
+    """(stage input N(0, 1), output gradient N(0, 1e-3)) of micro-batch mb as device tensors in the workload dtype."""
+    import torch
+    g = torch.Generator(device="cuda")
+    dt = torch.bfloat16 if cfg.dtype == BF16 else torch.float32
+    shape = (cfg.seq * cfg.micro_batch, cfg.hidden)
+    g.manual_seed(cfg.seed * 1000003 + 50000 + mb)
+    x = torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(dt)
+    g.manual_seed(cfg.seed * 1000003 + 90000 + mb)
+    dy = (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * 1e-3).to(dt)
+    return x.contiguous(), dy.contiguous()

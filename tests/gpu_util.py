@@ -32,20 +32,48 @@ def rms_err(got, ref):
     return float(num / den) if den > 0 else float(num)
 
 
-# RMS-relative bound beside TOL.  Every stored bf16 value carries a rounding error of up to 2^-9 of its magnitude,
-# 2^-9 / sqrt(3) = 1.1e-3 RMS; a result that went through n roundings of comparable weight sits near sqrt(n) times
-# that (4-5 layers of ten stored tensors each: about 8e-3).  fp32: 2^-24 / sqrt(3) per operation.
-RMS_TOL = {0: 2e-5, 1: 1e-2}
-OBSERVED = []       # (label, max-relative, RMS-relative) of every close() call, printed by the tests that want a record
+def block_rms_err(got, ref, blocks=8):
+    """Largest RMS-relative error over a blocks x blocks partition of the tensor (blocks pieces for a vector), each
+    block measured against its OWN reference energy: a wrong region whose values are small against the rest of the
+    tensor (early attention rows, one mis-scaled column group) stands out here and nowhere else."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if got.ndim == 1:
+        got, ref = got[None, :], ref[None, :]
+    got, ref = got.reshape(-1, got.shape[-1]), ref.reshape(-1, ref.shape[-1])
+    worst = 0.0
+    for rg, rr in zip(np.array_split(got, min(blocks, got.shape[0]), axis=0), np.array_split(ref, min(blocks, ref.shape[0]), axis=0)):
+        for cg, cr in zip(np.array_split(rg, min(blocks, rg.shape[1]), axis=1), np.array_split(rr, min(blocks, rr.shape[1]), axis=1)):
+            den = np.sqrt(np.mean(cr * cr))
+            num = np.sqrt(np.mean((cg - cr) ** 2))
+            worst = max(worst, float(num / den) if den > 0 else float(num))
+    return worst
+
+
+# Bounds on the two L2 measures, beside TOL on the infinity-norm one: the tolerance the workloads state, applied to
+# the whole tensor's RMS-relative error and to every block's.  What rounding alone predicts: a stored bf16 value is
+# off by up to 2^-9 of its magnitude, 2^-9 / sqrt(3) = 1.1e-3 RMS; a stage output has about 12 such roundings per
+# layer behind it (ten stored tensors, the attention probabilities and their gradients inside the kernels), a
+# gradient about 24, adding in quadrature: sqrt(24 * 5) * 1.1e-3 = 1.2e-2 for five layers.  fp32: 1e-4 as for TOL.
+RMS_TOL = {0: 1e-4, 1: 2e-2}
+OBSERVED = []       # (label, max-relative, RMS-relative, worst block RMS-relative) of every close() call
 
 
 def close(got, ref, dtype, label="", tol=None, rms_tol=None):
-    """Asserts both error measures and records them."""
-    e, r = rel_err(got, ref), rms_err(got, ref)
-    OBSERVED.append((label, e, r))
-    assert e < (TOL[dtype] if tol is None else tol), (label, "max-relative", e)
-    assert r < (RMS_TOL[dtype] if rms_tol is None else rms_tol), (label, "rms-relative", r)
+    """Asserts the three error measures and records them."""
+    e, r, bl = rel_err(got, ref), rms_err(got, ref), block_rms_err(got, ref)
+    OBSERVED.append((label, e, r, bl))
+    assert e < (TOL[dtype] if tol is None else tol), (label, "max-relative", e, r, bl)
+    assert r < (RMS_TOL[dtype] if rms_tol is None else rms_tol), (label, "rms-relative", e, r, bl)
+    assert bl < (RMS_TOL[dtype] if rms_tol is None else rms_tol), (label, "block rms-relative", e, r, bl)
     return e, r
+
+
+def report(out=print):
+    """Prints and clears the record of close() calls."""
+    for label, e, r, bl in OBSERVED:
+        out(f"  {label}: max-rel {e:.2e} rms-rel {r:.2e} worst-block rms-rel {bl:.2e}")
+    del OBSERVED[:]
 
 
 def dev(a, dtype):

@@ -15,7 +15,7 @@ from paper_2510_05186_amd.stage import Stage
 from stage_inputs import configs as CFG
 from stage_inputs import schedules as G
 from stage_inputs import tensors as T
-from gpu_util import TOL, host, ok, oracle_shape, oracle_weights, rel_err, stream
+from gpu_util import TOL, close, report, host, ok, oracle_shape, oracle_weights, rel_err, stream
 
 pytestmark = pytest.mark.gpu
 BF16 = 1
@@ -136,9 +136,10 @@ def test_attention_full_size_whole_heads(seq, nq, nkv, heads):
     assert rel_err(host(DQKV[:, (nq + nkv + g) * d:(nq + nkv + g + 1) * d]), dv[:, 0]) < TOL[BF16]
 
 
-@pytest.mark.parametrize("base", [CFG.CFG2, CFG.CFG6, CFG.CFG4], ids=lambda c: c.name)
+@pytest.mark.parametrize("base", [CFG.CFG2, CFG.CFG6, CFG.CFG4, CFG.CFG5], ids=lambda c: c.name)
 def test_one_whole_layer_at_full_shape_against_oracle(base):
-    """cfg 4 (hidden 8192, 64 query heads on 8 kv heads, MLP 28672) takes the oracle about 22 TFLOP in fp64."""
+    """cfg 4 (hidden 8192, 64 query heads on 8 kv heads, MLP 28672) takes the oracle about 22 TFLOP in fp64, the
+    long-sequence stage (16384 tokens, hidden 5120) about 41."""
     print(f"whole layer of {base.name}: GPU F/B/W, then the fp64 oracle on the host", flush=True)
     cfg = replace(base, name=base.name + "_one_layer", n_layers=1, n_microbatches=1)
     ws = T.stage_weights(cfg)
@@ -149,12 +150,13 @@ def test_one_whole_layer_at_full_shape_against_oracle(base):
     st.run([("F", 0), ("B", 0), ("W", 0)])
     st.synchronize()
     y, dx, dW, dn = O.stage_fbw(oracle_shape(cfg), oracle_weights(ws), x.astype(np.float64), dy.astype(np.float64), attn_chunk=1024)
-    tol = TOL[BF16]
-    assert rel_err(host(st.y[0]), y) < tol and rel_err(host(st.dx[0]), dx) < tol
+    close(host(st.y[0]), y, BF16, f"{base.name} one layer y")
+    close(host(st.dx[0]), dx, BF16, f"{base.name} one layer dx")
     for name in ("wqkv", "wo", "wgu", "wd"):
-        assert rel_err(host(st.grads[0][name]), dW[0][name]) < tol, name
+        close(host(st.grads[0][name]), dW[0][name], BF16, f"{base.name} one layer dW {name}")
     for name in dn[0]:                     # norm gains (and biases for LayerNorm)
-        assert rel_err(host(st.grads[0][name]), dn[0][name]) < tol, name
+        close(host(st.grads[0][name]), dn[0][name], BF16, f"{base.name} one layer d{name}")
+    report()
     assert st.stats().live_bytes == 0
     st.close()
 

@@ -651,3 +651,116 @@ def test_create_rejects_bad_descriptors():
     d.struct_size = 8
     assert lib.optstage_query_sizes(C.byref(d), None, None, None) == B.E_ARG
     assert lib.optstage_create(None, C.byref(h)) == B.E_ARG
+
+
+def test_stepwise_calls_drive_a_whole_iteration_with_offload():
+    """Every step-wise symbol on its success path: two micro-batches through forward, offload, offload_wait,
+    reload, backward_input, backward_weight; results against the oracle, accounting against the oracle's after
+    every call, the offloaded buffer bit for bit."""
+    cfg = replace(SMALL2, n_microbatches=2)
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    lib = B.lib()
+    mask = (1 << B.KIND_ID["X_IN"]) | (1 << B.KIND_ID["QKV"])
+    kinds = ("X_IN", "QKV")
+    pool = 4 * sum(t[k] for k in kinds)
+    st = Stage(cfg, host_pool_bytes=pool)
+    st.set_weights(ws)
+    for j in range(2):
+        st.bind(j, T.stage_input(cfg, j), T.output_grad(cfg, j))
+    steps = [("F", 0), ("O", 0, 1, kinds), ("F", 1), ("OWAIT", 0, 1, kinds), ("R", 0, 1, kinds), ("B", 0), ("W", 0),
+             ("O", 1, 0, kinds), ("OWAIT", 1, 0, kinds), ("R", 1, 0, kinds), ("B", 1), ("W", 1)]
+    S.check_order(steps, 2, cfg.n_layers)
+    _, trace = S.account_memory(steps, cfg.n_layers, t)
+    call = {"F": lambda e: lib.optstage_forward(st.h, e[1]), "B": lambda e: lib.optstage_backward_input(st.h, e[1]),
+            "W": lambda e: lib.optstage_backward_weight(st.h, e[1]),
+            "O": lambda e: lib.optstage_offload(st.h, e[1], e[2], mask),
+            "OWAIT": lambda e: lib.optstage_offload_wait(st.h, e[1], e[2], mask),
+            "R": lambda e: lib.optstage_reload(st.h, e[1], e[2], mask)}
+    sums = {}
+    st._order_after_torch()
+    for n, e in enumerate(steps):
+        if e[0] == "O":
+            sums[e[1:3]] = [st.checksum(e[1], e[2], k) for k in kinds]
+        B.check(call[e[0]](e))
+        assert st.stats().live_bytes == trace[n], (n, e)
+        if e[0] == "O":
+            assert [st.checksum(e[1], e[2], k, where=1) for k in kinds] == sums[e[1:3]]
+        if e[0] == "R":
+            assert [st.checksum(e[1], e[2], k) for k in kinds] == sums[e[1:3]]
+    st.synchronize()
+    compare(cfg, st, oracle_run(cfg, ws))
+    s = st.stats()
+    assert s.bytes_offloaded == s.bytes_reloaded == 2 * sum(t[k] for k in kinds)
+    st.close()
+
+
+def test_grad_overwrite_mode_needs_no_cleared_accumulators():
+    """The first B / W of an iteration store the parameter gradients: accumulators full of NaN before every
+    iteration end up bit for bit where zeroed accumulators end up, on the grouped, the single-product and the
+    fp32 weight-gradient paths."""
+    for cfg in (SMALL2, SMALLG, replace(CFG.CFG1, n_microbatches=3)):
+        ws = T.stage_weights(cfg)
+        events = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches)[cfg.stage_index]
+        ref = gpu_run(cfg, ws, events)
+        st = Stage(cfg, grad_overwrite=True)
+        st.set_weights(ws)
+        for j in range(cfg.n_microbatches):
+            st.bind(j, T.stage_input(cfg, j), T.output_grad(cfg, j))
+        for it in range(2):
+            for g in st.grads:
+                for v in g.values():
+                    v.fill_(float("nan"))
+            st.reset()
+            st.run(events)
+            st.synchronize()
+            for l in range(cfg.n_layers):
+                for name in st.grads[l]:
+                    assert torch.equal(st.grads[l][name], ref.grads[l][name]), (cfg.name, it, l, name)
+        st.close()
+        ref.close()
+
+
+def test_stats_report_the_trace_the_live_levels_and_the_stalls():
+    cfg = SMALL2
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    comp = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches)[cfg.stage_index]
+    events = G.add_offload(comp, cfg.n_layers, ("X_IN", "QKV", "X_MID"), min_gap=1, lead=0, wait_delay=0)
+    S.check_order(events, cfg.n_microbatches, cfg.n_layers)
+    peak, trace = S.account_memory(events, cfg.n_layers, t)
+    pool = sum(t[k] for k in ("X_IN", "QKV", "X_MID")) * cfg.n_layers * cfg.n_microbatches
+    st = gpu_run(cfg, ws, events, host_pool_bytes=pool)
+    s = st.stats()
+    tr = st.trace()
+    assert s.n_trace == len(events) == len(tr)
+    names = {v: k for k, v in B.KIND_ID.items()}
+    for e, got in zip(events, tr):
+        assert got[0] == e[0] and got[1] == e[1]
+        if e[0] in ("O", "OWAIT", "R"):
+            assert got[2] == e[2] and {names[b] for b in range(12) if got[3] >> b & 1} == set(e[3])
+    assert [g[4] for g in tr] == trace
+    assert s.avg_live_bytes == pytest.approx(sum(trace) / len(trace), rel=1e-12)
+    in_flight, level = 0, []
+    for e, lv in zip(events, trace):
+        in_flight += (e[0] == "F") - (e[0] == "W")
+        if in_flight:
+            level.append(lv)
+    assert s.min_live_bytes == min(level) > 0 and s.peak_bytes == peak
+    # times: compute ops do not overlap and follow list order; a transfer lies after the F that made its data; every
+    # OWAIT here has nothing between it and its offload, and every reload nothing between it and its B, so the compute
+    # stream must have waited for them
+    ends = {}
+    last_end = 0.0
+    for g in tr:
+        if g[0] in ("F", "B", "W"):
+            assert g[5] >= last_end - 1e-3 and g[6] > g[5]
+            last_end = g[6]
+            ends[(g[0], g[1])] = g[6]
+        elif g[0] == "OWAIT":
+            assert g[5] == -1.0 and g[7] >= 0.0
+        elif g[0] == "O":
+            assert g[5] >= ends[("F", g[1])] - 1e-3 and g[6] > g[5]
+    assert s.stall_ms[0] > 0.0 and s.stall_ms[1] > 0.0
+    assert s.stall_ms[0] + s.stall_ms[1] == pytest.approx(sum(g[7] for g in tr), rel=1e-6)
+    st.close()
