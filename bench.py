@@ -1,10 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the stage hot path on one MI355X.
 
-A step is one pass of the whole per-stage schedule (all m micro-batches: F, B, W of every one, in the
-schedule's order) over synthetic tensors already resident in HBM.  Default workload: the Llama-style
-bf16 stage (4 layers, hidden 4096, 32 heads x 128, SwiGLU 11008, seq 4096; stage 1 of p = 8, m = 16,
-split B/W schedule, no offload).  Prints ONE JSON line.
+A step is one pass of the whole per-stage schedule (all m micro-batches: F, B, W of every one, plus the offloads
+and reloads its memory budget needs, in the schedule's order) over synthetic tensors already resident in HBM.
+
+Headline workload: the largest one a single GPU holds, the grouped-query bf16 stage (5 layers, hidden 8192,
+64 query / 8 kv heads x 128, SwiGLU 28672, seq 4096; stage 3 of p = 16, m = 32) under its 120 GB activation budget,
+with the dense-fill split B/W list the library's generator builds for that budget (offloads chosen item by item).
+The other single-GPU workloads run as short named legs in the same process: the Llama bf16 stage without a budget,
+the same shapes under 40 % of its activation peak (one transfer channel and two), the long-sequence stage under
+64 GB.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -12,6 +17,7 @@ import argparse
 import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,6 +27,16 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBPS = 8000.0
+HEADLINE = "cfg4_gqa_bf16"
+KERNEL_SOURCES = {"gemm": "gemm_bf16.hip", "attn": "attention_mfma.hip", "norm": "elementwise.hip", "act": "elementwise.hip",
+                  "rope": "elementwise.hip"}
+KERNEL_NAMES = {"gemm_nt_store": "gemm_bf16_direct_kernel<NT, store>", "gemm_nt_resid": "gemm_bf16_direct_kernel<NT, residual>",
+                "gemm_tn_accum": "gemm_bf16_direct_grouped_kernel<TN, fp32 accumulate>", "attn_fwd": "attn_fwd_mfma",
+                "attn_bwd": "attn_bwd_dq_mfma + attn_bwd_dkv_mfma"}
+
+CHUNKS = 1      # --chunks: model chunks on the stage (interleaved 1F1B instead of the configuration's schedule)
+RECOMPUTE = 0   # --recompute: the memory-table variant in which F keeps no norm outputs and no MLP activation output
 
 
 def schedule_flops(cfg):
@@ -32,116 +48,87 @@ def schedule_flops(cfg):
     return cfg.n_layers * (3 * gemm + 7 * att)
 
 
-def nt_store_algorithmic_bytes(cfg):
-    """Mean algorithmic HBM bytes of one launch of the dominant kernel class (C = A B^T, plain store): each
-    operand read once and the result written once, (M K + N K + M N) * elem_size, averaged over the six such
-    GEMMs a layer runs per micro-batch (QKV and gate/up projections in F; the four dX GEMMs of B)."""
+def class_algorithmic_bytes(cfg, name):
+    """Mean algorithmic HBM bytes of one launch of a GEMM kernel class: every operand read once, the result written
+    once (and read once where the epilogue adds to it), averaged over the launches of the class in one layer."""
     t, h, f = cfg.seq * cfg.micro_batch, cfg.hidden, cfg.ffn
     hq = cfg.n_q_heads * cfg.head_dim
-    shapes = [(t, cfg.qkv_width, h), (t, cfg.up_width, h), (t, f, h), (t, h, cfg.up_width), (t, hq, h), (t, h, cfg.qkv_width)]
     es = 2 if cfg.dtype == 1 else 4
-    return sum((m * k + n * k + m * n) * es for m, n, k in shapes) / len(shapes)
+    if name == "gemm_nt_store":       # QKV and gate/up projections in F; the four dX products of B
+        shapes = [(t, cfg.qkv_width, h), (t, cfg.up_width, h), (t, f, h), (t, h, cfg.up_width), (t, hq, h), (t, h, cfg.qkv_width)]
+        return sum((m * k + n * k + m * n) * es for m, n, k in shapes) / len(shapes)
+    if name == "gemm_nt_resid":       # output and down projections with the residual added
+        shapes = [(t, h, hq), (t, h, f)]
+        return sum((m * k + n * k + 2 * m * n) * es for m, n, k in shapes) / len(shapes)
+    if name == "gemm_tn_accum":       # one grouped launch: the 4 L weight-gradient products of a W op
+        shapes = [(h, f, t), (cfg.up_width, h, t), (h, hq, t), (cfg.qkv_width, h, t)]
+        return cfg.n_layers * sum((m * k + n * k) * es + 2 * m * n * 4 for m, n, k in shapes)
+    return None
 
 
-def measured_traffic(cfg):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of this same
-    command (FETCH_SIZE and WRITE_SIZE, scaled by what a plain copy of known size reads); None when no
-    summary exists for this workload."""
-    import re
+def measured_traffic(cfg, kernel_class):
+    """HBM bytes per launch of a kernel class from the committed rocprofv3 --pmc summary of this same command
+    (FETCH_SIZE and WRITE_SIZE scaled by what a plain copy of known size reads), and the digest of the kernel source
+    the summary was taken with; None when there is no summary for this workload and class, or when the kernel
+    source has changed since (the figure would describe another kernel)."""
     path = os.path.join(ROOT, "profiles", f"bench_{cfg.name.split('_')[0]}_hbm_traffic.md")
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), re.M)
+        text = open(path).read()
     except OSError:
         return None
-    return int(m.group(1)) if m else None
+    m = re.search(rf"^traffic_bytes_per_launch\[{kernel_class}\]:\s*(\d+)", text, re.M)
+    d = re.search(r"^kernel_source_sha256\[(\S+)\]:\s*([0-9a-f]+)", text, re.M)
+    if not m or not d:
+        return None
+    src = os.path.join(ROOT, "paper_2510_05186_amd", "csrc", d.group(1))
+    if hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] != d.group(2)[:16]:
+        return None
+    return int(m.group(1))
 
 
-CHUNKS = 1      # --chunks: model chunks on the stage (interleaved 1F1B instead of the configuration's schedule)
-RECOMPUTE = 0   # --recompute: the memory-table variant in which F keeps no norm outputs and no MLP activation output
-
-
-def adaoffload_instance(cfg, budget, tflops=900.0, link_gbps=56.0):
-    """The paper's abstract instance for this workload (all p stages alike): op times from the flop counts at a
-    nominal rate, transfer time from the offloadable bytes at the measured host-link rate, Eq. 7's parameters
-    from the library's memory table."""
+def workload_budget(cfg):
     from paper_2510_05186_amd import binding as B
-    from paper_2510_05186_amd import scheduler as SC
-    s, h, f = cfg.seq * cfg.micro_batch, cfg.hidden, cfg.ffn
-    gemm = 2 * s * (cfg.qkv_width * h + h * cfg.n_q_heads * cfg.head_dim + cfg.up_width * h + h * f)
-    att = cfg.micro_batch * cfg.seq * cfg.seq * cfg.n_q_heads * cfg.head_dim
-    ms = lambda fl: cfg.n_layers * fl / (tflops * 1e9)
-    t_op = {"F": ms(gemm + 2 * att), "B": ms(gemm + 5 * att), "W": ms(gemm)}
-    _, act_per_mb, kb = B.query_sizes(cfg, recompute=RECOMPUTE)
-    gamma = sum(kb[k] for k in cfg.offload_kinds) * cfg.n_layers
-    slack = 2 * (kb["DY"] + kb["DX_MID"])                 # what B holds beyond the forward activations
-    rebuilt = RECOMPUTE * cfg.n_layers * (kb["N1"] + kb["N2"] + kb["A"])    # B makes them, W releases them
-    p = cfg.n_stages
-    return SC.Instance(p=p, m=cfg.n_microbatches, t_op=[t_op] * p, t_comm=0.0, t_off=[gamma / (link_gbps * 1e6)] * p,
-                       delta=[{"F": act_per_mb, "B": rebuilt, "W": -act_per_mb - rebuilt}] * p, gamma=[gamma] * p,
-                       limit=[max(budget - slack, act_per_mb)] * p, offload_stages=tuple(range(p)),
-                       item=(0, tuple(cfg.offload_kinds)))
-
-
-def build_schedule(cfg, budget=0, generator="greedy"):
-    """Event list of this stage for the configuration's schedule family; with a budget the generator's
-    knobs (in-flight cap, which micro-batches to offload, how long copies may overlap) are searched with the
-    library's own planner until the list fits.  generator "adaoffload": the dense-fill list of the paper's
-    Alg. 1 for the whole pipeline, this stage's part, repaired against the planner if it does not fit as is."""
-    from paper_2510_05186_amd import binding as B
+    from stage_inputs import configs as CFG
     from stage_inputs import schedules as G
-    p, m, i = cfg.n_stages, cfg.n_microbatches, cfg.stage_index
+    if cfg.budget_bytes:
+        return cfg.budget_bytes
+    if cfg.budget_frac_of_peak:
+        base = G.split_bw_greedy(CFG.CFG2.n_stages, CFG.CFG2.n_microbatches)[CFG.CFG2.stage_index]
+        return int(cfg.budget_frac_of_peak * B.plan(CFG.CFG2, base)[2])
+    return 0
+
+
+def build_lists(cfg, budget, duplex=False, t_op=None, link_gbps=55.0):
+    """The lists of all p stages (each shaped like this one) and what the generator decided."""
+    from paper_2510_05186_amd import scheduler as SC
+    from stage_inputs import schedules as G
+    p, m = cfg.n_stages, cfg.n_microbatches
     if CHUNKS > 1:
         if budget:
-            raise RuntimeError("--chunks runs the interleaved list without a budget search")
-        return G.interleaved_one_f_one_b(p, m, i, CHUNKS), {"schedule": "interleaved 1F1B", "chunks": CHUNKS}
-    if budget and generator == "adaoffload":
-        from paper_2510_05186_amd import scheduler as SC
-        inst = adaoffload_instance(cfg, budget)
-        sol = SC.adaoffload(inst, tolerance=0.5 * inst.t_op[0]["F"])
-        ev = SC.expand_items(sol.lists[i], cfg.n_layers, cfg.offload_kinds)
-        fits = lambda e: (lambda r: (r[0] == B.OK, r[1]))(B.plan(cfg, e, budget=budget, recompute=RECOMPUTE))
-        knobs = {"generator": "adaoffload", "offload": any(e[0] == "O" for e in ev), "placement": "as generated"}
-        build_schedule.all_stages = [SC.expand_items(l, cfg.n_layers, cfg.offload_kinds) for l in sol.lists]
-        if not fits(ev)[0]:
-            ev = G.repair_to_fit(ev, fits)
-            knobs["placement"] = "repaired"
-        if ev is not None:
-            return ev, knobs
+            raise RuntimeError("--chunks runs the interleaved list without a budget")
+        return [G.interleaved_one_f_one_b(p, m, i, CHUNKS) for i in range(p)], {"schedule": "interleaved 1F1B", "chunks": CHUNKS}
     if cfg.schedule == "1f1b":
-        return G.one_f_one_b(p, m, i), {}
-    if not budget:
-        return G.split_bw_greedy(p, m)[i], {}
-    for cap in range(p - i, 0, -1):
-        comp = G.split_bw_greedy(p, m, cap_of_stage=lambda s, c=cap: c)[i]
-        if B.plan(cfg, comp, budget=budget, recompute=RECOMPUTE)[0] == B.OK:
-            return comp, {"in_flight_cap": cap, "offload": False}
-        def fits(ev):
-            st, bad, _, _ = B.plan(cfg, ev, budget=budget, recompute=RECOMPUTE)
-            return st == B.OK, bad
-        for lead in (2, 1):
-            # optimistic placement (copies overlap neighbouring ops), then repaired against the planner
-            ev = G.add_offload(comp, cfg.n_layers, cfg.offload_kinds, min_gap=1, lead=lead, wait_delay=2)
-            if not any(e[0] == "O" for e in ev):
-                continue
-            ev = G.repair_to_fit(ev, fits)
-            if ev is not None:
-                return ev, {"in_flight_cap": cap, "offload": True, "lead": lead, "placement": "repaired"}
-    raise RuntimeError("no schedule fits the budget")
+        return [G.one_f_one_b(p, m, i) for i in range(p)], {"schedule": "1F1B"}
+    lists, info = SC.workload_lists(cfg, budget, t_op=t_op, link_gbps=link_gbps, duplex=duplex, recompute=RECOMPUTE)
+    i = cfg.stage_index
+    knobs = {"generator": "split B/W greedy fill" + (", per-item offload under the budget, fill level by modelled makespan" if budget else ""),
+             "in_flight_cap": info["caps"][i], "extra_fill": info["extra_fill"],
+             "offload": info["offloaded_bytes"][i] > 0, "offloaded_bytes_per_step": info["offloaded_bytes"][i]}
+    if "makespan_model" in info:
+        knobs["model_makespan_ms"] = info["makespan_model"]
+        knobs["candidates"] = [(c["extra_fill"], round(c["makespan_model"], 1)) for c in info["candidates"]]
+    return lists, knobs
 
 
-def make_stage(cfg, events, budget, torch, duplex=False):
+def make_stage(cfg, events, budget, duplex=False):
     from paper_2510_05186_amd import binding as B
-    from stage_inputs import tensors as T
     from paper_2510_05186_amd.stage import Stage
+    from stage_inputs import tensors as T
     _, _, peak, _ = B.plan(cfg, events, budget=0, recompute=RECOMPUTE, n_chunks=CHUNKS)
-    n_off = sum(1 for e in events if e[0] == "O")
-    pool = 0
-    if n_off:
-        kb = B.query_sizes(cfg)[2]
-        per_mb = sum(kb[k] for k in cfg.offload_kinds) * cfg.n_layers
-        pool = per_mb * cfg.n_microbatches
-    st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=pool, duplex=duplex,
-               recompute=bool(RECOMPUTE), n_chunks=CHUNKS)
+    kb = B.query_sizes(cfg)[2]
+    moved = sum(kb[k] for e in events if e[0] == "O" for k in e[3])
+    st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=moved + (64 << 20) if moved else 0,
+               duplex=duplex, recompute=bool(RECOMPUTE), n_chunks=CHUNKS, grad_overwrite=True)
     st.set_weights_device(T.device_weights(cfg))
     for c in range(CHUNKS):
         for j in range(cfg.n_microbatches):
@@ -151,14 +138,14 @@ def make_stage(cfg, events, budget, torch, duplex=False):
 
 
 def time_steps(st, events, steps, warmup, torch, kernel_timing=True):
+    """W untimed steps, then K timed ones bracketed by device synchronisation.  The gradient accumulators are not
+    cleared between steps: the first B / W of a step overwrite them (grad_overwrite)."""
     from paper_2510_05186_amd import binding as B
     arr = B.make_events(events)
     n = len(events)
 
     def one_step():
         st.reset()
-        with torch.cuda.stream(st.compute_stream):
-            st.zero_grads_async()
         st.run_raw(arr, n)
         st.synchronize()
 
@@ -172,28 +159,111 @@ def time_steps(st, events, steps, warmup, torch, kernel_timing=True):
         one_step()
         s = st.stats()
         cur = {"ms_ops": list(s.ms_ops), "k_ms": list(s.kernel_ms), "k_work": list(s.kernel_work),
-               "k_n": list(s.kernel_launches), "peak": s.peak_bytes, "off": s.bytes_offloaded, "rel": s.bytes_reloaded}
+               "k_n": list(s.kernel_launches), "stall": list(s.stall_ms)}
         if agg is None:
             agg = cur
         else:
-            for k in ("ms_ops", "k_ms", "k_work", "k_n"):
+            for k in cur:
                 agg[k] = [a + b for a, b in zip(agg[k], cur[k])]
+        agg.update(peak=s.peak_bytes, off=s.bytes_offloaded, rel=s.bytes_reloaded, min_live=s.min_live_bytes,
+                   avg_live=s.avg_live_bytes)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     B.check(st.lib.optstage_set_kernel_timing(st.h, 0))
     return wall, agg
 
 
-def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event, duplex=False, n_chunks=1):
-    """CPU baseline: the fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample
-    (ONE layer of the workload's stage, one micro-batch, F + B + W at full shape), and the oracle's
-    pipeline simulator fed with the measured op times (all p stages assumed identical to this one)."""
-    import numpy as np
+def leg_record(cfg, events, budget, steps, wall, agg, knobs):
+    """Throughput, op times, memory and transfer figures of one measured list."""
+    flops = schedule_flops(cfg) * cfg.n_microbatches
+    ms = wall / steps * 1e3
+    n_f = cfg.n_microbatches * CHUNKS
+    busy = sum(agg["ms_ops"][:3]) / steps
+    rec = {"workload": cfg.name, "value": flops * steps / wall / 1e12, "unit": "TFLOP/s", "ms_per_step": ms, "steps": steps,
+           "frac_of_bf16_peak": flops * steps / wall / 1e12 / (PEAK_BF16_TFLOPS if cfg.dtype == 1 else PEAK_FP32_TFLOPS),
+           "mean_op_ms": {c: agg["ms_ops"][k] / steps / n_f for k, c in enumerate("FBW")},
+           "stage_busy_frac": busy / ms, "hbm_budget_bytes": budget or None, "peak_hbm_bytes": agg["peak"],
+           "avg_live_bytes": agg["avg_live"], "min_live_bytes_in_flight": agg["min_live"],
+           "events": len(events), "events_sha256": hashlib.sha256(repr(list(map(tuple, events))).encode()).hexdigest()[:16],
+           "schedule_knobs": knobs}
+    if agg["off"]:
+        rec["offload"] = {"bytes_offloaded_per_step": agg["off"], "bytes_reloaded_per_step": agg["rel"],
+                          "d2h_GBps": agg["off"] * steps / (agg["ms_ops"][3] * 1e-3) / 1e9,
+                          "h2d_GBps": agg["rel"] * steps / (agg["ms_ops"][5] * 1e-3) / 1e9,
+                          "compute_stall_ms_per_step": {"at_owait": agg["stall"][0] / steps, "before_b": agg["stall"][1] / steps},
+                          "stall_frac_of_step": (agg["stall"][0] + agg["stall"][1]) / steps / ms}
+    return rec
 
-    from oracle import schedule as S
+
+def kernel_table(agg, steps, ms_per_step):
+    from paper_2510_05186_amd import binding as B
+    out = {}
+    for i, name in enumerate(B.KERNEL_CLASSES):
+        if agg["k_n"][i]:
+            ms = agg["k_ms"][i]
+            flop_class = i < 5
+            out[name] = {"launches_per_step": agg["k_n"][i] // steps, "avg_ms": ms / agg["k_n"][i],
+                         "achieved": agg["k_work"][i] / (ms * 1e-3) / (1e12 if flop_class else 1e9),
+                         "unit": "TFLOP/s" if flop_class else "GB/s", "share_of_step": ms / steps / ms_per_step}
+    return out
+
+
+def run_leg(cfg, duplex, steps, warmup, torch, kernel_timing=False, calibrate=True):
+    """Builds the workload's lists, runs this stage's list, returns (record, kernels, context for the pipeline model)."""
+    budget = workload_budget(cfg)
+    lists, knobs = build_lists(cfg, budget, duplex)
+    events = lists[cfg.stage_index]
+    st, _ = make_stage(cfg, events, budget, duplex)
+    if budget and calibrate and CHUNKS == 1:
+        # one untimed step with the list built from nominal op times, then the generator again with the op times and
+        # the host-link rate this box shows: the same handle takes the new list (a list may change every iteration)
+        _, a0 = time_steps(st, events, 1, 0, torch, kernel_timing=False)
+        n_f = cfg.n_microbatches
+        t_op = {c: a0["ms_ops"][k] / n_f for k, c in enumerate("FBW")}
+        link = a0["off"] / (a0["ms_ops"][3] * 1e-3) / 1e9 if a0["off"] and a0["ms_ops"][3] > 0 else 55.0
+        lists2, knobs2 = build_lists(cfg, budget, duplex, t_op=t_op, link_gbps=link)
+        knobs2["calibrated_with"] = {"t_op_ms": t_op, "link_GBps": link}
+        ev2 = lists2[cfg.stage_index]
+        from paper_2510_05186_amd import binding as B
+        kb = B.query_sizes(cfg)[2]
+        moved = lambda ev: sum(kb[k] for e in ev if e[0] == "O" for k in e[3])
+        if moved(ev2) <= moved(events) + (32 << 20) and B.plan(cfg, ev2, budget=0)[2] <= B.plan(cfg, events, budget=0)[2]:
+            lists, knobs, events = lists2, knobs2, ev2       # fits the pool and the arena this stage was created with
+        else:
+            knobs["calibrated_list_not_taken"] = "needs a larger pinned pool or arena than this handle has"
+    wall, agg = time_steps(st, events, steps, warmup, torch, kernel_timing=kernel_timing)
+    rec = leg_record(cfg, events, budget, steps, wall, agg, knobs)
+    rec["transfer_channels"] = 2 if duplex else 1
+    kernels = kernel_table(agg, steps, rec["ms_per_step"]) if kernel_timing else None
+    n_x = sum(1 for e in events if e[0] in ("O", "R"))
+    ctx = {"cfg": cfg, "lists": lists, "events": events, "duplex": duplex, "budget": budget, "peak": agg["peak"],
+           "t_op": [rec["mean_op_ms"][c] for c in "FBW"],
+           "ms_per_byte": ((agg["ms_ops"][3] + agg["ms_ops"][5]) / steps / (agg["off"] + agg["rel"])) if n_x and agg["off"] else 0.0}
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    return rec, kernels, ctx
+
+
+def compute_only_ms(cfg, events, torch):
+    """The same compute order with no transfer and no budget: what the step would take if copies cost nothing."""
+    comp = [e for e in events if e[0] in ("F", "B", "W")]
+    st, _ = make_stage(cfg, comp, 0)
+    wall, _ = time_steps(st, comp, 1, 1, torch, kernel_timing=False)
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    return wall * 1e3
+
+
+def cpu_baseline(cfg):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample of the headline workload:
+    ONE layer, one micro-batch, F + B + W at full shape."""
+    import numpy as np
+    from dataclasses import replace
+
     from oracle import stage_fp64 as O
     from stage_inputs import tensors as T
-    from dataclasses import replace
     one = replace(cfg, n_layers=1)
     sh = O.StageShape(one.family, 1, one.hidden, one.n_q_heads, one.n_kv_heads, one.head_dim, one.ffn, one.seq,
                       one.norm_eps, one.rope_base)
@@ -209,22 +279,33 @@ def oracle_leg(cfg, t_op_ms, events_all_stages, copy_ms_per_event, duplex=False,
         threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
     except Exception:
         threads = os.cpu_count()
-    base = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"1 of {cfg.n_layers} layers, 1 of {cfg.n_microbatches} micro-batches, F+B+W at full shape "
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 of {cfg.n_layers} layers, 1 of {cfg.n_microbatches} micro-batches of {cfg.name}, F+B+W at full shape "
                       f"({fl / 1e12:.2f} TFLOP fp64 in {dt:.1f} s)", "host_cpus": os.cpu_count()}
-    p = cfg.n_stages
-    t_op = [{"F": t_op_ms[0], "B": t_op_ms[1], "W": t_op_ms[2]}] * p
-    tm = S.simulate(events_all_stages, t_op, t_comm=0.0, t_copy=lambda i, ev: copy_ms_per_event, duplex=duplex,
-                    n_chunks=n_chunks, layers_per_chunk=cfg.n_layers // n_chunks)
+
+
+def pipeline_model(ctx):
+    """The oracle's simulator over all p stages' lists (every stage shaped like this one), fed with this stage's
+    measured mean op times and its measured transfer time per byte: the stage's bubble fraction under the budget and
+    the peak of the oracle's list-order accounting, which must equal what the library's allocator recorded."""
+    from oracle import schedule as S
+    cfg = ctx["cfg"]
+    p, i = cfg.n_stages, cfg.stage_index
+    t = S.memory_table(cfg.family, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.ffn,
+                       cfg.seq * cfg.micro_batch, cfg.elem_size)
+    t_op = [dict(zip("FBW", ctx["t_op"]))] * p
+    copy = lambda st, ev: ctx["ms_per_byte"] * sum(t[k] for k in ev[3])
+    kw = dict(t_copy=copy, duplex=ctx["duplex"], n_chunks=CHUNKS, layers_per_chunk=cfg.n_layers // CHUNKS)
+    tm = S.simulate(ctx["lists"], t_op, t_comm=0.0, **kw)
     # second run with the neighbour exchange priced: one [tokens, hidden] tensor over a 153 GB/s point-to-point link
-    t_comm_ms = cfg.seq * cfg.micro_batch * cfg.hidden * cfg.elem_size / 153e9 * 1e3
-    tc = S.simulate(events_all_stages, t_op, t_comm=t_comm_ms, t_copy=lambda i, ev: copy_ms_per_event, duplex=duplex,
-                    n_chunks=n_chunks, layers_per_chunk=cfg.n_layers // n_chunks)
-    model = {"stage_bubble_frac": tm.bubble[cfg.stage_index], "makespan_ms": tm.makespan_global,
-             "assumption": "p identical stages with this stage's measured mean T_F/T_B/T_W, T_comm = 0",
-             "with_t_comm": {"t_comm_ms": t_comm_ms, "stage_bubble_frac": tc.bubble[cfg.stage_index],
-                             "makespan_ms": tc.makespan_global}}
-    return base, model
+    t_comm = cfg.seq * cfg.micro_batch * cfg.hidden * cfg.elem_size / 153e9 * 1e3
+    tc = S.simulate(ctx["lists"], t_op, t_comm=t_comm, **kw)
+    peak, _ = S.account_memory(ctx["events"], cfg.n_layers, t, limit=ctx["budget"] or None, recompute=bool(RECOMPUTE), n_chunks=CHUNKS)
+    return {"stage_bubble_frac": tm.bubble[i], "makespan_ms": tm.makespan_global, "simulator_peak_bytes": peak,
+            "allocator_peak_bytes": ctx["peak"], "peaks_equal": peak == ctx["peak"],
+            "assumption": "p identical stages with this stage's measured mean T_F / T_B / T_W and transfer time per byte, "
+                          "every device under the same byte budget, T_comm = 0",
+            "with_t_comm": {"t_comm_ms": t_comm, "stage_bubble_frac": tc.bubble[i], "makespan_ms": tc.makespan_global}}
 
 
 def main():
@@ -232,13 +313,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="cfg2_llama_bf16")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-offload-leg", action="store_true")
-    ap.add_argument("--generator", default="greedy", choices=("greedy", "adaoffload"),
-                    help="how the event list of a budgeted workload is produced")
+    ap.add_argument("--config", default=HEADLINE)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle legs (cpu_baseline, pipeline models)")
+    ap.add_argument("--no-legs", action="store_true", help="run the headline workload only")
     ap.add_argument("--duplex", action="store_true",
-                    help="reloads on a stream of their own instead of the single transfer channel (offload workloads)")
+                    help="reloads on a stream of their own instead of the single transfer channel (headline workload)")
     ap.add_argument("--chunks", type=int, default=1,
                     help="model chunks on the stage: runs interleaved 1F1B over them (layers split evenly)")
     ap.add_argument("--recompute", action="store_true",
@@ -254,9 +333,7 @@ def main():
 
     import torch
 
-    from paper_2510_05186_amd import binding as B
     from stage_inputs import configs as CFG
-    from stage_inputs import schedules as G
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the stage has no CPU path", file=sys.stderr)
         sys.exit(3)
@@ -264,111 +341,78 @@ def main():
     global RECOMPUTE, CHUNKS
     RECOMPUTE = int(args.recompute)
     CHUNKS = max(1, args.chunks)
-    budget = 0
-    if cfg.budget_bytes:
-        budget = cfg.budget_bytes
-    elif cfg.budget_frac_of_peak:
-        base_ev, _ = build_schedule(CFG.CFG2)
-        budget = int(cfg.budget_frac_of_peak * B.plan(CFG.CFG2, base_ev)[2])
-    events, knobs = build_schedule(cfg, budget, args.generator)
     if args.calibration_copy_mib:
         src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    st, peak_plan = make_stage(cfg, events, budget, torch, args.duplex)
-    wall, agg = time_steps(st, events, args.steps, args.warmup, torch)
-    flops = schedule_flops(cfg) * cfg.n_microbatches
-    ms_per_step = wall / args.steps * 1e3
-    value = flops * args.steps / wall / 1e12
-    peak_tf = PEAK_BF16_TFLOPS if cfg.dtype == 1 else PEAK_FP32_TFLOPS
 
-    kernels = {}
-    for i, name in enumerate(B.KERNEL_CLASSES):
-        if agg["k_n"][i]:
-            ms = agg["k_ms"][i]
-            unit = "TFLOP/s" if i < 5 else "GB/s"
-            rate = agg["k_work"][i] / (ms * 1e-3) / (1e12 if i < 5 else 1e9)
-            kernels[name] = {"launches_per_step": agg["k_n"][i] // args.steps, "avg_ms": ms / agg["k_n"][i],
-                             "achieved": rate, "unit": unit, "share_of_step": ms / args.steps / ms_per_step}
-    dom = kernels.get("gemm_nt_store", {"achieved": 0.0})
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_direct_kernel<NT,store>" if cfg.dtype == 1 else "gemm_f32_kernel",
-                "achieved": dom["achieved"], "peak": peak_tf, "unit": "TFLOP/s", "frac": dom["achieved"] / peak_tf,
-                "avg_launch_ms": dom.get("avg_ms"), "launches_per_step": dom.get("launches_per_step"),
-                "algorithmic_bytes": nt_store_algorithmic_bytes(cfg), "traffic": measured_traffic(cfg)}
-    busy_ms = sum(agg["ms_ops"][:3]) / args.steps
-    n_f = cfg.n_microbatches * CHUNKS
-    t_op_ms = [agg["ms_ops"][k] / args.steps / n_f for k in range(3)]
+    rec, kernels, ctx = run_leg(cfg, args.duplex, args.steps, args.warmup, torch, kernel_timing=True)
+    peak_tf = PEAK_BF16_TFLOPS if cfg.dtype == 1 else PEAK_FP32_TFLOPS
+    # the dominant kernel: the class with the largest share of the step
+    dom_name = max(kernels, key=lambda k: kernels[k]["share_of_step"])
+    dom = kernels[dom_name]
+    flop_class = dom["unit"] == "TFLOP/s"
+    peak = peak_tf if flop_class else PEAK_HBM_GBPS
+    roofline = {"bound": "mfma" if flop_class else "hbm", "kernel": KERNEL_NAMES.get(dom_name, dom_name), "kernel_class": dom_name,
+                "achieved": dom["achieved"], "peak": peak, "unit": dom["unit"], "frac": dom["achieved"] / peak,
+                "avg_launch_ms": dom["avg_ms"], "launches_per_step": dom["launches_per_step"], "share_of_step": dom["share_of_step"],
+                "algorithmic_bytes": class_algorithmic_bytes(cfg, dom_name), "traffic": measured_traffic(cfg, dom_name)}
     out = {
         "metric": "stage TFLOP/s (F+B+W) + bubble % under HBM budget; MFMA util vs bf16 peak",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": rec["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": cfg.n_layers, "hidden": cfg.hidden, "heads": cfg.n_q_heads,
                    "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim, "ffn": cfg.ffn, "seq": cfg.seq,
                    "micro_batch": cfg.micro_batch, "stage": cfg.stage_index, "p": cfg.n_stages,
-                   "m": cfg.n_microbatches, "schedule": cfg.schedule, "schedule_knobs": knobs,
-                   "events": len(events), "events_sha256": hashlib.sha256(repr(list(map(tuple, events))).encode()).hexdigest()[:16],
+                   "m": cfg.n_microbatches, "schedule": cfg.schedule, "schedule_knobs": rec["schedule_knobs"],
+                   "events": rec["events"], "events_sha256": rec["events_sha256"], "transfer_channels": rec["transfer_channels"],
                    "memory_table": "recompute n1, n2, a in B" if RECOMPUTE else "store all"},
-        "frac_of_bf16_peak": value / peak_tf,
-        "stage_busy_frac": busy_ms / ms_per_step,
-        "stage_idle_frac": 1.0 - busy_ms / ms_per_step,
-        "mean_op_ms": {"F": t_op_ms[0], "B": t_op_ms[1], "W": t_op_ms[2]},
-        "peak_hbm_bytes": agg["peak"], "hbm_budget_bytes": budget or None,
+        "frac_of_bf16_peak": rec["frac_of_bf16_peak"], "stage_busy_frac": rec["stage_busy_frac"],
+        "mean_op_ms": rec["mean_op_ms"], "hbm_budget_bytes": rec["hbm_budget_bytes"], "peak_hbm_bytes": rec["peak_hbm_bytes"],
+        "avg_live_bytes": rec["avg_live_bytes"], "min_live_bytes_in_flight": rec["min_live_bytes_in_flight"],
         "roofline": roofline, "kernels": kernels,
     }
-    if agg["off"]:
-        out["offload"] = {"duplex": bool(args.duplex), "bytes_per_step": agg["off"], "d2h_GBps": agg["off"] * args.steps / (agg["ms_ops"][3] * 1e-3) / 1e9,
-                          "h2d_GBps": agg["rel"] * args.steps / (agg["ms_ops"][5] * 1e-3) / 1e9}
-    st.close()
-    del st
-    torch.cuda.empty_cache()
+    if "offload" in rec:
+        out["offload"] = rec["offload"]
+        out["offload"]["ms_same_order_without_copies"] = compute_only_ms(cfg, ctx["events"], torch)
+        out["offload"]["overlap_cost"] = rec["ms_per_step"] / out["offload"]["ms_same_order_without_copies"]
+    models = [("headline", ctx)]
 
-    if not args.no_offload_leg and cfg.name == "cfg2_llama_bf16" and CHUNKS == 1:
-        # same shapes under 40 % of this run's activation peak, with offload of (attention input, QKV, MLP input):
-        # on the single transfer channel of the paper's model and with reloads on a stream of their own
-        c3 = CFG.CFG3
-        b3 = int(c3.budget_frac_of_peak * peak_plan)
-        ev3, knobs3 = build_schedule(c3, b3, args.generator)
-        comp_only = [e for e in ev3 if e[0] in ("F", "B", "W")]
-        st3b, _ = make_stage(c3, comp_only, 0, torch)
-        w3b, _ = time_steps(st3b, comp_only, 1, 1, torch, kernel_timing=False)
-        st3b.close()
-        del st3b
-        torch.cuda.empty_cache()
-        legs = {}
+    legs = {}
+    if not args.no_legs and cfg.name == HEADLINE and CHUNKS == 1 and not RECOMPUTE:
+        r2, k2, c2 = run_leg(CFG.CFG2, False, 3, 1, torch, kernel_timing=True)
+        r2["kernels"] = k2
+        legs["cfg2_llama_bf16"] = r2
+        models.append(("cfg2_llama_bf16", c2))
+        base3 = None
         for duplex in (False, True):
-            st3, _ = make_stage(c3, ev3, b3, torch, duplex)
-            w3, a3 = time_steps(st3, ev3, 1, 1, torch, kernel_timing=False)
-            st3.close()
-            del st3
-            torch.cuda.empty_cache()
-            legs[duplex] = {
-                "value": flops / w3 / 1e12, "unit": "TFLOP/s", "ms_per_step": w3 * 1e3, "overlap_cost": w3 / w3b,
-                "d2h_GBps": a3["off"] / (a3["ms_ops"][3] * 1e-3) / 1e9 if a3["ms_ops"][3] else None,
-                "h2d_GBps": a3["rel"] / (a3["ms_ops"][5] * 1e-3) / 1e9 if a3["ms_ops"][5] else None}
-            peak3, off3, rel3 = a3["peak"], a3["off"], a3["rel"]
-        out["offload_leg"] = {
-            "workload": c3.name, "hbm_budget_bytes": b3, "peak_hbm_bytes": peak3, "schedule_knobs": knobs3,
-            "ms_same_order_without_copies": w3b * 1e3, "bytes_offloaded": off3, "bytes_reloaded": rel3,
-            "single_channel": legs[False], "duplex": legs[True]}
+            r3, _, c3 = run_leg(CFG.CFG3, duplex, 2, 1, torch)
+            if base3 is None:
+                base3 = compute_only_ms(CFG.CFG3, c3["events"], torch)
+            r3["ms_same_order_without_copies"] = base3
+            r3["overlap_cost"] = r3["ms_per_step"] / base3
+            name = "cfg3_llama_bf16_offload" + ("_duplex" if duplex else "")
+            legs[name] = r3
+            models.append((name, c3))
+        r5, _, c5 = run_leg(CFG.CFG5, False, 2, 1, torch)
+        r5["ms_same_order_without_copies"] = compute_only_ms(CFG.CFG5, c5["events"], torch)
+        r5["overlap_cost"] = r5["ms_per_step"] / r5["ms_same_order_without_copies"]
+        legs["cfg5_longseq_bf16"] = r5
+        models.append(("cfg5_longseq_bf16", c5))
+        out["legs"] = legs
 
     if not args.no_cpu_baseline:
-        lists = G.split_bw_greedy(cfg.n_stages, cfg.n_microbatches) if cfg.schedule != "1f1b" else \
-            [G.one_f_one_b(cfg.n_stages, cfg.n_microbatches, i) for i in range(cfg.n_stages)]
-        if CHUNKS > 1:
-            lists = [G.interleaved_one_f_one_b(cfg.n_stages, cfg.n_microbatches, i, CHUNKS) for i in range(cfg.n_stages)]
-        copy_ms = 0.0
-        if args.generator == "adaoffload" and getattr(build_schedule, "all_stages", None) and budget:
-            # the generator's lists for every stage, transfers included, with this stage's measured mean copy time
-            lists = build_schedule.all_stages
-            n_x = agg["k_n"] and sum(1 for e in events if e[0] in ("O", "R"))
-            copy_ms = (agg["ms_ops"][3] + agg["ms_ops"][5]) / args.steps / n_x if n_x else 0.0
-        base, model = oracle_leg(cfg, t_op_ms, lists, copy_ms, args.duplex, CHUNKS)
-        model["lists"] = "adaoffload, all stages, transfers included" if copy_ms else "compute ops only"
-        out["cpu_baseline"] = base
-        out["pipeline_model"] = model
+        out["cpu_baseline"] = cpu_baseline(cfg)
+        for name, c in models:
+            pm = pipeline_model(c)
+            if name == "headline":
+                out["pipeline_model"] = pm
+                out["bubble_frac_under_budget"] = pm["stage_bubble_frac"]
+            else:
+                legs[name]["pipeline_model"] = pm
     print(json.dumps(out))
 
 
