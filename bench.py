@@ -35,6 +35,7 @@ KERNEL_NAMES = {"gemm_nt_store": "gemm_bf16_direct_kernel<NT, store>", "gemm_nt_
                 "gemm_tn_accum": "gemm_bf16_direct_grouped_kernel<TN, fp32 accumulate>", "attn_fwd": "attn_fwd_mfma",
                 "attn_bwd": "attn_bwd_dq_mfma + attn_bwd_dkv_mfma"}
 
+PINNED = {}     # the process's pinned offload pool
 CHUNKS = 1      # --chunks: model chunks on the stage (interleaved 1F1B instead of the configuration's schedule)
 RECOMPUTE = 0   # --recompute: the memory-table variant in which F keeps no norm outputs and no MLP activation output
 
@@ -98,7 +99,7 @@ def workload_budget(cfg):
     return 0
 
 
-def build_lists(cfg, budget, duplex=False, t_op=None, link_gbps=55.0):
+def build_lists(cfg, budget, duplex=False, t_op=None, link_gbps=55.0, reload_gbps=None):
     """The lists of all p stages (each shaped like this one) and what the generator decided."""
     from paper_2510_05186_amd import scheduler as SC
     from stage_inputs import schedules as G
@@ -109,7 +110,8 @@ def build_lists(cfg, budget, duplex=False, t_op=None, link_gbps=55.0):
         return [G.interleaved_one_f_one_b(p, m, i, CHUNKS) for i in range(p)], {"schedule": "interleaved 1F1B", "chunks": CHUNKS}
     if cfg.schedule == "1f1b":
         return [G.one_f_one_b(p, m, i) for i in range(p)], {"schedule": "1F1B"}
-    lists, info = SC.workload_lists(cfg, budget, t_op=t_op, link_gbps=link_gbps, duplex=duplex, recompute=RECOMPUTE)
+    lists, info = SC.workload_lists(cfg, budget, t_op=t_op, link_gbps=link_gbps, reload_gbps=reload_gbps, duplex=duplex,
+                                    recompute=RECOMPUTE)
     i = cfg.stage_index
     knobs = {"generator": "split B/W greedy fill" + (", per-item offload under the budget, fill level by modelled makespan" if budget else ""),
              "in_flight_cap": info["caps"][i], "extra_fill": info["extra_fill"],
@@ -127,7 +129,19 @@ def make_stage(cfg, events, budget, duplex=False):
     _, _, peak, _ = B.plan(cfg, events, budget=0, recompute=RECOMPUTE, n_chunks=CHUNKS)
     kb = B.query_sizes(cfg)[2]
     moved = sum(kb[k] for e in events if e[0] == "O" for k in e[3])
-    st = Stage(cfg, budget=budget, arena_bytes=int(peak * 1.15) + (256 << 20), host_pool_bytes=moved + (64 << 20) if moved else 0,
+    # a budgeted handle is sized for ANY list under its budget (the generator is asked again once op times are
+    # measured): arena from the budget, pinned pool for half as much again as the first list moves
+    arena = int((min(peak, budget) if budget else peak) * 1.15) + (256 << 20)
+    pool = None
+    if moved:
+        # one pinned block for the whole process, handed to every stage that offloads (the first one is the largest)
+        import torch
+        need = moved + moved // 2 + (256 << 20)
+        if PINNED.get("pool") is None or PINNED["pool"].numel() < need:
+            PINNED["pool"] = None
+            PINNED["pool"] = torch.empty(need, dtype=torch.uint8, pin_memory=True)
+        pool = PINNED["pool"]
+    st = Stage(cfg, budget=budget, arena_bytes=arena, host_pool=pool,
                duplex=duplex, recompute=bool(RECOMPUTE), n_chunks=CHUNKS, grad_overwrite=True)
     st.set_weights_device(T.device_weights(cfg))
     for c in range(CHUNKS):
@@ -221,14 +235,15 @@ def run_leg(cfg, duplex, steps, warmup, torch, kernel_timing=False, calibrate=Tr
         n_f = cfg.n_microbatches
         t_op = {c: a0["ms_ops"][k] / n_f for k, c in enumerate("FBW")}
         link = a0["off"] / (a0["ms_ops"][3] * 1e-3) / 1e9 if a0["off"] and a0["ms_ops"][3] > 0 else 55.0
-        lists2, knobs2 = build_lists(cfg, budget, duplex, t_op=t_op, link_gbps=link)
-        knobs2["calibrated_with"] = {"t_op_ms": t_op, "link_GBps": link}
+        back = a0["rel"] / (a0["ms_ops"][5] * 1e-3) / 1e9 if a0["rel"] and a0["ms_ops"][5] > 0 else link
+        lists2, knobs2 = build_lists(cfg, budget, duplex, t_op=t_op, link_gbps=link, reload_gbps=back)
+        knobs2["calibrated_with"] = {"t_op_ms": t_op, "d2h_GBps": link, "h2d_GBps": back}
         ev2 = lists2[cfg.stage_index]
         from paper_2510_05186_amd import binding as B
         kb = B.query_sizes(cfg)[2]
         moved = lambda ev: sum(kb[k] for e in ev if e[0] == "O" for k in e[3])
-        if moved(ev2) <= moved(events) + (32 << 20) and B.plan(cfg, ev2, budget=0)[2] <= B.plan(cfg, events, budget=0)[2]:
-            lists, knobs, events = lists2, knobs2, ev2       # fits the pool and the arena this stage was created with
+        if moved(ev2) + (64 << 20) <= st.host_pool.numel():
+            lists, knobs, events = lists2, knobs2, ev2       # fits the pinned pool this stage was created with
         else:
             knobs["calibrated_list_not_taken"] = "needs a larger pinned pool or arena than this handle has"
     wall, agg = time_steps(st, events, steps, warmup, torch, kernel_timing=kernel_timing)

@@ -982,18 +982,21 @@ hipError_t launch_attn_bwd_mfma(const void* qkv, const void* o, const void* dout
   hipError_t e;
   static LdsAttrOnce dq_attr, dkv_attr;
   if ((e = dq_attr.ensure(reinterpret_cast<const void*>(attn_bwd_dq_mfma), DQ_SMEM)) != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 255) / 256), dim3(256), DQ_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
+  hipLaunchKernelGGL(attn_bwd_dq_mfma, dim3(n_q, batch, (seq + 255) / 256), dim3(256), DQ_SMEM, s, (const bf16_t*)qkv,
+      (const bf16_t*)o, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, seq, n_q, n_kv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = dkv_attr.ensure(reinterpret_cast<const void*>(attn_bwd_dkv_mfma), DKV_SMEM)) != hipSuccess) return e;
   const int split = attn_dkv_split(seq, batch, n_q, n_kv);
   float* partial = ws + (size_t)batch * n_q * seq;            // behind the D array
-  hipLaunchKernelGGL(attn_bwd_dkv_mfma, dim3(n_kv * split, batch, (seq + 255) / 256), dim3(256), DKV_SMEM, s, (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, partial, split, seq, n_q, n_kv);
+  hipLaunchKernelGGL(attn_bwd_dkv_mfma, dim3(n_kv * split, batch, (seq + 255) / 256), dim3(256), DKV_SMEM, s,
+      (const bf16_t*)qkv, (const bf16_t*)dout, lse, ws, (bf16_t*)dqkv, partial, split, seq, n_q, n_kv);
   if (split > 1) {
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t quads = (size_t)batch * seq * n_kv * 2 * D / 4;
-    hipLaunchKernelGGL(attn_bwd_dkv_reduce, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, partial, (bf16_t*)dqkv, split, batch * seq, n_q, n_kv);
+    hipLaunchKernelGGL(attn_bwd_dkv_reduce, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, partial, (bf16_t*)dqkv,
+        split, batch * seq, n_q, n_kv);
   }
   return hipGetLastError();
 }

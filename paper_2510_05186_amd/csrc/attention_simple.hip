@@ -194,10 +194,12 @@ hipError_t fwd_t(const void* qkv, void* o, float* lse, int seq, int batch, int n
 template <typename T, int DPL>
 hipError_t bwd_t(const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv, float* ws, int seq,
                  int batch, int n_q, int n_kv, hipStream_t s) {
-  hipLaunchKernelGGL((attn_bwd_dq_simple<T, DPL>), dim3((seq + 3) / 4, n_q, batch), dim3(256), 0, s, (const T*)qkv, (const T*)o, (const T*)dout, lse, (T*)dqkv, ws, seq, n_q, n_kv);
+  hipLaunchKernelGGL((attn_bwd_dq_simple<T, DPL>), dim3((seq + 3) / 4, n_q, batch), dim3(256), 0, s, (const T*)qkv,
+      (const T*)o, (const T*)dout, lse, (T*)dqkv, ws, seq, n_q, n_kv);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bwd_dkv_simple<T, DPL>), dim3((seq + 3) / 4, n_kv, batch), dim3(256), 0, s, (const T*)qkv, (const T*)dout, lse, ws, (T*)dqkv, seq, n_q, n_kv);
+  hipLaunchKernelGGL((attn_bwd_dkv_simple<T, DPL>), dim3((seq + 3) / 4, n_kv, batch), dim3(256), 0, s, (const T*)qkv,
+      (const T*)dout, lse, ws, (T*)dqkv, seq, n_q, n_kv);
   return hipGetLastError();
 }
 

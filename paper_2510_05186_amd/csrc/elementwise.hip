@@ -510,12 +510,16 @@ hipError_t launch_norm_fwd(int dtype, int family, const void* x, const void* gam
   const bool ln = family == FAM_GPT;
   if (dtype == DT_BF16) {
     if (!norm_shape_ok<bf16_t>(h)) return hipErrorInvalidValue;
-    if (ln) hipLaunchKernelGGL((norm_fwd_kernel<bf16_t, true>), dim3(rows), dim3(NT), 0, s, (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, stats, rows, h, eps);
-    else hipLaunchKernelGGL((norm_fwd_kernel<bf16_t, false>), dim3(rows), dim3(NT), 0, s, (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, stats, rows, h, eps);
+    if (ln) hipLaunchKernelGGL((norm_fwd_kernel<bf16_t, true>), dim3(rows), dim3(NT), 0, s, (const bf16_t*)x,
+        (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, stats, rows, h, eps);
+    else hipLaunchKernelGGL((norm_fwd_kernel<bf16_t, false>), dim3(rows), dim3(NT), 0, s, (const bf16_t*)x,
+        (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)out, stats, rows, h, eps);
   } else {
     if (!norm_shape_ok<float>(h)) return hipErrorInvalidValue;
-    if (ln) hipLaunchKernelGGL((norm_fwd_kernel<float, true>), dim3(rows), dim3(NT), 0, s, (const float*)x, (const float*)gamma, (const float*)beta, (float*)out, stats, rows, h, eps);
-    else hipLaunchKernelGGL((norm_fwd_kernel<float, false>), dim3(rows), dim3(NT), 0, s, (const float*)x, (const float*)gamma, (const float*)beta, (float*)out, stats, rows, h, eps);
+    if (ln) hipLaunchKernelGGL((norm_fwd_kernel<float, true>), dim3(rows), dim3(NT), 0, s, (const float*)x,
+        (const float*)gamma, (const float*)beta, (float*)out, stats, rows, h, eps);
+    else hipLaunchKernelGGL((norm_fwd_kernel<float, false>), dim3(rows), dim3(NT), 0, s, (const float*)x,
+        (const float*)gamma, (const float*)beta, (float*)out, stats, rows, h, eps);
   }
   return hipGetLastError();
 }
@@ -534,17 +538,25 @@ hipError_t launch_norm_bwd(int dtype, int family, const void* dn, const void* x,
   if (dtype == DT_BF16) {
     if (!norm_shape_ok<bf16_t>(h)) return hipErrorInvalidValue;
     const bool narrow = h / 8 <= 64 * MAXC && rows >= 4 * nb;   // one row per wave
-    if (ln && narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
-    else if (narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<bf16_t, false>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
-    else if (ln) hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
-    else hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, false>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    if (ln && narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn,
+        (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    else if (narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<bf16_t, false>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn,
+        (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    else if (ln) hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, true>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn,
+        (const bf16_t*)x, stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
+    else hipLaunchKernelGGL((norm_bwd_kernel<bf16_t, false>), dim3(nb), dim3(NT), 0, s, (const bf16_t*)dn, (const bf16_t*)x,
+        stats, (const bf16_t*)gamma, (const bf16_t*)dres, (bf16_t*)dx, partial, rows, h);
   } else {
     if (!norm_shape_ok<float>(h)) return hipErrorInvalidValue;
     const bool narrow = h / 4 <= 64 * MAXC && rows >= 4 * nb;
-    if (ln && narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
-    else if (narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<float, false>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
-    else if (ln) hipLaunchKernelGGL((norm_bwd_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
-    else hipLaunchKernelGGL((norm_bwd_kernel<float, false>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    if (ln && narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn,
+        (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    else if (narrow) hipLaunchKernelGGL((norm_bwd_wave_kernel<float, false>), dim3(nb), dim3(NT), 0, s, (const float*)dn,
+        (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    else if (ln) hipLaunchKernelGGL((norm_bwd_kernel<float, true>), dim3(nb), dim3(NT), 0, s, (const float*)dn,
+        (const float*)x, stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
+    else hipLaunchKernelGGL((norm_bwd_kernel<float, false>), dim3(nb), dim3(NT), 0, s, (const float*)dn, (const float*)x,
+        stats, (const float*)gamma, (const float*)dres, (float*)dx, partial, rows, h);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -605,7 +617,8 @@ hipError_t launch_rope(int dtype, const void* src, void* dst, const float* table
   int g = grid_for(items, 256);
   float sign = backward ? -1.f : 1.f;
 #define OPTSTAGE_ROPE(T, HG) \
-  hipLaunchKernelGGL((rope_kernel<T, HG>), dim3(g), dim3(256), 0, s, (const T*)src, (T*)dst, (const float2*)table, rows, seq, n_rot, n_kv, d, sign, do_rotate)
+  hipLaunchKernelGGL((rope_kernel<T, HG>), dim3(g), dim3(256), 0, s, (const T*)src, (T*)dst, (const float2*)table, rows, \
+                     seq, n_rot, n_kv, d, sign, do_rotate)
   if (dtype == DT_BF16) { if (hg == 8) OPTSTAGE_ROPE(bf16_t, 8); else if (hg == 4) OPTSTAGE_ROPE(bf16_t, 4); else OPTSTAGE_ROPE(bf16_t, 1); }
   else { if (hg == 8) OPTSTAGE_ROPE(float, 8); else if (hg == 4) OPTSTAGE_ROPE(float, 4); else OPTSTAGE_ROPE(float, 1); }
 #undef OPTSTAGE_ROPE
@@ -624,7 +637,8 @@ hipError_t launch_slabs(const void* src, void* dst, int N, int K, int transposed
 hipError_t launch_transpose(int dtype, const void* src, void* dst, int rows, int cols, hipStream_t s) {
   if (rows <= 0 || cols <= 0) return hipErrorInvalidValue;
   dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-  if (dtype == DT_BF16) hipLaunchKernelGGL(transpose_kernel<unsigned short>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, rows, cols);
+  if (dtype == DT_BF16) hipLaunchKernelGGL(transpose_kernel<unsigned short>, grid, dim3(256), 0, s,
+      (const unsigned short*)src, (unsigned short*)dst, rows, cols);
   else hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, s, (const float*)src, (float*)dst, rows, cols);
   return hipGetLastError();
 }
@@ -633,6 +647,7 @@ hipError_t launch_checksum(const void* buf, uint64_t bytes, uint64_t* out_dev, h
   if (bytes % 8) return hipErrorInvalidValue;
   hipLaunchKernelGGL(checksum_zero_kernel, dim3(1), dim3(1), 0, s, (unsigned long long*)out_dev);
   size_t n = bytes / 8;
-  if (n) hipLaunchKernelGGL(checksum_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, (const unsigned long long*)buf, n, (unsigned long long*)out_dev);
+  if (n) hipLaunchKernelGGL(checksum_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, (const unsigned long long*)buf, n,
+      (unsigned long long*)out_dev);
   return hipGetLastError();
 }

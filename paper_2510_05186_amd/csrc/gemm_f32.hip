@@ -73,7 +73,8 @@ hipError_t launch_gemm_f32(int layout, int epi, const void* A, const void* B, vo
   dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
   const float *a = (const float*)A, *b = (const float*)B, *r = (const float*)R;
   float* c = (float*)C;
-  if (epi == EPI_STORE || epi == EPI_STOREF) hipLaunchKernelGGL(gemm_f32_kernel<EPI_STORE>, grid, block, 0, s, a, b, c, r, M, N, K, sam, sak, sbn, sbk, ldc);
+  if (epi == EPI_STORE || epi == EPI_STOREF) hipLaunchKernelGGL(gemm_f32_kernel<EPI_STORE>, grid, block, 0, s, a, b, c, r,
+      M, N, K, sam, sak, sbn, sbk, ldc);
   else if (epi == EPI_RESID) hipLaunchKernelGGL(gemm_f32_kernel<EPI_RESID>, grid, block, 0, s, a, b, c, r, M, N, K, sam, sak, sbn, sbk, ldc);
   else if (epi == EPI_ACCUM) hipLaunchKernelGGL(gemm_f32_kernel<EPI_ACCUM>, grid, block, 0, s, a, b, c, r, M, N, K, sam, sak, sbn, sbk, ldc);
   else return hipErrorInvalidValue;

@@ -82,7 +82,8 @@ optstage_status optstage_op_weight_slabs(const void* src, void* dst, uint32_t N,
 
 optstage_status optstage_op_gemm_grouped(uint32_t layout, uint32_t epilogue, uint32_t n,
                                          const optstage_gemm_problem* problems, uint32_t K, void* stream) {
-  REQ(problems && n >= 1 && n <= 16 && layout <= 1 && (epilogue == 0 || epilogue == 2 || (epilogue == 3 && layout == 1)), "gemm_grouped: bad argument");
+  REQ(problems && n >= 1 && n <= 16 && layout <= 1 && (epilogue == 0 || epilogue == 2 || (epilogue == 3 && layout == 1)),
+      "gemm_grouped: bad argument");
   GemmProblem pr[16];
   for (uint32_t i = 0; i < n; ++i) {
     const optstage_gemm_problem& q = problems[i];
@@ -167,7 +168,8 @@ optstage_status optstage_op_norm_bwd_static(uint32_t dtype, uint32_t family, con
   optstage_status st = static_scratch(&partial);
   if (st != OPTSTAGE_OK) return st;
   // every partial row the reduction reads is written in full by the first kernel: nothing needs clearing
-  return wrap(launch_norm_bwd(dtype, family, dn, x, stats, gamma, dres, dx, partial, dgamma, dbeta, rows, hidden, (hipStream_t)stream), "norm_bwd_static");
+  return wrap(launch_norm_bwd(dtype, family, dn, x, stats, gamma, dres, dx, partial, dgamma, dbeta, rows, hidden,
+      (hipStream_t)stream), "norm_bwd_static");
 }
 
 optstage_status optstage_op_act_fwd(uint32_t dtype, uint32_t family, const void* gu, void* a, uint32_t rows,

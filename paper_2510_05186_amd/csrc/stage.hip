@@ -207,6 +207,7 @@ struct optstage {
   std::vector<const void*> x_in, dy_out;
   std::vector<void*> y_out, dx_in;
   std::vector<hipEvent_t> ev_f, ev_o, ev_r, ev_pos;   // [mb], [mb][layer] x3
+  std::vector<hipEvent_t> ev_fl;                      // [mb][layer]: that layer's forward kernels of F mb have ended
   hipEvent_t last_r = nullptr;   // event of the most recent reload (separate reload stream only)
   std::vector<hipEvent_t> tpool;
   size_t tnext = 0;
@@ -337,14 +338,16 @@ optstage_status apply_event(Logical& lg, const optstage_event& ev, OpBufs* out) 
     case OPTSTAGE_O:
     case OPTSTAGE_OWAIT:
     case OPTSTAGE_R: {
-      if (!ev.kind_mask || (ev.kind_mask >> NFK)) return fail(OPTSTAGE_E_ARG, "kind_mask 0x%x names no offloadable kind or a non-offloadable one", ev.kind_mask);
+      if (!ev.kind_mask || (ev.kind_mask >> NFK)) return fail(OPTSTAGE_E_ARG,
+          "kind_mask 0x%x names no offloadable kind or a non-offloadable one", ev.kind_mask);
       const int l = (int)ev.layer;
       for (int k = 0; k < NFK; ++k) {
         if (!(ev.kind_mask & (1u << k))) continue;
         BufRec& b = lg.buf(j, l, k);
         if (ev.op == OPTSTAGE_O) {
           if (!mb.f || mb.b) return fail(OPTSTAGE_E_ORDER, "offload of micro-batch %d outside its F..B window", j);
-          if (b.state != B_DEV) return fail(OPTSTAGE_E_ORDER, "offload of micro-batch %d layer %d kind %d: not resident or already offloaded", j, l, k);
+          if (b.state != B_DEV) return fail(OPTSTAGE_E_ORDER,
+              "offload of micro-batch %d layer %d kind %d: not resident or already offloaded", j, l, k);
           uint64_t ho = lg.host.alloc(lg.bytes[k]);
           if (ho == UINT64_MAX) return fail(OPTSTAGE_E_HOSTPOOL, "pinned host pool exhausted (%llu bytes)", (unsigned long long)lg.host.capacity());
           b.host_off = ho;
@@ -465,27 +468,33 @@ optstage_status k_gemm_grouped(optstage* st, int layout, int epi, int n, const G
 }
 optstage_status k_norm_fwd(optstage* st, const void* x, const void* g, const void* b, void* out, float* stats) {
   const Shape& s = st->sh;
-  KT(OPTSTAGE_KC_NORM_FWD, 2.0 * s.e * s.tokens * s.h, launch_norm_fwd(s.dtype, s.family, x, g, b, out, stats, s.tokens, s.h, st->desc.norm_eps, st->cs));
+  KT(OPTSTAGE_KC_NORM_FWD, 2.0 * s.e * s.tokens * s.h, launch_norm_fwd(s.dtype, s.family, x, g, b, out, stats, s.tokens,
+      s.h, st->desc.norm_eps, st->cs));
   return OPTSTAGE_OK;
 }
-optstage_status k_norm_bwd(optstage* st, const void* dn, const void* x, const float* stats, const void* g, const void* dres, void* dx, float* dg, float* db, bool store) {
+optstage_status k_norm_bwd(optstage* st, const void* dn, const void* x, const float* stats, const void* g, const void* dres,
+    void* dx, float* dg, float* db, bool store) {
   const Shape& s = st->sh;
-  KT(OPTSTAGE_KC_NORM_BWD, 4.0 * s.e * s.tokens * s.h, launch_norm_bwd(s.dtype, s.family, dn, x, stats, g, dres, dx, (float*)(st->wsp() + st->ws.partial), dg, db, s.tokens, s.h, st->cs, store ? 1 : 0));
+  KT(OPTSTAGE_KC_NORM_BWD, 4.0 * s.e * s.tokens * s.h, launch_norm_bwd(s.dtype, s.family, dn, x, stats, g, dres, dx,
+      (float*)(st->wsp() + st->ws.partial), dg, db, s.tokens, s.h, st->cs, store ? 1 : 0));
   return OPTSTAGE_OK;
 }
 optstage_status k_act_fwd(optstage* st, const void* gu, void* a) {
   const Shape& s = st->sh;
-  KT(OPTSTAGE_KC_ACT_FWD, (s.family == OPTSTAGE_LLAMA ? 3.0 : 2.0) * s.e * s.tokens * s.f, launch_act_fwd(s.dtype, s.family, gu, a, s.tokens, s.f, st->cs));
+  KT(OPTSTAGE_KC_ACT_FWD, (s.family == OPTSTAGE_LLAMA ? 3.0 : 2.0) * s.e * s.tokens * s.f, launch_act_fwd(s.dtype, s.family,
+      gu, a, s.tokens, s.f, st->cs));
   return OPTSTAGE_OK;
 }
 optstage_status k_act_bwd(optstage* st, const void* da, const void* gu, void* dgu) {
   const Shape& s = st->sh;
-  KT(OPTSTAGE_KC_ACT_BWD, (s.family == OPTSTAGE_LLAMA ? 5.0 : 3.0) * s.e * s.tokens * s.f, launch_act_bwd(s.dtype, s.family, da, gu, dgu, s.tokens, s.f, st->cs));
+  KT(OPTSTAGE_KC_ACT_BWD, (s.family == OPTSTAGE_LLAMA ? 5.0 : 3.0) * s.e * s.tokens * s.f, launch_act_bwd(s.dtype, s.family,
+      da, gu, dgu, s.tokens, s.f, st->cs));
   return OPTSTAGE_OK;
 }
 optstage_status k_rope(optstage* st, const void* src, void* dst, int backward) {
   const Shape& s = st->sh;
-  KT(OPTSTAGE_KC_ROPE, 2.0 * s.e * s.tokens * (s.nq + s.nkv) * s.d, launch_rope(s.dtype, src, dst, (const float*)(st->wsp() + st->ws.rope), s.tokens, s.seq, s.nq, s.nkv, s.d, backward, 1, st->cs));
+  KT(OPTSTAGE_KC_ROPE, 2.0 * s.e * s.tokens * (s.nq + s.nkv) * s.d, launch_rope(s.dtype, src, dst,
+      (const float*)(st->wsp() + st->ws.rope), s.tokens, s.seq, s.nq, s.nkv, s.d, backward, 1, st->cs));
   return OPTSTAGE_OK;
 }
 optstage_status k_attn_fwd(optstage* st, const void* qkv, void* o, float* lse) {
@@ -495,7 +504,8 @@ optstage_status k_attn_fwd(optstage* st, const void* qkv, void* o, float* lse) {
 }
 optstage_status k_attn_bwd(optstage* st, const void* qkv, const void* o, const void* dout, const float* lse, void* dqkv) {
   const Shape& s = st->sh;
-  KT(OPTSTAGE_KC_ATTN_BWD, 5.0 * s.mb * s.seq * s.seq * s.nq * s.d, launch_attn_bwd(s.dtype, qkv, o, dout, lse, dqkv, (float*)(st->wsp() + st->ws.attn), s.seq, s.mb, s.nq, s.nkv, s.d, st->cs));
+  KT(OPTSTAGE_KC_ATTN_BWD, 5.0 * s.mb * s.seq * s.seq * s.nq * s.d, launch_attn_bwd(s.dtype, qkv, o, dout, lse, dqkv,
+      (float*)(st->wsp() + st->ws.attn), s.seq, s.mb, s.nq, s.nkv, s.d, st->cs));
   return OPTSTAGE_OK;
 }
 
@@ -543,6 +553,9 @@ optstage_status exec_forward(optstage* st, int j, int c, const OpBufs& ob) {
     void* y = l + 1 < l1 ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[io];
     const void* wd = fwd_operand(st, l, OPTSTAGE_W_D, &lay);
     TRY(k_gemm(st, lay, EPI_RESID, a, wd, y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
+    // everything this layer keeps is final from here on: an offload of its activations may start while the layers
+    // after it still run
+    HIP_TRY(hipEventRecord(st->ev_fl[(size_t)j * s.L + l], cs));
   }
   return OPTSTAGE_OK;
 }
@@ -573,9 +586,11 @@ optstage_status exec_backward_input(optstage* st, int j, int c, const OpBufs& ob
     TRY(k_act_bwd(st, da, P(l, OPTSTAGE_K_GU), P(l, OPTSTAGE_K_GU)));
     const void* wgu = bwd_operand(st, l, OPTSTAGE_W_GU, &lay);
     TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_GU), wgu, dn, nullptr, T, s.h, s.up_w, s.up_w, s.up_w, s.h));
-    if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l, OPTSTAGE_K_N2), stats + (size_t)nstat * T));
+    if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), P(l,
+        OPTSTAGE_K_N2), stats + (size_t)nstat * T));
     // dx_mid = dy + norm2'(dn2)
-    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l, OPTSTAGE_K_DX_MID), GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2), store));
+    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_MID), stats + (size_t)nstat * T, W(st, l, OPTSTAGE_W_G2), dy, P(l,
+        OPTSTAGE_K_DX_MID), GW(st, l, OPTSTAGE_W_G2), GW(st, l, OPTSTAGE_W_B2), store));
     // do = dx_mid W_o ; attention backward ; rotary backward into the qkv buffer
     const void* wo = bwd_operand(st, l, OPTSTAGE_W_O, &lay);
     TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_DX_MID), wo, dout, nullptr, T, s.nq * s.d, s.h, s.h, s.h, s.nq * s.d));
@@ -589,7 +604,8 @@ optstage_status exec_backward_input(optstage* st, int j, int c, const OpBufs& ob
     TRY(k_gemm(st, lay, EPI_STORE, P(l, OPTSTAGE_K_QKV), wq, dn, nullptr, T, s.h, s.qkv_w, s.qkv_w, s.qkv_w, s.h));
     if (rc) TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_IN), W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), P(l, OPTSTAGE_K_N1), stats));
     void* dx = l > l0 ? P(l - 1, OPTSTAGE_K_DY) : st->dx_in[io];
-    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l, OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1), store));
+    TRY(k_norm_bwd(st, dn, P(l, OPTSTAGE_K_X_IN), stats, W(st, l, OPTSTAGE_W_G1), P(l, OPTSTAGE_K_DX_MID), dx, GW(st, l,
+        OPTSTAGE_W_G1), GW(st, l, OPTSTAGE_W_B1), store));
   }
   return OPTSTAGE_OK;
 }
@@ -664,8 +680,10 @@ optstage_status exec_event(optstage* st, const optstage_event& ev, const OpBufs&
       if ((rc = span_end(st, st->cs, sp)) != OPTSTAGE_OK) return rc;
       break;
     case OPTSTAGE_O: {
-      // the offload starts after the F that produced the data has ended
-      HIP_TRY(hipStreamWaitEvent(st->xs, ev_f, 0));
+      // the offload starts once the layer that produced the data has ended (the F it belongs to may still be running
+      // its later layers; the list has the O after that F, so the layer's event has been recorded)
+      (void)ev_f;
+      HIP_TRY(hipStreamWaitEvent(st->xs, st->ev_fl[(size_t)j * L + ev.layer], 0));
       // a pinned slot released by a reload listed earlier may be handed to this offload: with a reload stream
       // of its own that reload must have drained first (on a shared channel stream order already says so)
       if (st->rs != st->xs && st->last_r) HIP_TRY(hipStreamWaitEvent(st->xs, st->last_r, 0));
@@ -719,8 +737,10 @@ optstage_status precheck(optstage* st, const optstage_event* events, size_t n) {
     if (ev.op <= OPTSTAGE_W && ev.layer >= (uint32_t)st->sh.chunks) return fail(OPTSTAGE_E_ARG, "event %zu: chunk %u out of range", i, ev.layer);
     if (ev.op > OPTSTAGE_W && ev.layer >= (uint32_t)st->sh.L) return fail(OPTSTAGE_E_ARG, "event %zu: layer %u out of range", i, ev.layer);
     const size_t io = ev.op <= OPTSTAGE_W ? (size_t)ev.layer * st->desc.n_microbatches + j : 0;
-    if (ev.op == OPTSTAGE_F && (!st->x_in[io] || !st->y_out[io])) return fail(OPTSTAGE_E_STATE, "event %zu: x_in / y_out of micro-batch %d not bound", i, j);
-    if (ev.op == OPTSTAGE_B && (!st->dy_out[io] || !st->dx_in[io])) return fail(OPTSTAGE_E_STATE, "event %zu: dy_out / dx_in of micro-batch %d not bound", i, j);
+    if (ev.op == OPTSTAGE_F && (!st->x_in[io] || !st->y_out[io])) return fail(OPTSTAGE_E_STATE,
+        "event %zu: x_in / y_out of micro-batch %d not bound", i, j);
+    if (ev.op == OPTSTAGE_B && (!st->dy_out[io] || !st->dx_in[io])) return fail(OPTSTAGE_E_STATE,
+        "event %zu: dy_out / dx_in of micro-batch %d not bound", i, j);
     if (ev.op == OPTSTAGE_O) needs_host = true;
   }
   if (needs_host && !st->desc.host_pool) return fail(OPTSTAGE_E_HOSTPOOL, "offload requested but no pinned host pool was given");
@@ -860,7 +880,7 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
     optstage_destroy(st);
     return fail(OPTSTAGE_E_HIP, "hipEventCreate failed");
   }
-  if (!mk(st->ev_f, nio) || !mk(st->ev_o, m * L) || !mk(st->ev_r, m * L) || !mk(st->ev_pos, m * L)) {
+  if (!mk(st->ev_f, nio) || !mk(st->ev_o, m * L) || !mk(st->ev_r, m * L) || !mk(st->ev_pos, m * L) || !mk(st->ev_fl, m * L)) {
     optstage_destroy(st);
     return fail(OPTSTAGE_E_HIP, "hipEventCreateWithFlags failed");
   }
@@ -875,7 +895,7 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
 
 void optstage_destroy(optstage_t* st) {
   if (!st) return;
-  for (auto* v : {&st->ev_f, &st->ev_o, &st->ev_r, &st->ev_pos, &st->tpool})
+  for (auto* v : {&st->ev_f, &st->ev_o, &st->ev_r, &st->ev_pos, &st->ev_fl, &st->tpool})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
   if (st->origin) (void)hipEventDestroy(st->origin);
   delete st;
@@ -884,7 +904,8 @@ void optstage_destroy(optstage_t* st) {
 optstage_status optstage_set_weight(optstage_t* st, uint32_t layer, uint32_t which, const void* weight_dev, float* grad) {
   if (!st || !weight_dev) return fail(OPTSTAGE_E_ARG, "null argument");
   if (layer >= (uint32_t)st->sh.L || which >= OPTSTAGE_N_WEIGHTS) return fail(OPTSTAGE_E_ARG, "layer or weight id out of range");
-  if (st->sh.family == OPTSTAGE_LLAMA && (which == OPTSTAGE_W_B1 || which == OPTSTAGE_W_B2)) return fail(OPTSTAGE_E_ARG, "this family has no norm bias");
+  if (st->sh.family == OPTSTAGE_LLAMA && (which == OPTSTAGE_W_B1 || which == OPTSTAGE_W_B2)) return fail(OPTSTAGE_E_ARG,
+      "this family has no norm bias");
   if (((uintptr_t)weight_dev | (uintptr_t)grad) & 15) return fail(OPTSTAGE_E_ARG, "weights and gradients must be 16-byte aligned");
   st->w[(size_t)layer * OPTSTAGE_N_WEIGHTS + which] = weight_dev;
   st->gw[(size_t)layer * OPTSTAGE_N_WEIGHTS + which] = grad;
@@ -904,7 +925,8 @@ optstage_status optstage_bind_io_chunk(optstage_t* st, uint32_t chunk, uint32_t 
   if (!st) return fail(OPTSTAGE_E_ARG, "null handle");
   if (chunk >= (uint32_t)st->sh.chunks) return fail(OPTSTAGE_E_ARG, "chunk out of range");
   if (mb >= st->desc.n_microbatches) return fail(OPTSTAGE_E_ARG, "micro-batch out of range");
-  if (((uintptr_t)x_in | (uintptr_t)dy_out | (uintptr_t)y_out | (uintptr_t)dx_in) & 15) return fail(OPTSTAGE_E_ARG, "io tensors must be 16-byte aligned");
+  if (((uintptr_t)x_in | (uintptr_t)dy_out | (uintptr_t)y_out | (uintptr_t)dx_in) & 15) return fail(OPTSTAGE_E_ARG,
+      "io tensors must be 16-byte aligned");
   const size_t io = (size_t)chunk * st->desc.n_microbatches + mb;
   st->x_in[io] = x_in; st->dy_out[io] = dy_out; st->y_out[io] = y_out; st->dx_in[io] = dx_in;
   return OPTSTAGE_OK;

@@ -732,21 +732,26 @@ def fit_offloads(comp, n_layers, kinds, kind_bytes, fits, lead=1):
     return None
 
 
-def budgeted_lists(p, m, n_layers, kinds, kind_bytes, fits, base_lists, t_op, t_copy_of_bytes, duplex=False,
-                   t_comm=0.0, max_extra=None, lead=1):
+def budgeted_lists(p, m, n_layers, kinds, kind_bytes, fits, base_lists, t_op, t_copy_of_event, duplex=False,
+                   t_comm=0.0, max_extra=None, leads=(1, 2)):
     """Per-stage lists for a pipeline in which every device has the same byte budget, chosen by modelled makespan.
 
     base_lists(cap_of_stage) -> p compute orders (split B/W) in which stage i holds at most cap_of_stage(i)
     micro-batches between F and W; `fits` as in fit_offloads (all stages have the same shape).  For every fill
     level e = 0 .. max_extra the caps are p - i + e (a denser fill than p - i in flight shortens the bubble and
     costs memory); a stage whose list cannot be made to fit even with offloads gets its cap lowered until it can.
-    Every candidate is timed with pipeline_timeline from the given op and transfer times; the fastest is returned
-    as (lists, info)."""
+    Every candidate is timed with pipeline_timeline from the given op times and t_copy_of_event(event) -> ms; the
+    fastest is returned as (lists, info).  A stage that has to offload gets, of the reload leads in `leads`, the one
+    whose list the timeline of that stage alone finishes first (how far ahead of its B a reload is listed decides
+    whether it runs under compute or holds B up, and how early the offload before it must be credited).  Fill levels
+    tried: 0 to 3, then every fourth, and the densest."""
     max_extra = p - 1 if max_extra is None else max_extra
+    size = lambda e: sum(kind_bytes[k] for k in e[3])
+    memo = {}
     best = None
     tried = []
     seen = set()
-    for extra in range(max_extra + 1):
+    for extra in sorted({e for e in range(max_extra + 1) if e < 4 or e % 4 == 0 or e == max_extra}):
         caps = [min(m, p - i + extra) for i in range(p)]
         lists = None
         while True:
@@ -755,7 +760,19 @@ def budgeted_lists(p, m, n_layers, kinds, kind_bytes, fits, base_lists, t_op, t_
             for i in range(p):
                 ev = comp[i]
                 if not fits(ev)[0]:
-                    ev = fit_offloads(comp[i], n_layers, kinds, kind_bytes, fits, lead=lead)
+                    key = (tuple(sorted(t_op[i].items())), tuple(comp[i]))
+                    if key not in memo:                  # many fill levels give a stage the same compute order
+                        pick, t_pick = None, None
+                        for ld in leads:
+                            cand = fit_offloads(comp[i], n_layers, kinds, kind_bytes, fits, lead=ld)
+                            if cand is None:
+                                continue
+                            t = pipeline_timeline([cand], [t_op[i]], t_copy=lambda s_, e: t_copy_of_event(e),
+                                                  duplex=duplex).makespan
+                            if t_pick is None or t < t_pick * (1 - 1e-9):
+                                pick, t_pick = cand, t
+                        memo[key] = pick
+                    ev = memo[key]
                 if ev is None:
                     if caps[i] == 1:
                         raise RuntimeError("one micro-batch does not fit the budget")
@@ -770,8 +787,7 @@ def budgeted_lists(p, m, n_layers, kinds, kind_bytes, fits, base_lists, t_op, t_
         if key in seen:
             continue
         seen.add(key)
-        size = lambda e: sum(kind_bytes[k] for k in e[3])
-        tl = pipeline_timeline(lists, t_op, t_comm=t_comm, t_copy=lambda i, e: t_copy_of_bytes(size(e)), duplex=duplex)
+        tl = pipeline_timeline(lists, t_op, t_comm=t_comm, t_copy=lambda i, e: t_copy_of_event(e), duplex=duplex)
         info = {"extra_fill": extra, "caps": list(caps), "makespan_model": tl.makespan, "bubble_model": list(tl.bubble),
                 "stall_model": list(tl.stall),
                 "offloaded_bytes": [sum(size(e) for e in ev if e[0] == "O") for ev in lists]}
@@ -794,11 +810,12 @@ def nominal_op_times(cfg, tflops=1100.0):
 
 
 def workload_lists(cfg, budget, t_op=None, link_gbps=55.0, copy_latency_ms=0.02, duplex=False, m=None, max_extra=None,
-                   recompute=0):
+                   recompute=0, reload_gbps=None):
     """The lists of all p stages for a benchmark workload with a split B/W schedule under `budget` bytes of
     activations per device (0 = no budget: the plain split B/W lists with p - i micro-batches in flight), every stage
     shaped like cfg.  The library's planner decides what fits; offloads are chosen item by item (fit_offloads), the
-    fill level by modelled makespan (budgeted_lists) from t_op (default: nominal_op_times) and the host-link rate.
+    fill level by modelled makespan (budgeted_lists) from t_op (default: nominal_op_times) and the host-link rate
+    (reload_gbps: the rate of reloads where it differs from that of offloads, as it does when both run at once).
     m overrides the micro-batch count (tests run fewer).  -> (lists, info)"""
     from stage_inputs import schedules as G
     from . import binding as B
@@ -815,9 +832,11 @@ def workload_lists(cfg, budget, t_op=None, link_gbps=55.0, copy_latency_ms=0.02,
         st, bad, _, _ = B.plan(c, ev, budget=budget, recompute=recompute)
         return st == B.OK, bad
 
+    rate = {"O": link_gbps, "R": reload_gbps or link_gbps}
     return budgeted_lists(p, m, cfg.n_layers, tuple(cfg.offload_kinds), kb, fits,
                           lambda cap: G.split_bw_greedy(p, m, cap_of_stage=cap), [dict(t_op)] * p,
-                          lambda nbytes: nbytes / (link_gbps * 1e6) + copy_latency_ms, duplex=duplex, max_extra=max_extra)
+                          lambda e: sum(kb[k] for k in e[3]) / (rate[e[0]] * 1e6) + copy_latency_ms, duplex=duplex,
+                          max_extra=max_extra)
 
 
 # ------------------------------------------------------------------------------- online scheduling (Sec. 4.3)

@@ -33,12 +33,15 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 
 class Stage:
     def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0,
-                 duplex: bool = False, recompute: bool = False, n_chunks: int = 1, grad_overwrite: bool = False):
+                 duplex: bool = False, recompute: bool = False, n_chunks: int = 1, grad_overwrite: bool = False,
+                 host_pool: torch.Tensor | None = None):
         """duplex: reloads get a stream of their own instead of sharing the offloads' (single channel).
         recompute: F keeps no norm outputs and no MLP activation output; B rebuilds them for W.
         n_chunks: model chunks on this stage (cfg.n_layers counts all of them).
         grad_overwrite: the first B / W of an iteration store the parameter gradients instead of adding to them, so
-        the accumulators need no clearing between iterations."""
+        the accumulators need no clearing between iterations.
+        host_pool: a pinned uint8 tensor to use as the offload pool instead of allocating host_pool_bytes (a process
+        that runs several stages one after the other can hand the same block to each)."""
         if not torch.cuda.is_available():
             raise RuntimeError("optstage needs a GPU: there is no CPU path")
         self.cfg = cfg
@@ -52,7 +55,12 @@ class Stage:
         self.n_chunks = int(n_chunks)
         self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-        self.host_pool = torch.empty(host_pool_bytes, dtype=torch.uint8, pin_memory=True) if host_pool_bytes else None
+        if host_pool is not None:
+            if not host_pool.is_pinned() or host_pool.dtype != torch.uint8:
+                raise ValueError("host_pool must be a pinned uint8 tensor")
+            self.host_pool, host_pool_bytes = host_pool, host_pool.numel()
+        else:
+            self.host_pool = torch.empty(host_pool_bytes, dtype=torch.uint8, pin_memory=True) if host_pool_bytes else None
         self.compute_stream, self.copy_stream, self.reload_stream = _streams()
         self.desc = B.make_desc(
             cfg, budget=budget, arena=self.arena.data_ptr(), arena_bytes=arena_bytes,

@@ -747,20 +747,21 @@ def test_stats_report_the_trace_the_live_levels_and_the_stalls():
         if in_flight:
             level.append(lv)
     assert s.min_live_bytes == min(level) > 0 and s.peak_bytes == peak
-    # times: compute ops do not overlap and follow list order; a transfer lies after the F that made its data; every
+    # times: compute ops do not overlap and follow list order; an offload starts after its layer's part of the F that
+    # made its data (the F itself may still be running its later layers) and ends after that F has started; every
     # OWAIT here has nothing between it and its offload, and every reload nothing between it and its B, so the compute
     # stream must have waited for them
-    ends = {}
+    starts = {}
     last_end = 0.0
     for g in tr:
         if g[0] in ("F", "B", "W"):
             assert g[5] >= last_end - 1e-3 and g[6] > g[5]
             last_end = g[6]
-            ends[(g[0], g[1])] = g[6]
+            starts[(g[0], g[1])] = g[5]
         elif g[0] == "OWAIT":
             assert g[5] == -1.0 and g[7] >= 0.0
         elif g[0] == "O":
-            assert g[5] >= ends[("F", g[1])] - 1e-3 and g[6] > g[5]
+            assert g[5] > starts[("F", g[1])] and g[6] > g[5]
     assert s.stall_ms[0] > 0.0 and s.stall_ms[1] > 0.0
     assert s.stall_ms[0] + s.stall_ms[1] == pytest.approx(sum(g[7] for g in tr), rel=1e-6)
     st.close()
