@@ -95,6 +95,13 @@ typedef struct {
                                            chunk c is layers c * n_layers / n_chunks onwards.  Every chunk has its
                                            own F / B / W per micro-batch and its own boundary tensors; arena,
                                            budget and transfer channel are shared */
+  uint32_t no_fusion;                   /* 0: where the shapes allow it (bf16 LLAMA, head_dim 128, ffn % 128 == 0, products
+                                           large enough for the direct GEMM kernel) the rotary embedding runs in the
+                                           epilogue of the QKV projection and the MLP activation in the epilogue of the
+                                           gate / up projection, each from the fp32 accumulators (one rounding to the
+                                           storage type less than the separate kernels; the stored kinds and their
+                                           bytes are the same).  1: always the separate kernels */
+  uint32_t reserved;                    /* 0 */
   uint64_t hbm_budget_bytes;            /* M_limit_i for activations (Eq. 7); 0 = unlimited */
   void* arena; uint64_t arena_bytes;          /* DEVICE block for activations, 256-byte aligned */
   void* workspace; uint64_t workspace_bytes;  /* DEVICE block for transients, >= optstage_query_sizes' figure */

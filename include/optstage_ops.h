@@ -36,9 +36,27 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
 
 /* Writes a bf16 matrix into the slab layout of layout 2: dst (DEVICE, ceil(N / 256) * 256 * K elements) receives
  * B(n,k) = src[n * K + k] (transposed = 0) or src[k * N + n] (transposed = 1: the source is [K,N]); rows past N are
- * zero.  K % 64 must be 0.  The stage does this for its weight copies in optstage_set_weight. */
+ * zero.  K % 64 must be 0.  transposed = 2 (paired, for optstage_op_gemm_swiglu): src is a [gate | up] weight of N = 2 f
+ * rows [N,K], f % 128 == 0, and slab row 256 t + 128 w + 64 q + o holds source row q f + 128 t + 64 w + o (q = 0 gate,
+ * 1 up), so that every 128-column half of an output tile is 64 gate columns beside the 64 matching up columns.  The
+ * stage does this for its weight copies in optstage_set_weight. */
 optstage_status optstage_op_weight_slabs(const void* src, void* dst, uint32_t N, uint32_t K, uint32_t transposed,
                                          void* stream);
+
+/* The QKV projection with the rotary embedding fused into its epilogue (bf16): C = A B^T as optstage_op_gemm with
+ * layout 0 or 2, then, before the one rounding to bf16, the first rot_cols columns (the q and k heads, a multiple of
+ * 128; head_dim is 128) are rotated by position = row % seq with the pairing and the table of optstage_op_rope.  Needs
+ * N % 128 == 0 and a shape the direct kernel serves (K % 64 == 0, at least 128 output tiles of 256 x 256), else
+ * OPTSTAGE_E_ARG.  Same result as optstage_op_gemm followed by optstage_op_rope except for that one rounding less. */
+optstage_status optstage_op_gemm_rope(uint32_t layout, const void* A, const void* B, void* C, uint32_t M, uint32_t N,
+                                      uint32_t K, uint32_t lda, uint32_t ldb, uint32_t ldc, const float* table, uint32_t seq,
+                                      uint32_t rot_cols, void* stream);
+/* The gate / up projection with the MLP activation fused into its epilogue (bf16, LLAMA): B is the [gate | up] weight
+ * [2 ffn, K] in PAIRED slabs (optstage_op_weight_slabs with transposed = 2).  Writes GU [M, 2 ffn] = A B^T in the plain
+ * [gate | up] layout (what the backward pass reads) and a_out [M, ffn] = silu(gate) * up formed from the fp32
+ * accumulators.  ffn % 128 == 0, K % 64 == 0 and at least 128 output tiles, else OPTSTAGE_E_ARG. */
+optstage_status optstage_op_gemm_swiglu(const void* A, const void* B, void* GU, void* a_out, uint32_t M, uint32_t ffn,
+                                        uint32_t K, uint32_t lda, void* stream);
 
 /* n (1..16) independent bf16 products of the same layout, epilogue and K in ONE launch (the weight-gradient GEMMs
  * of a W op, dW = dY^T X for every linear of every layer, do not depend on one another: Sec. 2.2).  problems is a

@@ -30,7 +30,7 @@ class Desc(C.Structure):
                 ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32), ("ffn", C.c_uint32), ("seq", C.c_uint32),
                 ("micro_batch", C.c_uint32), ("stage_index", C.c_uint32), ("n_stages", C.c_uint32),
                 ("n_microbatches", C.c_uint32), ("norm_eps", C.c_float), ("rope_base", C.c_float),
-                ("recompute", C.c_uint32), ("n_chunks", C.c_uint32),
+                ("recompute", C.c_uint32), ("n_chunks", C.c_uint32), ("no_fusion", C.c_uint32), ("reserved", C.c_uint32),
                 ("hbm_budget_bytes", C.c_uint64), ("arena", C.c_void_p), ("arena_bytes", C.c_uint64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64), ("host_pool", C.c_void_p),
                 ("host_pool_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
@@ -93,6 +93,8 @@ _SIGS = {
     "optstage_debug_read": [_vp, _u32, _u32, _u32, _vp, _u64],
     "optstage_plan": [C.POINTER(Desc), C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(_u64), C.POINTER(_u64)],
     "optstage_op_gemm": [_u32, _u32, _u32, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _u32, _vp],
+    "optstage_op_gemm_rope": [_u32, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _u32, _u32, _vp, _u32, _u32, _vp],
+    "optstage_op_gemm_swiglu": [_vp, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _vp],
     "optstage_op_gemm_grouped": [_u32, _u32, _u32, _vp, _u32, _vp],
     "optstage_op_weight_slabs": [_vp, _vp, _u32, _u32, _u32, _vp],
     "optstage_op_norm_fwd": [_u32, _u32, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _f32, _vp],
@@ -154,7 +156,8 @@ def make_events(events) -> "C.Array":
 
 
 def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_bytes=0, host_pool=0,
-              host_pool_bytes=0, compute_stream=0, copy_stream=0, reload_stream=0, recompute=0, n_chunks=1) -> Desc:
+              host_pool_bytes=0, compute_stream=0, copy_stream=0, reload_stream=0, recompute=0, n_chunks=1,
+              no_fusion=0) -> Desc:
     d = Desc()
     d.struct_size = C.sizeof(Desc)
     d.family, d.dtype = cfg.family, cfg.dtype
@@ -170,6 +173,7 @@ def make_desc(cfg, budget=0, arena=0, arena_bytes=0, workspace=0, workspace_byte
     d.reload_stream = reload_stream
     d.recompute = int(recompute)
     d.n_chunks = int(n_chunks)
+    d.no_fusion = int(no_fusion)
     return d
 
 

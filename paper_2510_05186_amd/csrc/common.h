@@ -35,8 +35,17 @@ enum { FAM_GPT = 0, FAM_LLAMA = 1 };
 // GEMM_NT_SLAB: C = A B^T with B stored in slabs of 256 rows x 64 columns, slab (n / 256, k / 64) at element offset
 // ((n / 256) * (K / 64) + k / 64) * 16384, row-major inside, rows padded to a multiple of 256
 enum { GEMM_NT = 0, GEMM_TN = 1, GEMM_NT_SLAB = 2 };
-// epilogues: store C (stage dtype); store C + R (R like C); C (fp32) += product; C (fp32) = product
-enum { EPI_STORE = 0, EPI_RESID = 1, EPI_ACCUM = 2, EPI_STOREF = 3 };
+// epilogues: store C (stage dtype); store C + R (R like C); C (fp32) += product; C (fp32) = product;
+// EPI_ROPE: store C with the q and k head columns rotated by position (rotary embedding fused into the QKV projection);
+// EPI_SWIGLU: B holds the gate / up weight in paired slabs (GEMM_NT_SLAB with rows paired, see launch_slabs): stores the
+// product in the plain [gate | up] layout AND a = silu(gate) * up (the MLP activation fused into the gate / up projection)
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_ACCUM = 2, EPI_STOREF = 3, EPI_ROPE = 4, EPI_SWIGLU = 5 };
+// what the two fused epilogues need beyond C: the rotary table [seq][64] (cos, sin), the sequence length (position =
+// row % seq) and the number of leading columns that are q / k heads; the activation output [M, f] and f
+struct GemmExtra {
+  const float2* table = nullptr; int seq = 0; int rot_cols = 0;
+  void* a_out = nullptr; int f = 0;
+};
 
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
@@ -77,7 +86,8 @@ struct GemmProblem { const void* A; const void* B; void* C; const void* R; int M
 bool gemm_bf16_grouped_applies(int layout, int n, const GemmProblem* problems, int K);
 hipError_t launch_gemm_bf16_grouped(int layout, int epi, int n, const GemmProblem* problems, int K, hipStream_t s);
 hipError_t launch_gemm_bf16(int layout, int epi, const void* A, const void* B, void* C, const void* R, int M, int N,
-                            int K, int lda, int ldb, int ldc, hipStream_t s);
+                            int K, int lda, int ldb, int ldc, hipStream_t s, const GemmExtra* extra = nullptr);
+bool gemm_bf16_fused_applies(int epi, int M, int N, int K, int lda, int head_dim);
 hipError_t launch_gemm_f32(int layout, int epi, const void* A, const void* B, void* C, const void* R, int M, int N,
                            int K, int lda, int ldb, int ldc, hipStream_t s);
 hipError_t launch_norm_fwd(int dtype, int family, const void* x, const void* gamma, const void* beta, void* out,
@@ -93,7 +103,10 @@ hipError_t launch_rope_table(float* table, int seq, int d, float base, hipStream
 hipError_t launch_rope(int dtype, const void* src, void* dst, const float* table, int rows, int seq, int n_q, int n_kv,
                        int d, int backward, int do_rotate, hipStream_t s);
 hipError_t launch_transpose(int dtype, const void* src, void* dst, int rows, int cols, hipStream_t s);
-// bf16 weight into the slab layout of GEMM_NT_SLAB: B[n][k] = src[n * K + k], or src[k * N + n] when transposed
+// bf16 weight into the slab layout of GEMM_NT_SLAB: B[n][k] = src[n * K + k], or src[k * N + n] when transposed = 1.
+// transposed = 2 (paired): src is a [gate | up] weight of N = 2 f rows; slab row 256 t + 128 w + 64 q + o holds source
+// row q f + 128 t + 64 w + o, so that each wave of an output tile owns 64 gate columns and the 64 matching up columns
+// (f % 128 == 0)
 hipError_t launch_slabs(const void* src, void* dst, int N, int K, int transposed, hipStream_t s);
 bool gemm_bf16_slab_applies(int M, int N, int K, int lda);
 hipError_t launch_checksum(const void* buf, uint64_t bytes, uint64_t* out_dev, hipStream_t s);

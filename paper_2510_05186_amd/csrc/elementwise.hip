@@ -441,15 +441,18 @@ __global__ void rope_kernel(const T* src, T* dst, const float2* __restrict__ tab
 // so that the 256 rows x 64 columns a workgroup loads per k-tile are consecutive in memory: slab (n / 256, k / 64) at
 // element offset ((n / 256) * (K / 64) + k / 64) * 16384, row-major inside, rows past N zero.
 // TRANSPOSED = false: B[n][k] = src[n * K + k]; true: B[n][k] = src[k * N + n] (the transposed weight)
+// pair_f > 0 (not TRANSPOSED): the source is a [gate | up] weight with pair_f rows each; the 64 slab rows of this
+// workgroup (tile t = n0 / 256, wave half w, q = 0 gate / 1 up) come from source rows q pair_f + 128 t + 64 w + 0..63
 template <bool TRANSPOSED>
-__global__ void slab_kernel(const unsigned short* __restrict__ src, unsigned short* __restrict__ dst, int N, int K) {
+__global__ void slab_kernel(const unsigned short* __restrict__ src, unsigned short* __restrict__ dst, int N, int K, int pair_f) {
   __shared__ unsigned short tile[64][65];
   const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
+  const int s0 = pair_f > 0 ? ((n0 >> 6) & 1) * pair_f + (n0 >> 8) * 128 + ((n0 >> 7) & 1) * 64 : n0;   // first source row
   for (int e = threadIdx.x; e < 64 * 64; e += blockDim.x) {
     const int hi = e / 64, lo = e % 64;               // lo runs along the source's contiguous direction
     const int nn = TRANSPOSED ? lo : hi, kk = TRANSPOSED ? hi : lo;
     unsigned short v = 0;
-    if (n0 + nn < N) v = TRANSPOSED ? src[(size_t)(k0 + kk) * N + n0 + nn] : src[(size_t)(n0 + nn) * K + k0 + kk];
+    if (n0 + nn < N) v = TRANSPOSED ? src[(size_t)(k0 + kk) * N + n0 + nn] : src[(size_t)(s0 + nn) * K + k0 + kk];
     tile[nn][kk] = v;
   }
   __syncthreads();
@@ -629,8 +632,10 @@ hipError_t launch_slabs(const void* src, void* dst, int N, int K, int transposed
   if (N <= 0 || K <= 0 || (K % 64)) return hipErrorInvalidValue;
   const int n_pad = (N + 255) / 256 * 256;
   dim3 grid(K / 64, n_pad / 64);
-  if (transposed) hipLaunchKernelGGL(slab_kernel<true>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, N, K);
-  else hipLaunchKernelGGL(slab_kernel<false>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, N, K);
+  if (transposed == 2 && (N % 256)) return hipErrorInvalidValue;      // paired: N = 2 f with f a multiple of 128
+  if (transposed == 1) hipLaunchKernelGGL(slab_kernel<true>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, N, K, 0);
+  else hipLaunchKernelGGL(slab_kernel<false>, grid, dim3(256), 0, s, (const unsigned short*)src, (unsigned short*)dst, N, K,
+                          transposed == 2 ? N / 2 : 0);
   return hipGetLastError();
 }
 

@@ -461,6 +461,79 @@ __device__ __forceinline__ void epilogue_bf16_rows(f32x16_t (&acc)[4][4], char* 
   }
 }
 
+// Rotary embedding on the accumulators of a wave tile that is one attention head (128 columns starting at a multiple
+// of 128): column c < 64 pairs with column c + 64, which the same lane holds in the same register of acc[i][j + 2]
+// (j = 0, 1), so the rotation by position * theta_c happens in registers, in fp32, before the one conversion to bf16.
+// table[pos * 64 + c] = (cos, sin); pos = row % seq.
+__device__ __forceinline__ void rope_rotate_acc(f32x16_t (&acc)[4][4], const float2* __restrict__ table, int seq, int M,
+                                                int mw, int lane) {
+  const int khalf = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int m = mw + i * 32 + (lane & 31);
+    m = m < M ? m : M - 1;                                 // rows past the end are never stored; keep the table read in bounds
+    const float4* row = reinterpret_cast<const float4*>(table + (size_t)(m % seq) * 64);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c = j * 32 + g * 8 + khalf * 4;          // this lane's 4 consecutive frequencies
+        const float4 t0 = row[c / 2], t1 = row[c / 2 + 1]; // (cos, sin) of c, c + 1 and of c + 2, c + 3
+        const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = acc[i][j][g * 4 + e], hi = acc[i][j + 2][g * 4 + e];
+          acc[i][j][g * 4 + e] = lo * cs[e] - hi * sn[e];
+          acc[i][j + 2][g * 4 + e] = hi * cs[e] + lo * sn[e];
+        }
+      }
+  }
+}
+
+// Epilogue of the gate / up projection with the MLP activation fused in.  B is in paired slabs, so the wave tile's
+// columns 0..63 are gate columns base..base + 63 (base = 128 tile_n + 64 wn) and its columns 64..127 the up columns of
+// the same indices: a = silu(gate) * up is formed from the fp32 accumulators.  Stored: gate and up (bf16) where the
+// plain [gate | up] layout has them (GU[m][base + c], GU[m][f + base + c]) and a (bf16) at A[m][base + c]; each of
+// the three is a 128-byte row segment.  32 rows at a time go through the wave's own LDS ([32][400 B]).
+__device__ __forceinline__ void epilogue_swiglu_rows(f32x16_t (&acc)[4][4], char* smem, int wave, int lane, bf16_t* GU,
+                                                     bf16_t* Aout, int M, int f, int ldgu, int mw, int base) {
+  char* const wl = smem + wave * 32768;
+  constexpr int RS = 400;                                  // row stride: 3 x 128 B + 16 (keeps 16-byte alignment)
+  const int khalf = lane >> 5, r = lane & 31;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4_t og, ou, oa;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float gv = acc[i][j][g * 4 + e], uv = acc[i][j + 2][g * 4 + e];
+          og[e] = (bf16_t)gv;
+          ou[e] = (bf16_t)uv;
+          oa[e] = (bf16_t)(gv / (1.f + expf(-gv)) * uv);
+        }
+        const int cb = (j * 32 + g * 8 + khalf * 4) * 2;   // byte offset of the 4 columns within a 128-byte segment
+        *reinterpret_cast<bf16x4_t*>(wl + r * RS + cb) = og;
+        *reinterpret_cast<bf16x4_t*>(wl + r * RS + 128 + cb) = ou;
+        *reinterpret_cast<bf16x4_t*>(wl + r * RS + 256 + cb) = oa;
+      }
+    // the wave reads back only what it wrote itself: no workgroup barrier (the compiler orders LDS accesses of a wave)
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int it = 0; it < 12; ++it) {                      // 32 rows x 24 chunks of 16 bytes
+      const int q = it * 64 + lane, row = q / 24, cc = q % 24, seg = cc >> 3, w8 = (cc & 7) * 8;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(wl + row * RS + seg * 128 + (cc & 7) * 16);
+      const int m = mw + i * 32 + row;
+      if (m < M) {
+        bf16_t* dst = seg == 2 ? Aout + (size_t)m * f + base + w8 : GU + (size_t)m * ldgu + (seg == 1 ? f : 0) + base + w8;
+        *reinterpret_cast<u32x4*>(dst) = v;
+      }
+    }
+  }
+}
+
 // f(std::integral_constant<int, P0>{}), ..., f(std::integral_constant<int, P1 - 1>{}): a loop whose index is a
 // constant expression inside the body
 template <int P0, class F, int... I>
@@ -483,7 +556,7 @@ template <bool TNL, int EPI>
 __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                             void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N, int K, int lda,
                                             int ldb, int ldc, int tiles_m, int tiles_n, unsigned a_bytes, unsigned b_bytes,
-                                            int pid, bool b_slab = false) {
+                                            int pid, bool b_slab = false, const GemmExtra& ex = GemmExtra()) {
   constexpr int BM = 256, BN = 256, WM = 2, WN = 2, TM = 4, TN = 4;
   constexpr int OPB = 32768;                    // one operand of one stage
   const int tid = threadIdx.x, lane = tid & 63;
@@ -704,11 +777,17 @@ __device__ __forceinline__ void direct_tile(char* smem, const bf16_t* __restrict
   trip(P0, P16, 0, 0, 0, 0, 0, false, false);
   OPTSTAGE_TILE_SYNC(0);                             // every wave is done with the operand tiles, nothing in flight
 #undef OPTSTAGE_TILE_SYNC
-  if (EPI == EPI_ACCUM || EPI == EPI_STOREF)
+  if (EPI == EPI_ACCUM || EPI == EPI_STOREF) {
     epilogue_via_lds<EPI, TM, TN, 4>(acc, smem, wave, lane, Cv, R, M, N, ldc, m0 + wm * (BM / WM), n0 + wn * (BN / WN));
-  else
-    epilogue_bf16_rows<EPI>(acc, smem, wave, lane, reinterpret_cast<bf16_t*>(Cv), R, M, N, ldc, m0 + wm * (BM / WM),
-                            n0 + wn * (BN / WN));
+  } else if (EPI == EPI_SWIGLU) {
+    epilogue_swiglu_rows(acc, smem, wave, lane, reinterpret_cast<bf16_t*>(Cv), reinterpret_cast<bf16_t*>(ex.a_out), M, ex.f, ldc,
+                         m0 + wm * (BM / WM), tile_n * 128 + wn * 64);
+  } else {
+    if (EPI == EPI_ROPE && n0 + wn * (BN / WN) < ex.rot_cols)      // this wave's 128 columns are a q or k head
+      rope_rotate_acc(acc, ex.table, ex.seq, M, m0 + wm * (BM / WM), lane);
+    epilogue_bf16_rows<(EPI == EPI_ROPE ? EPI_STORE : EPI)>(acc, smem, wave, lane, reinterpret_cast<bf16_t*>(Cv), R, M, N, ldc,
+                                                             m0 + wm * (BM / WM), n0 + wn * (BN / WN));
+  }
 }
 
 // Consecutive hardware workgroup ids go to different XCDs: give every XCD one contiguous range of the sequence
@@ -718,10 +797,10 @@ template <bool TNL, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                void* __restrict__ Cv, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n,
-                                                               unsigned a_bytes, unsigned b_bytes, int b_slab) {
+                                                               unsigned a_bytes, unsigned b_bytes, int b_slab, const GemmExtra ex) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   direct_tile<TNL, EPI>(smem, A, B, Cv, R, M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes,
-                        xcd_remap(blockIdx.x, tiles_m * tiles_n), !TNL && b_slab != 0);
+                        xcd_remap(blockIdx.x, tiles_m * tiles_n), !TNL && b_slab != 0, ex);
 }
 
 // Several independent products with the same K in one launch (the weight-gradient GEMMs of a W op: four per
@@ -749,7 +828,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_direct_grouped_kernel(const Gro
 
 template <bool TNL, int EPI>
 hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
-                         int ldc, hipStream_t s, bool b_slab = false) {
+                         int ldc, hipStream_t s, bool b_slab = false, const GemmExtra& ex = GemmExtra()) {
   auto kern = gemm_bf16_direct_kernel<TNL, EPI>;
   constexpr int smem = 163840;
   static LdsAttrOnce lds_attr;
@@ -760,7 +839,7 @@ hipError_t launch_direct(const void* A, const void* B, void* C, const void* R, i
   const unsigned b_bytes = b_slab ? (unsigned)((size_t)tiles_n * (K / 64) * 32768)
                                   : (unsigned)(TNL ? ((size_t)(K - 1) * ldb + N) * 2 : ((size_t)(N - 1) * ldb + K) * 2);
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, (const bf16_t*)A, (const bf16_t*)B, C, (const bf16_t*)R,
-                     M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes, b_slab ? 1 : 0);
+                     M, N, K, lda, ldb, ldc, tiles_m, tiles_n, a_bytes, b_bytes, b_slab ? 1 : 0, ex);
   return hipGetLastError();
 }
 
@@ -837,10 +916,37 @@ bool gemm_bf16_slab_applies(int M, int N, int K, int lda) {
   return direct_applies(false, M, N, K, lda, 8);
 }
 
+// The fused epilogues run on the direct kernel only, on whole heads / whole gate-up pairs: what must hold for them
+bool gemm_bf16_fused_applies(int epi, int M, int N, int K, int lda, int head_dim) {
+  if (epi == EPI_ROPE) return head_dim == 128 && (N % 128) == 0 && (N & 3) == 0 && direct_applies(false, M, N, K, lda, K) &&
+                              (long)((M + 255) / 256) * ((N + 255) / 256) >= 128 && (lda & 7) == 0 && (K % 64) == 0;
+  if (epi == EPI_SWIGLU) return (N % 256) == 0 && gemm_bf16_slab_applies(M, N, K, lda);
+  return false;
+}
+
 hipError_t launch_gemm_bf16(int layout, int epi, const void* A, const void* B, void* C, const void* R, int M, int N,
-                            int K, int lda, int ldb, int ldc, hipStream_t s) {
+                            int K, int lda, int ldb, int ldc, hipStream_t s, const GemmExtra* extra) {
   // host-side shape checks: 16-byte vector accesses need these
   if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
+  if (epi == EPI_ROPE) {
+    // whole heads per wave tile, rotated columns a whole number of heads, table and sequence length given
+    if (!extra || !extra->table || extra->seq <= 0 || extra->rot_cols < 0 || extra->rot_cols > N || (extra->rot_cols % 128) ||
+        (ldc & 7) || (layout != GEMM_NT && layout != GEMM_NT_SLAB) || !gemm_bf16_fused_applies(epi, M, N, K, lda, 128))
+      return hipErrorInvalidValue;
+    if (layout == GEMM_NT_SLAB) {
+      if (!gemm_bf16_slab_applies(M, N, K, lda)) return hipErrorInvalidValue;
+      return launch_direct<false, EPI_ROPE>(A, B, C, R, M, N, K, lda, 64, ldc, s, true, *extra);
+    }
+    if ((ldb & 7) || ldb < K) return hipErrorInvalidValue;
+    return launch_direct<false, EPI_ROPE>(A, B, C, R, M, N, K, lda, ldb, ldc, s, false, *extra);
+  }
+  if (epi == EPI_SWIGLU) {
+    // N = 2 f columns in paired slabs; GU rows of ldc elements, a rows of f elements, 16-byte row segments
+    if (!extra || !extra->a_out || extra->f <= 0 || N != 2 * extra->f || (extra->f % 128) || (ldc & 7) || ldc < N ||
+        layout != GEMM_NT_SLAB || !gemm_bf16_fused_applies(epi, M, N, K, lda, 0))
+      return hipErrorInvalidValue;
+    return launch_direct<false, EPI_SWIGLU>(A, B, C, R, M, N, K, lda, 64, ldc, s, true, *extra);
+  }
   if (layout == GEMM_NT_SLAB) {
     if ((ldc & 3) || !gemm_bf16_slab_applies(M, N, K, lda)) return hipErrorInvalidValue;
     if (epi == EPI_STORE) return launch_direct<false, EPI_STORE>(A, B, C, R, M, N, K, lda, 64, ldc, s, true);

@@ -76,8 +76,32 @@ optstage_status optstage_op_gemm(uint32_t dtype, uint32_t layout, uint32_t epilo
 optstage_status optstage_op_weight_slabs(const void* src, void* dst, uint32_t N, uint32_t K, uint32_t transposed,
                                          void* stream) {
   REQ(src && dst, "weight_slabs: null operand");
-  REQ(N && K && (K % 64) == 0 && N < (1u << 30) && K < (1u << 30) && transposed <= 1, "weight_slabs: bad extent (K must be a multiple of 64)");
+  REQ(N && K && (K % 64) == 0 && N < (1u << 30) && K < (1u << 30) && transposed <= 2, "weight_slabs: bad extent (K must be a multiple of 64)");
+  REQ(transposed != 2 || (N % 256) == 0, "weight_slabs: the paired layout needs N = 2 f with f a multiple of 128");
   return wrap(launch_slabs(src, dst, (int)N, (int)K, (int)transposed, (hipStream_t)stream), "weight_slabs");
+}
+
+optstage_status optstage_op_gemm_rope(uint32_t layout, const void* A, const void* B, void* C, uint32_t M, uint32_t N,
+                                      uint32_t K, uint32_t lda, uint32_t ldb, uint32_t ldc, const float* table, uint32_t seq,
+                                      uint32_t rot_cols, void* stream) {
+  REQ(A && B && C && table, "gemm_rope: null operand");
+  REQ(aligned16(A) && aligned16(B) && aligned16(C) && aligned16(table), "gemm_rope: operands must be 16-byte aligned");
+  REQ((layout == 0 || layout == 2) && M && N && K && seq && M < (1u << 30) && N < (1u << 30) && K < (1u << 30), "gemm_rope: bad argument");
+  REQ(lda >= K && (layout == 2 || ldb >= K) && ldc >= N, "gemm_rope: leading dimension too small");
+  GemmExtra ex;
+  ex.table = (const float2*)table; ex.seq = (int)seq; ex.rot_cols = (int)rot_cols;
+  return wrap(launch_gemm_bf16((int)layout, EPI_ROPE, A, B, C, nullptr, M, N, K, lda, ldb, ldc, (hipStream_t)stream, &ex), "gemm_rope");
+}
+
+optstage_status optstage_op_gemm_swiglu(const void* A, const void* B, void* GU, void* a_out, uint32_t M, uint32_t ffn,
+                                        uint32_t K, uint32_t lda, void* stream) {
+  REQ(A && B && GU && a_out, "gemm_swiglu: null operand");
+  REQ(aligned16(A) && aligned16(B) && aligned16(GU) && aligned16(a_out), "gemm_swiglu: operands must be 16-byte aligned");
+  REQ(M && ffn && K && M < (1u << 30) && ffn < (1u << 29) && K < (1u << 30) && lda >= K, "gemm_swiglu: bad argument");
+  GemmExtra ex;
+  ex.a_out = a_out; ex.f = (int)ffn;
+  return wrap(launch_gemm_bf16(GEMM_NT_SLAB, EPI_SWIGLU, A, B, GU, nullptr, M, 2 * ffn, K, lda, 64, 2 * ffn, (hipStream_t)stream, &ex),
+              "gemm_swiglu");
 }
 
 optstage_status optstage_op_gemm_grouped(uint32_t layout, uint32_t epilogue, uint32_t n,

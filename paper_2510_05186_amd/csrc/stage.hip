@@ -51,12 +51,13 @@ uint64_t round_up(uint64_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
 struct Shape {
   int family, dtype, L, h, nq, nkv, d, f, seq, mb, tokens, qkv_w, up_w, e;
   int chunks, Lc;   // model chunks on this stage and layers per chunk (L = chunks * Lc)
+  bool fuse_rope, fuse_act;   // rotary in the QKV projection's epilogue, MLP activation in the gate / up projection's
 };
 
 optstage_status shape_from_desc(const optstage_desc* d, Shape* s) {
   if (!d) return fail(OPTSTAGE_E_ARG, "desc is null");
   if (d->struct_size != sizeof(optstage_desc)) return fail(OPTSTAGE_E_ARG, "desc.struct_size mismatch");
-  if (d->family > 1 || d->dtype > 1 || d->recompute > 1) return fail(OPTSTAGE_E_ARG, "bad family, dtype or recompute");
+  if (d->family > 1 || d->dtype > 1 || d->recompute > 1 || d->no_fusion > 1 || d->reserved) return fail(OPTSTAGE_E_ARG, "bad family, dtype, recompute or no_fusion");
   if (!d->n_layers || !d->hidden || !d->n_q_heads || !d->n_kv_heads || !d->ffn || !d->seq || !d->micro_batch || !d->n_microbatches)
     return fail(OPTSTAGE_E_ARG, "zero-sized shape field");
   if (d->head_dim != 64 && d->head_dim != 128) return fail(OPTSTAGE_E_ARG, "head_dim must be 64 or 128");
@@ -74,6 +75,11 @@ optstage_status shape_from_desc(const optstage_desc* d, Shape* s) {
   s->chunks = d->n_chunks ? (int)d->n_chunks : 1;
   if (s->L % s->chunks) return fail(OPTSTAGE_E_ARG, "n_layers must be a multiple of n_chunks");
   s->Lc = s->L / s->chunks;
+  const bool fusable = !d->no_fusion && s->family == OPTSTAGE_LLAMA && s->dtype == OPTSTAGE_BF16;
+  s->fuse_rope = fusable && gemm_bf16_fused_applies(EPI_ROPE, s->tokens, s->qkv_w, s->h, s->h, s->d);
+  // not in the recompute variant: B rebuilds the activation output from the stored gate / up tensor and has to arrive
+  // at the very bits F multiplied with
+  s->fuse_act = fusable && !d->recompute && (s->f % 128) == 0 && gemm_bf16_fused_applies(EPI_SWIGLU, s->tokens, s->up_w, s->h, s->h, 0);
   return OPTSTAGE_OK;
 }
 
@@ -460,6 +466,12 @@ optstage_status k_gemm(optstage* st, int layout, int epi, const void* A, const v
   KT(cls, 2.0 * M * N * K, gemm(st->sh, layout, epi, A, B, C, R, M, N, K, lda, ldb, ldc, st->cs));
   return OPTSTAGE_OK;
 }
+// the two projections with a fused epilogue (bf16 only); booked with the plain NT products
+optstage_status k_gemm_fused(optstage* st, int layout, int epi, const void* A, const void* B, void* C, int M, int N, int K,
+                             int lda, int ldb, int ldc, const GemmExtra& ex) {
+  KT(OPTSTAGE_KC_GEMM_NT_STORE, 2.0 * M * N * K, launch_gemm_bf16(layout, epi, A, B, C, nullptr, M, N, K, lda, ldb, ldc, st->cs, &ex));
+  return OPTSTAGE_OK;
+}
 optstage_status k_gemm_grouped(optstage* st, int layout, int epi, int n, const GemmProblem* pr, int K) {
   double flops = 0;
   for (int i = 0; i < n; ++i) flops += 2.0 * pr[i].M * pr[i].N * K;
@@ -540,16 +552,28 @@ optstage_status exec_forward(optstage* st, int j, int c, const OpBufs& ob) {
     TRY(k_norm_fwd(st, x, W(st, l, OPTSTAGE_W_G1), W(st, l, OPTSTAGE_W_B1), n1, stats));
     int lay;
     const void* wq = fwd_operand(st, l, OPTSTAGE_W_QKV, &lay);
-    TRY(k_gemm(st, lay, EPI_STORE, n1, wq, P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
-    if (s.family == OPTSTAGE_LLAMA)
-      TRY(k_rope(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), 0));
+    if (s.fuse_rope) {
+      GemmExtra ex;
+      ex.table = (const float2*)(st->wsp() + st->ws.rope); ex.seq = s.seq; ex.rot_cols = (s.nq + s.nkv) * s.d;
+      TRY(k_gemm_fused(st, lay, EPI_ROPE, n1, wq, P(l, OPTSTAGE_K_QKV), T, s.qkv_w, s.h, s.h, s.h, s.qkv_w, ex));
+    } else {
+      TRY(k_gemm(st, lay, EPI_STORE, n1, wq, P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
+      if (s.family == OPTSTAGE_LLAMA)
+        TRY(k_rope(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), 0));
+    }
     TRY(k_attn_fwd(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_O), (float*)P(l, OPTSTAGE_K_LSE)));
     const void* wo = fwd_operand(st, l, OPTSTAGE_W_O, &lay);
     TRY(k_gemm(st, lay, EPI_RESID, P(l, OPTSTAGE_K_O), wo, P(l, OPTSTAGE_K_X_MID), x, T, s.h, s.nq * s.d, s.nq * s.d, s.nq * s.d, s.h));
     TRY(k_norm_fwd(st, P(l, OPTSTAGE_K_X_MID), W(st, l, OPTSTAGE_W_G2), W(st, l, OPTSTAGE_W_B2), n2, stats + (size_t)nstat * T));
     const void* wgu = fwd_operand(st, l, OPTSTAGE_W_GU, &lay);
-    TRY(k_gemm(st, lay, EPI_STORE, n2, wgu, P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
-    TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), a));
+    if (s.fuse_act) {                      // wgu is the paired slab copy: gate / up product and activation in one kernel
+      GemmExtra ex;
+      ex.a_out = a; ex.f = s.f;
+      TRY(k_gemm_fused(st, GEMM_NT_SLAB, EPI_SWIGLU, n2, wgu, P(l, OPTSTAGE_K_GU), T, s.up_w, s.h, s.h, 64, s.up_w, ex));
+    } else {
+      TRY(k_gemm(st, lay, EPI_STORE, n2, wgu, P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
+      TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), a));
+    }
     void* y = l + 1 < l1 ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[io];
     const void* wd = fwd_operand(st, l, OPTSTAGE_W_D, &lay);
     TRY(k_gemm(st, lay, EPI_RESID, a, wd, y, P(l, OPTSTAGE_K_X_MID), T, s.h, s.f, s.f, s.f, s.h));
@@ -916,7 +940,8 @@ optstage_status optstage_set_weight(optstage_t* st, uint32_t layer, uint32_t whi
   slab_modes(s, which, &sf, &sb);
   if (sb) HIP_TRY(launch_slabs(weight_dev, (void*)WT(st, layer, which), cols, rows, 1, st->cs));
   else HIP_TRY(launch_transpose(s.dtype, weight_dev, (void*)WT(st, layer, which), rows, cols, st->cs));
-  if (sf) HIP_TRY(launch_slabs(weight_dev, (void*)WF(st, layer, which), rows, cols, 0, st->cs));
+  // the forward copy of the gate / up weight is in paired slabs when the activation runs in that product's epilogue
+  if (sf) HIP_TRY(launch_slabs(weight_dev, (void*)WF(st, layer, which), rows, cols, which == OPTSTAGE_W_GU && s.fuse_act ? 2 : 0, st->cs));
   return OPTSTAGE_OK;
 }
 

@@ -34,12 +34,14 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 class Stage:
     def __init__(self, cfg, budget: int = 0, arena_bytes: int | None = None, host_pool_bytes: int = 0,
                  duplex: bool = False, recompute: bool = False, n_chunks: int = 1, grad_overwrite: bool = False,
-                 host_pool: torch.Tensor | None = None):
+                 host_pool: torch.Tensor | None = None, no_fusion: bool = False):
         """duplex: reloads get a stream of their own instead of sharing the offloads' (single channel).
         recompute: F keeps no norm outputs and no MLP activation output; B rebuilds them for W.
         n_chunks: model chunks on this stage (cfg.n_layers counts all of them).
         grad_overwrite: the first B / W of an iteration store the parameter gradients instead of adding to them, so
         the accumulators need no clearing between iterations.
+        no_fusion: rotary and the MLP activation always run as kernels of their own (by default they run in the
+        epilogues of the QKV and gate / up projections where the shapes allow it).
         host_pool: a pinned uint8 tensor to use as the offload pool instead of allocating host_pool_bytes (a process
         that runs several stages one after the other can hand the same block to each)."""
         if not torch.cuda.is_available():
@@ -69,7 +71,7 @@ class Stage:
             host_pool_bytes=host_pool_bytes, compute_stream=self.compute_stream.cuda_stream,
             copy_stream=self.copy_stream.cuda_stream,
             reload_stream=self.reload_stream.cuda_stream if duplex else 0, recompute=int(recompute),
-            n_chunks=self.n_chunks)
+            n_chunks=self.n_chunks, no_fusion=int(no_fusion))
         h = C.c_void_p()
         B.check(self.lib.optstage_create(C.byref(self.desc), C.byref(h)))
         self.h = h

@@ -6,7 +6,7 @@ import torch
 
 from oracle import stage_fp64 as O
 from paper_2510_05186_amd import binding as B
-from gpu_util import TOL, dev, host, ok, q, rel_err, stream
+from gpu_util import TOL, dev, host, ok, q, rel_err, rms_err, stream
 
 pytestmark = pytest.mark.gpu
 RNG = np.random.default_rng(42)
@@ -348,3 +348,71 @@ def test_empty_inputs_are_refused_not_launched():
     assert L_.optstage_op_weight_slabs(p, q, 0, 64, 0, stream()) == B.E_ARG
     torch.cuda.synchronize()
     assert float(a.float().abs().sum()) == 0.0 and float(f.abs().sum()) == 0.0
+
+
+# ------------------------------------------------------------------ projections with a fused epilogue
+@pytest.mark.parametrize("layout,M,N,K,seq,rot", [(B.GEMM_NT, 2000, 4096, 256, 500, 3072), (2, 2048, 4096, 192, 2048, 4096),
+                                                  (B.GEMM_NT, 4096, 2048, 128, 1024, 1024)])
+def test_gemm_with_rotary_in_the_epilogue(layout, M, N, K, seq, rot):
+    d = 128
+    a = q(RNG.standard_normal((M, K)), BF16)
+    w = q(0.1 * RNG.standard_normal((N, K)), BF16)
+    A, W = dev(a, BF16), dev(w, BF16)
+    L_ = lib()
+    Wop = W
+    if layout == 2:
+        Wop = torch.empty((N + 255) // 256 * 256 * K, dtype=torch.bfloat16, device="cuda")
+        ok(L_.optstage_op_weight_slabs(W.data_ptr(), Wop.data_ptr(), N, K, 0, stream()))
+    table = torch.empty(seq * (d // 2) * 2, dtype=torch.float32, device="cuda")
+    ok(L_.optstage_op_rope_table(table.data_ptr(), seq, d, 10000.0, stream()))
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ok(L_.optstage_op_gemm_rope(layout, A.data_ptr(), Wop.data_ptr(), C.data_ptr(), M, N, K, K, K, N, table.data_ptr(), seq, rot, stream()))
+    # the unfused pair of kernels on the same operands
+    C2 = torch.empty_like(C)
+    ok(L_.optstage_op_gemm(BF16, B.GEMM_NT, B.EPI_STORE, A.data_ptr(), W.data_ptr(), C2.data_ptr(), 0, M, N, K, K, K, N, stream()))
+    packed = (N // d) % 4 == 0 and rot == N // 4 * 3          # a packed qkv row: n_q = 2 n_kv query heads, n_kv key and value heads
+    if packed:
+        ok(L_.optstage_op_rope(BF16, C2.data_ptr(), C2.data_ptr(), table.data_ptr(), M, seq, N // d // 2, N // d // 4, d, 0, stream()))
+    torch.cuda.synchronize()
+    ref = a @ w.T
+    heads = ref.reshape(M, N // d, d).copy()
+    for s0 in range(0, M, seq):
+        s1 = min(M, s0 + seq)
+        heads[s0:s1, : rot // d] = O.rope_apply(heads[s0:s1, : rot // d], 10000.0)[: s1 - s0]
+    ref = heads.reshape(M, N)
+    assert rel_err(host(C), ref) < TOL[BF16] / 4 and rms_err(host(C), ref) < TOL[BF16] / 8
+    if packed:            # against the two separate kernels: the same numbers up to the one extra rounding those make
+        assert rms_err(host(C), host(C2)) < TOL[BF16] / 8
+    # a shape the direct kernel does not serve, a head split by a tile, a missing table: refused, nothing written
+    Z = torch.zeros(64, 256, dtype=torch.bfloat16, device="cuda")
+    assert L_.optstage_op_gemm_rope(0, A.data_ptr(), W.data_ptr(), Z.data_ptr(), 64, 256, K, K, K, 256, table.data_ptr(), seq, 256, stream()) == B.E_ARG
+    assert L_.optstage_op_gemm_rope(0, A.data_ptr(), W.data_ptr(), C.data_ptr(), M, N, K, K, K, N, table.data_ptr(), seq, 192, stream()) == B.E_ARG
+    assert L_.optstage_op_gemm_rope(0, A.data_ptr(), W.data_ptr(), C.data_ptr(), M, N, K, K, K, N, 0, seq, rot, stream()) == B.E_ARG
+    torch.cuda.synchronize()
+    assert float(Z.float().abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("M,f,K", [(2000, 2048, 192), (4096, 1024, 256), (2048, 2304, 64)])
+def test_gate_up_projection_with_the_activation_in_the_epilogue(M, f, K):
+    a = q(RNG.standard_normal((M, K)), BF16)
+    w = q(0.15 * RNG.standard_normal((2 * f, K)), BF16)
+    A, W = dev(a, BF16), dev(w, BF16)
+    L_ = lib()
+    Wp = torch.empty(2 * f * K, dtype=torch.bfloat16, device="cuda")
+    ok(L_.optstage_op_weight_slabs(W.data_ptr(), Wp.data_ptr(), 2 * f, K, 2, stream()))
+    GU = torch.full((M, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ACT = torch.full((M, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ok(L_.optstage_op_gemm_swiglu(A.data_ptr(), Wp.data_ptr(), GU.data_ptr(), ACT.data_ptr(), M, f, K, K, stream()))
+    torch.cuda.synchronize()
+    gu = a @ w.T
+    assert rel_err(host(GU), gu) < TOL[BF16] / 4 and rms_err(host(GU), gu) < TOL[BF16] / 8       # plain [gate | up] layout
+    act = O.swiglu_fwd(gu)
+    assert rel_err(host(ACT), act) < TOL[BF16] / 4 and rms_err(host(ACT), act) < TOL[BF16] / 8
+    # the stored gate / up tensor is what the separate projection stores, bit for bit
+    GU2 = torch.empty_like(GU)
+    ok(L_.optstage_op_gemm(BF16, B.GEMM_NT, B.EPI_STORE, A.data_ptr(), W.data_ptr(), GU2.data_ptr(), 0, M, 2 * f, K, K, K, 2 * f, stream()))
+    torch.cuda.synchronize()
+    assert torch.equal(GU, GU2)
+    assert L_.optstage_op_gemm_swiglu(A.data_ptr(), Wp.data_ptr(), GU.data_ptr(), ACT.data_ptr(), M, f + 64, K, K, stream()) == B.E_ARG
+    assert L_.optstage_op_gemm_swiglu(A.data_ptr(), Wp.data_ptr(), GU.data_ptr(), 0, M, f, K, K, stream()) == B.E_ARG
+    assert L_.optstage_op_weight_slabs(W.data_ptr(), Wp.data_ptr(), 2 * f - 128, K, 2, stream()) == B.E_ARG

@@ -765,3 +765,38 @@ def test_stats_report_the_trace_the_live_levels_and_the_stalls():
     assert s.stall_ms[0] > 0.0 and s.stall_ms[1] > 0.0
     assert s.stall_ms[0] + s.stall_ms[1] == pytest.approx(sum(g[7] for g in tr), rel=1e-6)
     st.close()
+
+
+def test_fused_epilogues_against_the_oracle_and_the_separate_kernels():
+    """A stage large enough for the direct GEMM kernel, so that rotary runs in the QKV projection's epilogue and SwiGLU
+    in the gate / up projection's: results against the oracle, and against the same stage with no_fusion (separate
+    kernels), which differs only by the roundings the fusion saves."""
+    cfg = CFG.shrunken(CFG.CFG4, hidden=2048, n_q=16, n_kv=8, ffn=2048, seq=2048, n_layers=2, n_microbatches=2, name="cfg4_fusable")
+    ws = T.stage_weights(cfg)
+    events = [("F", 0), ("F", 1), ("B", 0), ("W", 0), ("B", 1), ("W", 1)]
+    ref = oracle_run(cfg, ws)
+    runs = []
+    for no_fusion in (False, True):
+        st = Stage(cfg, no_fusion=no_fusion)
+        st.set_weights(ws)
+        for j in range(cfg.n_microbatches):
+            st.bind(j, T.stage_input(cfg, j), T.output_grad(cfg, j))
+        B.check(B.lib().optstage_set_kernel_timing(st.h, 1))
+        st.run(events)
+        st.synchronize()
+        compare(cfg, st, ref)
+        check_accounting(cfg, st, events)
+        s = st.stats()
+        launches = dict(zip(B.KERNEL_CLASSES, s.kernel_launches))
+        # fused: no forward rotary launch (the backward ones remain), no forward activation launch
+        assert launches["act_fwd"] == (2 * cfg.n_layers if no_fusion else 0)
+        assert launches["rope"] == (4 if no_fusion else 2) * cfg.n_layers
+        runs.append(([host(st.y[j]) for j in range(2)], [host(st.dx[j]) for j in range(2)],
+                     {(l, n): host(v) for l in range(cfg.n_layers) for n, v in st.grads[l].items()}))
+        st.close()
+    from gpu_util import rms_err
+    for j in range(2):
+        assert rms_err(runs[0][0][j], runs[1][0][j]) < 1e-2 and rms_err(runs[0][1][j], runs[1][1][j]) < 1e-2
+    for key in runs[0][2]:
+        assert rms_err(runs[0][2][key], runs[1][2][key]) < 1e-2, key
+    assert any(not np.array_equal(runs[0][0][j], runs[1][0][j]) for j in range(2))
