@@ -464,7 +464,8 @@ __device__ __forceinline__ void epilogue_bf16_rows(f32x16_t (&acc)[4][4], char* 
 // Rotary embedding on the accumulators of a wave tile that is one attention head (128 columns starting at a multiple
 // of 128): column c < 64 pairs with column c + 64, which the same lane holds in the same register of acc[i][j + 2]
 // (j = 0, 1), so the rotation by position * theta_c happens in registers, in fp32, before the one conversion to bf16.
-// table[pos * 64 + c] = (cos, sin); pos = row % seq.
+// table[pos * 64 + c] = (cos, sin); pos = row % seq.  Every lane reads the 32-byte pieces of its own row's table row
+// straight from memory (the table stays in L2); staging the rows through LDS with coalesced loads measured slower.
 __device__ __forceinline__ void rope_rotate_acc(f32x16_t (&acc)[4][4], const float2* __restrict__ table, int seq, int M,
                                                 int mw, int lane) {
   const int khalf = lane >> 5;
@@ -512,7 +513,8 @@ __device__ __forceinline__ void epilogue_swiglu_rows(f32x16_t (&acc)[4][4], char
           const float gv = acc[i][j][g * 4 + e], uv = acc[i][j + 2][g * 4 + e];
           og[e] = (bf16_t)gv;
           ou[e] = (bf16_t)uv;
-          oa[e] = (bf16_t)(gv / (1.f + expf(-gv)) * uv);
+          // silu(g) u = g u / (1 + 2^(-g log2 e)): hardware exp2 and reciprocal (1 ulp each), far below bf16's 2^-9
+          oa[e] = (bf16_t)(gv * uv * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * gv)));
         }
         const int cb = (j * 32 + g * 8 + khalf * 4) * 2;   // byte offset of the 4 columns within a 128-byte segment
         *reinterpret_cast<bf16x4_t*>(wl + r * RS + cb) = og;
