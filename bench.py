@@ -32,6 +32,7 @@ HEADLINE = "cfg4_gqa_bf16"
 KERNEL_SOURCES = {"gemm": "gemm_bf16.hip", "attn": "attention_mfma.hip", "norm": "elementwise.hip", "act": "elementwise.hip",
                   "rope": "elementwise.hip"}
 KERNEL_NAMES = {"gemm_nt_store": "gemm_bf16_direct_kernel<NT, store>", "gemm_nt_resid": "gemm_bf16_direct_kernel<NT, residual>",
+                "gemm_nt_qkv": "gemm_bf16_direct_kernel<NT, rotary epilogue>", "gemm_nt_gu": "gemm_bf16_direct_kernel<NT, SwiGLU epilogue>",
                 "gemm_tn_accum": "gemm_bf16_direct_grouped_kernel<TN, fp32 accumulate>", "attn_fwd": "attn_fwd_mfma",
                 "attn_bwd": "attn_bwd_dq_mfma + attn_bwd_dkv_mfma"}
 
@@ -55,15 +56,20 @@ def class_algorithmic_bytes(cfg, name):
     t, h, f = cfg.seq * cfg.micro_batch, cfg.hidden, cfg.ffn
     hq = cfg.n_q_heads * cfg.head_dim
     es = 2 if cfg.dtype == 1 else 4
-    if name == "gemm_nt_store":       # QKV and gate/up projections in F; the four dX products of B
-        shapes = [(t, cfg.qkv_width, h), (t, cfg.up_width, h), (t, f, h), (t, h, cfg.up_width), (t, hq, h), (t, h, cfg.qkv_width)]
+    if name == "gemm_nt_store":       # the four dX products of B
+        shapes = [(t, f, h), (t, h, cfg.up_width), (t, hq, h), (t, h, cfg.qkv_width)]
         return sum((m * k + n * k + m * n) * es for m, n, k in shapes) / len(shapes)
+    if name == "gemm_nt_qkv":
+        return (t * h + cfg.qkv_width * h + t * cfg.qkv_width) * es
+    if name == "gemm_nt_gu":          # reads n2 and the weight, writes gate / up and (fused) the activation output
+        return (t * h + cfg.up_width * h + t * cfg.up_width + t * f) * es
     if name == "gemm_nt_resid":       # output and down projections with the residual added
         shapes = [(t, h, hq), (t, h, f)]
         return sum((m * k + n * k + 2 * m * n) * es for m, n, k in shapes) / len(shapes)
-    if name == "gemm_tn_accum":       # one grouped launch: the 4 L weight-gradient products of a W op
+    if name == "gemm_tn_accum":       # grouped launches over the 4 L weight-gradient products of a W op (class mean)
         shapes = [(h, f, t), (cfg.up_width, h, t), (h, hq, t), (cfg.qkv_width, h, t)]
-        return cfg.n_layers * sum((m * k + n * k) * es + 2 * m * n * 4 for m, n, k in shapes)
+        launches = -(-4 * cfg.n_layers // 16)                          # 16 products per grouped launch
+        return cfg.n_layers * sum((m * k + n * k) * es + 2 * m * n * 4 for m, n, k in shapes) / launches
     return None
 
 
@@ -215,7 +221,7 @@ def kernel_table(agg, steps, ms_per_step):
     for i, name in enumerate(B.KERNEL_CLASSES):
         if agg["k_n"][i]:
             ms = agg["k_ms"][i]
-            flop_class = i < 5
+            flop_class = i < 5 or i >= 10
             out[name] = {"launches_per_step": agg["k_n"][i] // steps, "avg_ms": ms / agg["k_n"][i],
                          "achieved": agg["k_work"][i] / (ms * 1e-3) / (1e12 if flop_class else 1e9),
                          "unit": "TFLOP/s" if flop_class else "GB/s", "share_of_step": ms / steps / ms_per_step}

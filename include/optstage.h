@@ -124,9 +124,13 @@ typedef struct {
 } optstage_event;
 
 typedef enum {
-  OPTSTAGE_KC_GEMM_NT_STORE = 0, OPTSTAGE_KC_GEMM_NT_RESID = 1, OPTSTAGE_KC_GEMM_TN_ACCUM = 2,
+  OPTSTAGE_KC_GEMM_NT_STORE = 0 /* the four dX products of B (C = A B^T, plain store) */,
+  OPTSTAGE_KC_GEMM_NT_RESID = 1 /* output and down projection, residual added */, OPTSTAGE_KC_GEMM_TN_ACCUM = 2,
   OPTSTAGE_KC_ATTN_FWD = 3, OPTSTAGE_KC_ATTN_BWD = 4, OPTSTAGE_KC_NORM_FWD = 5, OPTSTAGE_KC_NORM_BWD = 6,
-  OPTSTAGE_KC_ACT_FWD = 7, OPTSTAGE_KC_ACT_BWD = 8, OPTSTAGE_KC_ROPE = 9, OPTSTAGE_N_KERNEL_CLASSES = 10
+  OPTSTAGE_KC_ACT_FWD = 7, OPTSTAGE_KC_ACT_BWD = 8, OPTSTAGE_KC_ROPE = 9,
+  OPTSTAGE_KC_GEMM_NT_QKV = 10 /* QKV projection (rotary in its epilogue when fused) */,
+  OPTSTAGE_KC_GEMM_NT_GU = 11 /* gate / up projection (activation in its epilogue when fused) */,
+  OPTSTAGE_N_KERNEL_CLASSES = 12
 } optstage_kernel_class;
 
 typedef struct {
@@ -137,7 +141,7 @@ typedef struct {
                                                    stream; O, R on the copy stream); valid after synchronize */
   uint64_t arena_high_water;                    /* highest physical arena offset ever used */
   /* per kernel class, filled only while kernel timing is on (optstage_set_kernel_timing): launches,
-   * summed device time, and summed algorithmic work (flops for GEMM / attention classes: 2*M*N*K, causal
+   * summed device time, and summed algorithmic work (flops for the GEMM / attention classes 0-4, 10, 11: 2*M*N*K, causal
    * attention 2*s^2*n_q*d forward and 5*s^2*n_q*d backward; bytes for the elementwise classes: norm
    * forward 2e per element, norm backward 4e, activation forward 3e per output element, backward 5e,
    * rotary 2e over the q and k heads; e = element size) */

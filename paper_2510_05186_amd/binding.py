@@ -19,7 +19,7 @@ N_KINDS, N_F_KINDS = 12, 10
 WEIGHTS = ("g1", "b1", "wqkv", "wo", "g2", "b2", "wgu", "wd")
 WEIGHT_ID = {k: i for i, k in enumerate(WEIGHTS)}
 KERNEL_CLASSES = ("gemm_nt_store", "gemm_nt_resid", "gemm_tn_accum", "attn_fwd", "attn_bwd", "norm_fwd", "norm_bwd",
-                  "act_fwd", "act_bwd", "rope")
+                  "act_fwd", "act_bwd", "rope", "gemm_nt_qkv", "gemm_nt_gu")
 GEMM_NT, GEMM_TN, GEMM_NT_SLAB = 0, 1, 2
 EPI_STORE, EPI_RESID, EPI_ACCUM = 0, 1, 2
 
@@ -49,8 +49,8 @@ class Event(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("live_bytes", C.c_uint64), ("peak_bytes", C.c_uint64), ("bytes_offloaded", C.c_uint64),
                 ("bytes_reloaded", C.c_uint64), ("n_ops", C.c_uint64 * 6), ("ms_ops", C.c_double * 6),
-                ("arena_high_water", C.c_uint64), ("kernel_launches", C.c_uint64 * 10),
-                ("kernel_ms", C.c_double * 10), ("kernel_work", C.c_double * 10),
+                ("arena_high_water", C.c_uint64), ("kernel_launches", C.c_uint64 * 12),
+                ("kernel_ms", C.c_double * 12), ("kernel_work", C.c_double * 12),
                 ("min_live_bytes", C.c_uint64), ("avg_live_bytes", C.c_double), ("stall_ms", C.c_double * 2),
                 ("n_trace", C.c_uint64)]
 

@@ -461,15 +461,15 @@ const void* bwd_operand(optstage* st, int l, int which, int* layout) {
   } while (0)
 
 optstage_status k_gemm(optstage* st, int layout, int epi, const void* A, const void* B, void* C, const void* R, int M,
-                       int N, int K, int lda, int ldb, int ldc) {
-  const int cls = layout == GEMM_TN ? OPTSTAGE_KC_GEMM_TN_ACCUM : (epi == EPI_RESID ? OPTSTAGE_KC_GEMM_NT_RESID : OPTSTAGE_KC_GEMM_NT_STORE);
+                       int N, int K, int lda, int ldb, int ldc, int cls = -1) {
+  if (cls < 0) cls = layout == GEMM_TN ? OPTSTAGE_KC_GEMM_TN_ACCUM : (epi == EPI_RESID ? OPTSTAGE_KC_GEMM_NT_RESID : OPTSTAGE_KC_GEMM_NT_STORE);
   KT(cls, 2.0 * M * N * K, gemm(st->sh, layout, epi, A, B, C, R, M, N, K, lda, ldb, ldc, st->cs));
   return OPTSTAGE_OK;
 }
-// the two projections with a fused epilogue (bf16 only); booked with the plain NT products
+// the two projections with a fused epilogue (bf16 only)
 optstage_status k_gemm_fused(optstage* st, int layout, int epi, const void* A, const void* B, void* C, int M, int N, int K,
                              int lda, int ldb, int ldc, const GemmExtra& ex) {
-  KT(OPTSTAGE_KC_GEMM_NT_STORE, 2.0 * M * N * K, launch_gemm_bf16(layout, epi, A, B, C, nullptr, M, N, K, lda, ldb, ldc, st->cs, &ex));
+  KT(epi == EPI_ROPE ? OPTSTAGE_KC_GEMM_NT_QKV : OPTSTAGE_KC_GEMM_NT_GU, 2.0 * M * N * K, launch_gemm_bf16(layout, epi, A, B, C, nullptr, M, N, K, lda, ldb, ldc, st->cs, &ex));
   return OPTSTAGE_OK;
 }
 optstage_status k_gemm_grouped(optstage* st, int layout, int epi, int n, const GemmProblem* pr, int K) {
@@ -557,7 +557,7 @@ optstage_status exec_forward(optstage* st, int j, int c, const OpBufs& ob) {
       ex.table = (const float2*)(st->wsp() + st->ws.rope); ex.seq = s.seq; ex.rot_cols = (s.nq + s.nkv) * s.d;
       TRY(k_gemm_fused(st, lay, EPI_ROPE, n1, wq, P(l, OPTSTAGE_K_QKV), T, s.qkv_w, s.h, s.h, s.h, s.qkv_w, ex));
     } else {
-      TRY(k_gemm(st, lay, EPI_STORE, n1, wq, P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w));
+      TRY(k_gemm(st, lay, EPI_STORE, n1, wq, P(l, OPTSTAGE_K_QKV), nullptr, T, s.qkv_w, s.h, s.h, s.h, s.qkv_w, OPTSTAGE_KC_GEMM_NT_QKV));
       if (s.family == OPTSTAGE_LLAMA)
         TRY(k_rope(st, P(l, OPTSTAGE_K_QKV), P(l, OPTSTAGE_K_QKV), 0));
     }
@@ -571,7 +571,7 @@ optstage_status exec_forward(optstage* st, int j, int c, const OpBufs& ob) {
       ex.a_out = a; ex.f = s.f;
       TRY(k_gemm_fused(st, GEMM_NT_SLAB, EPI_SWIGLU, n2, wgu, P(l, OPTSTAGE_K_GU), T, s.up_w, s.h, s.h, 64, s.up_w, ex));
     } else {
-      TRY(k_gemm(st, lay, EPI_STORE, n2, wgu, P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w));
+      TRY(k_gemm(st, lay, EPI_STORE, n2, wgu, P(l, OPTSTAGE_K_GU), nullptr, T, s.up_w, s.h, s.h, s.h, s.up_w, OPTSTAGE_KC_GEMM_NT_GU));
       TRY(k_act_fwd(st, P(l, OPTSTAGE_K_GU), a));
     }
     void* y = l + 1 < l1 ? P(l + 1, OPTSTAGE_K_X_IN) : st->y_out[io];
