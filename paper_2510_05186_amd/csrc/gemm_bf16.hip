@@ -140,7 +140,7 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* 
         const size_t off = (size_t)m * ldc + n;
         if (EPI == EPI_ACCUM) {
           f32x4_t z = {0.f, 0.f, 0.f, 0.f};
-          cold[p2] = ok ? *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off) : z;
+          cold[p2] = ok ? __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off)) : z;
         } else {
           bf16x4_t z = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
           rold[p2] = ok ? *reinterpret_cast<const bf16x4_t*>(R + off) : z;
@@ -169,11 +169,11 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16_t (&acc)[TM][TN], char* 
       if (m < M && n < N) {
         const size_t off = (size_t)m * ldc + n;
         if (EPI == EPI_STOREF) {
-          *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off) = v;
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off));
         } else if (EPI == EPI_ACCUM) {
           const f32x4_t o = PRE ? cold[PRE ? p2 : 0] : *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(Cv) + off);
           v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
-          *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off) = v;
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + off));
         } else {
           if (EPI == EPI_RESID) {
             const bf16x4_t r = PRE ? rold[PRE ? p2 : 0] : *reinterpret_cast<const bf16x4_t*>(R + off);
