@@ -68,7 +68,7 @@ def class_algorithmic_bytes(cfg, name):
         return sum((m * k + n * k + 2 * m * n) * es for m, n, k in shapes) / len(shapes)
     if name == "gemm_tn_accum":       # grouped launches over the 4 L weight-gradient products of a W op (class mean)
         shapes = [(h, f, t), (cfg.up_width, h, t), (h, hq, t), (cfg.qkv_width, h, t)]
-        launches = -(-4 * cfg.n_layers // 16)                          # 16 products per grouped launch
+        launches = -(-4 * cfg.n_layers // 32)                          # up to 32 products per grouped launch
         return cfg.n_layers * sum((m * k + n * k) * es + 2 * m * n * 4 for m, n, k in shapes) / launches
     return None
 
