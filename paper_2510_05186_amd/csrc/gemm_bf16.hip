@@ -852,8 +852,8 @@ struct GroupedArgs { int n, K, total, order; GroupedProblem p[MAX_GROUP]; };
 template <bool TNL, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_direct_grouped_kernel(const GroupedArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  // order 1 needs every problem to start at a multiple of 256 workgroups (so that id % 8 within the problem is the
-  // XCD); the host falls back to order 0 for the whole launch otherwise
+  // order 1 within each problem: workgroups with equal (id - first_tile) % 8 are on one XCD whatever first_tile is,
+  // and any 256 consecutive ids are in flight together, which is all the patch mapping relies on
   const int id = g.order == 1 ? (int)blockIdx.x : xcd_remap(blockIdx.x, g.total);
   int q = 0;
   for (int i = 1; i < g.n; ++i)
@@ -926,8 +926,6 @@ hipError_t launch_direct_grouped(int n, const GemmProblem* pr, int K, hipStream_
   }
   g.total = total;
   g.order = tile_order(TNL);
-  for (int i = 0; i < n; ++i)
-    if (g.p[i].first_tile % 256) g.order = 0;
   hipLaunchKernelGGL(kern, dim3(total), dim3(256), smem, s, g);
   return hipGetLastError();
 }
