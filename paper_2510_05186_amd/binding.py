@@ -117,6 +117,13 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise OptstageError(E_STATE, f"{LIB_PATH} is missing: run `python -m paper_2510_05186_amd.build` "
                                          "(there is no CPU fallback)")
+        # PyTorch supplies the device memory and the streams this library works on, and it ships a HIP runtime of its
+        # own: that runtime has to be the one in the process before liboptstage.so is mapped (a second runtime, pulled
+        # in by this library's own dependency when it is loaded first, sees no device)
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         for name, args in _SIGS.items():
             fn = getattr(L, name)

@@ -899,10 +899,10 @@ optstage_status optstage_create(const optstage_desc* desc, optstage_t** out) {
     return true;
   };
   st->reloaded.assign(nio, 0);
-  if (hipEventCreate(&st->origin) != hipSuccess) {
+  if (hipError_t e = hipEventCreate(&st->origin); e != hipSuccess) {
     st->origin = nullptr;
     optstage_destroy(st);
-    return fail(OPTSTAGE_E_HIP, "hipEventCreate failed");
+    return fail(OPTSTAGE_E_HIP, "hipEventCreate: %s", hipGetErrorString(e));
   }
   if (!mk(st->ev_f, nio) || !mk(st->ev_o, m * L) || !mk(st->ev_r, m * L) || !mk(st->ev_pos, m * L) || !mk(st->ev_fl, m * L)) {
     optstage_destroy(st);
