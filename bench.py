@@ -68,7 +68,7 @@ def class_algorithmic_bytes(cfg, name):
         return sum((m * k + n * k + 2 * m * n) * es for m, n, k in shapes) / len(shapes)
     if name == "gemm_tn_accum":       # grouped launches over the 4 L weight-gradient products of a W op (class mean)
         shapes = [(h, f, t), (cfg.up_width, h, t), (h, hq, t), (cfg.qkv_width, h, t)]
-        launches = -(-4 * cfg.n_layers // 32)                          # up to 32 products per grouped launch
+        launches = -(-4 * cfg.n_layers // 16)                          # 16 products per grouped launch
         return cfg.n_layers * sum((m * k + n * k) * es + 2 * m * n * 4 for m, n, k in shapes) / launches
     return None
 
@@ -248,7 +248,7 @@ def run_leg(cfg, duplex, steps, warmup, torch, kernel_timing=False, calibrate=Tr
         from paper_2510_05186_amd import binding as B
         kb = B.query_sizes(cfg)[2]
         moved = lambda ev: sum(kb[k] for e in ev if e[0] == "O" for k in e[3])
-        if moved(ev2) + (64 << 20) <= st.host_pool.numel():
+        if moved(ev2) == 0 or (st.host_pool is not None and moved(ev2) + (64 << 20) <= st.host_pool.numel()):
             lists, knobs, events = lists2, knobs2, ev2       # fits the pinned pool this stage was created with
         else:
             knobs["calibrated_list_not_taken"] = "needs a larger pinned pool or arena than this handle has"
@@ -343,6 +343,9 @@ def main():
                     help="model chunks on the stage: runs interleaved 1F1B over them (layers split evenly)")
     ap.add_argument("--recompute", action="store_true",
                     help="memory-table variant: F keeps no norm outputs and no MLP activation output, B rebuilds them")
+    ap.add_argument("--microbatches", type=int, default=0,
+                    help="run the workload with this many micro-batches instead of its own count (a shorter run for "
+                         "counter profiles: the per-dispatch figures of a kernel do not depend on it); implies --no-legs")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a kernel of known traffic "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -359,6 +362,10 @@ def main():
         print("bench.py: no GPU visible; the stage has no CPU path", file=sys.stderr)
         sys.exit(3)
     cfg = CFG.CONFIGS[args.config]
+    if args.microbatches:
+        from dataclasses import replace
+        cfg = replace(cfg, n_microbatches=args.microbatches)
+        args.no_legs = True
     global RECOMPUTE, CHUNKS
     RECOMPUTE = int(args.recompute)
     CHUNKS = max(1, args.chunks)

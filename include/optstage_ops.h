@@ -58,7 +58,7 @@ optstage_status optstage_op_gemm_rope(uint32_t layout, const void* A, const void
 optstage_status optstage_op_gemm_swiglu(const void* A, const void* B, void* GU, void* a_out, uint32_t M, uint32_t ffn,
                                         uint32_t K, uint32_t lda, void* stream);
 
-/* n (1..32) independent bf16 products of the same layout, epilogue and K in ONE launch (the weight-gradient GEMMs
+/* n (1..16) independent bf16 products of the same layout, epilogue and K in ONE launch (the weight-gradient GEMMs
  * of a W op, dW = dY^T X for every linear of every layer, do not depend on one another: Sec. 2.2).  problems is a
  * HOST array; pointers inside are DEVICE.  Each problem must satisfy optstage_op_gemm's alignment rules, K % 64
  * must be 0 and the set must hold at least 128 tiles of 256 x 256; otherwise OPTSTAGE_E_ARG and nothing runs. */

@@ -841,7 +841,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(const bf16_t* __r
 // Several independent products with the same K in one launch (the weight-gradient GEMMs of a W op: four per
 // layer, none depending on another): their tiles form one sequence, so the partly filled last round of
 // workgroups that every product would leave behind on its own happens once.
-constexpr int MAX_GROUP = 32;
+constexpr int MAX_GROUP = 16;
 struct GroupedProblem {
   const bf16_t* A; const bf16_t* B; void* C; const bf16_t* R;
   int M, N, lda, ldb, ldc, tiles_m, tiles_n, first_tile;

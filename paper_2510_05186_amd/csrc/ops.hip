@@ -106,9 +106,9 @@ optstage_status optstage_op_gemm_swiglu(const void* A, const void* B, void* GU, 
 
 optstage_status optstage_op_gemm_grouped(uint32_t layout, uint32_t epilogue, uint32_t n,
                                          const optstage_gemm_problem* problems, uint32_t K, void* stream) {
-  REQ(problems && n >= 1 && n <= 32 && layout <= 1 && (epilogue == 0 || epilogue == 2 || (epilogue == 3 && layout == 1)),
+  REQ(problems && n >= 1 && n <= 16 && layout <= 1 && (epilogue == 0 || epilogue == 2 || (epilogue == 3 && layout == 1)),
       "gemm_grouped: bad argument");
-  GemmProblem pr[32];
+  GemmProblem pr[16];
   for (uint32_t i = 0; i < n; ++i) {
     const optstage_gemm_problem& q = problems[i];
     REQ(q.A && q.B && q.C, "gemm_grouped: null operand");

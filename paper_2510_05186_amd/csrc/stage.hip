@@ -640,7 +640,7 @@ optstage_status exec_backward_weight(optstage* st, int j, int c, const OpBufs& o
   const int T = s.tokens;
   auto P = [&](int l, int k) { return (void*)(st->arena() + ob.dev[(size_t)l * NK + k]); };
   // dW += dY^T X for the four linears of every layer (fp32 accumulators).  None of these products depends on
-  // another: bf16 stages hand them to one grouped launch per 32, so that only the last launch leaves a partly
+  // another: bf16 stages hand them to one grouped launch per 16, so that only the last launch leaves a partly
   // filled round of workgroups; anything the grouped path does not take runs product by product.
   std::vector<GemmProblem> pr;
   for (int l = c * s.Lc; l < (c + 1) * s.Lc; ++l) {
@@ -652,8 +652,8 @@ optstage_status exec_backward_weight(optstage* st, int j, int c, const OpBufs& o
   // W ops of a chunk run in micro-batch order: in overwrite mode micro-batch 0 stores its products (no read of the
   // accumulators, and nobody has to clear them between iterations), the others add
   const int epi = st->overwrite && j == 0 ? EPI_STOREF : EPI_ACCUM;
-  for (size_t i0 = 0; i0 < pr.size(); i0 += 32) {
-    const int n = (int)std::min<size_t>(32, pr.size() - i0);
+  for (size_t i0 = 0; i0 < pr.size(); i0 += 16) {
+    const int n = (int)std::min<size_t>(16, pr.size() - i0);
     const bool grouped = s.dtype == OPTSTAGE_BF16 && gemm_bf16_grouped_applies(GEMM_TN, n, &pr[i0], T);
     if (grouped) TRY(k_gemm_grouped(st, GEMM_TN, epi, n, &pr[i0], T));
     if (!grouped)
