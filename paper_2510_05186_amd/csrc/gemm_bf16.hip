@@ -8,7 +8,8 @@
 // of five operand slots in the direct kernels) with one barrier per step.
 // Large problems with K % 64 == 0 load their tiles straight from global memory into LDS (no registers, no
 // ds_write; see the direct kernels below); everything else stages tiles global -> registers -> LDS.  LDS tiles
-// are always [row][64 k] with the 16-byte chunk index XOR-swizzled by the row so that both the 16-byte operand reads of v_mfma_f32_32x32x16_bf16 and the tile writes are bank-conflict
+// are always [row][64 k] with the 16-byte chunk index XOR-swizzled by the row so that both the 16-byte operand reads
+// of v_mfma_f32_32x32x16_bf16 and the tile writes are bank-conflict
 // free.  Operands that are contiguous along their output index (TN) are transposed in registers on the
 // way into LDS (each thread gathers a KV x 8 patch and writes 8 k-contiguous pieces), so the MFMA read
 // path is identical for every layout.  The MFMA is issued with the B fragment as its first operand:

@@ -57,7 +57,8 @@ struct Shape {
 optstage_status shape_from_desc(const optstage_desc* d, Shape* s) {
   if (!d) return fail(OPTSTAGE_E_ARG, "desc is null");
   if (d->struct_size != sizeof(optstage_desc)) return fail(OPTSTAGE_E_ARG, "desc.struct_size mismatch");
-  if (d->family > 1 || d->dtype > 1 || d->recompute > 1 || d->no_fusion > 1 || d->reserved) return fail(OPTSTAGE_E_ARG, "bad family, dtype, recompute or no_fusion");
+  if (d->family > 1 || d->dtype > 1 || d->recompute > 1 || d->no_fusion > 1 || d->reserved)
+    return fail(OPTSTAGE_E_ARG, "bad family, dtype, recompute or no_fusion");
   if (!d->n_layers || !d->hidden || !d->n_q_heads || !d->n_kv_heads || !d->ffn || !d->seq || !d->micro_batch || !d->n_microbatches)
     return fail(OPTSTAGE_E_ARG, "zero-sized shape field");
   if (d->head_dim != 64 && d->head_dim != 128) return fail(OPTSTAGE_E_ARG, "head_dim must be 64 or 128");
@@ -469,7 +470,8 @@ optstage_status k_gemm(optstage* st, int layout, int epi, const void* A, const v
 // the two projections with a fused epilogue (bf16 only)
 optstage_status k_gemm_fused(optstage* st, int layout, int epi, const void* A, const void* B, void* C, int M, int N, int K,
                              int lda, int ldb, int ldc, const GemmExtra& ex) {
-  KT(epi == EPI_ROPE ? OPTSTAGE_KC_GEMM_NT_QKV : OPTSTAGE_KC_GEMM_NT_GU, 2.0 * M * N * K, launch_gemm_bf16(layout, epi, A, B, C, nullptr, M, N, K, lda, ldb, ldc, st->cs, &ex));
+  KT(epi == EPI_ROPE ? OPTSTAGE_KC_GEMM_NT_QKV : OPTSTAGE_KC_GEMM_NT_GU, 2.0 * M * N * K,
+     launch_gemm_bf16(layout, epi, A, B, C, nullptr, M, N, K, lda, ldb, ldc, st->cs, &ex));
   return OPTSTAGE_OK;
 }
 optstage_status k_gemm_grouped(optstage* st, int layout, int epi, int n, const GemmProblem* pr, int K) {
