@@ -29,8 +29,6 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBPS = 8000.0
 HEADLINE = "cfg4_gqa_bf16"
-KERNEL_SOURCES = {"gemm": "gemm_bf16.hip", "attn": "attention_mfma.hip", "norm": "elementwise.hip", "act": "elementwise.hip",
-                  "rope": "elementwise.hip"}
 KERNEL_NAMES = {"gemm_nt_store": "gemm_bf16_direct_kernel<NT, store>", "gemm_nt_resid": "gemm_bf16_direct_kernel<NT, residual>",
                 "gemm_nt_qkv": "gemm_bf16_direct_kernel<NT, rotary epilogue>", "gemm_nt_gu": "gemm_bf16_direct_kernel<NT, SwiGLU epilogue>",
                 "gemm_tn_accum": "gemm_bf16_direct_grouped_kernel<TN, fp32 accumulate>", "attn_fwd": "attn_fwd_mfma",
