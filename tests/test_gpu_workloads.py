@@ -220,8 +220,8 @@ def regime_check(cfg, budget, events, label):
 def test_cfg3_full_shape_offload_under_40_percent_of_the_peak():
     cfg2_list = G.split_bw_greedy(CFG.CFG2.n_stages, CFG.CFG2.n_microbatches)[CFG.CFG2.stage_index]
     budget = int(CFG.CFG3.budget_frac_of_peak * S.account_memory(cfg2_list, CFG.CFG2.n_layers, oracle_table(CFG.CFG2))[0])
-    m = 8
-    cfg = replace(CFG.CFG3, n_microbatches=m)
+    m = CFG.CFG3.n_microbatches                     # the whole list the benchmark runs: all 16 micro-batches
+    cfg = CFG.CFG3
     lists, info = SC.workload_lists(CFG.CFG3, budget, m=m)
     regime_check(cfg, budget, lists[cfg.stage_index], "cfg3")
 
