@@ -418,3 +418,17 @@ def test_workload_lists_fill_the_budget_and_are_chosen_by_modelled_makespan():
     # with room to spare the fill is denser than p - i in flight, and it pays in the model
     assert info["extra_fill"] > 0 and info["makespan_model"] < info["candidates"][0]["makespan_model"]
     assert SC.workload_lists(cfg, 0)[0] == base
+
+
+def test_workload_lists_in_the_recompute_variant_fit_the_oracles_recompute_accounting():
+    cfg = _small_cfg()
+    t = _table(cfg)
+    p, m = cfg.n_stages, cfg.n_microbatches
+    base = G.split_bw_greedy(p, m)
+    peak0 = max(S.account_memory(ev, cfg.n_layers, t, recompute=True)[0] for ev in base)
+    budget = int(0.8 * peak0)
+    lists, info = SC.workload_lists(cfg, budget, recompute=1)
+    assert any(e[0] == "O" for ev in lists for e in ev)
+    for ev in lists:
+        S.check_order(ev, m, cfg.n_layers, recompute=True)
+        assert S.account_memory(ev, cfg.n_layers, t, limit=budget, recompute=True)[0] <= budget
