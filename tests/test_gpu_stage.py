@@ -800,3 +800,53 @@ def test_fused_epilogues_against_the_oracle_and_the_separate_kernels():
     for key in runs[0][2]:
         assert rms_err(runs[0][2][key], runs[1][2][key]) < 1e-2, key
     assert any(not np.array_equal(runs[0][0][j], runs[1][0][j]) for j in range(2))
+
+
+def test_every_forward_kind_survives_offload_and_reload():
+    """The paper's coarse decision (the whole activation of a forward op leaves): all ten kinds of every layer of a
+    micro-batch offloaded and reloaded, checksums per kind, results bitwise those of the run without transfers; an
+    empty list and a short trace buffer on the way."""
+    cfg = replace(SMALL4, n_microbatches=3)
+    ws = T.stage_weights(cfg)
+    t = oracle_table(cfg)
+    kinds = tuple(S.F_KINDS)
+    comp = [("F", 0), ("F", 1), ("F", 2), ("B", 0), ("W", 0), ("B", 1), ("W", 1), ("B", 2), ("W", 2)]
+    events = [("F", 0), ("F", 1)] + [("O", 1, l, kinds) for l in range(cfg.n_layers)] + [("F", 2)] + \
+             [("OWAIT", 1, l, kinds) for l in range(cfg.n_layers)] + [("B", 0), ("W", 0)] + \
+             [("R", 1, l, kinds) for l in reversed(range(cfg.n_layers))] + [("B", 1), ("W", 1), ("B", 2), ("W", 2)]
+    S.check_order(events, 3, cfg.n_layers)
+    peak, trace = S.account_memory(events, cfg.n_layers, t)
+    ref = gpu_run(cfg, ws, comp)
+    pool = 2 * sum(t[k] for k in kinds) * cfg.n_layers
+    st = Stage(cfg, host_pool_bytes=pool)
+    st.set_weights(ws)
+    for j in range(3):
+        st.bind(j, T.stage_input(cfg, j), T.output_grad(cfg, j))
+    st.run([])                                                   # an empty list is valid and does nothing
+    assert st.stats().n_trace == 0
+    sums = {}
+    for ev in events:
+        if ev[0] == "O":
+            for k in kinds:
+                sums[(ev[2], k)] = st.checksum(1, ev[2], k)
+        st.run([ev])
+        if ev[0] == "O":
+            assert all(st.checksum(1, ev[2], k, where=1) == sums[(ev[2], k)] for k in kinds)
+        if ev[0] == "R":
+            assert all(st.checksum(1, ev[2], k) == sums[(ev[2], k)] for k in kinds)
+    st.synchronize()
+    s = st.stats()
+    assert s.peak_bytes == peak and s.live_bytes == 0 and [e[4] for e in st.trace()] == trace
+    assert s.bytes_offloaded == s.bytes_reloaded == sum(t[k] for k in kinds) * cfg.n_layers
+    # a trace buffer shorter than the trace receives its first entries and the total
+    n = C.c_size_t(0)
+    few = (B.TraceEntry * 3)()
+    B.check(B.lib().optstage_get_trace(st.h, few, 3, C.byref(n)))
+    assert n.value == len(events) and [few[i].op for i in range(3)] == [B.OP_CODE[e[0]] for e in events[:3]]
+    for j in range(3):
+        assert torch.equal(st.y[j], ref.y[j]) and torch.equal(st.dx[j], ref.dx[j])
+    for l in range(cfg.n_layers):
+        for name in st.grads[l]:
+            assert torch.equal(st.grads[l][name], ref.grads[l][name]), (l, name)
+    st.close()
+    ref.close()
